@@ -1,0 +1,16 @@
+"""CPU oracle of the Cutoff-SGD predictor: test infrastructure, not product code.
+
+Thin ctypes binding over `cutoff_oracle.c` (double precision, plain loops).
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package; the GPU library never does.
+"""
+from .binding import (  # noqa: F401
+    OracleModel,
+    build,
+    cutoff_select,
+    num_threads,
+    set_threads,
+    NO_ELIGIBLE,
+    OK,
+    WARMUP,
+)

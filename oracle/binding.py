@@ -1,0 +1,186 @@
+"""ctypes binding for the C oracle (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "cutoff_oracle.c"
+_LIB = _HERE / "libcutoff_oracle.so"
+
+OK, WARMUP, NO_ELIGIBLE = 0, 1, 2
+
+
+class _Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_workers", "lag", "z_dim", "hidden", "rnn_dim", "emit_mean_act")]
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (plain C99 + OpenMP)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        subprocess.run(
+            ["gcc", "-std=c99", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = C.CDLL(str(_LIB))
+    dp, fp, ip = C.POINTER(C.c_double), C.POINTER(C.c_float), C.POINTER(C.c_int32)
+    lib.oracle_blob_bytes.restype = C.c_size_t
+    lib.oracle_blob_bytes.argtypes = [C.POINTER(_Config)]
+    lib.oracle_load_weights.restype = C.c_void_p
+    lib.oracle_load_weights.argtypes = [C.POINTER(_Config), C.c_void_p, C.c_size_t]
+    lib.oracle_free.argtypes = [C.c_void_p]
+    lib.oracle_reset.argtypes = [C.c_void_p]
+    lib.oracle_scale.restype = C.c_double
+    lib.oracle_scale.argtypes = [C.c_void_p]
+    lib.oracle_filter_step.argtypes = [C.c_void_p, dp]
+    lib.oracle_encode_window.argtypes = [C.c_void_p, dp, dp]
+    lib.oracle_sample_runtimes.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp]
+    lib.oracle_cutoff_select.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
+    lib.oracle_cutoff_select_f32.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
+    lib.oracle_predict_cutoff.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_double, ip]
+    lib.oracle_num_threads.restype = C.c_int
+    lib.oracle_set_threads.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().oracle_set_threads(int(n))
+
+
+def _dp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_double)) if a is not None else None
+
+
+def _fp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_float)) if a is not None else None
+
+
+def _ip(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32)) if a is not None else None
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class OracleModel:
+    """Weights + fixed-lag window of one predictor, on the CPU, in float64."""
+
+    def __init__(self, cfg, blob: np.ndarray, emit_mean_act: int = 0):
+        lib = _load()
+        self.cfg = cfg
+        self._c = _Config(cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim, int(emit_mean_act))
+        raw = np.ascontiguousarray(blob).view(np.uint8)
+        self._h = lib.oracle_load_weights(C.byref(self._c), raw.ctypes.data, raw.size)
+        if not self._h:
+            raise ValueError("oracle_load_weights rejected the configuration or blob")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _load().oracle_free(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def reset(self):
+        _load().oracle_reset(self._h)
+
+    @property
+    def scale(self) -> float:
+        return float(_load().oracle_scale(self._h))
+
+    def filter_step(self, x_obs) -> int:
+        x = np.ascontiguousarray(x_obs, dtype=np.float64)
+        assert x.shape == (self.cfg.n_workers,)
+        rc = _load().oracle_filter_step(self._h, _dp(x))
+        if rc < 0:
+            raise ValueError(f"oracle_filter_step: error {rc}")
+        return rc
+
+    def encode_window(self):
+        L, R = self.cfg.lag, self.cfg.rnn_dim
+        hl, hr = np.empty((L, R)), np.empty((L, R))
+        rc = _load().oracle_encode_window(self._h, _dp(hl), _dp(hr))
+        if rc < 0:
+            raise RuntimeError(f"oracle_encode_window: error {rc}")
+        return hl, hr
+
+    def sample_runtimes(self, eps_q, eps_z, eps_x, rows=None, stages: bool = False):
+        """Samples [n][N] in seconds (float64); with stages=True also z_T, z_{T+1}, I, J."""
+        cfg = self.cfg
+        eps_q, eps_z, eps_x = _f32(eps_q), _f32(eps_z), _f32(eps_x)
+        S = eps_z.shape[0]
+        assert eps_q.shape == (cfg.lag, S, cfg.z_dim) and eps_z.shape == (S, cfg.z_dim)
+        assert eps_x.shape == (S, cfg.n_workers)
+        r = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+        n = S if r is None else r.size
+        x = np.empty((n, cfg.n_workers))
+        zT = np.empty((n, cfg.z_dim)) if stages else None
+        zn = np.empty((n, cfg.z_dim)) if stages else None
+        mean = np.empty((n, cfg.n_workers)) if stages else None
+        sd = np.empty((n, cfg.n_workers)) if stages else None
+        rc = _load().oracle_sample_runtimes(self._h, S, _ip(r), n, _fp(eps_q), _fp(eps_z), _fp(eps_x),
+                                            _dp(x), _dp(zT), _dp(zn), _dp(mean), _dp(sd))
+        if rc < 0:
+            raise RuntimeError(f"oracle_sample_runtimes: error {rc}")
+        if stages:
+            return x, dict(z_T=zT, z_next=zn, emit_mean=mean, emit_sd=sd)
+        return x
+
+    def predict_cutoff(self, eps_q, eps_z, eps_x, c_min=1, c_max=None, t_floor=0.0):
+        eps_q, eps_z, eps_x = _f32(eps_q), _f32(eps_z), _f32(eps_x)
+        c_max = self.cfg.n_workers if c_max is None else c_max
+        out = np.zeros(1, dtype=np.int32)
+        rc = _load().oracle_predict_cutoff(self._h, eps_z.shape[0], _fp(eps_q), _fp(eps_z), _fp(eps_x),
+                                           c_min, c_max, float(t_floor), _ip(out))
+        if rc < 0:
+            raise RuntimeError(f"oracle_predict_cutoff: error {rc}")
+        return int(out[0]), rc
+
+
+def cutoff_select(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=True, want_perm=True):
+    """Sort rows, average ranks, Omega(c) = c / mean, argmax.  Returns a dict."""
+    a = np.ascontiguousarray(samples)
+    if a.ndim != 2:
+        raise ValueError("samples must be [S][N]")
+    S, N = a.shape
+    c_max = N if c_max is None else c_max
+    srt = np.empty((S, N)) if want_sorted else None
+    perm = np.empty((S, N), dtype=np.int32) if want_perm else None
+    mean, omega = np.empty(N), np.empty(N)
+    cstar = np.zeros(1, dtype=np.int32)
+    lib = _load()
+    if a.dtype == np.float32:
+        rc = lib.oracle_cutoff_select_f32(_fp(a), S, N, c_min, c_max, float(t_floor),
+                                          _dp(srt), _ip(perm), _dp(mean), _dp(omega), _ip(cstar))
+    else:
+        a = np.ascontiguousarray(a, dtype=np.float64)
+        rc = lib.oracle_cutoff_select(_dp(a), S, N, c_min, c_max, float(t_floor),
+                                      _dp(srt), _ip(perm), _dp(mean), _dp(omega), _ip(cstar))
+    if rc < 0:
+        raise ValueError(f"oracle_cutoff_select: error {rc}")
+    return dict(status=rc, cstar=int(cstar[0]), mean=mean, omega=omega, sorted=srt, perm=perm)

@@ -1,0 +1,412 @@
+/*
+ * CPU oracle for the Cutoff-SGD predictor: TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision restatement of what the paper's
+ * predict_cutoff computes (Teng & Wood, "High Throughput Synchronous
+ * Distributed SGD", Alg. 1 server loop; Sec. 3, 3.1.1-3.1.3).  Nothing in the
+ * product path may call into this file; it shares no code with the GPU
+ * library and exists so that tests, the smoke check and the benchmark's CPU
+ * baseline have something independent to compare against.
+ *
+ * Every layer is written as  y = act(W x + b)  with W stored [out][in], one
+ * loop nest per layer, no blocking, no fusion, no BLAS.  The only parallelism
+ * is an OpenMP loop over the independent Monte-Carlo samples.
+ *
+ * Readings taken where the paper is silent or ambiguous are marked READING.
+ *
+ * Parity pins (tests, CPU only): closed-form order statistics of iid
+ * uniform / exponential / normal rows, brute-force argmax on tiny N, the
+ * paper's 10 s / 8 s example, degenerate-weight cases that collapse the
+ * network to closed forms, and an independent numpy float64 transcription of
+ * the equations.  The trained-model behaviour of the whole pipeline (the
+ * paper's Fig. 2/3) is "parity unpinned": no trained weights, traces or
+ * printed predictions exist to compare with.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_OK 0
+#define ORACLE_WARMUP 1
+#define ORACLE_NO_ELIGIBLE 2
+#define ORACLE_EINVAL (-1)
+#define ORACLE_ENOTREADY (-2)
+#define ORACLE_EBADOBS (-3)
+
+typedef struct {
+    int32_t n_workers, lag, z_dim, hidden, rnn_dim;
+    int32_t emit_mean_act; /* 0: identity hidden layer in I (paper), 1: ReLU */
+} oracle_config;
+
+typedef struct {
+    oracle_config cfg;
+    /* inference network (Sec. 3.1.3, guide program) */
+    double *rnn_f_w_ih, *rnn_f_b_ih, *rnn_f_w_hh, *rnn_f_b_hh;
+    double *rnn_b_w_ih, *rnn_b_b_ih, *rnn_b_w_hh, *rnn_b_b_hh;
+    double *comb_w, *comb_b, *mu_w, *mu_b, *sig_w, *sig_b, *z0;
+    /* gated transition G, H */
+    double *gate1_w, *gate1_b, *gate2_w, *gate2_b;
+    double *prop1_w, *prop1_b, *prop2_w, *prop2_b;
+    double *lin_w, *lin_b, *tscale_w, *tscale_b;
+    /* emission I, J */
+    double *emean1_w, *emean1_b, *emean2_w, *emean2_b;
+    double *escale1_w, *escale1_b, *escale2_w, *escale2_b;
+    double *store;
+    /* fixed-lag window of raw observations, oldest first */
+    double *window; /* [L][N] */
+    int32_t count;  /* observations pushed so far (saturates at INT32_MAX) */
+    double scale;   /* normaliser s; 0 until the first window is complete */
+} oracle_model;
+
+static size_t blob_floats(const oracle_config *c) {
+    size_t N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
+    size_t rnn = 2 * (R * N + R + R * R + R);
+    size_t guide = R * Z + R + Z * R + Z + Z * Z + Z + Z;
+    size_t trans = 2 * (H * Z + H + Z * H + Z) + 2 * (Z * Z + Z);
+    size_t emit = H * Z + H + N * H + N + H * N + H + N * H + N;
+    return rnn + guide + trans + emit;
+}
+
+size_t oracle_blob_bytes(const oracle_config *c) { return 32 + 4 * blob_floats(c); }
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+void oracle_free(oracle_model *m) {
+    if (!m) return;
+    free(m->store);
+    free(m->window);
+    free(m);
+}
+
+/* Weight blob: int32[8] header {magic 'DKFW', version, N, L, Z, H, R, 0}, then
+ * fp32 tensors in the fixed order below, each matrix [out][in] row-major. */
+oracle_model *oracle_load_weights(const oracle_config *c, const void *blob, size_t bytes) {
+    if (!c || !blob) return NULL;
+    if (c->n_workers < 1 || c->lag < 1 || c->z_dim < 1 || c->hidden < 1 || c->rnn_dim < 1) return NULL;
+    if (bytes != oracle_blob_bytes(c)) return NULL;
+    int32_t head[8];
+    memcpy(head, blob, 32);
+    if (head[0] != 0x57464B44 || head[1] != 1 || head[2] != c->n_workers || head[3] != c->lag ||
+        head[4] != c->z_dim || head[5] != c->hidden || head[6] != c->rnn_dim)
+        return NULL;
+    oracle_model *m = (oracle_model *)calloc(1, sizeof *m);
+    if (!m) return NULL;
+    m->cfg = *c;
+    size_t nf = blob_floats(c);
+    m->store = (double *)malloc(nf * sizeof(double));
+    m->window = (double *)calloc((size_t)c->lag * c->n_workers, sizeof(double));
+    if (!m->store || !m->window) { oracle_free(m); return NULL; }
+    const float *src = (const float *)((const char *)blob + 32);
+    for (size_t i = 0; i < nf; ++i) m->store[i] = (double)src[i];
+    size_t N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
+    double *p = m->store;
+#define TAKE(field, count) do { m->field = p; p += (count); } while (0)
+    TAKE(rnn_f_w_ih, R * N); TAKE(rnn_f_b_ih, R); TAKE(rnn_f_w_hh, R * R); TAKE(rnn_f_b_hh, R);
+    TAKE(rnn_b_w_ih, R * N); TAKE(rnn_b_b_ih, R); TAKE(rnn_b_w_hh, R * R); TAKE(rnn_b_b_hh, R);
+    TAKE(comb_w, R * Z); TAKE(comb_b, R);
+    TAKE(mu_w, Z * R); TAKE(mu_b, Z);
+    TAKE(sig_w, Z * Z); TAKE(sig_b, Z);
+    TAKE(z0, Z);
+    TAKE(gate1_w, H * Z); TAKE(gate1_b, H); TAKE(gate2_w, Z * H); TAKE(gate2_b, Z);
+    TAKE(prop1_w, H * Z); TAKE(prop1_b, H); TAKE(prop2_w, Z * H); TAKE(prop2_b, Z);
+    TAKE(lin_w, Z * Z); TAKE(lin_b, Z);
+    TAKE(tscale_w, Z * Z); TAKE(tscale_b, Z);
+    TAKE(emean1_w, H * Z); TAKE(emean1_b, H); TAKE(emean2_w, N * H); TAKE(emean2_b, N);
+    TAKE(escale1_w, H * N); TAKE(escale1_b, H); TAKE(escale2_w, N * H); TAKE(escale2_b, N);
+#undef TAKE
+    m->count = 0;
+    m->scale = 0.0;
+    return m;
+}
+
+void oracle_reset(oracle_model *m) {
+    m->count = 0;
+    m->scale = 0.0;
+    memset(m->window, 0, sizeof(double) * (size_t)m->cfg.lag * m->cfg.n_workers);
+}
+
+double oracle_scale(const oracle_model *m) { return m->scale; }
+
+/* ---- elementary functions ------------------------------------------------ */
+
+static double relu(double v) { return v > 0.0 ? v : 0.0; }
+static double softplus(double v) { return (v > 0.0 ? v : 0.0) + log1p(exp(-fabs(v))); }
+static double sigmoid(double v) {
+    if (v >= 0.0) return 1.0 / (1.0 + exp(-v));
+    double e = exp(v);
+    return e / (1.0 + e);
+}
+
+/* y[out] = W[out][in] x + b */
+static void affine(const double *W, const double *b, const double *x, int n_in, int n_out, double *y) {
+    for (int o = 0; o < n_out; ++o) {
+        double acc = b[o];
+        for (int i = 0; i < n_in; ++i) acc += W[(size_t)o * n_in + i] * x[i];
+        y[o] = acc;
+    }
+}
+
+/* ---- fixed-lag window and normaliser (Sec. 3.1.2; end of Sec. 3.1.3) ------ */
+
+/* Append one observed N-vector of run-times (seconds).  The window holds the
+ * last L vectors.  READING: the normaliser is one scalar, twice the mean of
+ * the first complete window, fixed from then on.  Returns ORACLE_WARMUP until
+ * L vectors have been seen. */
+int oracle_filter_step(oracle_model *m, const double *x_obs) {
+    int N = m->cfg.n_workers, L = m->cfg.lag;
+    for (int j = 0; j < N; ++j)
+        if (!isfinite(x_obs[j]) || !(x_obs[j] > 0.0)) return ORACLE_EBADOBS;
+    if (m->count >= L) memmove(m->window, m->window + N, sizeof(double) * (size_t)(L - 1) * N);
+    int slot = m->count < L ? m->count : L - 1;
+    memcpy(m->window + (size_t)slot * N, x_obs, sizeof(double) * N);
+    if (m->count < INT32_MAX) m->count++;
+    if (m->count == L) {
+        double sum = 0.0;
+        for (size_t i = 0; i < (size_t)L * N; ++i) sum += m->window[i];
+        m->scale = 2.0 * sum / ((double)L * N);
+    }
+    return m->count < L ? ORACLE_WARMUP : ORACLE_OK;
+}
+
+/* The RNN encodings of the guide (Sec. 3.1.3): h_left runs forward over the
+ * window from a zero state, h_right backward.  READING: single-layer Elman
+ * cells with ReLU, h_t = ReLU(W_ih x_t + b_ih + W_hh h_prev + b_hh); the
+ * encodings at position t include x_t on both sides.  hl, hr: [L][R]. */
+int oracle_encode_window(const oracle_model *m, double *hl, double *hr) {
+    int N = m->cfg.n_workers, L = m->cfg.lag, R = m->cfg.rnn_dim;
+    if (m->count < L) return ORACLE_ENOTREADY;
+    double *xn = (double *)malloc(sizeof(double) * N);
+    double *a = (double *)malloc(sizeof(double) * R);
+    double *b = (double *)malloc(sizeof(double) * R);
+    double *prev = (double *)malloc(sizeof(double) * R);
+    for (int dir = 0; dir < 2; ++dir) {
+        const double *w_ih = dir ? m->rnn_b_w_ih : m->rnn_f_w_ih, *b_ih = dir ? m->rnn_b_b_ih : m->rnn_f_b_ih;
+        const double *w_hh = dir ? m->rnn_b_w_hh : m->rnn_f_w_hh, *b_hh = dir ? m->rnn_b_b_hh : m->rnn_f_b_hh;
+        double *out = dir ? hr : hl;
+        for (int r = 0; r < R; ++r) prev[r] = 0.0;
+        for (int step = 0; step < L; ++step) {
+            int t = dir ? L - 1 - step : step;
+            for (int j = 0; j < N; ++j) xn[j] = m->window[(size_t)t * N + j] / m->scale;
+            affine(w_ih, b_ih, xn, N, R, a);
+            affine(w_hh, b_hh, prev, R, R, b);
+            for (int r = 0; r < R; ++r) prev[r] = relu(a[r] + b[r]);
+            memcpy(out + (size_t)t * R, prev, sizeof(double) * R);
+        }
+    }
+    free(xn); free(a); free(b); free(prev);
+    return ORACLE_OK;
+}
+
+/* ---- one Monte-Carlo sample (Sec. 3.1.3, posterior-predictive approximation) */
+
+typedef struct { double *r1, *r2, *z, *mu, *pre, *zn, *g, *h, *lin, *G, *hid, *mean, *sd; } scratch;
+
+static scratch scratch_new(const oracle_config *c) {
+    scratch s;
+    int N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
+    int big = H > R ? H : R;
+    s.r1 = (double *)malloc(sizeof(double) * big);
+    s.r2 = (double *)malloc(sizeof(double) * big);
+    s.hid = (double *)malloc(sizeof(double) * big);
+    s.z = (double *)malloc(sizeof(double) * Z);
+    s.mu = (double *)malloc(sizeof(double) * Z);
+    s.pre = (double *)malloc(sizeof(double) * Z);
+    s.zn = (double *)malloc(sizeof(double) * Z);
+    s.g = (double *)malloc(sizeof(double) * Z);
+    s.h = (double *)malloc(sizeof(double) * Z);
+    s.lin = (double *)malloc(sizeof(double) * Z);
+    s.G = (double *)malloc(sizeof(double) * Z);
+    s.mean = (double *)malloc(sizeof(double) * N);
+    s.sd = (double *)malloc(sizeof(double) * N);
+    return s;
+}
+
+static void scratch_free(scratch *s) {
+    free(s->r1); free(s->r2); free(s->hid); free(s->z); free(s->mu); free(s->pre); free(s->zn);
+    free(s->g); free(s->h); free(s->lin); free(s->G); free(s->mean); free(s->sd);
+}
+
+static void sample_one(const oracle_model *m, const double *hl, const double *hr, int S, int k,
+                       const float *eps_q, const float *eps_z, const float *eps_x, scratch *w,
+                       double *x_out, double *zT_out, double *zn_out, double *mean_out, double *sd_out) {
+    int N = m->cfg.n_workers, L = m->cfg.lag, Z = m->cfg.z_dim, H = m->cfg.hidden, R = m->cfg.rnn_dim;
+    /* Guide chain: z_t ~ N(mu_q, sigma_q) for t = 1..L, sequential in t.
+     * READING: the latent before the window is a learned vector z0. */
+    for (int i = 0; i < Z; ++i) w->z[i] = m->z0[i];
+    for (int t = 0; t < L; ++t) {
+        affine(m->comb_w, m->comb_b, w->z, Z, R, w->r1);
+        for (int r = 0; r < R; ++r)
+            w->r2[r] = (tanh(w->r1[r]) + hl[(size_t)t * R + r] + hr[(size_t)t * R + r]) / 3.0; /* h_out */
+        affine(m->mu_w, m->mu_b, w->r2, R, Z, w->mu);                                         /* mu_q = K(h_out) */
+        affine(m->sig_w, m->sig_b, w->mu, Z, Z, w->pre);                                      /* sigma_q = L(mu_q) */
+        for (int i = 0; i < Z; ++i) {
+            double sigma = softplus(w->pre[i]);
+            /* READING: the second argument of N(.,.) is a standard deviation */
+            w->z[i] = w->mu[i] + sigma * (double)eps_q[((size_t)t * S + k) * Z + i];
+        }
+    }
+    if (zT_out) memcpy(zT_out, w->z, sizeof(double) * Z);
+    /* Gated transition z_{T+1} ~ N(G(z_T), H(z_T)) */
+    affine(m->gate1_w, m->gate1_b, w->z, Z, H, w->hid);
+    for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
+    affine(m->gate2_w, m->gate2_b, w->hid, H, Z, w->g);
+    for (int i = 0; i < Z; ++i) w->g[i] = sigmoid(w->g[i]);
+    affine(m->prop1_w, m->prop1_b, w->z, Z, H, w->hid);
+    for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
+    affine(m->prop2_w, m->prop2_b, w->hid, H, Z, w->h);
+    affine(m->lin_w, m->lin_b, w->z, Z, Z, w->lin);
+    for (int i = 0; i < Z; ++i) w->G[i] = (1.0 - w->g[i]) * w->lin[i] + w->g[i] * w->h[i];
+    for (int i = 0; i < Z; ++i) w->mu[i] = relu(w->G[i]);
+    affine(m->tscale_w, m->tscale_b, w->mu, Z, Z, w->pre);
+    for (int i = 0; i < Z; ++i)
+        w->zn[i] = w->G[i] + softplus(w->pre[i]) * (double)eps_z[(size_t)k * Z + i];
+    if (zn_out) memcpy(zn_out, w->zn, sizeof(double) * Z);
+    /* Emission x_{T+1} ~ N(I(z_{T+1}), J(z_{T+1})), J fed by I's output */
+    affine(m->emean1_w, m->emean1_b, w->zn, Z, H, w->hid);
+    if (m->cfg.emit_mean_act == 1)
+        for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
+    affine(m->emean2_w, m->emean2_b, w->hid, H, N, w->mean);
+    affine(m->escale1_w, m->escale1_b, w->mean, N, H, w->hid);
+    for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
+    affine(m->escale2_w, m->escale2_b, w->hid, H, N, w->sd);
+    for (int j = 0; j < N; ++j) {
+        w->sd[j] = softplus(w->sd[j]);
+        /* back to seconds: the model lives in units of the normaliser */
+        x_out[j] = m->scale * (w->mean[j] + w->sd[j] * (double)eps_x[(size_t)k * N + j]);
+    }
+    if (mean_out) memcpy(mean_out, w->mean, sizeof(double) * N);
+    if (sd_out) memcpy(sd_out, w->sd, sizeof(double) * N);
+}
+
+/* Draw run-time vectors for the samples listed in `rows` (or all S samples
+ * when rows == NULL, then n_rows is ignored).  Noise tensors are inputs:
+ * eps_q [L][S][Z], eps_z [S][Z], eps_x [S][N], fp32 standard normals.
+ * Outputs are [n_out][.] in the order of `rows`; optional ones may be NULL. */
+int oracle_sample_runtimes(const oracle_model *m, int S, const int32_t *rows, int n_rows,
+                           const float *eps_q, const float *eps_z, const float *eps_x,
+                           double *out_samples, double *out_zT, double *out_znext,
+                           double *out_mean, double *out_sd) {
+    int N = m->cfg.n_workers, L = m->cfg.lag, Z = m->cfg.z_dim, R = m->cfg.rnn_dim;
+    if (S < 1 || !eps_q || !eps_z || !eps_x || !out_samples) return ORACLE_EINVAL;
+    if (m->count < L) return ORACLE_ENOTREADY;
+    int n_out = rows ? n_rows : S;
+    for (int i = 0; rows && i < n_rows; ++i)
+        if (rows[i] < 0 || rows[i] >= S) return ORACLE_EINVAL;
+    double *hl = (double *)malloc(sizeof(double) * (size_t)L * R);
+    double *hr = (double *)malloc(sizeof(double) * (size_t)L * R);
+    oracle_encode_window(m, hl, hr);
+#pragma omp parallel
+    {
+        scratch w = scratch_new(&m->cfg);
+#pragma omp for schedule(static)
+        for (int i = 0; i < n_out; ++i) {
+            int k = rows ? rows[i] : i;
+            sample_one(m, hl, hr, S, k, eps_q, eps_z, eps_x, &w, out_samples + (size_t)i * N,
+                       out_zT ? out_zT + (size_t)i * Z : NULL, out_znext ? out_znext + (size_t)i * Z : NULL,
+                       out_mean ? out_mean + (size_t)i * N : NULL, out_sd ? out_sd + (size_t)i * N : NULL);
+        }
+        scratch_free(&w);
+    }
+    free(hl); free(hr);
+    return ORACLE_OK;
+}
+
+/* ---- Monte-Carlo order statistics and the cutoff (Sec. 3; Sec. 3.1.1) ------ */
+
+typedef struct { double v; int32_t idx; } keyed;
+
+/* READING: ties are ordered -0 before +0, NaN last, then by worker index, so
+ * the permutation is unique. */
+static int keyed_cmp(const void *pa, const void *pb) {
+    const keyed *a = (const keyed *)pa, *b = (const keyed *)pb;
+    int na = isnan(a->v), nb = isnan(b->v);
+    if (na != nb) return na ? 1 : -1;
+    if (!na) {
+        if (a->v < b->v) return -1;
+        if (a->v > b->v) return 1;
+        int sa = signbit(a->v) != 0, sb = signbit(b->v) != 0;
+        if (sa != sb) return sa ? -1 : 1;
+    }
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+/* samples [S][N]: sort every row ascending ("sample, sort, record"), average
+ * each rank over the S rows, form Omega(c) = c / mean x_(c) and return the
+ * maximiser, 1-based.  READING: only c in [c_min, c_max] whose mean exceeds
+ * t_floor are eligible; ties go to the largest c; with nothing eligible the
+ * answer is c_max and the status ORACLE_NO_ELIGIBLE.
+ * out_sorted [S][N], out_perm [S][N] (0-based worker per rank), out_mean [N],
+ * out_omega [N] (-inf where ineligible) are optional. */
+int oracle_cutoff_select(const double *samples, int S, int N, int c_min, int c_max, double t_floor,
+                         double *out_sorted, int32_t *out_perm, double *out_mean, double *out_omega,
+                         int32_t *out_cstar) {
+    if (!samples || !out_cstar || S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return ORACLE_EINVAL;
+    double *sum = (double *)calloc(N, sizeof(double));
+    keyed *row = (keyed *)malloc(sizeof(keyed) * N);
+    for (int k = 0; k < S; ++k) {
+        for (int j = 0; j < N; ++j) { row[j].v = samples[(size_t)k * N + j]; row[j].idx = j; }
+        qsort(row, N, sizeof(keyed), keyed_cmp);
+        for (int c = 0; c < N; ++c) {
+            sum[c] += row[c].v;
+            if (out_sorted) out_sorted[(size_t)k * N + c] = row[c].v;
+            if (out_perm) out_perm[(size_t)k * N + c] = row[c].idx;
+        }
+    }
+    int best = -1;
+    double best_omega = -INFINITY;
+    for (int c = 1; c <= N; ++c) {
+        double mean = sum[c - 1] / (double)S;
+        double omega = -INFINITY;
+        if (c >= c_min && c <= c_max && mean > t_floor) omega = (double)c / mean;
+        if (out_mean) out_mean[c - 1] = mean;
+        if (out_omega) out_omega[c - 1] = omega;
+        if (omega > -INFINITY && omega >= best_omega) { best_omega = omega; best = c; }
+    }
+    free(sum); free(row);
+    if (best < 0) { *out_cstar = c_max; return ORACLE_NO_ELIGIBLE; }
+    *out_cstar = best;
+    return ORACLE_OK;
+}
+
+/* Same, for an fp32 sample matrix (what the GPU hands over): every float is
+ * exactly representable as a double, so order and ties are unchanged. */
+int oracle_cutoff_select_f32(const float *samples, int S, int N, int c_min, int c_max, double t_floor,
+                             double *out_sorted, int32_t *out_perm, double *out_mean, double *out_omega,
+                             int32_t *out_cstar) {
+    if (!samples || S < 1 || N < 1) return ORACLE_EINVAL;
+    double *wide = (double *)malloc(sizeof(double) * (size_t)S * N);
+    for (size_t i = 0; i < (size_t)S * N; ++i) wide[i] = (double)samples[i];
+    int rc = oracle_cutoff_select(wide, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean, out_omega, out_cstar);
+    free(wide);
+    return rc;
+}
+
+/* The whole decision for the current window: sample, sort, average, argmax. */
+int oracle_predict_cutoff(const oracle_model *m, int S, const float *eps_q, const float *eps_z,
+                          const float *eps_x, int c_min, int c_max, double t_floor, int32_t *out_cstar) {
+    int N = m->cfg.n_workers;
+    if (S < 1) return ORACLE_EINVAL;
+    double *x = (double *)malloc(sizeof(double) * (size_t)S * N);
+    int rc = oracle_sample_runtimes(m, S, NULL, 0, eps_q, eps_z, eps_x, x, NULL, NULL, NULL, NULL);
+    if (rc == ORACLE_OK) rc = oracle_cutoff_select(x, S, N, c_min, c_max, t_floor, NULL, NULL, NULL, NULL, out_cstar);
+    free(x);
+    return rc;
+}
