@@ -1,0 +1,182 @@
+/*
+ * cutoff_dkf.h -- C ABI of the MI355X (gfx950) Cutoff-SGD run-time predictor.
+ *
+ * The library implements the parameter server's predict_cutoff call of
+ * Teng & Wood, "High Throughput Synchronous Distributed Stochastic Gradient
+ * Descent" (Alg. 1, server loop): from the last L observed N-worker run-time
+ * vectors it draws S joint predictions of the next run-time vector from the
+ * learned deep generative dynamical model (Sec. 3.1.2-3.1.3) and returns the
+ * cutoff c* = argmax_c c / E[x_(c)] (Sec. 3; Monte-Carlo order statistics,
+ * Sec. 3.1.1, last paragraph).
+ *
+ * Conventions
+ *   - Every function returns an int: 0 = DKF_OK, > 0 = informational status,
+ *     < 0 = error.  Nothing throws, aborts or prints.
+ *   - "host" pointers are ordinary process memory, "dev" pointers are HIP
+ *     device memory on the current device.  The caller owns every buffer it
+ *     passes in and must keep it alive until the work queued on `stream` has
+ *     finished; the library never frees or reallocates caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Unless stated otherwise calls only enqueue work and return; results are
+ *     valid once the caller has synchronised the stream.
+ *   - Matrices are row-major; sample tensors are sample-major ([S][.]), so one
+ *     sampled N-vector is contiguous.
+ *   - Calls on one dkf_model must not overlap in time (one stream at a time).
+ */
+#ifndef CUTOFF_DKF_H
+#define CUTOFF_DKF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status / error codes */
+#define DKF_OK 0
+#define DKF_WARMUP 1             /* fewer than L observations so far: no prediction possible, use c = N */
+#define CUTOFF_NO_ELIGIBLE 2     /* no cutoff passed the floor; c* was set to c_max */
+#define DKF_EINVAL (-1)          /* bad dimension, NULL pointer, c_min > c_max, S < 1 ... */
+#define DKF_ENOTREADY (-2)       /* sampling requested before L observations were pushed */
+#define DKF_EBADOBS (-3)         /* an observed run-time was non-finite or <= 0 */
+#define DKF_EHIP (-4)            /* a HIP runtime call failed; see dkf_last_hip_error() */
+#define DKF_ENOMEM (-5)          /* host or device allocation failed */
+#define DKF_EBLOB (-6)           /* weight blob header/size does not match the configuration */
+#define DKF_EUNSUPPORTED (-7)    /* a size beyond what the kernels are built for (see each call) */
+
+#define DKF_DTYPE_F32 0          /* MLP GEMMs in fp32 */
+#define DKF_DTYPE_BF16 1         /* MLP GEMM inputs rounded to bf16, fp32 accumulate */
+
+typedef struct dkf_model dkf_model; /* opaque: device weights, fixed-lag window, workspace */
+
+typedef struct {
+    int32_t n_workers;     /* N  */
+    int32_t lag;           /* L: window length (the paper's l; l = 20 in its experiments, Sec. 4) */
+    int32_t z_dim;         /* Z: latent dimension */
+    int32_t hidden;        /* H: hidden width of every two-layer MLP (transition, emission) */
+    int32_t rnn_dim;       /* R: width of the two RNN encoders = width of h_out */
+    int32_t mlp_dtype;     /* DKF_DTYPE_F32 or DKF_DTYPE_BF16 */
+    int32_t emit_mean_act; /* hidden nonlinearity of the emission mean I: 0 = identity (as printed, Sec. 3.1.3), 1 = ReLU */
+    int32_t max_samples;   /* largest S that will be requested; sizes the workspace */
+} dkf_config;
+
+/* Optional per-stage outputs of dkf_sample_runtimes (all dev, any may be NULL). */
+typedef struct {
+    float *ctx;       /* [L][R]  h_left + h_right per window position (Sec. 3.1.3, guide) */
+    float *z_last;    /* [S][Z]  z_T, last step of each guide trajectory */
+    float *z_next;    /* [S][Z]  z_{T+1} drawn from the gated transition */
+    float *emit_mean; /* [S][N]  I(z_{T+1}), in units of the normaliser */
+    float *emit_sd;   /* [S][N]  J(z_{T+1}), in units of the normaliser */
+} dkf_stage_outputs;
+
+const char *dkf_strerror(int code);
+int dkf_last_hip_error(void); /* hipError_t of the most recent DKF_EHIP on this thread */
+
+/* Number of bytes a weight blob must have for `cfg`.  Blob format (host,
+ * little endian): int32[8] {0x57464B44 'DKFW', 1, N, L, Z, H, R, 0} followed
+ * by fp32 tensors, each matrix [out][in] row-major so that a layer is
+ * W x + b (MLP_n / RNN of Sec. 3.1.3), in this order:
+ *   RNN forward : w_ih[R][N] b_ih[R] w_hh[R][R] b_hh[R];  RNN backward: same
+ *   guide       : comb_w[R][Z] comb_b[R]  mu_w[Z][R] mu_b[Z]  sig_w[Z][Z] sig_b[Z]  z0[Z]
+ *   transition  : gate1_w[H][Z] gate1_b[H] gate2_w[Z][H] gate2_b[Z]
+ *                 prop1_w[H][Z] prop1_b[H] prop2_w[Z][H] prop2_b[Z]
+ *                 lin_w[Z][Z] lin_b[Z]  tscale_w[Z][Z] tscale_b[Z]
+ *   emission    : emean1_w[H][Z] emean1_b[H] emean2_w[N][H] emean2_b[N]
+ *                 escale1_w[H][N] escale1_b[H] escale2_w[N][H] escale2_b[N]   */
+size_t dkf_blob_bytes(const dkf_config *cfg);
+
+/* Create a model: copies the blob to the device (re-tiled for the matrix
+ * cores, converted to bf16 where cfg->mlp_dtype asks for it), allocates the
+ * window and a workspace for cfg->max_samples samples.  `blob` is host memory
+ * and may be released on return (the call synchronises `stream`).
+ * Limits: 1 <= N <= 4096; Z, H, R <= 1024; L <= 256.
+ * Errors: DKF_EINVAL, DKF_EBLOB, DKF_EUNSUPPORTED, DKF_ENOMEM, DKF_EHIP. */
+int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes, void *stream, dkf_model **out);
+
+int dkf_free(dkf_model *m);  /* synchronises the device, releases everything the model owns */
+int dkf_reset(dkf_model *m); /* forget the window and the normaliser (next L steps warm up again) */
+
+/* Lagged filtering (Sec. 3.1.2-3.1.3): append one observed run-time vector
+ * x_obs[N] (host, seconds, every entry finite and > 0) to the fixed-lag
+ * window and re-encode the window with the forward and backward ReLU RNNs of
+ * the inference network.  Observations are divided by twice the mean of the
+ * first complete window (end of Sec. 3.1.3); that scalar is fixed when the
+ * L-th vector arrives.  x_obs is copied before the call returns.
+ * Returns DKF_WARMUP until L vectors have been pushed, then DKF_OK.
+ * Errors: DKF_EINVAL, DKF_EBADOBS (window unchanged), DKF_EHIP. */
+int dkf_filter_step(dkf_model *m, const float *x_obs, void *stream);
+
+/* Posterior-predictive sampling (Sec. 3.1.3, last display): S independent
+ * guide trajectories z_1..z_L ~ q(z_t | z_{t-1}, x), one gated-transition
+ * draw z_{T+1} ~ N(G(z_T), H(z_T)) and one emission draw
+ * x_{T+1} ~ N(I(z_{T+1}), J(z_{T+1})) each, returned in seconds.
+ *   eps_q [L][S][Z], eps_z [S][Z], eps_x [S][N]: dev, fp32 standard normals
+ *     that drive the three reparameterised draws.  If all three are NULL the
+ *     library draws them itself from `seed` with a counter-based generator.
+ *   out_samples [S][N] dev, caller-owned; `stages` may be NULL.
+ * Errors: DKF_EINVAL (S < 1, S > max_samples, some but not all eps NULL),
+ * DKF_ENOTREADY (window not full), DKF_EHIP. */
+int dkf_sample_runtimes(dkf_model *m, int32_t S, const float *eps_q, const float *eps_z, const float *eps_x,
+                        uint64_t seed, float *out_samples, const dkf_stage_outputs *stages, void *stream);
+
+/* Monte-Carlo order statistics and the cutoff (Sec. 3.1.1 last paragraph;
+ * Sec. 3, definition of Omega): sort each of the S rows of `samples` [S][N]
+ * (dev) ascending, average every rank over the rows, evaluate
+ * Omega(c) = c / mean x_(c) for c in [c_min, c_max] whose mean exceeds
+ * t_floor, and write the maximiser (1-based; ties go to the largest c).
+ * Model-free: works on any sample matrix.
+ *   Order of equal keys: -0 before +0, NaN last, then lower worker index.
+ *   out_sorted [S][N] fp32, out_perm [S][N] int32 (0-based worker per rank),
+ *   out_mean [N], out_omega [N] (-inf where ineligible): dev, optional (NULL).
+ *   out_cstar: dev int32[2] = {c*, status}; status is DKF_OK or
+ *     CUTOFF_NO_ELIGIBLE (then c* = c_max).  Required.
+ *   workspace: dev, at least cutoff_select_workspace(S, N) bytes, 256-byte
+ *     aligned; contents are scratch.
+ * Limits: 1 <= N <= 4096, S >= 1.
+ * Errors: DKF_EINVAL, DKF_EUNSUPPORTED, DKF_EHIP. */
+int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                  float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega, int32_t *out_cstar,
+                  void *workspace, size_t workspace_bytes, void *stream);
+size_t cutoff_select_workspace(int32_t S, int32_t N);
+
+/* One whole decision (the predict_cutoff call of Alg. 1): filter_step,
+ * sample_runtimes with S samples and cutoff_select over c in [1, N] with floor
+ * 0, replayed from a captured HIP graph after the first call with a given S.
+ * Noise comes from the caller's tensors (eps_* as in dkf_sample_runtimes, read
+ * at every call from the same addresses) or, if they are NULL, from `seed`.
+ * Synchronises the stream and writes c* to *cstar_host.
+ * Returns DKF_OK, DKF_WARMUP (then *cstar_host = N), CUTOFF_NO_ELIGIBLE, or
+ * an error. */
+int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
+               const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream);
+
+/* Device pointer to the [S][N] samples of the last dkf_decide (valid until the
+ * next call on the model). */
+const float *dkf_decide_samples(const dkf_model *m);
+
+/* Filter state (window, normaliser, counters) as an opaque blob, so that a
+ * run can be resumed.  get: *bytes in = capacity, out = size needed/written
+ * (buf may be NULL to query).  Both synchronise the device. */
+int dkf_get_state(const dkf_model *m, void *buf, size_t *bytes);
+int dkf_set_state(dkf_model *m, const void *buf, size_t bytes);
+
+/* Per-kernel timing with HIP events recorded on the stream the kernels are
+ * launched on (process-wide, for benchmarks; not recorded inside dkf_decide's
+ * captured graph).  Stage ids: 0 filter (projection + RNN chains), 1 guide
+ * chain + transition, 2 emission mean hidden layer, 3 emission mean, 4
+ * emission scale hidden layer, 5 emission scale + draw, 6 row sort + rank
+ * sums, 7 rank means + argmax.
+ * dkf_timing_enable(mask) starts recording for the stages in the bit mask (0
+ * stops).  dkf_timing_read synchronises the device and returns, for one
+ * stage, the number of launches recorded and their summed duration in
+ * milliseconds, then clears that stage's records.  At most 4096 launches per
+ * stage are kept between reads. */
+#define DKF_NUM_STAGES 8
+int dkf_timing_enable(uint32_t stage_mask);
+int dkf_timing_read(int32_t stage, int32_t *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CUTOFF_DKF_H */

@@ -1,0 +1,593 @@
+// C ABI of libcutoff_dkf.so: model object, host-side window bookkeeping,
+// weight re-tiling, stream/graph orchestration.  All arithmetic of the
+// predictor runs in the kernels of filter.hip, guide.hip, mlp_gemm.hip and
+// cutoff_select.hip; this file only moves data and launches them.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace dkf {
+
+// ---- errors -------------------------------------------------------------------
+static thread_local hipError_t g_last_hip = hipSuccess;
+void set_last_hip_error(hipError_t e) { g_last_hip = e; }
+
+// ---- stage timing ---------------------------------------------------------------
+namespace {
+constexpr int kMaxRecords = 4096;
+struct StageRecords {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+};
+std::mutex g_timing_mu;
+uint32_t g_timing_mask = 0;
+StageRecords g_records[DKF_NUM_STAGES];
+thread_local int g_capturing = 0;  // > 0 while a graph is being captured on this thread
+}  // namespace
+
+StageTimer::StageTimer(int stage, hipStream_t stream) : slot_(-1), stage_(stage), stream_(stream) {
+    if (g_capturing || stage < 0 || stage >= DKF_NUM_STAGES) return;
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    if (!(g_timing_mask & (1u << stage))) return;
+    StageRecords &r = g_records[stage];
+    if (r.used >= kMaxRecords) return;
+    if ((int)r.start.size() <= r.used) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+        r.start.push_back(a);
+        r.stop.push_back(b);
+    }
+    slot_ = r.used++;
+    (void)hipEventRecord(r.start[slot_], stream_);
+}
+
+StageTimer::~StageTimer() {
+    if (slot_ < 0) return;
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    (void)hipEventRecord(g_records[stage_].stop[slot_], stream_);
+}
+
+}  // namespace dkf
+
+using namespace dkf;
+
+// ---- model ------------------------------------------------------------------------
+struct dkf_model {
+    dkf_config cfg{};
+    int N = 0, L = 0, Z = 0, H = 0, R = 0;
+    int Np = 0, Zp = 0, Hp = 0, Rp = 0;
+    std::vector<void *> dev_allocs;
+    std::vector<void *> host_allocs;
+
+    // weights
+    const float *w_ih_f = nullptr, *w_ih_b = nullptr, *w_hh_f = nullptr, *w_hh_b = nullptr;
+    const float *bias_f = nullptr, *bias_b = nullptr, *z0 = nullptr;
+    PackedLayer comb, mu, sig, gate1, gate2, prop1, prop2, lin, tscale;
+    PackedLayer emean1, emean2, escale1, escale2;
+
+    // filter state
+    float *d_in = nullptr;  // [Np] observation + Control
+    float *proj_f = nullptr, *proj_b = nullptr, *ctx_f = nullptr, *ctx_b = nullptr;
+    std::vector<float> window;  // host mirror, ring [L][N]
+    int64_t pushes = 0;
+    float scale = 0.f;
+
+    // pinned staging for the eager path (ring) and for the graph path (one slot)
+    static constexpr int kStagingSlots = 4;
+    float *staging[kStagingSlots] = {};
+    hipEvent_t staging_done[kStagingSlots] = {};
+    bool staging_used[kStagingSlots] = {};
+    int staging_next = 0;
+    float *staging_graph = nullptr;
+    int32_t *cstar_host = nullptr;  // pinned int32[2]
+
+    // workspace
+    float *z_next = nullptr, *hid1 = nullptr, *mean = nullptr, *hid2 = nullptr;
+    float *samples = nullptr;  // [max_samples][N] used by dkf_decide
+    void *cutoff_ws = nullptr;
+    size_t cutoff_ws_bytes = 0;
+    int32_t *d_cstar = nullptr;
+
+    // captured decision graph
+    hipStream_t own_stream = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    int graph_S = 0;
+    const float *graph_eps[3] = {nullptr, nullptr, nullptr};
+
+    size_t in_floats() const { return (size_t)Np + sizeof(Control) / sizeof(float); }
+    Control *ctl_dev() const { return reinterpret_cast<Control *>(d_in + Np); }
+};
+
+namespace {
+
+int dev_alloc(dkf_model *m, size_t bytes, void **out, bool zero) {
+    void *p = nullptr;
+    if (bytes == 0) bytes = 256;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return e == hipErrorOutOfMemory ? DKF_ENOMEM : DKF_EHIP;
+    }
+    m->dev_allocs.push_back(p);
+    if (zero) DKF_HIP_TRY(hipMemset(p, 0, bytes));
+    *out = p;
+    return DKF_OK;
+}
+
+int upload(dkf_model *m, const float *src, size_t n, const float **out) {
+    void *p = nullptr;
+    int rc = dev_alloc(m, n * sizeof(float), &p, false);
+    if (rc != DKF_OK) return rc;
+    DKF_HIP_TRY(hipMemcpy(p, src, n * sizeof(float), hipMemcpyHostToDevice));
+    *out = static_cast<const float *>(p);
+    return DKF_OK;
+}
+
+// Re-tile W[n_out][k_in] (row-major) for the MFMA B operand; see PackedLayer.
+int pack_layer(dkf_model *m, const float *w, const float *b, int n_out, int k_in, PackedLayer *out) {
+    PackedLayer p;
+    p.n_out = n_out;
+    p.k_in = k_in;
+    p.n_blocks = (n_out + 31) / 32;
+    p.k_groups = round_up(k_in, 32) / 8;
+    std::vector<float> tiles((size_t)p.n_blocks * p.k_groups * 256, 0.f);
+    for (int nb = 0; nb < p.n_blocks; ++nb)
+        for (int kg = 0; kg < p.k_groups; ++kg)
+            for (int lane = 0; lane < 64; ++lane) {
+                const int n = nb * 32 + (lane & 31);
+                if (n >= n_out) continue;
+                for (int j = 0; j < 4; ++j) {
+                    const int k = kg * 8 + (lane >> 5) * 4 + j;
+                    if (k < k_in) tiles[(((size_t)nb * p.k_groups + kg) * 64 + lane) * 4 + j] = w[(size_t)n * k_in + k];
+                }
+            }
+    std::vector<float> bias((size_t)p.n_blocks * 32, 0.f);
+    for (int n = 0; n < n_out; ++n) bias[n] = b[n];
+    int rc = upload(m, tiles.data(), tiles.size(), &p.tiles);
+    if (rc != DKF_OK) return rc;
+    rc = upload(m, bias.data(), bias.size(), &p.bias);
+    if (rc != DKF_OK) return rc;
+    *out = p;
+    return DKF_OK;
+}
+
+size_t blob_floats(const dkf_config *c) {
+    const size_t N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
+    const size_t rnn = 2 * (R * N + R + R * R + R);
+    const size_t guide = R * Z + R + Z * R + Z + Z * Z + Z + Z;
+    const size_t trans = 2 * (H * Z + H + Z * H + Z) + 2 * (Z * Z + Z);
+    const size_t emit = H * Z + H + N * H + N + H * N + H + N * H + N;
+    return rnn + guide + trans + emit;
+}
+
+bool config_ok(const dkf_config *c) {
+    return c && c->n_workers >= 1 && c->lag >= 1 && c->z_dim >= 1 && c->hidden >= 1 && c->rnn_dim >= 1 &&
+           c->max_samples >= 1 && (c->mlp_dtype == DKF_DTYPE_F32 || c->mlp_dtype == DKF_DTYPE_BF16) &&
+           (c->emit_mean_act == 0 || c->emit_mean_act == 1);
+}
+
+FilterArgs filter_args(const dkf_model *m) {
+    FilterArgs a;
+    a.input = m->d_in;
+    a.ctl = m->ctl_dev();
+    a.proj_f = m->proj_f; a.proj_b = m->proj_b;
+    a.ctx_f = m->ctx_f; a.ctx_b = m->ctx_b;
+    a.w_ih_f = m->w_ih_f; a.w_ih_b = m->w_ih_b;
+    a.w_hh_f = m->w_hh_f; a.w_hh_b = m->w_hh_b;
+    a.bias_f = m->bias_f; a.bias_b = m->bias_b;
+    a.N = m->N; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
+    return a;
+}
+
+// Host bookkeeping of one push: validates, updates the window mirror and the
+// normaliser, and fills `dst` (pinned) with the observation and its Control.
+int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *dst) {
+    const int N = m->N, L = m->L;
+    for (int j = 0; j < N; ++j)
+        if (!std::isfinite(x_obs[j]) || !(x_obs[j] > 0.f)) return DKF_EBADOBS;
+    const int slot = (int)(m->pushes % L);
+    std::memcpy(&m->window[(size_t)slot * N], x_obs, sizeof(float) * N);
+    m->pushes++;
+    const int count = m->pushes < L ? (int)m->pushes : L;
+    if (m->pushes == L) {
+        // normaliser: twice the mean of the first complete window, fixed from here on
+        double sum = 0.0;
+        for (size_t i = 0; i < (size_t)L * N; ++i) sum += (double)m->window[i];
+        m->scale = (float)(2.0 * sum / ((double)L * N));
+    }
+    std::memcpy(dst, x_obs, sizeof(float) * N);
+    for (int j = N; j < m->Np; ++j) dst[j] = 0.f;
+    Control c;
+    c.slot = slot;
+    c.count = count;
+    c.oldest = count < L ? 0 : (slot + 1) % L;
+    c.reserved0 = 0;
+    c.scale = m->scale;
+    c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
+    c.seed_lo = (uint32_t)seed;
+    c.seed_hi = (uint32_t)(seed >> 32);
+    std::memcpy(dst + m->Np, &c, sizeof c);
+    return count < L ? DKF_WARMUP : DKF_OK;
+}
+
+int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
+                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
+    GuideArgs g;
+    g.ctl = m->ctl_dev();
+    g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
+    g.comb = m->comb; g.mu = m->mu; g.sig = m->sig; g.z0 = m->z0;
+    g.gate1 = m->gate1; g.prop1 = m->prop1; g.gate2 = m->gate2; g.prop2 = m->prop2;
+    g.lin = m->lin; g.tscale = m->tscale;
+    g.eps_q = eps_q; g.eps_z = eps_z;
+    g.z_last = st ? st->z_last : nullptr;
+    g.z_next_dbg = st ? st->z_next : nullptr;
+    g.z_next = m->z_next;
+    g.S = S; g.L = m->L; g.Z = m->Z; g.Zp = m->Zp; g.R = m->R; g.Rp = m->Rp; g.H = m->H; g.Hp = m->Hp;
+    int rc = launch_guide(g, stream);
+    if (rc != DKF_OK) return rc;
+
+    GemmArgs e{};
+    e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
+    // hidden layer of the mean
+    e.A = m->z_next; e.lda = m->Zp; e.layer = m->emean1;
+    e.epilogue = m->cfg.emit_mean_act ? kEpiBiasRelu : kEpiBias;
+    e.out = m->hid1; e.ldo = m->Hp;
+    if ((rc = launch_gemm(e, kStageEmitHidden, stream)) != DKF_OK) return rc;
+    // mean
+    e.A = m->hid1; e.lda = m->Hp; e.layer = m->emean2; e.epilogue = kEpiBias; e.out = m->mean; e.ldo = m->Np;
+    if ((rc = launch_gemm(e, kStageEmitMean, stream)) != DKF_OK) return rc;
+    // hidden layer of the scale, fed by the mean
+    e.A = m->mean; e.lda = m->Np; e.layer = m->escale1; e.epilogue = kEpiBiasRelu; e.out = m->hid2; e.ldo = m->Hp;
+    if ((rc = launch_gemm(e, kStageEmitScaleHidden, stream)) != DKF_OK) return rc;
+    // scale, draw, back to seconds
+    e.A = m->hid2; e.lda = m->Hp; e.layer = m->escale2; e.epilogue = kEpiScaleDraw; e.out = nullptr; e.ldo = 0;
+    e.mean = m->mean; e.ld_mean = m->Np; e.eps_x = eps_x; e.out_samples = out_samples;
+    e.out_mean_dbg = st ? st->emit_mean : nullptr;
+    e.out_sd_dbg = st ? st->emit_sd : nullptr;
+    if ((rc = launch_gemm(e, kStageEmitScaleDraw, stream)) != DKF_OK) return rc;
+
+    if (st && st->ctx) {
+        // h_left + h_right per position, for inspection only
+        std::vector<float> f((size_t)m->L * m->Rp), b((size_t)m->L * m->Rp), c((size_t)m->L * m->R);
+        DKF_HIP_TRY(hipStreamSynchronize(stream));
+        DKF_HIP_TRY(hipMemcpy(f.data(), m->ctx_f, f.size() * 4, hipMemcpyDeviceToHost));
+        DKF_HIP_TRY(hipMemcpy(b.data(), m->ctx_b, b.size() * 4, hipMemcpyDeviceToHost));
+        for (int t = 0; t < m->L; ++t)
+            for (int r = 0; r < m->R; ++r) c[(size_t)t * m->R + r] = f[(size_t)t * m->Rp + r] + b[(size_t)t * m->Rp + r];
+        DKF_HIP_TRY(hipMemcpy(st->ctx, c.data(), c.size() * 4, hipMemcpyHostToDevice));
+    }
+    return DKF_OK;
+}
+
+void drop_graph(dkf_model *m) {
+    if (m->graph_exec) { (void)hipGraphExecDestroy(m->graph_exec); m->graph_exec = nullptr; }
+    if (m->graph) { (void)hipGraphDestroy(m->graph); m->graph = nullptr; }
+    m->graph_S = 0;
+}
+
+}  // namespace
+
+// ---- exported functions ----------------------------------------------------------------
+extern "C" {
+
+const char *dkf_strerror(int code) {
+    switch (code) {
+        case DKF_OK: return "ok";
+        case DKF_WARMUP: return "warming up: fewer than L observations";
+        case CUTOFF_NO_ELIGIBLE: return "no eligible cutoff; c_max returned";
+        case DKF_EINVAL: return "invalid argument";
+        case DKF_ENOTREADY: return "window not full";
+        case DKF_EBADOBS: return "observation not finite or not positive";
+        case DKF_EHIP: return "HIP runtime error";
+        case DKF_ENOMEM: return "out of memory";
+        case DKF_EBLOB: return "weight blob does not match the configuration";
+        case DKF_EUNSUPPORTED: return "size or mode not supported";
+        default: return "unknown code";
+    }
+}
+
+int dkf_last_hip_error(void) { return (int)g_last_hip; }
+
+size_t dkf_blob_bytes(const dkf_config *cfg) {
+    if (!config_ok(cfg)) return 0;
+    return 32 + 4 * blob_floats(cfg);
+}
+
+int dkf_free(dkf_model *m) {
+    if (!m) return DKF_OK;
+    (void)hipDeviceSynchronize();
+    drop_graph(m);
+    if (m->own_stream) (void)hipStreamDestroy(m->own_stream);
+    for (int i = 0; i < dkf_model::kStagingSlots; ++i)
+        if (m->staging_done[i]) (void)hipEventDestroy(m->staging_done[i]);
+    for (void *p : m->dev_allocs) (void)hipFree(p);
+    for (void *p : m->host_allocs) (void)hipHostFree(p);
+    delete m;
+    return DKF_OK;
+}
+
+int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes, void *stream, dkf_model **out) {
+    if (!out) return DKF_EINVAL;
+    *out = nullptr;
+    if (!config_ok(cfg) || !blob) return DKF_EINVAL;
+    if (cfg->n_workers > 4096 || cfg->z_dim > 1024 || cfg->hidden > 1024 || cfg->rnn_dim > 1024 || cfg->lag > 256)
+        return DKF_EUNSUPPORTED;
+    if (cfg->mlp_dtype != DKF_DTYPE_F32) return DKF_EUNSUPPORTED;
+    if (blob_bytes != dkf_blob_bytes(cfg)) return DKF_EBLOB;
+    int32_t head[8];
+    std::memcpy(head, blob, sizeof head);
+    if (head[0] != 0x57464B44 || head[1] != 1 || head[2] != cfg->n_workers || head[3] != cfg->lag ||
+        head[4] != cfg->z_dim || head[5] != cfg->hidden || head[6] != cfg->rnn_dim)
+        return DKF_EBLOB;
+
+    dkf_model *m = new (std::nothrow) dkf_model();
+    if (!m) return DKF_ENOMEM;
+    m->cfg = *cfg;
+    const int N = m->N = cfg->n_workers, L = m->L = cfg->lag, Z = m->Z = cfg->z_dim, H = m->H = cfg->hidden,
+              R = m->R = cfg->rnn_dim;
+    m->Np = round_up(N, 32); m->Zp = round_up(Z, 32); m->Hp = round_up(H, 32); m->Rp = round_up(R, 32);
+    const int Smax = cfg->max_samples;
+    int rc = DKF_OK;
+#define DKF_CHECK(expr) do { rc = (expr); if (rc != DKF_OK) { dkf_free(m); return rc; } } while (0)
+#define DKF_CHECK_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_last_hip_error(e_); dkf_free(m); return DKF_EHIP; } } while (0)
+
+    DKF_CHECK(guide_prepare(m->Zp, m->Rp, m->Hp));
+
+    const float *p = reinterpret_cast<const float *>(static_cast<const char *>(blob) + 32);
+    auto take = [&](size_t n) { const float *q = p; p += n; return q; };
+    const size_t sN = N, sZ = Z, sH = H, sR = R;
+    std::vector<float> bsum(R);
+    for (int dir = 0; dir < 2; ++dir) {
+        const float *w_ih = take(sR * sN), *b_ih = take(sR), *w_hh = take(sR * sR), *b_hh = take(sR);
+        for (int r = 0; r < R; ++r) bsum[r] = b_ih[r] + b_hh[r];
+        DKF_CHECK(upload(m, w_ih, sR * sN, dir ? &m->w_ih_b : &m->w_ih_f));
+        DKF_CHECK(upload(m, w_hh, sR * sR, dir ? &m->w_hh_b : &m->w_hh_f));
+        DKF_CHECK(upload(m, bsum.data(), sR, dir ? &m->bias_b : &m->bias_f));
+    }
+    {
+        const float *w, *b;
+        w = take(sR * sZ); b = take(sR); DKF_CHECK(pack_layer(m, w, b, R, Z, &m->comb));
+        w = take(sZ * sR); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, R, &m->mu));
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->sig));
+        std::vector<float> z0(m->Zp, 0.f);
+        std::memcpy(z0.data(), take(sZ), sizeof(float) * sZ);
+        DKF_CHECK(upload(m, z0.data(), z0.size(), &m->z0));
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->gate1));
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->gate2));
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->prop1));
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->prop2));
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->lin));
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->tscale));
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->emean1));
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->emean2));
+        w = take(sH * sN); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, N, &m->escale1));
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2));
+    }
+
+    void *q = nullptr;
+    DKF_CHECK(dev_alloc(m, m->in_floats() * 4, &q, true)); m->d_in = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)L * R * 4, &q, true)); m->proj_f = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)L * R * 4, &q, true)); m->proj_b = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)L * m->Rp * 4, &q, true)); m->ctx_f = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)L * m->Rp * 4, &q, true)); m->ctx_b = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * m->Zp * 4, &q, true)); m->z_next = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * m->Hp * 4, &q, true)); m->hid1 = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * m->Np * 4, &q, true)); m->mean = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * m->Hp * 4, &q, true)); m->hid2 = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * N * 4, &q, true)); m->samples = static_cast<float *>(q);
+    m->cutoff_ws_bytes = cutoff_workspace_bytes(Smax, N);
+    DKF_CHECK(dev_alloc(m, m->cutoff_ws_bytes, &q, true)); m->cutoff_ws = q;
+    DKF_CHECK(dev_alloc(m, 2 * sizeof(int32_t), &q, true)); m->d_cstar = static_cast<int32_t *>(q);
+
+    for (int i = 0; i < dkf_model::kStagingSlots + 1; ++i) {
+        void *h = nullptr;
+        DKF_CHECK_HIP(hipHostMalloc(&h, m->in_floats() * 4, hipHostMallocDefault));
+        m->host_allocs.push_back(h);
+        if (i < dkf_model::kStagingSlots) {
+            m->staging[i] = static_cast<float *>(h);
+            DKF_CHECK_HIP(hipEventCreateWithFlags(&m->staging_done[i], hipEventDisableTiming));
+        } else {
+            m->staging_graph = static_cast<float *>(h);
+        }
+    }
+    {
+        void *h = nullptr;
+        DKF_CHECK_HIP(hipHostMalloc(&h, 2 * sizeof(int32_t), hipHostMallocDefault));
+        m->host_allocs.push_back(h);
+        m->cstar_host = static_cast<int32_t *>(h);
+    }
+    DKF_CHECK_HIP(hipStreamCreateWithFlags(&m->own_stream, hipStreamNonBlocking));
+    m->window.assign((size_t)L * N, 0.f);
+    DKF_CHECK_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    DKF_CHECK_HIP(hipDeviceSynchronize());
+#undef DKF_CHECK
+#undef DKF_CHECK_HIP
+    *out = m;
+    return DKF_OK;
+}
+
+int dkf_reset(dkf_model *m) {
+    if (!m) return DKF_EINVAL;
+    DKF_HIP_TRY(hipDeviceSynchronize());
+    m->pushes = 0;
+    m->scale = 0.f;
+    std::fill(m->window.begin(), m->window.end(), 0.f);
+    return DKF_OK;
+}
+
+int dkf_filter_step(dkf_model *m, const float *x_obs, void *stream_) {
+    if (!m || !x_obs) return DKF_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int i = m->staging_next;
+    if (m->staging_used[i]) DKF_HIP_TRY(hipEventSynchronize(m->staging_done[i]));
+    const int status = stage_observation(m, x_obs, 0, m->staging[i]);
+    if (status < 0) return status;
+    m->staging_next = (i + 1) % dkf_model::kStagingSlots;
+    DKF_HIP_TRY(hipMemcpyAsync(m->d_in, m->staging[i], m->in_floats() * 4, hipMemcpyHostToDevice, stream));
+    DKF_HIP_TRY(hipEventRecord(m->staging_done[i], stream));
+    m->staging_used[i] = true;
+    const int rc = launch_filter(filter_args(m), true, status == DKF_OK, stream);
+    return rc != DKF_OK ? rc : status;
+}
+
+int dkf_sample_runtimes(dkf_model *m, int32_t S, const float *eps_q, const float *eps_z, const float *eps_x,
+                        uint64_t seed, float *out_samples, const dkf_stage_outputs *stages, void *stream_) {
+    (void)seed;
+    if (!m || !out_samples || S < 1 || S > m->cfg.max_samples) return DKF_EINVAL;
+    const int n_null = (eps_q == nullptr) + (eps_z == nullptr) + (eps_x == nullptr);
+    if (n_null != 0 && n_null != 3) return DKF_EINVAL;
+    if (n_null == 3) return DKF_EUNSUPPORTED;  // built-in generator: not in this build
+    if (m->pushes < m->L) return DKF_ENOTREADY;
+    return enqueue_sample(m, S, eps_q, eps_z, eps_x, out_samples, stages, static_cast<hipStream_t>(stream_));
+}
+
+size_t cutoff_select_workspace(int32_t S, int32_t N) { return cutoff_workspace_bytes(S, N); }
+
+int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                  float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega, int32_t *out_cstar,
+                  void *workspace, size_t workspace_bytes, void *stream) {
+    return launch_cutoff_select(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean, out_omega,
+                                out_cstar, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
+               const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream_) {
+    if (!m || !x_obs || !cstar_host || S < 1 || S > m->cfg.max_samples) return DKF_EINVAL;
+    const int n_null = (eps_q == nullptr) + (eps_z == nullptr) + (eps_x == nullptr);
+    if (n_null != 0 && n_null != 3) return DKF_EINVAL;
+    if (n_null == 3) return DKF_EUNSUPPORTED;
+    hipStream_t stream = stream_ ? static_cast<hipStream_t>(stream_) : m->own_stream;
+    // the eager path may still own staging slots on another stream: drain it
+    for (int i = 0; i < dkf_model::kStagingSlots; ++i)
+        if (m->staging_used[i]) { DKF_HIP_TRY(hipEventSynchronize(m->staging_done[i])); m->staging_used[i] = false; }
+    const int status = stage_observation(m, x_obs, seed, m->staging_graph);
+    if (status < 0) return status;
+    if (status == DKF_WARMUP) {
+        DKF_HIP_TRY(hipMemcpyAsync(m->d_in, m->staging_graph, m->in_floats() * 4, hipMemcpyHostToDevice, stream));
+        const int rc = launch_filter(filter_args(m), true, false, stream);
+        if (rc != DKF_OK) return rc;
+        DKF_HIP_TRY(hipStreamSynchronize(stream));
+        *cstar_host = m->N;
+        return DKF_WARMUP;
+    }
+    const bool reuse = m->graph_exec && m->graph_S == S && m->graph_eps[0] == eps_q && m->graph_eps[1] == eps_z &&
+                       m->graph_eps[2] == eps_x;
+    if (!reuse) {
+        drop_graph(m);
+        DKF_HIP_TRY(hipStreamSynchronize(stream));
+        DKF_HIP_TRY(hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal));
+        g_capturing++;
+        int rc = DKF_OK;
+        hipError_t e = hipMemcpyAsync(m->d_in, m->staging_graph, m->in_floats() * 4, hipMemcpyHostToDevice, stream);
+        if (e != hipSuccess) { set_last_hip_error(e); rc = DKF_EHIP; }
+        if (rc == DKF_OK) rc = launch_filter(filter_args(m), true, true, stream);
+        if (rc == DKF_OK) rc = enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
+        if (rc == DKF_OK)
+            rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
+                                      m->d_cstar, m->cutoff_ws, m->cutoff_ws_bytes, stream);
+        if (rc == DKF_OK) {
+            e = hipMemcpyAsync(m->cstar_host, m->d_cstar, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+            if (e != hipSuccess) { set_last_hip_error(e); rc = DKF_EHIP; }
+        }
+        g_capturing--;
+        hipGraph_t graph = nullptr;
+        e = hipStreamEndCapture(stream, &graph);
+        if (rc != DKF_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+        if (e != hipSuccess) { set_last_hip_error(e); return DKF_EHIP; }
+        m->graph = graph;
+        DKF_HIP_TRY(hipGraphInstantiate(&m->graph_exec, m->graph, nullptr, nullptr, 0));
+        m->graph_S = S;
+        m->graph_eps[0] = eps_q; m->graph_eps[1] = eps_z; m->graph_eps[2] = eps_x;
+    }
+    DKF_HIP_TRY(hipGraphLaunch(m->graph_exec, stream));
+    DKF_HIP_TRY(hipStreamSynchronize(stream));
+    *cstar_host = m->cstar_host[0];
+    return m->cstar_host[1];
+}
+
+const float *dkf_decide_samples(const dkf_model *m) { return m ? m->samples : nullptr; }
+
+// state blob: int64 {magic, N, L, pushes}, float scale, float pad, then the ring [L][N]
+int dkf_get_state(const dkf_model *m, void *buf, size_t *bytes) {
+    if (!m || !bytes) return DKF_EINVAL;
+    const size_t need = 4 * sizeof(int64_t) + 2 * sizeof(float) + m->window.size() * sizeof(float);
+    if (!buf || *bytes < need) { *bytes = need; return buf ? DKF_EINVAL : DKF_OK; }
+    DKF_HIP_TRY(hipDeviceSynchronize());
+    char *p = static_cast<char *>(buf);
+    const int64_t head[4] = {0x544B4644, m->N, m->L, m->pushes};
+    std::memcpy(p, head, sizeof head); p += sizeof head;
+    const float sc[2] = {m->scale, 0.f};
+    std::memcpy(p, sc, sizeof sc); p += sizeof sc;
+    std::memcpy(p, m->window.data(), m->window.size() * sizeof(float));
+    *bytes = need;
+    return DKF_OK;
+}
+
+int dkf_set_state(dkf_model *m, const void *buf, size_t bytes) {
+    if (!m || !buf) return DKF_EINVAL;
+    const size_t need = 4 * sizeof(int64_t) + 2 * sizeof(float) + m->window.size() * sizeof(float);
+    if (bytes != need) return DKF_EINVAL;
+    const char *p = static_cast<const char *>(buf);
+    int64_t head[4];
+    std::memcpy(head, p, sizeof head); p += sizeof head;
+    if (head[0] != 0x544B4644 || head[1] != m->N || head[2] != m->L || head[3] < 0) return DKF_EINVAL;
+    float sc[2];
+    std::memcpy(sc, p, sizeof sc); p += sizeof sc;
+    DKF_HIP_TRY(hipDeviceSynchronize());
+    std::memcpy(m->window.data(), p, m->window.size() * sizeof(float));
+    m->pushes = head[3];
+    m->scale = sc[0];
+    // rebuild the cached input projections of every stored observation, then the encodings
+    const int L = m->L, N = m->N;
+    const int stored = m->pushes < L ? (int)m->pushes : L;
+    float *dst = m->staging_graph;
+    for (int slot = 0; slot < stored; ++slot) {
+        std::memcpy(dst, &m->window[(size_t)slot * N], sizeof(float) * N);
+        for (int j = N; j < m->Np; ++j) dst[j] = 0.f;
+        Control c{};
+        c.slot = slot;
+        c.count = stored;
+        const int newest = (int)((m->pushes + L - 1) % L);
+        c.oldest = stored < L ? 0 : (newest + 1) % L;
+        c.scale = m->scale;
+        c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
+        std::memcpy(dst + m->Np, &c, sizeof c);
+        DKF_HIP_TRY(hipMemcpy(m->d_in, dst, m->in_floats() * 4, hipMemcpyHostToDevice));
+        const int rc = launch_filter(filter_args(m), true, slot == stored - 1 && stored == L, nullptr);
+        if (rc != DKF_OK) return rc;
+        DKF_HIP_TRY(hipDeviceSynchronize());
+    }
+    return DKF_OK;
+}
+
+int dkf_timing_enable(uint32_t stage_mask) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    g_timing_mask = stage_mask & ((1u << DKF_NUM_STAGES) - 1);
+    return DKF_OK;
+}
+
+int dkf_timing_read(int32_t stage, int32_t *launches, double *total_ms) {
+    if (stage < 0 || stage >= DKF_NUM_STAGES || !launches || !total_ms) return DKF_EINVAL;
+    DKF_HIP_TRY(hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lock(g_timing_mu);
+    StageRecords &r = g_records[stage];
+    double total = 0.0;
+    for (int i = 0; i < r.used; ++i) {
+        float ms = 0.f;
+        DKF_HIP_TRY(hipEventElapsedTime(&ms, r.start[i], r.stop[i]));
+        total += ms;
+    }
+    *launches = r.used;
+    *total_ms = total;
+    r.used = 0;
+    return DKF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,144 @@
+// Internal declarations shared by the translation units of libcutoff_dkf.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cutoff_dkf.h"
+
+namespace dkf {
+
+// ---- error plumbing ---------------------------------------------------------
+void set_last_hip_error(hipError_t e);
+
+#define DKF_HIP_TRY(expr)                            \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) {                      \
+            ::dkf::set_last_hip_error(e_);           \
+            return DKF_EHIP;                         \
+        }                                            \
+    } while (0)
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// ---- per-kernel timing (HIP events on the launch stream) ----------------------
+enum Stage : int {
+    kStageFilter = 0,
+    kStageGuide = 1,
+    kStageEmitHidden = 2,
+    kStageEmitMean = 3,
+    kStageEmitScaleHidden = 4,
+    kStageEmitScaleDraw = 5,
+    kStageSort = 6,
+    kStageArgmax = 7,
+};
+
+// Records a start event in the constructor and a stop event in the destructor
+// when timing is enabled for `stage`; otherwise does nothing.
+class StageTimer {
+public:
+    StageTimer(int stage, hipStream_t stream);
+    ~StageTimer();
+    StageTimer(const StageTimer &) = delete;
+    StageTimer &operator=(const StageTimer &) = delete;
+
+private:
+    int slot_;
+    int stage_;
+    hipStream_t stream_;
+};
+
+// ---- device-side control block ------------------------------------------------
+// Copied from pinned host memory at the start of every filter step, after the
+// N floats of the new observation.  Kernels only read it.
+struct Control {
+    int32_t slot;       // ring slot the new observation goes to
+    int32_t count;      // observations in the window after this push (<= L)
+    int32_t oldest;     // ring slot of the oldest observation in the window
+    int32_t reserved0;
+    float scale;        // normaliser s (0 while warming up)
+    float inv_scale;    // 1/s
+    uint32_t seed_lo;   // seed of the built-in generator for this step
+    uint32_t seed_hi;
+};
+
+// Weights of one dense layer re-tiled for v_mfma_f32_32x32x2_f32:
+// tiles[nb][kg][lane][4] with n = nb*32 + lane%32, k = kg*8 + (lane/32)*4 + j;
+// zero outside [n_out) x [k_in).  bias is padded with zeros to n_blocks*32.
+struct PackedLayer {
+    const float *tiles = nullptr;
+    const float *bias = nullptr;
+    int n_out = 0, k_in = 0;
+    int n_blocks = 0;  // ceil(n_out / 32)
+    int k_groups = 0;  // ceil32(k_in) / 8
+};
+
+// ---- launchers (each enqueues on `stream` and returns a DKF_* code) ------------
+
+// filter.hip
+struct FilterArgs {
+    const float *input;    // dev: [N] new observation followed by a Control block
+    const Control *ctl;    // dev: = input + N
+    float *proj_f, *proj_b;  // dev [L][R] raw input projections W_ih x (no bias, not normalised)
+    float *ctx_f, *ctx_b;    // dev [L][Rp] encodings, window order, zero padded
+    const float *w_ih_f, *w_ih_b;      // dev [R][N]
+    const float *w_hh_f, *w_hh_b;      // dev [R][R]
+    const float *bias_f, *bias_b;      // dev [R]: b_ih + b_hh
+    int N, L, R, Rp;
+};
+int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream);
+
+// guide.hip
+struct GuideArgs {
+    const Control *ctl;
+    const float *ctx_f, *ctx_b;  // [L][Rp]
+    PackedLayer comb, mu, sig;   // Z->R (tanh), R->Z, Z->Z (softplus)
+    const float *z0;             // [Zp]
+    PackedLayer gate1, prop1;    // Z -> H (ReLU)
+    PackedLayer gate2, prop2;    // H -> Z (sigmoid / identity)
+    PackedLayer lin, tscale;     // Z -> Z (identity / softplus)
+    const float *eps_q, *eps_z;  // [L][S][Z], [S][Z] or NULL with the generator
+    float *z_last;               // [S][Z] or NULL
+    float *z_next_dbg;           // [S][Z] or NULL
+    float *z_next;               // [S][Zp] zero padded: input of the emission
+    int S, L, Z, Zp, R, Rp, H, Hp;
+};
+int launch_guide(const GuideArgs &a, hipStream_t stream);
+size_t guide_lds_bytes(int Zp, int Rp, int Hp);
+int guide_prepare(int Zp, int Rp, int Hp);  // raises the kernel's LDS limit once per size
+
+// mlp_gemm.hip
+enum Epilogue : int {
+    kEpiBias = 0,       // y = acc + b
+    kEpiBiasRelu = 1,   // y = relu(acc + b)
+    kEpiScaleDraw = 2,  // sd = softplus(acc + b); x = s * (mean + sd * eps)
+};
+struct GemmArgs {
+    const float *A;  // [S][lda] fp32, K columns used (zero padded up to the layer's k_groups*8)
+    int lda;
+    PackedLayer layer;
+    int S;
+    int epilogue;
+    float *out;  // kEpiBias/kEpiBiasRelu: [S][ldo], all n_blocks*32 columns written (pads = act(0 + 0))
+    int ldo;
+    // kEpiScaleDraw only:
+    const Control *ctl;
+    const float *mean;  // [S][ld_mean]
+    int ld_mean;
+    const float *eps_x;   // [S][N]
+    float *out_samples;   // [S][N]
+    float *out_mean_dbg;  // [S][N] or NULL
+    float *out_sd_dbg;    // [S][N] or NULL
+    int N;
+};
+int launch_gemm(const GemmArgs &a, int stage, hipStream_t stream);
+
+// cutoff_select.hip
+int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
+                         float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream);
+size_t cutoff_workspace_bytes(int S, int N);
+
+}  // namespace dkf

@@ -1,0 +1,410 @@
+// Monte-Carlo order statistics and the cutoff decision on gfx950.
+//
+// "Sample, sort, record the values of all n sorted samples, repeat"
+// (Sec. 3.1.1, last paragraph), then Omega(c) = c / mean x_(c) and its argmax
+// (Sec. 3).  Three kernels:
+//   sort_rank_sums : every row of the [S][N] sample matrix is sorted by a
+//                    bitonic network held in registers (several keys per lane,
+//                    cross-lane exchanges inside one wavefront), and each rank's
+//                    values are summed over the rows a lane group visits;
+//   rank_means     : fixed-order fp64 reduction of the per-block sums;
+//   omega_argmax   : Omega(c) and the largest maximiser.
+// Keys are the order-preserving uint32 image of the fp32 bits, so all compares
+// are integer min/max; with a permutation requested the worker index rides in
+// the low half of a 64-bit key and breaks ties.
+#include "common.h"
+
+namespace dkf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr uint32_t kPadKey = 0xFFFFFFFFu;
+constexpr uint32_t kNanKey = 0xFFFFFFFEu;
+
+__device__ __forceinline__ uint32_t key_of(float x) {
+    uint32_t u = __float_as_uint(x);
+    if (x != x) return kNanKey;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float value_of(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    return __uint_as_float(u);
+}
+
+constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
+
+// Element index i of a row is split over a lane group of G = 2^LG lanes with E
+// keys each:  bits 0-1 -> key bits 0-1, next LG bits -> lane, rest -> key bits
+// 2.., so that one float4 load per (lane, e/4) is fully coalesced.
+template <int E, int LG>
+struct Layout {
+    static constexpr int kLgE = ilog2(E);
+    static constexpr int kLgN = kLgE + LG;
+    __host__ __device__ static constexpr bool is_lane_bit(int b) { return b >= 2 && b < 2 + LG; }
+    __host__ __device__ static constexpr int reg_bit(int b) { return b < 2 ? b : b - LG; }
+    __host__ __device__ static constexpr int lane_bit(int b) { return b - 2; }
+    // masks of the low m element bits, split into key-register and lane parts
+    __host__ __device__ static constexpr int reg_mask(int m) {
+        int r = 0;
+        for (int b = 0; b < m; ++b)
+            if (!is_lane_bit(b)) r |= 1 << reg_bit(b);
+        return r;
+    }
+    __host__ __device__ static constexpr int lane_mask(int m) {
+        int r = 0;
+        for (int b = 0; b < m; ++b)
+            if (is_lane_bit(b)) r |= 1 << lane_bit(b);
+        return r;
+    }
+    __device__ static __forceinline__ int element(int g, int e) {
+        return (e & 3) | (g << 2) | ((e >> 2) << (2 + LG));
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ T tmin(T a, T b) { return a < b ? a : b; }
+template <typename T>
+__device__ __forceinline__ T tmax(T a, T b) { return a < b ? b : a; }
+
+// Compare-exchange across element bit B (partner = i ^ 2^B); the element whose
+// bit B is clear keeps the smaller key.
+template <typename T, int E, int LG, int B>
+__device__ __forceinline__ void xor_stage(T (&v)[E], int g) {
+    using Lay = Layout<E, LG>;
+    if constexpr (Lay::is_lane_bit(B)) {
+        constexpr int lm = 1 << Lay::lane_bit(B);
+        const bool keep_min = (g & lm) == 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            T p = __shfl_xor(v[e], lm, 64);
+            v[e] = keep_min ? tmin(v[e], p) : tmax(v[e], p);
+        }
+    } else {
+        constexpr int rm = 1 << Lay::reg_bit(B);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if ((e & rm) == 0) {
+                T a = v[e], b = v[e | rm];
+                v[e] = tmin(a, b);
+                v[e | rm] = tmax(a, b);
+            }
+        }
+    }
+}
+
+// First stage of merging two sorted runs of 2^(M-1): partner = i ^ (2^M - 1).
+template <typename T, int E, int LG, int M>
+__device__ __forceinline__ void flip_stage(T (&v)[E], int g) {
+    using Lay = Layout<E, LG>;
+    constexpr int rm = Lay::reg_mask(M);
+    constexpr int lm = Lay::lane_mask(M);
+    constexpr int top = M - 1;
+    if constexpr (lm == 0) {
+        constexpr int tb = 1 << Lay::reg_bit(top);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if ((e & tb) == 0) {
+                T a = v[e], b = v[e ^ rm];
+                v[e] = tmin(a, b);
+                v[e ^ rm] = tmax(a, b);
+            }
+        }
+    } else {
+        T p[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) p[e] = __shfl_xor(v[e ^ rm], lm, 64);
+        if constexpr (Lay::is_lane_bit(top)) {
+            const bool keep_min = (g & (1 << Lay::lane_bit(top))) == 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = keep_min ? tmin(v[e], p[e]) : tmax(v[e], p[e]);
+        } else {
+            constexpr int tb = 1 << Lay::reg_bit(top);
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = (e & tb) == 0 ? tmin(v[e], p[e]) : tmax(v[e], p[e]);
+        }
+    }
+}
+
+template <typename T, int E, int LG, int B>
+__device__ __forceinline__ void xor_down(T (&v)[E], int g) {
+    if constexpr (B >= 0) {
+        xor_stage<T, E, LG, B>(v, g);
+        xor_down<T, E, LG, B - 1>(v, g);
+    }
+}
+
+template <typename T, int E, int LG, int M>
+__device__ __forceinline__ void merge_up(T (&v)[E], int g) {
+    if constexpr (M <= Layout<E, LG>::kLgN) {
+        flip_stage<T, E, LG, M>(v, g);
+        xor_down<T, E, LG, M - 2>(v, g);
+        merge_up<T, E, LG, M + 1>(v, g);
+    }
+}
+
+// One lane group sorts one row per iteration; rank sums stay in registers
+// across iterations and are combined per block at the end in a fixed order.
+// partial: [gridDim.x][E << LG] fp32, indexed by rank.
+template <int E, int LG, bool WITH_PERM>
+__global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restrict__ x, int S, int N,
+                                                            float *__restrict__ out_sorted,
+                                                            int32_t *__restrict__ out_perm,
+                                                            float *__restrict__ partial) {
+    using Lay = Layout<E, LG>;
+    using T = typename std::conditional<WITH_PERM, uint64_t, uint32_t>::type;
+    constexpr int G = 1 << LG;
+    constexpr int NPAD = E * G;
+    constexpr int kGroupsPerBlock = kThreads / G;
+    const int tid = threadIdx.x;
+    const int g = tid & (G - 1);
+    const int group = tid >> LG;
+    const int total_groups = gridDim.x * kGroupsPerBlock;
+    const int iters = (S + total_groups - 1) / total_groups;
+    const bool vec_ok = (N & 3) == 0;
+
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.f;
+
+    for (int it = 0; it < iters; ++it) {
+        const int row = (it * gridDim.x + blockIdx.x) * kGroupsPerBlock + group;
+        const bool valid = row < S;
+        const float *src = x + (size_t)(valid ? row : 0) * N;
+        T v[E];
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            const int i0 = Lay::element(g, q * 4);
+            float f[4];
+            if (vec_ok && valid && i0 + 3 < N) {
+                const float4 t = *reinterpret_cast<const float4 *>(src + i0);
+                f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) f[j] = (valid && i0 + j < N) ? src[i0 + j] : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool live = valid && i0 + j < N;
+                const uint32_t k = live ? key_of(f[j]) : kPadKey;
+                if constexpr (WITH_PERM)
+                    v[q * 4 + j] = ((uint64_t)k << 32) | (uint32_t)(i0 + j);
+                else
+                    v[q * 4 + j] = k;
+            }
+        }
+
+        merge_up<T, E, LG, 1>(v, g);
+
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            const int i0 = Lay::element(g, q * 4);
+            float f[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t k;
+                if constexpr (WITH_PERM) k = (uint32_t)(v[q * 4 + j] >> 32); else k = v[q * 4 + j];
+                f[j] = value_of(k);
+                if (valid && i0 + j < N) acc[q * 4 + j] += f[j];
+            }
+            if (valid && out_sorted) {
+                float *dst = out_sorted + (size_t)row * N;
+                if (vec_ok && i0 + 3 < N) {
+                    *reinterpret_cast<float4 *>(dst + i0) = make_float4(f[0], f[1], f[2], f[3]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (i0 + j < N) dst[i0 + j] = f[j];
+                }
+            }
+            if constexpr (WITH_PERM) {
+                if (valid && out_perm) {
+                    int32_t *dst = out_perm + (size_t)row * N;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (i0 + j < N) dst[i0 + j] = (int32_t)(uint32_t)v[q * 4 + j];
+                }
+            }
+        }
+    }
+
+    // Combine the groups of this block: first the groups inside a wavefront
+    // (lanes g, g+G, ...), then the wavefronts through LDS, 16 keys at a time.
+#pragma unroll
+    for (int d = G; d < 64; d <<= 1) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] += __shfl_xor(acc[e], d, 64);
+    }
+    constexpr int kChunk = E < 16 ? E : 16;
+    __shared__ float red[kWaves][kChunk][G];
+    const int wave = tid >> 6;
+    const int lane = tid & 63;
+    for (int c0 = 0; c0 < E; c0 += kChunk) {
+        if (lane < G) {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                if (e >= c0 && e < c0 + kChunk) red[wave][e - c0][lane] = acc[e];
+        }
+        __syncthreads();
+        for (int idx = tid; idx < kChunk * G; idx += kThreads) {
+            const int e = c0 + idx / G, gg = idx % G;
+            float s = red[0][idx / G][gg];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) s += red[w][idx / G][gg];
+            const int i = Lay::element(gg, e);
+            partial[(size_t)blockIdx.x * NPAD + i] = s;
+        }
+        __syncthreads();
+    }
+}
+
+// mean[c] = (1/S) sum over blocks of partial[b][c], in fp64, fixed order.
+__global__ __launch_bounds__(256) void rank_means(const float *__restrict__ partial, int blocks, int npad,
+                                                  int N, int S, double *__restrict__ mean) {
+    __shared__ double red[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int part = threadIdx.x >> 6;
+    double s = 0.0;
+    if (col < N)
+        for (int b = part; b < blocks; b += 4) s += (double)partial[(size_t)b * npad + col];
+    red[part][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (part == 0 && col < N) {
+        const int l = threadIdx.x;
+        mean[col] = (((red[0][l] + red[1][l]) + red[2][l]) + red[3][l]) / (double)S;
+    }
+}
+
+// Omega(c) = c / mean[c] where eligible; c* = largest maximiser.
+__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ mean, int N, int c_min, int c_max,
+                                                    float t_floor, float *__restrict__ out_mean,
+                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar) {
+    __shared__ double best_v[256];
+    __shared__ int best_c[256];
+    double bv = -INFINITY;
+    int bc = 0;
+    for (int c = threadIdx.x + 1; c <= N; c += 256) {
+        const double m = mean[c - 1];
+        double om = -INFINITY;
+        if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
+        if (out_mean) out_mean[c - 1] = (float)m;
+        if (out_omega) out_omega[c - 1] = (float)om;
+        if (om > -INFINITY && om >= bv) { bv = om; bc = c; }
+    }
+    best_v[threadIdx.x] = bv;
+    best_c[threadIdx.x] = bc;
+    __syncthreads();
+    for (int d = 128; d > 0; d >>= 1) {
+        if (threadIdx.x < d) {
+            const double ov = best_v[threadIdx.x + d];
+            const int oc = best_c[threadIdx.x + d];
+            const double mv = best_v[threadIdx.x];
+            const int mc = best_c[threadIdx.x];
+            const bool take = oc != 0 && (mc == 0 || ov > mv || (ov == mv && oc > mc));
+            if (take) { best_v[threadIdx.x] = ov; best_c[threadIdx.x] = oc; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const bool none = best_c[0] == 0;
+        out_cstar[0] = none ? c_max : best_c[0];
+        out_cstar[1] = none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
+    }
+}
+
+struct SortPlan {
+    int e, lg;       // keys per lane, log2(lanes per row)
+    int npad;        // e << lg
+    int blocks;      // grid of sort_rank_sums
+};
+
+SortPlan plan_for(int S, int N) {
+    int npad = 8;
+    while (npad < N) npad <<= 1;
+    SortPlan p;
+    p.e = npad / 64 > 8 ? npad / 64 : 8;
+    int g = npad / p.e;
+    p.lg = 0;
+    while ((1 << p.lg) < g) ++p.lg;
+    p.npad = npad;
+    const int rows_per_block = kThreads / g;
+    int blocks = (S + rows_per_block - 1) / rows_per_block;
+    const int cap = 1024;  // a few blocks per compute unit; more rows per group beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    p.blocks = blocks;
+    return p;
+}
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+template <int E, int LG>
+void launch_sort(bool perm, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt, int32_t *pm,
+                 float *partial) {
+    if (perm)
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, true>), grid, dim3(kThreads), 0, st, x, S, N, srt, pm, partial);
+    else
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false>), grid, dim3(kThreads), 0, st, x, S, N, srt, pm, partial);
+}
+
+}  // namespace
+
+size_t cutoff_workspace_bytes(int S, int N) {
+    if (S < 1 || N < 1 || N > 4096) return 0;
+    const SortPlan p = plan_for(S, N);
+    return align256((size_t)p.blocks * p.npad * sizeof(float)) + align256((size_t)N * sizeof(double));
+}
+
+int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
+                         float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream) {
+    if (!samples || !out_cstar || !workspace) return DKF_EINVAL;
+    if (S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return DKF_EINVAL;
+    if (t_floor != t_floor) return DKF_EINVAL;
+    if (N > 4096) return DKF_EUNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return DKF_EINVAL;
+    if (workspace_bytes < cutoff_workspace_bytes(S, N)) return DKF_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(samples) & 15) != 0) return DKF_EINVAL;
+    if (out_sorted && (reinterpret_cast<uintptr_t>(out_sorted) & 15) != 0) return DKF_EINVAL;
+
+    const SortPlan p = plan_for(S, N);
+    float *partial = static_cast<float *>(workspace);
+    double *mean = reinterpret_cast<double *>(static_cast<char *>(workspace) +
+                                              align256((size_t)p.blocks * p.npad * sizeof(float)));
+    const bool perm = out_perm != nullptr;
+    const dim3 grid(p.blocks);
+    {
+        StageTimer timer(kStageSort, stream);
+#define DKF_SORT_CASE(E_, LG_)                                                                    \
+    launch_sort<E_, LG_>(perm, grid, stream, samples, S, N, out_sorted, out_perm, partial);        \
+    break
+        switch (p.npad) {
+            case 8: DKF_SORT_CASE(8, 0);
+            case 16: DKF_SORT_CASE(8, 1);
+            case 32: DKF_SORT_CASE(8, 2);
+            case 64: DKF_SORT_CASE(8, 3);
+            case 128: DKF_SORT_CASE(8, 4);
+            case 256: DKF_SORT_CASE(8, 5);
+            case 512: DKF_SORT_CASE(8, 6);
+            case 1024: DKF_SORT_CASE(16, 6);
+            case 2048: DKF_SORT_CASE(32, 6);
+            case 4096: DKF_SORT_CASE(64, 6);
+            default: return DKF_EUNSUPPORTED;
+        }
+#undef DKF_SORT_CASE
+        DKF_HIP_TRY(hipGetLastError());
+    }
+    {
+        StageTimer timer(kStageArgmax, stream);
+        hipLaunchKernelGGL(rank_means, dim3((N + 63) / 64), dim3(256), 0, stream, partial, p.blocks, p.npad, N, S,
+                           mean);
+        DKF_HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, mean, N, c_min, c_max, t_floor, out_mean,
+                           out_omega, out_cstar);
+        DKF_HIP_TRY(hipGetLastError());
+    }
+    return DKF_OK;
+}
+
+}  // namespace dkf

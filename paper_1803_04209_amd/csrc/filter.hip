@@ -1,0 +1,109 @@
+// Lagged filtering: fixed-lag window and the two RNN encoders of the inference
+// network (Sec. 3.1.3: h_left runs forward over the window, h_right backward,
+// both single-layer ReLU cells started from zero).
+//
+// The input projection W_ih x_t does not depend on where x_t sits in the
+// window, so it is computed once per observation (project_observation) and
+// kept in a ring; it is stored un-normalised, and the normaliser 1/s is
+// applied when the recurrence consumes it (W_ih (x/s) = (W_ih x)/s).
+// The recurrences are two chains of L dependent R x R mat-vecs: one workgroup
+// per direction, the hidden state in LDS (encode_window).
+#include "common.h"
+
+namespace dkf {
+namespace {
+
+constexpr int kProjThreads = 256;
+constexpr int kProjRowsPerBlock = 16;
+constexpr int kChainThreads = 1024;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// proj_dir[slot][r] = sum_j w_ih_dir[r][j] * x[j]      grid: (ceil(R/16), 2)
+__global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a) {
+    const Control ctl = *a.ctl;
+    const int dir = blockIdx.y;
+    const float *__restrict__ w = dir ? a.w_ih_b : a.w_ih_f;
+    float *__restrict__ proj = (dir ? a.proj_b : a.proj_f) + (size_t)ctl.slot * a.R;
+    const float *__restrict__ x = a.input;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int N = a.N;
+    for (int i = wave; i < kProjRowsPerBlock; i += kProjThreads / 64) {
+        const int r = blockIdx.x * kProjRowsPerBlock + i;
+        if (r >= a.R) break;
+        const float *__restrict__ wr = w + (size_t)r * N;
+        float s = 0.f;
+        if ((N & 3) == 0) {
+            for (int j = lane * 4; j < N; j += 256) {
+                const float4 wv = *reinterpret_cast<const float4 *>(wr + j);
+                const float4 xv = *reinterpret_cast<const float4 *>(x + j);
+                s += wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
+            }
+        } else {
+            for (int j = lane; j < N; j += 64) s += wr[j] * x[j];
+        }
+        s = wave_sum(s);
+        if (lane == 0) proj[r] = s;
+    }
+}
+
+// ctx_dir[t][r] = h_t,  h_t = relu(proj[slot(t)][r] / s + b[r] + sum_k w_hh[r][k] h_prev[k])
+// grid: 2 (direction), block 1024; dynamic LDS: 2 * Rp floats.
+__global__ __launch_bounds__(kChainThreads) void encode_window(FilterArgs a) {
+    extern __shared__ float lds[];
+    const Control ctl = *a.ctl;
+    if (ctl.count < a.L) return;  // still warming up: nothing to encode
+    const int dir = blockIdx.x;
+    const int R = a.R, Rp = a.Rp, L = a.L;
+    const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
+    const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
+    const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
+    float *__restrict__ ctx = dir ? a.ctx_b : a.ctx_f;
+    float *h_prev = lds, *h_next = lds + Rp;
+    for (int r = threadIdx.x; r < Rp; r += kChainThreads) { h_prev[r] = 0.f; h_next[r] = 0.f; }
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    constexpr int kWaves = kChainThreads / 64;
+    for (int step = 0; step < L; ++step) {
+        const int t = dir ? L - 1 - step : step;
+        int slot = ctl.oldest + t;
+        if (slot >= L) slot -= L;
+        const float *__restrict__ p = proj + (size_t)slot * R;
+        for (int r = wave; r < R; r += kWaves) {
+            const float *__restrict__ wr = w + (size_t)r * R;
+            float s = 0.f;
+            if (step > 0)
+                for (int k = lane; k < R; k += 64) s += wr[k] * h_prev[k];
+            s = wave_sum(s);
+            if (lane == 0) {
+                const float v = fmaxf(p[r] * ctl.inv_scale + bias[r] + s, 0.f);
+                h_next[r] = v;
+                ctx[(size_t)t * Rp + r] = v;
+            }
+        }
+        __syncthreads();
+        float *tmp = h_prev; h_prev = h_next; h_next = tmp;
+    }
+}
+
+}  // namespace
+
+int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream) {
+    StageTimer timer(kStageFilter, stream);
+    if (project) {
+        const dim3 pgrid((a.R + kProjRowsPerBlock - 1) / kProjRowsPerBlock, 2);
+        hipLaunchKernelGGL(project_observation, pgrid, dim3(kProjThreads), 0, stream, a);
+        DKF_HIP_TRY(hipGetLastError());
+    }
+    if (encode) {
+        hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
+        DKF_HIP_TRY(hipGetLastError());
+    }
+    return DKF_OK;
+}
+
+}  // namespace dkf

@@ -1,0 +1,62 @@
+// Building blocks for dense layers on the gfx950 matrix cores (fp32 path).
+//
+// v_mfma_f32_32x32x2_f32: one wavefront multiplies A[32][2] by B[2][32] and
+// accumulates into D[32][32].  Lane l supplies A[l%32][l/32] and
+// B[l/32][l%32]; it owns D[8*(i/4) + 4*(l/32) + i%4][l%32] for i = 0..15.
+//
+// Activations ("A tile") live in LDS as planes of float4: plane q holds
+// columns 4q..4q+3 of every row, plane stride = rows + 1 float4 (the +1 keeps
+// consecutive planes on different banks).  Weights come straight from global
+// memory in the PackedLayer order, where one float4 per lane per k-group is a
+// fully coalesced 1 KiB read per wavefront.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace dkf {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
+// row (0..31) of accumulator element i held by `lane`
+__device__ __forceinline__ int acc_row(int i, int lane) { return (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3); }
+
+// scalar access into an A tile
+__device__ __forceinline__ float &tile_at(f32x4 *tile, int lda, int row, int col) {
+    return reinterpret_cast<float *>(tile)[((col >> 2) * lda + row) * 4 + (col & 3)];
+}
+
+// acc += A[rows r0..r0+31][k-groups kg0..kg1) * layer column block `tiles_nb`
+// tiles_nb points at the [k_groups][64] float4 of one 32-column block.
+__device__ __forceinline__ void mma_block(f32x16 &acc, const f32x4 *A, int lda, int r0,
+                                          const f32x4 *__restrict__ tiles_nb, int kg0, int kg1, int lane) {
+    const int r = r0 + (lane & 31), half = lane >> 5;
+#pragma unroll 4
+    for (int kg = kg0; kg < kg1; ++kg) {
+        const f32x4 b = tiles_nb[kg * 64 + lane];
+        const f32x4 a = A[(kg * 2 + half) * lda + r];
+        acc = mfma32(a.x, b.x, acc);
+        acc = mfma32(a.y, b.y, acc);
+        acc = mfma32(a.z, b.z, acc);
+        acc = mfma32(a.w, b.w, acc);
+    }
+}
+
+__device__ __forceinline__ float softplus_f(float v) { return fmaxf(v, 0.f) + log1pf(expf(-fabsf(v))); }
+
+__device__ __forceinline__ float sigmoid_f(float v) {
+    const float e = expf(-fabsf(v));
+    return v >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+}
+
+}  // namespace dkf

@@ -1,0 +1,170 @@
+// Dense layers of the emission network over all S samples (Sec. 3.1.3):
+//   I(z) = W_I2 act(W_I1 z + b) + b          (mean, N wide)
+//   J(z) = softplus(W_J2 relu(W_J1 I(z) + b) + b)   (scale, fed by the mean)
+//   x    = s * (I + J * eps_x)                 (draw, back in seconds)
+// One kernel template computes  out[S][n] = epilogue(A[S][K] W^T + b)  on the
+// fp32 matrix cores: a workgroup owns a 128 x 128 output tile, each of its four
+// wavefronts a 64 x 64 quarter (2 x 2 MFMA blocks).  The activation tile is
+// staged through LDS in K chunks of 32 (double buffered); the weights are read
+// straight from L2 in the pre-tiled PackedLayer order and prefetched one chunk
+// ahead in registers.  The scale layer's epilogue applies softplus, mixes in
+// the noise and writes the sample, so J is never materialised.
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace dkf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileM = 128;
+constexpr int kTileNB = 4;            // 32-column blocks per workgroup
+constexpr int kChunkKG = 4;           // k-groups (of 8) per LDS chunk: K chunk = 32
+constexpr int kLda = kTileM + 1;      // float4 plane stride
+constexpr int kPlanes = kChunkKG * 2; // float4 planes per chunk
+
+template <int EPI>
+__global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
+    __shared__ f32x4 As[2][kPlanes * kLda];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n_col_tiles = (a.layer.n_blocks + kTileNB - 1) / kTileNB;
+    // Workgroups that share a row tile run on the same XCD (consecutive ids are
+    // dealt round-robin to the 8 XCDs), so the activation rows are fetched into
+    // one L2 only.
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int row_tile = xcd + 8 * (seq / n_col_tiles);
+    const int col_tile = seq % n_col_tiles;
+    const int m0 = row_tile * kTileM;
+    if (m0 >= a.S) return;
+
+    const int wr = wave >> 1, wc = wave & 1;
+    const int KG = a.layer.k_groups;
+    const int n_chunks = KG / kChunkKG;
+    int nb[2];
+    const f32x4 *bt[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        nb[j] = col_tile * kTileNB + wc * 2 + j;
+        const int nbc = nb[j] < a.layer.n_blocks ? nb[j] : a.layer.n_blocks - 1;
+        bt[j] = reinterpret_cast<const f32x4 *>(a.layer.tiles) + (size_t)nbc * KG * 64 + lane;
+    }
+
+    // global -> LDS mapping of the activation chunk: plane q = tid % 8, rows tid/8 + 32 i
+    const int lq = tid & 7, lrow = tid >> 3;
+    const float *arow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = m0 + lrow + 32 * i;
+        if (r >= a.S) r = a.S - 1;
+        arow[i] = a.A + (size_t)r * a.lda + lq * 4;
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
+
+    f32x4 areg[4];
+    f32x4 breg[2][kChunkKG];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) areg[i] = *reinterpret_cast<const f32x4 *>(arow[i]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < kChunkKG; ++g) breg[j][g] = bt[j][(size_t)g * 64];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) As[0][lq * kLda + lrow + 32 * i] = areg[i];
+    __syncthreads();
+
+    const int r = lane & 31, half = lane >> 5;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const int cur = ch & 1;
+        f32x4 bcur[2][kChunkKG];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int g = 0; g < kChunkKG; ++g) bcur[j][g] = breg[j][g];
+        const bool more = ch + 1 < n_chunks;
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                areg[i] = *reinterpret_cast<const f32x4 *>(arow[i] + (size_t)(ch + 1) * kChunkKG * 8);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int g = 0; g < kChunkKG; ++g)
+                    breg[j][g] = bt[j][(size_t)((ch + 1) * kChunkKG + g) * 64];
+        }
+#pragma unroll
+        for (int g = 0; g < kChunkKG; ++g) {
+            const f32x4 a0 = As[cur][(g * 2 + half) * kLda + wr * 64 + r];
+            const f32x4 a1 = As[cur][(g * 2 + half) * kLda + wr * 64 + 32 + r];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[0][0] = mfma32(a0[e], bcur[0][g][e], acc[0][0]);
+                acc[0][1] = mfma32(a0[e], bcur[1][g][e], acc[0][1]);
+                acc[1][0] = mfma32(a1[e], bcur[0][g][e], acc[1][0]);
+                acc[1][1] = mfma32(a1[e], bcur[1][g][e], acc[1][1]);
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) As[cur ^ 1][lq * kLda + lrow + 32 * i] = areg[i];
+        }
+        __syncthreads();
+    }
+
+    // epilogue
+    float scale = 1.f;
+    if constexpr (EPI == kEpiScaleDraw) scale = a.ctl->scale;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if (nb[j] >= a.layer.n_blocks) continue;
+        const int col = nb[j] * 32 + r;
+        const float b = a.layer.bias[col];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = m0 + wr * 64 + i * 32 + acc_row(e, lane);
+                if (row >= a.S) continue;
+                const float v = acc[i][j][e] + b;
+                if constexpr (EPI == kEpiBias) {
+                    a.out[(size_t)row * a.ldo + col] = v;
+                } else if constexpr (EPI == kEpiBiasRelu) {
+                    a.out[(size_t)row * a.ldo + col] = fmaxf(v, 0.f);
+                } else {
+                    if (col < a.N) {
+                        const float sd = softplus_f(v);
+                        const float mean = a.mean[(size_t)row * a.ld_mean + col];
+                        const float eps = a.eps_x[(size_t)row * a.N + col];
+                        a.out_samples[(size_t)row * a.N + col] = scale * (mean + sd * eps);
+                        if (a.out_mean_dbg) a.out_mean_dbg[(size_t)row * a.N + col] = mean;
+                        if (a.out_sd_dbg) a.out_sd_dbg[(size_t)row * a.N + col] = sd;
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int launch_gemm(const GemmArgs &a, int stage, hipStream_t stream) {
+    if (a.layer.k_groups % kChunkKG != 0 || a.layer.k_groups * 8 > a.lda) return DKF_EINVAL;
+    StageTimer timer(stage, stream);
+    const int row_tiles = (a.S + kTileM - 1) / kTileM;
+    const int col_tiles = (a.layer.n_blocks + kTileNB - 1) / kTileNB;
+    const int row_tiles8 = (row_tiles + 7) / 8 * 8;
+    const dim3 grid(row_tiles8 * col_tiles);
+    switch (a.epilogue) {
+        case kEpiBias: hipLaunchKernelGGL(mlp_gemm<kEpiBias>, grid, dim3(kThreads), 0, stream, a); break;
+        case kEpiBiasRelu: hipLaunchKernelGGL(mlp_gemm<kEpiBiasRelu>, grid, dim3(kThreads), 0, stream, a); break;
+        case kEpiScaleDraw: hipLaunchKernelGGL(mlp_gemm<kEpiScaleDraw>, grid, dim3(kThreads), 0, stream, a); break;
+        default: return DKF_EINVAL;
+    }
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
+}  // namespace dkf
