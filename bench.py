@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the Cutoff-SGD predictor hot path on one MI355X.
+
+A step is one whole decision: push one observed run-time vector (host -> GPU),
+re-encode the window, draw S joint run-time vectors, sort them, average the
+ranks, pick c*, and bring c* back (GPU -> host), i.e. one `dkf_decide` call.
+Prints ONE JSON line; see the design doc for how the figures are defined.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload medium|contended|replay|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+METRIC = "sampled N-worker run-time vectors/sec + cutoff decisions/sec (p50 latency)"
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}  # MI355X dense MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def stage_work(cfg):
+    """Algorithmic flops (MLP stages) and bytes (sort) of one decision, per stage id."""
+    S, N, L, Z, H, R = cfg.samples, cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim
+    return {
+        1: ("mfma", 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)),
+        2: ("mfma", 2.0 * S * Z * H),
+        3: ("mfma", 2.0 * S * H * N),
+        4: ("mfma", 2.0 * S * N * H),
+        5: ("mfma", 2.0 * S * H * N),
+        6: ("hbm", 4.0 * S * N),
+    }
+
+
+def cpu_baseline(cfg, blob, trace, noise, budget_s):
+    """The oracle as it stands, on the host cores, on a bounded number of samples."""
+    import oracle
+
+    eq, ez, ex = noise
+    m = oracle.OracleModel(cfg, blob)
+    for t in range(cfg.lag):
+        m.filter_step(trace[t])
+
+    def run(n):
+        t0 = time.perf_counter()
+        m.filter_step(trace[cfg.lag])
+        m.predict_cutoff(eq[:, :n].copy(), ez[:n], ex[:n])
+        return time.perf_counter() - t0
+
+    probe_n = min(cfg.samples, 4 * oracle.num_threads())
+    run(probe_n)
+    dt = run(probe_n)
+    n = int(min(cfg.samples, max(probe_n, probe_n * budget_s / max(dt, 1e-6))))
+    reps, total = 0, 0.0
+    while total < budget_s and reps < 10000:  # whole decisions until the budget is used
+        total += run(n)
+        reps += 1
+    dt = total / reps
+    return {
+        "value": n / dt, "unit": "vectors/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{reps} decision(s) (filter step + predict_cutoff) with {n} of {cfg.samples} samples each, "
+                  f"{total:.1f} s wall in total, fp64, OpenMP over samples",
+        "decisions_per_s_extrapolated": 1.0 / (dt * cfg.samples / n),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "contended", "replay"])
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1803_04209_amd import api, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    S, N = cfg.samples, cfg.n_workers
+    K, W = args.steps, args.warmup
+    blob = synth.make_blob(cfg)
+    trace = synth.make_trace(cfg, max(cfg.trace_len, cfg.lag + 2 * (K + W) + 64))
+    noise = synth.make_noise(cfg)
+    eq, ez, ex = (torch.from_numpy(a).cuda() for a in noise)
+    pred = api.Predictor(cfg, blob)
+    t_idx = 0
+    for _ in range(cfg.lag - 1):  # fill the window (untimed); the next push completes it
+        pred.filter_step(trace[t_idx]); t_idx += 1
+
+    # ---- region 1: synchronous decisions through the captured graph ----------------
+    for _ in range(W):
+        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+    torch.cuda.synchronize()
+    lat = np.empty(K)
+    cuts = np.empty(K, dtype=np.int64)
+    t_start = time.perf_counter()
+    for i in range(K):
+        t0 = time.perf_counter()
+        cuts[i], _ = pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+        lat[i] = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    ms_per_step = wall / K * 1e3
+
+    # ---- region 2: the same steps enqueued eagerly, HIP events around each stage -----
+    out = torch.empty((S, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(api.cutoff_select_workspace(S, N), dtype=torch.uint8, device="cuda")
+    cst = torch.zeros(2, dtype=torch.int32, device="cuda")
+
+    def eager_steps(n):
+        nonlocal t_idx
+        for _ in range(n):
+            pred.filter_step(trace[t_idx]); t_idx += 1
+            api.dkf_sample_runtimes(pred.handle, S, eq, ez, ex, 0, out)
+            api.cutoff_select(out, 1, N, 0.0, None, None, None, None, cst, ws)
+
+    work = stage_work(cfg)
+    api.dkf_timing_enable(0xFF)
+    eager_steps(min(W, 20) + 1)
+    for s in range(api.DKF_NUM_STAGES):
+        api.dkf_timing_read(s)
+    eager_steps(min(K, 50))
+    stage_us = {}
+    for s in range(api.DKF_NUM_STAGES):
+        n, ms = api.dkf_timing_read(s)
+        stage_us[s] = ms / max(n, 1) * 1e3
+    dominant = max(work, key=lambda s: stage_us[s])
+    # dominant kernel alone: one event pair per launch, host running ahead of the GPU
+    api.dkf_timing_enable(1 << dominant)
+    eager_steps(min(W, 20) + 1)
+    api.dkf_timing_read(dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eager_steps(K)
+    torch.cuda.synchronize()
+    eager_wall = time.perf_counter() - t0
+    n_launch, total_ms = api.dkf_timing_read(dominant)
+    api.dkf_timing_enable(0)
+    kernel_s = total_ms / max(n_launch, 1) * 1e-3
+    bound, amount = work[dominant]
+    if bound == "mfma":
+        achieved, peak, unit = amount / kernel_s / 1e12, PEAK_TFLOPS[cfg.mlp_dtype], "TFLOP/s"
+    else:
+        achieved, peak, unit = amount / kernel_s / 1e9, PEAK_HBM_GBS, "GB/s"
+    roofline = {
+        "kernel": api.STAGE_NAMES[dominant], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+        "frac": achieved / peak, "traffic": None, "launches": n_launch, "avg_launch_us": kernel_s * 1e6,
+        "work_per_launch": amount,
+    }
+    mlp_flops = sum(v for s, (b, v) in work.items() if b == "mfma")
+    mlp_us = sum(stage_us[s] for s, (b, _) in work.items() if b == "mfma")
+
+    result = {
+        "metric": METRIC, "value": S * K / wall, "unit": "vectors/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.mlp_dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: N={N} L={cfg.lag} Z={cfg.z_dim} H={cfg.hidden} S={S}",
+                   "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay)"},
+        "decisions_per_s": K / wall,
+        "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3)},
+        "mean_cutoff": float(cuts.mean()),
+        "eager_pipelined": {"vectors_per_s": S * K / eager_wall, "ms_per_step": eager_wall / K * 1e3},
+        "stage_us": {api.STAGE_NAMES[s]: round(stage_us[s], 2) for s in range(api.DKF_NUM_STAGES)},
+        "mlp_stages": {"flops": mlp_flops, "us": mlp_us, "tflops": mlp_flops / (mlp_us * 1e-6) / 1e12,
+                       "frac_of_peak": mlp_flops / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype]},
+        "roofline": roofline,
+    }
+    pred.close()
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, blob, trace, noise, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

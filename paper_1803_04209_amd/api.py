@@ -230,12 +230,16 @@ class Predictor:
         self.config = make_config(cfg, max_samples, emit_mean_act, mlp_dtype)
         self.handle = dkf_load_weights(self.config, blob)
 
-    def close(self):
+    def close(self, _free=dkf_free):
         if getattr(self, "handle", None):
-            dkf_free(self.handle)
-            self.handle = None
+            handle, self.handle = self.handle, None
+            _free(handle)
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: the library may already be gone
+            pass
 
     def reset(self):
         dkf_reset(self.handle)
