@@ -70,6 +70,9 @@ struct dkf_model {
     const float *bias_f = nullptr, *bias_b = nullptr, *z0 = nullptr;
     PackedLayer comb, mu, sig, gate1, gate2, prop1, prop2, lin, tscale;
     PackedLayer emean1, emean2, escale1, escale2;
+    bool use_chain = false;  // sizes covered by the register-chained sampler
+    const float *chain_guide = nullptr, *chain_stream = nullptr;
+    int chain_chunks = 0;
 
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
@@ -158,6 +161,63 @@ int pack_layer(dkf_model *m, const float *w, const float *b, int n_out, int k_in
     return DKF_OK;
 }
 
+// One 16 x 16 weight tile for v_mfma_f32_16x16x4_f32 with the weights as the A operand:
+// lane = 16*q + i holds W[ob*16 + i][ib*16 + 4q .. 4q+3] (zero outside the matrix).
+void append_tile(std::vector<float> &dst, const float *w, int n_out, int k_in, int ob, int ib) {
+    const size_t base = dst.size();
+    dst.resize(base + 256, 0.f);
+    for (int lane = 0; lane < 64; ++lane) {
+        const int n = ob * 16 + (lane & 15);
+        if (n >= n_out) continue;
+        for (int j = 0; j < 4; ++j) {
+            const int k = ib * 16 + (lane >> 4) * 4 + j;
+            if (k < k_in) dst[base + lane * 4 + j] = w[(size_t)n * k_in + k];
+        }
+    }
+}
+
+struct RawLayers {
+    const float *comb, *mu, *sig, *gate1, *gate2, *prop1, *prop2, *lin, *tscale, *emean1, *emean2, *escale1, *escale2;
+};
+
+// Tile streams of the chained sampler.  Guide: comb [ob][ib], mu [zb][ib], sig [zb][ib].
+// Stream, in chunks of HB tiles, in the order the kernel consumes them:
+//   gate1 (one chunk per input block: tiles ob = 0..HB-1), gate2 (one chunk per output block:
+//   tiles ib = 0..HB-1), prop1, prop2, lin and tscale ([ob][ib] tiles padded to whole chunks),
+//   emean1 (as gate1), then per 16-worker block nb: emean2 row nb (ib = 0..HB-1) followed by
+//   escale1 column nb (ob = 0..HB-1), then per block nb: escale2 row nb.
+int pack_chain(dkf_model *m, const RawLayers &r) {
+    const int Z = m->Z, R = m->R, H = m->H, N = m->N;
+    const int ZB = (Z + 15) / 16, RB = (R + 15) / 16, HB = (H + 15) / 16, NB = (N + 15) / 16;
+    std::vector<float> g, s;
+    for (int ob = 0; ob < RB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(g, r.comb, R, Z, ob, ib);
+    for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < RB; ++ib) append_tile(g, r.mu, Z, R, zb, ib);
+    for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(g, r.sig, Z, Z, zb, ib);
+    auto wide = [&](const float *w) {  // Z -> H
+        for (int ib = 0; ib < ZB; ++ib) for (int ob = 0; ob < HB; ++ob) append_tile(s, w, H, Z, ob, ib);
+    };
+    auto narrow = [&](const float *w) {  // H -> Z
+        for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < HB; ++ib) append_tile(s, w, Z, H, zb, ib);
+    };
+    auto small = [&](const float *w) {  // Z -> Z, padded to whole chunks
+        for (int ob = 0; ob < ZB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(s, w, Z, Z, ob, ib);
+        const size_t chunk = (size_t)HB * 256;
+        s.resize((s.size() + chunk - 1) / chunk * chunk, 0.f);
+    };
+    wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale);
+    wide(r.emean1);
+    for (int nb = 0; nb < NB; ++nb) {
+        for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
+        for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
+    }
+    for (int nb = 0; nb < NB; ++nb)
+        for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
+    m->chain_chunks = (int)(s.size() / ((size_t)HB * 256));
+    int rc = upload(m, g.data(), g.size(), &m->chain_guide);
+    if (rc != DKF_OK) return rc;
+    return upload(m, s.data(), s.size(), &m->chain_stream);
+}
+
 size_t blob_floats(const dkf_config *c) {
     const size_t N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
     const size_t rnn = 2 * (R * N + R + R * R + R);
@@ -217,8 +277,38 @@ int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *ds
     return count < L ? DKF_WARMUP : DKF_OK;
 }
 
+int copy_ctx(dkf_model *m, float *dst, hipStream_t stream);
+
+int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
+                  float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
+    ChainArgs c{};
+    c.ctl = m->ctl_dev();
+    c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
+    c.guide_tiles = m->chain_guide; c.stream_tiles = m->chain_stream; c.stream_chunks = m->chain_chunks;
+    c.z0 = m->z0;
+    c.b_comb = m->comb.bias; c.b_mu = m->mu.bias; c.b_sig = m->sig.bias;
+    c.b_gate1 = m->gate1.bias; c.b_gate2 = m->gate2.bias; c.b_prop1 = m->prop1.bias; c.b_prop2 = m->prop2.bias;
+    c.b_lin = m->lin.bias; c.b_tscale = m->tscale.bias;
+    c.b_emean1 = m->emean1.bias; c.b_emean2 = m->emean2.bias; c.b_escale1 = m->escale1.bias;
+    c.b_escale2 = m->escale2.bias;
+    c.eps_q = eps_q; c.eps_z = eps_z; c.eps_x = eps_x;
+    c.mean = m->mean; c.ld_mean = m->Np;
+    c.out_samples = out_samples;
+    c.z_last = st ? st->z_last : nullptr;
+    c.z_next_dbg = st ? st->z_next : nullptr;
+    c.out_mean_dbg = st ? st->emit_mean : nullptr;
+    c.out_sd_dbg = st ? st->emit_sd : nullptr;
+    c.S = S; c.L = m->L; c.Z = m->Z; c.R = m->R; c.H = m->H; c.N = m->N; c.NB = (m->N + 15) / 16;
+    c.emit_mean_act = m->cfg.emit_mean_act;
+    const int rc = launch_chain(c, stream);
+    if (rc != DKF_OK) return rc;
+    if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
+    return DKF_OK;
+}
+
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
+    if (m->use_chain) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
     GuideArgs g;
     g.ctl = m->ctl_dev();
     g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
@@ -253,16 +343,20 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
     e.out_sd_dbg = st ? st->emit_sd : nullptr;
     if ((rc = launch_gemm(e, kStageEmitScaleDraw, stream)) != DKF_OK) return rc;
 
-    if (st && st->ctx) {
-        // h_left + h_right per position, for inspection only
-        std::vector<float> f((size_t)m->L * m->Rp), b((size_t)m->L * m->Rp), c((size_t)m->L * m->R);
-        DKF_HIP_TRY(hipStreamSynchronize(stream));
-        DKF_HIP_TRY(hipMemcpy(f.data(), m->ctx_f, f.size() * 4, hipMemcpyDeviceToHost));
-        DKF_HIP_TRY(hipMemcpy(b.data(), m->ctx_b, b.size() * 4, hipMemcpyDeviceToHost));
-        for (int t = 0; t < m->L; ++t)
-            for (int r = 0; r < m->R; ++r) c[(size_t)t * m->R + r] = f[(size_t)t * m->Rp + r] + b[(size_t)t * m->Rp + r];
-        DKF_HIP_TRY(hipMemcpy(st->ctx, c.data(), c.size() * 4, hipMemcpyHostToDevice));
-    }
+    if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
+    return DKF_OK;
+}
+
+// h_left + h_right per window position into a caller buffer [L][R]; inspection only
+// (synchronises the stream and goes through the host).
+int copy_ctx(dkf_model *m, float *dst, hipStream_t stream) {
+    std::vector<float> f((size_t)m->L * m->Rp), b((size_t)m->L * m->Rp), c((size_t)m->L * m->R);
+    DKF_HIP_TRY(hipStreamSynchronize(stream));
+    DKF_HIP_TRY(hipMemcpy(f.data(), m->ctx_f, f.size() * 4, hipMemcpyDeviceToHost));
+    DKF_HIP_TRY(hipMemcpy(b.data(), m->ctx_b, b.size() * 4, hipMemcpyDeviceToHost));
+    for (int t = 0; t < m->L; ++t)
+        for (int r = 0; r < m->R; ++r) c[(size_t)t * m->R + r] = f[(size_t)t * m->Rp + r] + b[(size_t)t * m->Rp + r];
+    DKF_HIP_TRY(hipMemcpy(dst, c.data(), c.size() * 4, hipMemcpyHostToDevice));
     return DKF_OK;
 }
 
@@ -351,25 +445,29 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
         DKF_CHECK(upload(m, w_hh, sR * sR, dir ? &m->w_hh_b : &m->w_hh_f));
         DKF_CHECK(upload(m, bsum.data(), sR, dir ? &m->bias_b : &m->bias_f));
     }
+    RawLayers raw{};
     {
         const float *w, *b;
-        w = take(sR * sZ); b = take(sR); DKF_CHECK(pack_layer(m, w, b, R, Z, &m->comb));
-        w = take(sZ * sR); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, R, &m->mu));
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->sig));
+        w = take(sR * sZ); b = take(sR); DKF_CHECK(pack_layer(m, w, b, R, Z, &m->comb)); raw.comb = w;
+        w = take(sZ * sR); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, R, &m->mu)); raw.mu = w;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->sig)); raw.sig = w;
         std::vector<float> z0(m->Zp, 0.f);
         std::memcpy(z0.data(), take(sZ), sizeof(float) * sZ);
         DKF_CHECK(upload(m, z0.data(), z0.size(), &m->z0));
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->gate1));
-        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->gate2));
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->prop1));
-        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->prop2));
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->lin));
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->tscale));
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->emean1));
-        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->emean2));
-        w = take(sH * sN); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, N, &m->escale1));
-        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2));
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->gate1)); raw.gate1 = w;
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->gate2)); raw.gate2 = w;
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->prop1)); raw.prop1 = w;
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->prop2)); raw.prop2 = w;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->lin)); raw.lin = w;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->tscale)); raw.tscale = w;
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->emean1)); raw.emean1 = w;
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->emean2)); raw.emean2 = w;
+        w = take(sH * sN); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, N, &m->escale1)); raw.escale1 = w;
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2)); raw.escale2 = w;
     }
+
+    m->use_chain = chain_supported(Z, R, H, L, N);
+    if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
 
     void *q = nullptr;
     DKF_CHECK(dev_alloc(m, m->in_floats() * 4, &q, true)); m->d_in = static_cast<float *>(q);

@@ -135,6 +135,28 @@ struct GemmArgs {
 };
 int launch_gemm(const GemmArgs &a, int stage, hipStream_t stream);
 
+// chain.hip: guide + transition + emission in one register-chained kernel
+struct ChainArgs {
+    const Control *ctl;
+    const float *ctx_f, *ctx_b;  // [L][Rp]
+    int Rp;
+    const float *guide_tiles;    // comb [RB][ZB], mu [ZB][RB], sig [ZB][ZB] tiles of 64 float4
+    const float *stream_tiles;   // chunks of HB tiles in consumption order (see pack_chain in api.hip)
+    int stream_chunks;
+    const float *z0;
+    const float *b_comb, *b_mu, *b_sig, *b_gate1, *b_gate2, *b_prop1, *b_prop2, *b_lin, *b_tscale;
+    const float *b_emean1, *b_emean2, *b_escale1, *b_escale2;  // zero padded to a multiple of 32
+    const float *eps_q, *eps_z, *eps_x;
+    float *mean;  // [S][ld_mean] scratch, also the emission mean for inspection
+    int ld_mean;
+    float *out_samples;  // [S][N]
+    float *z_last, *z_next_dbg, *out_mean_dbg, *out_sd_dbg;  // optional
+    int S, L, Z, R, H, N, NB;
+    int emit_mean_act;
+};
+bool chain_supported(int Z, int R, int H, int L, int N);
+int launch_chain(const ChainArgs &a, hipStream_t stream);
+
 // cutoff_select.hip
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
