@@ -7,8 +7,8 @@
 //                    bitonic network held in registers (several keys per lane,
 //                    cross-lane exchanges inside one wavefront), and each rank's
 //                    values are summed over the rows a lane group visits;
-//   rank_means     : fixed-order fp64 reduction of the per-block sums;
-//   omega_argmax   : Omega(c) and the largest maximiser.
+//   rank_partial_sums : fixed-order fp64 reduction of the per-block sums, 16 ways;
+//   omega_argmax   : the last 16-term sum, Omega(c) and the largest maximiser.
 // Keys are the order-preserving uint32 image of the fp32 bits, so all compares
 // are integer min/max; with a permutation requested the worker index rides in
 // the low half of a 64-bit key and breaks ties.
@@ -259,33 +259,48 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
     }
 }
 
-// mean[c] = (1/S) sum over blocks of partial[b][c], in fp64, fixed order.
-__global__ __launch_bounds__(256) void rank_means(const float *__restrict__ partial, int blocks, int npad,
-                                                  int N, int S, double *__restrict__ mean) {
+constexpr int kMeanParts = 16;  // second-level partial sums per rank
+
+// part2[p][c] = sum over blocks b = 4p + sub (mod 64) of partial[b][c], fp64, fixed order.
+// grid: (ceil(N/64), kMeanParts); 64 ranks x 4 interleaved block subsets per workgroup.
+__global__ __launch_bounds__(256) void rank_partial_sums(const float *__restrict__ partial, int blocks, int npad,
+                                                         int N, double *__restrict__ part2) {
     __shared__ double red[4][64];
-    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int part = threadIdx.x >> 6;
-    double s = 0.0;
-    if (col < N)
-        for (int b = part; b < blocks; b += 4) s += (double)partial[(size_t)b * npad + col];
-    red[part][threadIdx.x & 63] = s;
-    __syncthreads();
-    if (part == 0 && col < N) {
-        const int l = threadIdx.x;
-        mean[col] = (((red[0][l] + red[1][l]) + red[2][l]) + red[3][l]) / (double)S;
+    const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + lane;
+    const int first = blockIdx.y * 4 + sub;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    if (col < N) {
+        const int stride = kMeanParts * 4;
+        int b = first;
+        for (; b + 3 * stride < blocks; b += 4 * stride) {  // four independent loads in flight
+            const float v0 = partial[(size_t)b * npad + col];
+            const float v1 = partial[(size_t)(b + stride) * npad + col];
+            const float v2 = partial[(size_t)(b + 2 * stride) * npad + col];
+            const float v3 = partial[(size_t)(b + 3 * stride) * npad + col];
+            s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
+        }
+        for (; b < blocks; b += stride) s0 += (double)partial[(size_t)b * npad + col];
     }
+    red[sub][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (sub == 0 && col < N)
+        part2[(size_t)blockIdx.y * N + col] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
 }
 
 // Omega(c) = c / mean[c] where eligible; c* = largest maximiser.
-__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ mean, int N, int c_min, int c_max,
-                                                    float t_floor, float *__restrict__ out_mean,
+__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ part2, int N, int S, int c_min,
+                                                    int c_max, float t_floor, float *__restrict__ out_mean,
                                                     float *__restrict__ out_omega, int32_t *__restrict__ out_cstar) {
     __shared__ double best_v[256];
     __shared__ int best_c[256];
     double bv = -INFINITY;
     int bc = 0;
     for (int c = threadIdx.x + 1; c <= N; c += 256) {
-        const double m = mean[c - 1];
+        double sum = 0.0;
+#pragma unroll
+        for (int p = 0; p < kMeanParts; ++p) sum += part2[(size_t)p * N + c - 1];
+        const double m = sum / (double)S;
         double om = -INFINITY;
         if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
         if (out_mean) out_mean[c - 1] = (float)m;
@@ -296,7 +311,7 @@ __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ m
     best_c[threadIdx.x] = bc;
     __syncthreads();
     for (int d = 128; d > 0; d >>= 1) {
-        if (threadIdx.x < d) {
+        if ((int)threadIdx.x < d) {
             const double ov = best_v[threadIdx.x + d];
             const int oc = best_c[threadIdx.x + d];
             const double mv = best_v[threadIdx.x];
@@ -353,7 +368,7 @@ void launch_sort(bool perm, dim3 grid, hipStream_t st, const float *x, int S, in
 size_t cutoff_workspace_bytes(int S, int N) {
     if (S < 1 || N < 1 || N > 4096) return 0;
     const SortPlan p = plan_for(S, N);
-    return align256((size_t)p.blocks * p.npad * sizeof(float)) + align256((size_t)N * sizeof(double));
+    return align256((size_t)p.blocks * p.npad * sizeof(float)) + align256((size_t)kMeanParts * N * sizeof(double));
 }
 
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
@@ -370,8 +385,8 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
 
     const SortPlan p = plan_for(S, N);
     float *partial = static_cast<float *>(workspace);
-    double *mean = reinterpret_cast<double *>(static_cast<char *>(workspace) +
-                                              align256((size_t)p.blocks * p.npad * sizeof(float)));
+    double *part2 = reinterpret_cast<double *>(static_cast<char *>(workspace) +
+                                               align256((size_t)p.blocks * p.npad * sizeof(float)));
     const bool perm = out_perm != nullptr;
     const dim3 grid(p.blocks);
     {
@@ -397,10 +412,10 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     }
     {
         StageTimer timer(kStageArgmax, stream);
-        hipLaunchKernelGGL(rank_means, dim3((N + 63) / 64), dim3(256), 0, stream, partial, p.blocks, p.npad, N, S,
-                           mean);
+        hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
+                           p.blocks, p.npad, N, part2);
         DKF_HIP_TRY(hipGetLastError());
-        hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, mean, N, c_min, c_max, t_floor, out_mean,
+        hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, part2, N, S, c_min, c_max, t_floor, out_mean,
                            out_omega, out_cstar);
         DKF_HIP_TRY(hipGetLastError());
     }

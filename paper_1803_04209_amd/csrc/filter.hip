@@ -90,6 +90,96 @@ __global__ __launch_bounds__(kChainThreads) void encode_window(FilterArgs a) {
     }
 }
 
+// Same recurrence with the R x R matrix held in registers for the whole chain:
+// 1024 threads, TPR threads per row, each owning KPT consecutive columns
+// (TPR * KPT = rows covered = 1024 / TPR).  A step is KPT fused multiply-adds
+// per thread against the previous state in LDS, a log2(TPR)-step shuffle
+// reduction and one barrier.  The input term (W_ih x_t)/s + b_ih + b_hh of
+// every window position is staged in LDS before the loop, so the loop itself
+// touches no global memory except the ctx stores.
+// Dynamic LDS: (L * ROWS + 2 * HSTRIDE) floats.
+template <int TPR, int KPT>
+__global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a) {
+    constexpr int ROWS = kChainThreads / TPR;
+    static_assert(TPR * KPT == ROWS, "square tile");
+    constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;  // 4 pad floats per column segment: conflict-free b128 reads
+    extern __shared__ float lds[];
+    const Control ctl = *a.ctl;
+    if (ctl.count < a.L) return;
+    const int dir = blockIdx.x;
+    const int R = a.R, L = a.L;
+    const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
+    const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
+    const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
+    float *__restrict__ ctx = dir ? a.ctx_b : a.ctx_f;
+    float *pre = lds;               // [L][ROWS] in chain order (step), input term of every position
+    float *h0 = lds + L * ROWS;     // two state buffers, padded layout
+    float *h1 = h0 + HSTRIDE;
+    const int tid = threadIdx.x;
+    const int row = tid / TPR, seg = tid % TPR, k0 = seg * KPT;
+
+    float wreg[KPT];
+    if (KPT >= 4 && (R & 3) == 0) {
+#pragma unroll
+        for (int j = 0; j < KPT; j += 4) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < R && k0 + j < R) v = *reinterpret_cast<const float4 *>(w + (size_t)row * R + k0 + j);
+            wreg[j] = v.x; wreg[j + 1 < KPT ? j + 1 : j] = v.y; wreg[j + 2 < KPT ? j + 2 : j] = v.z;
+            wreg[j + 3 < KPT ? j + 3 : j] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) wreg[j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
+    }
+    for (int i = tid; i < L * ROWS; i += kChainThreads) {
+        const int step = i / ROWS, r = i % ROWS;
+        const int t = dir ? L - 1 - step : step;
+        int slot = ctl.oldest + t;
+        if (slot >= L) slot -= L;
+        pre[i] = r < R ? proj[(size_t)slot * R + r] * ctl.inv_scale + bias[r] : 0.f;
+    }
+    for (int i = tid; i < 2 * HSTRIDE; i += kChainThreads) h0[i] = 0.f;
+    __syncthreads();
+
+    float *h_prev = h0, *h_next = h1;
+    for (int step = 0; step < L; ++step) {
+        const int t = dir ? L - 1 - step : step;
+        float s = 0.f;
+        const float *hp = h_prev + k0 + seg * 4;
+        if (KPT >= 4) {
+#pragma unroll
+            for (int j = 0; j < KPT; j += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
+                s += wreg[j] * hv.x + wreg[j + 1 < KPT ? j + 1 : j] * hv.y + wreg[j + 2 < KPT ? j + 2 : j] * hv.z +
+                     wreg[j + 3 < KPT ? j + 3 : j] * hv.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) s += wreg[j] * hp[j];
+        }
+#pragma unroll
+        for (int d = 1; d < TPR; d <<= 1) s += __shfl_xor(s, d, 64);
+        if (seg == 0) {
+            const float v = fmaxf(pre[step * ROWS + row] + s, 0.f);
+            h_next[row + (row / KPT) * 4] = v;
+            if (row < R) ctx[(size_t)t * a.Rp + row] = v;
+        }
+        __syncthreads();
+        float *tmp = h_prev; h_prev = h_next; h_next = tmp;
+    }
+}
+
+template <int TPR, int KPT>
+int launch_encode_reg(const FilterArgs &a, hipStream_t stream) {
+    constexpr int ROWS = kChainThreads / TPR;
+    constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;
+    const size_t lds = ((size_t)a.L * ROWS + 2 * HSTRIDE) * sizeof(float);
+    if (lds > 64 * 1024) return DKF_EUNSUPPORTED;
+    hipLaunchKernelGGL((encode_window_reg<TPR, KPT>), dim3(2), dim3(kChainThreads), lds, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
 }  // namespace
 
 int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream) {
@@ -100,8 +190,17 @@ int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t st
         DKF_HIP_TRY(hipGetLastError());
     }
     if (encode) {
-        hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
-        DKF_HIP_TRY(hipGetLastError());
+        int rc = DKF_EUNSUPPORTED;
+        if (a.R <= 32) rc = launch_encode_reg<32, 1>(a, stream);
+        else if (a.R <= 64) rc = launch_encode_reg<16, 4>(a, stream);
+        else if (a.R <= 128) rc = launch_encode_reg<8, 16>(a, stream);
+        else if (a.R <= 256) rc = launch_encode_reg<4, 64>(a, stream);
+        if (rc == DKF_EUNSUPPORTED) {  // wide or long windows: matrix streamed from L2 every step
+            hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
+            DKF_HIP_TRY(hipGetLastError());
+        } else if (rc != DKF_OK) {
+            return rc;
+        }
     }
     return DKF_OK;
 }
