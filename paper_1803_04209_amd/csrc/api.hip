@@ -96,6 +96,7 @@ struct dkf_model {
     void *cutoff_ws = nullptr;
     size_t cutoff_ws_bytes = 0;
     int32_t *d_cstar = nullptr;
+    float *sink = nullptr;  // scratch for masked-off lanes of the sampler
 
     // captured decision graph
     hipStream_t own_stream = nullptr;
@@ -180,39 +181,56 @@ struct RawLayers {
     const float *comb, *mu, *sig, *gate1, *gate2, *prop1, *prop2, *lin, *tscale, *emean1, *emean2, *escale1, *escale2;
 };
 
-// Tile streams of the chained sampler.  Guide: comb [ob][ib], mu [zb][ib], sig [zb][ib].
-// Stream, in chunks of HB tiles, in the order the kernel consumes them:
-//   gate1 (one chunk per input block: tiles ob = 0..HB-1), gate2 (one chunk per output block:
-//   tiles ib = 0..HB-1), prop1, prop2, lin and tscale ([ob][ib] tiles padded to whole chunks),
-//   emean1 (as gate1), then per 16-worker block nb: emean2 row nb (ib = 0..HB-1) followed by
-//   escale1 column nb (ob = 0..HB-1), then per block nb: escale2 row nb.
+// Tile streams of the chained sampler.  Guide: comb [ob group][ib][ob in group], mu [zb][ib], sig [zb][ib].
+// Stream: chunks of CH = chain_chunk_tiles(HB) tiles in the order the kernel consumes them, every
+// layer padded with zero tiles to whole chunks:
+//   gate1 [ib][ob], gate2 [zb][ib], prop1, prop2, lin [ob][ib], tscale, emean1 [ib][ob] (one chunk each);
+//   then per group of K2 = CH / (2 HB) 16-worker blocks nb: { emean2 row nb (ib = 0..HB-1),
+//   escale1 column nb (ob = 0..HB-1) } for each nb of the group;
+//   then per group of 2 K2 blocks: escale2 row nb (ib = 0..HB-1) for each nb of the group.
 int pack_chain(dkf_model *m, const RawLayers &r) {
     const int Z = m->Z, R = m->R, H = m->H, N = m->N;
     const int ZB = (Z + 15) / 16, RB = (R + 15) / 16, HB = (H + 15) / 16, NB = (N + 15) / 16;
+    const int CH = chain_chunk_tiles(HB), K2 = CH / (2 * HB);
     std::vector<float> g, s;
-    for (int ob = 0; ob < RB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(g, r.comb, R, Z, ob, ib);
+    const int GO = RB < 4 ? RB : 4;
+    for (int og = 0; og < RB / GO; ++og)
+        for (int ib = 0; ib < ZB; ++ib)
+            for (int j = 0; j < GO; ++j) append_tile(g, r.comb, R, Z, og * GO + j, ib);
     for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < RB; ++ib) append_tile(g, r.mu, Z, R, zb, ib);
     for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(g, r.sig, Z, Z, zb, ib);
+    const size_t chunk = (size_t)CH * 256;
+    auto pad = [&] { s.resize((s.size() + chunk - 1) / chunk * chunk, 0.f); };
+    auto zeros = [&](int tiles) { s.resize(s.size() + (size_t)tiles * 256, 0.f); };
     auto wide = [&](const float *w) {  // Z -> H
         for (int ib = 0; ib < ZB; ++ib) for (int ob = 0; ob < HB; ++ob) append_tile(s, w, H, Z, ob, ib);
+        pad();
     };
     auto narrow = [&](const float *w) {  // H -> Z
         for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < HB; ++ib) append_tile(s, w, Z, H, zb, ib);
+        pad();
     };
-    auto small = [&](const float *w) {  // Z -> Z, padded to whole chunks
+    auto small = [&](const float *w) {  // Z -> Z
         for (int ob = 0; ob < ZB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(s, w, Z, Z, ob, ib);
-        const size_t chunk = (size_t)HB * 256;
-        s.resize((s.size() + chunk - 1) / chunk * chunk, 0.f);
+        pad();
     };
     wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale);
     wide(r.emean1);
-    for (int nb = 0; nb < NB; ++nb) {
-        for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
-        for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
-    }
-    for (int nb = 0; nb < NB; ++nb)
-        for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
-    m->chain_chunks = (int)(s.size() / ((size_t)HB * 256));
+    for (int c = 0; c < (NB + K2 - 1) / K2; ++c)
+        for (int u = 0; u < K2; ++u) {
+            const int nb = c * K2 + u;
+            if (nb >= NB) { zeros(2 * HB); continue; }
+            for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
+            for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
+        }
+    for (int c = 0; c < (NB + 2 * K2 - 1) / (2 * K2); ++c)
+        for (int u = 0; u < 2 * K2; ++u) {
+            const int nb = c * 2 * K2 + u;
+            if (nb >= NB) { zeros(HB); continue; }
+            for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
+        }
+    if (s.size() % chunk != 0) return DKF_EINVAL;
+    m->chain_chunks = (int)(s.size() / chunk);
     int rc = upload(m, g.data(), g.size(), &m->chain_guide);
     if (rc != DKF_OK) return rc;
     return upload(m, s.data(), s.size(), &m->chain_stream);
@@ -294,6 +312,7 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.eps_q = eps_q; c.eps_z = eps_z; c.eps_x = eps_x;
     c.mean = m->mean; c.ld_mean = m->Np;
     c.out_samples = out_samples;
+    c.sink = m->sink;
     c.z_last = st ? st->z_last : nullptr;
     c.z_next_dbg = st ? st->z_next : nullptr;
     c.out_mean_dbg = st ? st->emit_mean : nullptr;
@@ -483,6 +502,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     m->cutoff_ws_bytes = cutoff_workspace_bytes(Smax, N);
     DKF_CHECK(dev_alloc(m, m->cutoff_ws_bytes, &q, true)); m->cutoff_ws = q;
     DKF_CHECK(dev_alloc(m, 2 * sizeof(int32_t), &q, true)); m->d_cstar = static_cast<int32_t *>(q);
+    DKF_CHECK(dev_alloc(m, 4096, &q, true)); m->sink = static_cast<float *>(q);
 
     for (int i = 0; i < dkf_model::kStagingSlots + 1; ++i) {
         void *h = nullptr;

@@ -31,15 +31,6 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// acc += W_tile (16 out x 16 in) * x (16 in x 16 samples), x held as one f32x4
-__device__ __forceinline__ f32x4 tile_mma(f32x4 acc, f32x4 w, f32x4 x) {
-    acc = mfma16(w.x, x.x, acc);
-    acc = mfma16(w.y, x.y, acc);
-    acc = mfma16(w.z, x.z, acc);
-    acc = mfma16(w.w, x.w, acc);
-    return acc;
-}
-
 // Keeps the instruction scheduler from hoisting later blocks' operand loads above this point
 // (otherwise dozens of weight tiles are prefetched into registers and the kernel spills).
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
@@ -52,95 +43,134 @@ __device__ __forceinline__ f32x4 map4(f32x4 v, F f) {
     return r;
 }
 
-// Double-buffered stream of weight chunks (HB tiles each) from global memory through LDS.
-template <int HB>
+// Stream of weight chunks (CH tiles each) from global memory through a two-buffer LDS ring.
+// While chunk c is consumed from LDS, chunk c + 1 sits in registers (requested one chunk
+// earlier); advance() writes it to the free buffer, requests chunk c + 2 and synchronises the
+// workgroup.  A chunk is sized so that its matrix work outlasts an L2 round trip.
+template <int CH>
 struct WeightStream {
-    static constexpr int kChunkF4 = HB * kTileF4;
+    static constexpr int kChunkF4 = CH * kTileF4;
     static constexpr int kPerThread = (kChunkF4 + kThreads - 1) / kThreads;
+    typedef float Regs __attribute__((ext_vector_type(4 * kPerThread)));  // one value: stays in registers
     const f32x4 *src;
     f32x4 *buf;
-    int total, next_chunk, cur, tid;
-    f32x4 regs[kPerThread];
+    int total, cur_chunk, tid;
+    Regs regs;
 
-    __device__ __forceinline__ void fetch(int chunk) {
-        if (chunk >= total) return;
+    __device__ __forceinline__ Regs fetch(int chunk) const {
+        if (chunk >= total) chunk = total - 1;  // past the end: refetch the last chunk (never used)
+        Regs r;
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int idx = tid + i * kThreads;
-            if (idx < kChunkF4) regs[i] = src[(size_t)chunk * kChunkF4 + idx];
+            const f32x4 t = src[(size_t)chunk * kChunkF4 + (idx < kChunkF4 ? idx : 0)];
+            r[4 * i] = t.x; r[4 * i + 1] = t.y; r[4 * i + 2] = t.z; r[4 * i + 3] = t.w;
         }
+        return r;
     }
-    __device__ __forceinline__ void commit(int b) {
+    __device__ __forceinline__ void commit(Regs r, int b) const {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int idx = tid + i * kThreads;
-            if (idx < kChunkF4) buf[b * kChunkF4 + idx] = regs[i];
+            const f32x4 t = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
+            if (idx < kChunkF4) buf[b * kChunkF4 + idx] = t;
         }
     }
-    // chunk 0 becomes readable; chunk 1 is in flight
     __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int t) {
-        src = s; buf = b; total = n; tid = t; cur = 0;
-        fetch(0);
-        commit(0);
-        fetch(1);
-        next_chunk = 2;
+        src = s; buf = b; total = n; tid = t; cur_chunk = 0;
+        regs = fetch(0);
+        commit(regs, 0);
+        regs = fetch(1);
         __syncthreads();
     }
-    // done with the current chunk: publish the next one
     __device__ __forceinline__ void advance() {
-        cur ^= 1;
-        commit(cur);
-        fetch(next_chunk++);
+        ++cur_chunk;
+        commit(regs, cur_chunk & 1);
+        regs = fetch(cur_chunk + 1);
         __syncthreads();
     }
-    __device__ __forceinline__ f32x4 tile(int t, int lane) const { return buf[cur * kChunkF4 + t * kTileF4 + lane]; }
+    __device__ __forceinline__ f32x4 tile(int t, int lane) const {
+        return buf[(cur_chunk & 1) * kChunkF4 + t * kTileF4 + lane];
+    }
 };
 
-// Calls use(i, tile_i) for i = 0..COUNT-1.  Tiles are fetched GROUP at a time with the next
-// group already in flight while the current one feeds the matrix cores; the scheduling fence
-// after each group bounds how far ahead the compiler may hoist operand loads.
-template <int COUNT, int GROUP, typename LoadF, typename UseF>
-__device__ __forceinline__ void for_tiles(LoadF &&load, UseF &&use) {
-    constexpr int kGroups = (COUNT + GROUP - 1) / GROUP;
+// Calls use(g, tiles) for every group of GROUP consecutive tiles (COUNT must be a multiple of
+// GROUP).  The next group is already being fetched while the current one feeds the matrix
+// cores; the scheduling fence after each group bounds how far ahead the compiler may hoist
+// operand loads (unbounded hoisting spills).
+template <int COUNT, int GROUP, typename LoadF, typename UseG>
+__device__ __forceinline__ void for_tile_groups(LoadF &&load, UseG &&use) {
+    static_assert(COUNT % GROUP == 0, "whole groups");
+    constexpr int kGroups = COUNT / GROUP;
     f32x4 buf[2][GROUP];
 #pragma unroll
-    for (int j = 0; j < GROUP; ++j)
-        if (j < COUNT) buf[0][j] = load(j);
+    for (int j = 0; j < GROUP; ++j) buf[0][j] = load(j);
 #pragma unroll
     for (int g = 0; g < kGroups; ++g) {
+        if (g + 1 < kGroups) {
 #pragma unroll
-        for (int j = 0; j < GROUP; ++j)
-            if (g + 1 < kGroups && (g + 1) * GROUP + j < COUNT) buf[(g + 1) & 1][j] = load((g + 1) * GROUP + j);
-#pragma unroll
-        for (int j = 0; j < GROUP; ++j)
-            if (g * GROUP + j < COUNT) use(g * GROUP + j, buf[g & 1][j]);
+            for (int j = 0; j < GROUP; ++j) buf[(g + 1) & 1][j] = load((g + 1) * GROUP + j);
+        }
+        use(g, buf[g & 1]);
         sched_fence();
     }
 }
 
+// A dependent v_mfma_f32_16x16x4_f32 cannot issue until its predecessor has left the pipe, so
+// every product below is spread over four accumulator chains that advance in turn.
+
+// GROUP output blocks, one tile each, same input block x:  out[j] += W_j x
+template <int GROUP>
+__device__ __forceinline__ void mma_wide(f32x4 *out, const f32x4 (&t)[GROUP], f32x4 x) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int j = 0; j < GROUP; ++j) out[j] = mfma16(t[j][e], x[e], out[j]);
+}
+
+// one output block accumulated over GROUP input blocks in four chains (one per k-slice)
+struct Acc4 {
+    f32x4 c[4];
+    __device__ __forceinline__ void init(f32x4 first) {
+        c[0] = first;
+        c[1] = c[2] = c[3] = splat(0.f);
+    }
+    __device__ __forceinline__ f32x4 sum() const { return (c[0] + c[1]) + (c[2] + c[3]); }
+};
+template <int GROUP>
+__device__ __forceinline__ void mma_narrow(Acc4 &acc, const f32x4 (&t)[GROUP], const f32x4 *x) {
+#pragma unroll
+    for (int j = 0; j < GROUP; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc.c[e] = mfma16(t[j][e], x[j][e], acc.c[e]);
+}
+
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
 __device__ __forceinline__ float fast_tanh(float v) {
-    // 1 - 2 / (exp(2v) + 1); exp via the hardware exp2
-    const float e = __expf(2.0f * v);
-    return 1.0f - __fdividef(2.0f, e + 1.0f);
+    // 1 - 2 / (exp(2v) + 1) with the hardware exp2 and reciprocal
+    return 1.0f - 2.0f * fast_rcp(__expf(2.0f * v) + 1.0f);
 }
 __device__ __forceinline__ float fast_softplus(float v) {
     return fmaxf(v, 0.f) + __logf(1.0f + __expf(-fabsf(v)));
 }
 __device__ __forceinline__ float fast_sigmoid(float v) {
     const float e = __expf(-fabsf(v));
-    const float r = __fdividef(1.0f, 1.0f + e);
+    const float r = fast_rcp(1.0f + e);
     return v >= 0.f ? r : e * r;
 }
 
-template <int ZB, int RB, int HB>
+// VEC: N and Z are multiples of 4, so every per-lane load/store is one aligned float4 and the
+// hot loops are free of branches (dead lanes and pad columns are handled by clamped addresses,
+// selects and a sink buffer; control flow would force the compiler to drain all outstanding
+// memory requests at every join).  DBG: per-stage outputs are stored as well.
+template <int ZB, int RB, int HB, bool VEC, bool DBG>
 __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     extern __shared__ __align__(16) char lds_raw[];
     constexpr int kGuideTiles = 2 * RB * ZB + ZB * ZB;
     constexpr int Z16 = ZB * 16, R16 = RB * 16, H16 = HB * 16;
-    constexpr int kGroup = 4;
     f32x4 *gw = reinterpret_cast<f32x4 *>(lds_raw);
     f32x4 *sbuf = gw + kGuideTiles * kTileF4;
-    float *ctx = reinterpret_cast<float *>(sbuf + 2 * HB * kTileF4);  // [L][R16]
+    float *ctx = reinterpret_cast<float *>(sbuf + 2 * chain_chunk_tiles(HB) * kTileF4);  // [L][R16]
     float *bias = ctx + a.L * R16;
     const int N16 = a.NB * 16;
     // bias table in LDS, in the order the layers run
@@ -160,7 +190,10 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     // guide weights, encodings and all biases -> LDS
     {
         const f32x4 *src = reinterpret_cast<const f32x4 *>(a.guide_tiles);
-        for (int i = tid; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
+        constexpr int kCopies = kGuideTiles * kTileF4 / kThreads;  // kTileF4 * tiles is a multiple of 64
+#pragma unroll 8
+        for (int i = 0; i < kCopies; ++i) gw[tid + i * kThreads] = src[tid + i * kThreads];
+        for (int i = tid + kCopies * kThreads; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
         for (int i = tid; i < a.L * R16; i += kThreads) {
             const int t = i / R16, r = i % R16;
             ctx[i] = a.ctx_f[(size_t)t * a.Rp + r] + a.ctx_b[(size_t)t * a.Rp + r];
@@ -184,10 +217,14 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     auto z_valid = [&](int zb, int v) { return zb * 16 + 4 * q + v < Z; };
     auto load_z_noise = [&](const float *base, int zb) {  // base -> [S][Z]
         f32x4 e;
-        const float *p = base + (size_t)sc * Z + zb * 16 + 4 * q;
-        if ((Z & 3) == 0) {
-            e = zb * 16 + 4 * q < Z ? *reinterpret_cast<const f32x4 *>(p) : splat(0.f);
+        const int f0 = zb * 16 + 4 * q;
+        if constexpr (VEC) {
+            const int fc = f0 < Z ? f0 : Z - 4;  // clamped: always a valid address
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(base + (size_t)sc * Z + fc);
+            const float keep = f0 < Z ? 1.f : 0.f;
+            e = t * keep;
         } else {
+            const float *p = base + (size_t)sc * Z + f0;
 #pragma unroll
             for (int v = 0; v < 4; ++v) e[v] = z_valid(zb, v) ? p[v] : 0.f;
         }
@@ -211,42 +248,54 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for (int zb = 0; zb < ZB; ++zb) eps_next[zb] = load_z_noise(a.eps_q + (size_t)tn * S * Z, zb);
         f32x4 h[RB];
         {
-            f32x4 acc;
+            // comb tiles are stored [group of GO output blocks][input block][block in group]
+            constexpr int GO = RB < 4 ? RB : 4;
             const float *ctx_t = ctx + t * R16 + 4 * q;
-            for_tiles<RB * ZB, kGroup>(
-                [&](int i) { return w_comb[i * kTileF4 + lane]; },
-                [&](int i, f32x4 w) {
-                    const int ob = i / ZB, ib = i % ZB;
-                    if (ib == 0) acc = bias4(lb_comb, ob);
-                    acc = tile_mma(acc, w, z[ib]);
-                    if (ib == ZB - 1) {
-                        const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + ob * 16);
-                        h[ob] = (map4(acc, [](float v) { return fast_tanh(v); }) + c) * (1.0f / 3.0f);
-                    }
-                });
+            auto finish = [&](int ob) {  // h_out = (tanh(.) + h_left + h_right) / 3
+                const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + ob * 16);
+                h[ob] = (map4(h[ob], [](float v) { return fast_tanh(v); }) + c) * (1.0f / 3.0f);
+            };
+#pragma unroll
+            for (int ob = 0; ob < RB; ++ob) h[ob] = bias4(lb_comb, ob);
+            for_tile_groups<RB * ZB, GO>([&](int i) { return w_comb[i * kTileF4 + lane]; },
+                                         [&](int g, const f32x4(&tl)[GO]) {
+                                             const int og = g / ZB, ib = g % ZB;
+                                             if (ib == 0 && og > 0) {  // previous group's epilogue rides along
+#pragma unroll
+                                                 for (int j = 0; j < GO; ++j) finish((og - 1) * GO + j);
+                                             }
+                                             mma_wide<GO>(&h[og * GO], tl, z[ib]);
+                                         });
+#pragma unroll
+            for (int j = 0; j < GO; ++j) finish(RB - GO + j);
         }
         f32x4 mu[ZB];
+        {
+            constexpr int GI = RB < 4 ? RB : 4;
 #pragma unroll
-        for (int zb = 0; zb < ZB; ++zb) {
-            f32x4 acc0 = bias4(lb_mu, zb), acc1 = splat(0.f);
-            for_tiles<RB, kGroup>([&](int i) { return w_mu[(zb * RB + i) * kTileF4 + lane]; },
-                                  [&](int i, f32x4 w) {
-                                      if (i & 1) acc1 = tile_mma(acc1, w, h[i]);
-                                      else acc0 = tile_mma(acc0, w, h[i]);
-                                  });
-            mu[zb] = acc0 + acc1;
+            for (int zb = 0; zb < ZB; ++zb) {
+                Acc4 acc;
+                acc.init(bias4(lb_mu, zb));
+                for_tile_groups<RB, GI>([&](int i) { return w_mu[(zb * RB + i) * kTileF4 + lane]; },
+                                        [&](int g, const f32x4(&tl)[GI]) { mma_narrow<GI>(acc, tl, &h[g * GI]); });
+                mu[zb] = acc.sum();
+            }
         }
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) {
-            f32x4 acc = bias4(lb_sig, zb);
+            Acc4 acc;
+            acc.init(bias4(lb_sig, zb));
 #pragma unroll
-            for (int ib = 0; ib < ZB; ++ib) acc = tile_mma(acc, w_sig[(zb * ZB + ib) * kTileF4 + lane], mu[ib]);
-            z[zb] = mu[zb] + softplus4(acc) * eps[zb];
+            for (int ib = 0; ib < ZB; ++ib) {
+                const f32x4 tl[1] = {w_sig[(zb * ZB + ib) * kTileF4 + lane]};
+                mma_narrow<1>(acc, tl, &mu[ib]);
+            }
+            z[zb] = mu[zb] + softplus4(acc.sum()) * eps[zb];
             eps[zb] = eps_next[zb];
         }
     }
     auto store_z = [&](float *dst, int ld, int zb, f32x4 v) {
-        if (!dst || !live) return;
+        if (!DBG || !dst || !live) return;
         float *p = dst + (size_t)smp * ld + zb * 16 + 4 * q;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
@@ -256,45 +305,58 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     for (int zb = 0; zb < ZB; ++zb) store_z(a.z_last, Z, zb, z[zb]);
 
     // ---- streamed part: transition, then emission --------------------------------
-    WeightStream<HB> ws;
+    constexpr int CH = chain_chunk_tiles(HB);  // tiles per chunk
+    constexpr int K2 = CH / (2 * HB);          // 16-worker blocks per chunk in the fused mean/scale-hidden pass
+    constexpr int U3 = 2 * K2;                 // 16-worker blocks per chunk in the scale pass
+    constexpr int GH = HB < 4 ? HB : 4;
+    static_assert(ZB * HB <= CH && ZB * ZB <= CH, "a transition layer fits one chunk");
+    WeightStream<CH> ws;
     ws.start(reinterpret_cast<const f32x4 *>(a.stream_tiles), sbuf, a.stream_chunks, tid);
-    constexpr int kSmall = (ZB * ZB + HB - 1) / HB;  // chunks holding a Z x Z layer
 
-    // out = W1 x + b1 for a Z -> H layer streamed as ZB chunks (one per input block)
+    // out = W x + b for a Z -> H layer: one chunk, tiles [ib][ob]
     auto wide_from_z = [&](f32x4(&out)[HB], const float *tab, const f32x4(&x)[ZB]) {
 #pragma unroll
         for (int ob = 0; ob < HB; ++ob) out[ob] = bias4(tab, ob);
-#pragma unroll
-        for (int ib = 0; ib < ZB; ++ib) {
-            for_tiles<HB, kGroup>([&](int i) { return ws.tile(i, lane); },
-                                  [&](int i, f32x4 w) { out[i] = tile_mma(out[i], w, x[ib]); });
-            ws.advance();
-        }
-    };
-    // one 16-feature output block of an H -> . layer streamed as one chunk
-    auto narrow_from_h = [&](f32x4 b, const f32x4(&x)[HB]) {
-        f32x4 acc0 = b, acc1 = splat(0.f);
-        for_tiles<HB, kGroup>([&](int i) { return ws.tile(i, lane); },
-                              [&](int i, f32x4 w) {
-                                  if (i & 1) acc1 = tile_mma(acc1, w, x[i]);
-                                  else acc0 = tile_mma(acc0, w, x[i]);
-                              });
+        for_tile_groups<ZB * HB, GH>([&](int i) { return ws.tile(i, lane); },
+                                     [&](int g, const f32x4(&tl)[GH]) {
+                                         const int idx = g * GH;
+                                         mma_wide<GH>(&out[idx % HB], tl, x[idx / HB]);
+                                     });
         ws.advance();
-        return acc0 + acc1;
     };
-    // Z -> Z layer, tiles [ob][ib] packed into kSmall chunks
+    // one 16-feature output block from HB tiles starting at tile `base` of the current chunk;
+    // `ride` is vector work of an earlier block that may be interleaved with the first group
+    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB], auto &&ride) {
+        Acc4 acc;
+        acc.init(b);
+        for_tile_groups<HB, GH>([&](int i) { return ws.tile(base + i, lane); },
+                                [&](int g, const f32x4(&tl)[GH]) {
+                                    if (g == 0) ride();
+                                    mma_narrow<GH>(acc, tl, &x[g * GH]);
+                                });
+        return acc.sum();
+    };
+    auto nothing = [] {};
+    // out = W h + b for an H -> Z layer: one chunk, tiles [zb][ib]
+    auto narrow_from_h = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[HB]) {
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) out[zb] = narrow_block(zb * HB, bias4(tab, zb), x, nothing);
+        ws.advance();
+    };
+    // Z -> Z layer: one chunk, tiles [ob][ib]
     auto small_layer = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[ZB]) {
 #pragma unroll
-        for (int ob = 0; ob < ZB; ++ob) out[ob] = bias4(tab, ob);
+        for (int ob = 0; ob < ZB; ++ob) {
+            Acc4 acc;
+            acc.init(bias4(tab, ob));
 #pragma unroll
-        for (int c = 0; c < kSmall; ++c) {
-#pragma unroll
-            for (int i = 0; i < HB; ++i) {
-                const int idx = c * HB + i;
-                if (idx < ZB * ZB) out[idx / ZB] = tile_mma(out[idx / ZB], ws.tile(i, lane), x[idx % ZB]);
+            for (int ib = 0; ib < ZB; ++ib) {
+                const f32x4 tl[1] = {ws.tile(ob * ZB + ib, lane)};
+                mma_narrow<1>(acc, tl, &x[ib]);
             }
-            ws.advance();
+            out[ob] = acc.sum();
         }
+        ws.advance();
     };
 
     f32x4 zn[ZB];
@@ -303,18 +365,16 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         wide_from_z(hid, lb_gate1, z);
 #pragma unroll
         for (int ob = 0; ob < HB; ++ob) hid[ob] = relu4(hid[ob]);
-#pragma unroll
-        for (int zb = 0; zb < ZB; ++zb)
-            g[zb] = map4(narrow_from_h(bias4(lb_gate2, zb), hid), [](float v) { return fast_sigmoid(v); });
+        narrow_from_h(g, lb_gate2, hid);
         wide_from_z(hid, lb_prop1, z);
 #pragma unroll
         for (int ob = 0; ob < HB; ++ob) hid[ob] = relu4(hid[ob]);
-#pragma unroll
-        for (int zb = 0; zb < ZB; ++zb) prop[zb] = narrow_from_h(bias4(lb_prop2, zb), hid);
+        narrow_from_h(prop, lb_prop2, hid);
         small_layer(lin, lb_lin, z);
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) {
-            G[zb] = (splat(1.f) - g[zb]) * lin[zb] + g[zb] * prop[zb];
+            const f32x4 gate = map4(g[zb], [](float v) { return fast_sigmoid(v); });
+            G[zb] = (splat(1.f) - gate) * lin[zb] + gate * prop[zb];
             rG[zb] = relu4(G[zb]);
         }
         small_layer(pre, lb_tscale, rG);
@@ -329,53 +389,75 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         }
     }
 
-    // emission
+    // emission: hidden layer of the mean
     f32x4 h1[HB];
     wide_from_z(h1, lb_emean1, zn);
     if (a.emit_mean_act) {
 #pragma unroll
         for (int ob = 0; ob < HB; ++ob) h1[ob] = relu4(h1[ob]);
     }
+    // mean, 16 workers at a time, each block folded into the scale network's hidden layer at once
     f32x4 h2[HB];
 #pragma unroll
     for (int ob = 0; ob < HB; ++ob) h2[ob] = bias4(lb_escale1, ob);
     const int NB = a.NB;
     float *mean_row = a.mean + (size_t)sc * a.ld_mean + 4 * q;
-    for (int nb = 0; nb < NB; ++nb) {
-        const f32x4 m = narrow_from_h(bias4(lb_emean2, nb), h1);
-        if (live) *reinterpret_cast<f32x4 *>(mean_row + nb * 16) = m;
-        for_tiles<HB, kGroup>([&](int i) { return ws.tile(i, lane); },
-                              [&](int i, f32x4 w) { h2[i] = tile_mma(h2[i], w, m); });
+    for (int c = 0; c < (NB + K2 - 1) / K2; ++c) {
+#pragma unroll
+        for (int u = 0; u < K2; ++u) {
+            const int nb_raw = c * K2 + u;
+            const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, nothing kept
+            {
+                const f32x4 m = narrow_block(u * 2 * HB, bias4(lb_emean2, nb), h1, nothing);
+                // lanes past the last sample repeat sample S-1 exactly, so their store is a harmless
+                // duplicate; blocks past the end go to the sink
+                float *dst = nb_raw < NB ? mean_row + nb * 16 : a.sink + tid * 4;
+                *reinterpret_cast<f32x4 *>(dst) = m;
+                for_tile_groups<HB, GH>([&](int i) { return ws.tile(u * 2 * HB + HB + i, lane); },
+                                        [&](int g, const f32x4(&tl)[GH]) { mma_wide<GH>(&h2[g * GH], tl, m); });
+            }
+        }
         ws.advance();
     }
 #pragma unroll
     for (int ob = 0; ob < HB; ++ob) h2[ob] = relu4(h2[ob]);
+
+    // scale, draw, back to seconds
     const float scale = a.ctl->scale;
-    const bool vec_ok = (N & 3) == 0;
-    for (int nb = 0; nb < NB; ++nb) {
+    float *sink = a.sink + tid * 4;
+    auto load_eps_x = [&](int nb) {
         const int n0 = nb * 16 + 4 * q;
-        const f32x4 m = *reinterpret_cast<const f32x4 *>(mean_row + nb * 16);
         f32x4 e = splat(0.f);
-        const float *ep = a.eps_x + (size_t)sc * N + n0;
-        if (vec_ok) {
-            if (n0 < N) e = *reinterpret_cast<const f32x4 *>(ep);
+        if constexpr (VEC) {
+            const int nc = n0 < N ? n0 : N - 4;
+            e = *reinterpret_cast<const f32x4 *>(a.eps_x + (size_t)sc * N + nc);
         } else {
+            const float *ep = a.eps_x + (size_t)sc * N + n0;
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 if (n0 + v < N) e[v] = ep[v];
         }
-        const f32x4 sd = softplus4(narrow_from_h(bias4(lb_escale2, nb), h2));
+        return e;
+    };
+    auto load_mean = [&](int nb) { return *reinterpret_cast<const f32x4 *>(mean_row + nb * 16); };
+    auto emit = [&](int nb, f32x4 pre, f32x4 m, f32x4 e) {  // softplus, draw, store
+        const int n0 = nb * 16 + 4 * q;
+        const f32x4 sd = softplus4(pre);
         const f32x4 x = (m + sd * e) * scale;
-        if (live) {
-            float *xp = a.out_samples + (size_t)smp * N + n0;
-            if (vec_ok) {
-                if (n0 < N) *reinterpret_cast<f32x4 *>(xp) = x;
-            } else {
+        if constexpr (VEC) {
+            // columns past N and the not-yet-started pipeline slot (nb < 0) go to the sink
+            float *xp = (nb >= 0 && n0 < N) ? a.out_samples + (size_t)sc * N + n0 : sink;
+            *reinterpret_cast<f32x4 *>(xp) = x;
+        } else {
+            if (live && nb >= 0) {
+                float *xp = a.out_samples + (size_t)smp * N + n0;
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (n0 + v < N) xp[v] = x[v];
             }
-            if (a.out_mean_dbg || a.out_sd_dbg) {
+        }
+        if constexpr (DBG) {
+            if (live && nb >= 0) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     if (n0 + v >= N) continue;
@@ -384,31 +466,73 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
                 }
             }
         }
+    };
+    // The noise and the stored mean of a chunk's blocks are requested one chunk ahead, right
+    // after the weight stream's own request (loads return in order: nothing waits on a request
+    // younger than one chunk).  Each block's epilogue rides on the next block's first matrix
+    // instructions.
+    f32x4 e_next[U3], m_next[U3];
+#pragma unroll
+    for (int u = 0; u < U3; ++u) {
+        e_next[u] = load_eps_x(u < NB ? u : NB - 1);
+        m_next[u] = load_mean(u < NB ? u : NB - 1);
     }
+    f32x4 pre_p = splat(0.f), m_p = splat(0.f), e_p = splat(0.f);
+    int nb_p = -1;  // nothing pending
+    for (int c = 0; c < (NB + U3 - 1) / U3; ++c) {
+        f32x4 e[U3], m[U3];
+#pragma unroll
+        for (int u = 0; u < U3; ++u) { e[u] = e_next[u]; m[u] = m_next[u]; }
+#pragma unroll
+        for (int u = 0; u < U3; ++u) {
+            const int nn = (c + 1) * U3 + u;
+            e_next[u] = load_eps_x(nn < NB ? nn : NB - 1);
+            m_next[u] = load_mean(nn < NB ? nn : NB - 1);
+        }
+#pragma unroll
+        for (int u = 0; u < U3; ++u) {
+            const int nb_raw = c * U3 + u;
+            const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, result goes to the sink
+            const f32x4 pre = narrow_block(u * HB, bias4(lb_escale2, nb), h2, [&] { emit(nb_p, pre_p, m_p, e_p); });
+            pre_p = pre; m_p = m[u]; e_p = e[u]; nb_p = nb_raw < NB ? nb_raw : -1;
+        }
+        ws.advance();
+    }
+    emit(nb_p, pre_p, m_p, e_p);
 }
 
 template <int ZB, int RB, int HB>
 size_t chain_lds_bytes(int L, int N) {
     const size_t nb16 = (size_t)((N + 15) / 16) * 16;
     const size_t bias_floats = RB * 16 + 6 * ZB * 16 + 4 * HB * 16 + 2 * nb16;
-    return (size_t)(2 * RB * ZB + ZB * ZB + 2 * HB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
+    return (size_t)(2 * RB * ZB + ZB * ZB + 2 * chain_chunk_tiles(HB)) * kTileF4 * 16 +
+           ((size_t)L * RB * 16 + bias_floats) * 4;
+}
+
+template <int ZB, int RB, int HB, bool VEC, bool DBG>
+int launch_variant(const ChainArgs &a, size_t lds, hipStream_t stream) {
+    static size_t raised = 0;  // largest LDS size the attribute has been set to
+    if (lds > raised) {
+        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_chain<ZB, RB, HB, VEC, DBG>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = lds;
+    }
+    const int per_block = (kThreads / 64) * 16;
+    const dim3 grid((a.S + per_block - 1) / per_block);
+    hipLaunchKernelGGL((sample_chain<ZB, RB, HB, VEC, DBG>), grid, dim3(kThreads), lds, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
 }
 
 template <int ZB, int RB, int HB>
 int launch_one(const ChainArgs &a, hipStream_t stream) {
     const size_t lds = chain_lds_bytes<ZB, RB, HB>(a.L, a.N);
     if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
-    static size_t raised = 0;  // largest LDS size the attribute has been set to
-    if (lds > raised) {
-        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_chain<ZB, RB, HB>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        raised = lds;
-    }
-    const int per_block = (kThreads / 64) * 16;
-    const dim3 grid((a.S + per_block - 1) / per_block);
-    hipLaunchKernelGGL((sample_chain<ZB, RB, HB>), grid, dim3(kThreads), lds, stream, a);
-    DKF_HIP_TRY(hipGetLastError());
-    return DKF_OK;
+    const bool vec = (a.N & 3) == 0 && (a.Z & 3) == 0 && a.N >= 4 && a.Z >= 4;
+    const bool dbg = a.z_last || a.z_next_dbg || a.out_mean_dbg || a.out_sd_dbg;
+    if (vec) return dbg ? launch_variant<ZB, RB, HB, true, true>(a, lds, stream)
+                        : launch_variant<ZB, RB, HB, true, false>(a, lds, stream);
+    return launch_variant<ZB, RB, HB, false, true>(a, lds, stream);
 }
 
 }  // namespace

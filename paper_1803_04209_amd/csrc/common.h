@@ -141,7 +141,7 @@ struct ChainArgs {
     const float *ctx_f, *ctx_b;  // [L][Rp]
     int Rp;
     const float *guide_tiles;    // comb [RB][ZB], mu [ZB][RB], sig [ZB][ZB] tiles of 64 float4
-    const float *stream_tiles;   // chunks of HB tiles in consumption order (see pack_chain in api.hip)
+    const float *stream_tiles;   // chunks of chain_chunk_tiles(HB) tiles in consumption order (pack_chain, api.hip)
     int stream_chunks;
     const float *z0;
     const float *b_comb, *b_mu, *b_sig, *b_gate1, *b_gate2, *b_prop1, *b_prop2, *b_lin, *b_tscale;
@@ -150,10 +150,13 @@ struct ChainArgs {
     float *mean;  // [S][ld_mean] scratch, also the emission mean for inspection
     int ld_mean;
     float *out_samples;  // [S][N]
+    float *sink;         // >= 4 KiB of scratch that masked-off lanes may write to
     float *z_last, *z_next_dbg, *out_mean_dbg, *out_sd_dbg;  // optional
     int S, L, Z, R, H, N, NB;
     int emit_mean_act;
 };
+// tiles (16 x 16 weights, 1 KiB) per streamed chunk for a hidden width of hb 16-blocks
+__host__ __device__ constexpr int chain_chunk_tiles(int hb) { return hb >= 8 ? 32 : 4 * hb; }
 bool chain_supported(int Z, int R, int H, int L, int N);
 int launch_chain(const ChainArgs &a, hipStream_t stream);
 

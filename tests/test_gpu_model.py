@@ -79,6 +79,22 @@ def test_unaligned_sizes_every_stage(api, cfg, act):
     g.close()
 
 
+@pytest.mark.parametrize("cfg", [
+    custom(N=20, L=3, Z=12, H=32, R=32, S=50), custom(N=18, L=2, Z=10, H=31, R=30, S=70),
+    custom(N=100, L=4, Z=16, H=128, R=128, S=130), custom(N=1000, L=3, Z=32, H=256, R=256, S=40),
+    custom(N=36, L=5, Z=8, H=20, R=24, S=16)], ids=["vec-tail", "scalar", "medium-like", "contended-like", "one-wave"])
+@pytest.mark.parametrize("act", [0, 1])
+def test_register_chained_sampler_tails(api, cfg, act):
+    """Sizes that take the fused sampler kernel with ragged worker blocks, pad features and partial waves."""
+    g, o, _ = make_pair(api, cfg, act=act, std=0.3)
+    compare_stages(api, cfg, g, o)
+    eq, ez, ex = synth.make_noise(cfg)
+    x_plain = g.sample_runtimes(*cuda(eq, ez, ex))  # variant without the per-stage outputs
+    xo = o.sample_runtimes(eq, ez, ex)
+    assert rel_err(x_plain.cpu().numpy(), xo) <= TOL
+    g.close()
+
+
 def test_tiny_preset_every_decision_position(api):
     cfg = synth.CONFIGS["tiny"]
     g, o, tr = make_pair(api, cfg)
