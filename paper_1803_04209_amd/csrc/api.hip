@@ -71,7 +71,7 @@ struct dkf_model {
     PackedLayer comb, mu, sig, gate1, gate2, prop1, prop2, lin, tscale;
     PackedLayer emean1, emean2, escale1, escale2;
     bool use_chain = false;  // sizes covered by the register-chained sampler
-    const float *chain_guide = nullptr, *chain_stream = nullptr;
+    const float *chain_guide = nullptr, *chain_stream = nullptr, *chain_bias = nullptr;
     int chain_chunks = 0;
 
     // filter state
@@ -179,6 +179,8 @@ void append_tile(std::vector<float> &dst, const float *w, int n_out, int k_in, i
 
 struct RawLayers {
     const float *comb, *mu, *sig, *gate1, *gate2, *prop1, *prop2, *lin, *tscale, *emean1, *emean2, *escale1, *escale2;
+    const float *b_comb, *b_mu, *b_sig, *b_gate1, *b_gate2, *b_prop1, *b_prop2, *b_lin, *b_tscale, *b_emean1,
+        *b_emean2, *b_escale1, *b_escale2;
 };
 
 // Tile streams of the chained sampler.  Guide: comb [ob group][ib][ob in group], mu [zb][ib], sig [zb][ib].
@@ -231,6 +233,18 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
         }
     if (s.size() % chunk != 0) return DKF_EINVAL;
     m->chain_chunks = (int)(s.size() / chunk);
+    std::vector<float> bt;
+    auto add_bias = [&](const float *b, int n, int blocks) {
+        const size_t base = bt.size();
+        bt.resize(base + (size_t)blocks * 16, 0.f);
+        for (int i = 0; i < n; ++i) bt[base + i] = b[i];
+    };
+    add_bias(r.b_comb, R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
+    add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
+    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(r.b_escale1, H, HB);
+    add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);
+    int rcb = upload(m, bt.data(), bt.size(), &m->chain_bias);
+    if (rcb != DKF_OK) return rcb;
     int rc = upload(m, g.data(), g.size(), &m->chain_guide);
     if (rc != DKF_OK) return rc;
     return upload(m, s.data(), s.size(), &m->chain_stream);
@@ -304,11 +318,7 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
     c.guide_tiles = m->chain_guide; c.stream_tiles = m->chain_stream; c.stream_chunks = m->chain_chunks;
     c.z0 = m->z0;
-    c.b_comb = m->comb.bias; c.b_mu = m->mu.bias; c.b_sig = m->sig.bias;
-    c.b_gate1 = m->gate1.bias; c.b_gate2 = m->gate2.bias; c.b_prop1 = m->prop1.bias; c.b_prop2 = m->prop2.bias;
-    c.b_lin = m->lin.bias; c.b_tscale = m->tscale.bias;
-    c.b_emean1 = m->emean1.bias; c.b_emean2 = m->emean2.bias; c.b_escale1 = m->escale1.bias;
-    c.b_escale2 = m->escale2.bias;
+    c.bias_table = m->chain_bias;
     c.eps_q = eps_q; c.eps_z = eps_z; c.eps_x = eps_x;
     c.mean = m->mean; c.ld_mean = m->Np;
     c.out_samples = out_samples;
@@ -467,22 +477,22 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     RawLayers raw{};
     {
         const float *w, *b;
-        w = take(sR * sZ); b = take(sR); DKF_CHECK(pack_layer(m, w, b, R, Z, &m->comb)); raw.comb = w;
-        w = take(sZ * sR); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, R, &m->mu)); raw.mu = w;
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->sig)); raw.sig = w;
+        w = take(sR * sZ); b = take(sR); DKF_CHECK(pack_layer(m, w, b, R, Z, &m->comb)); raw.comb = w; raw.b_comb = b;
+        w = take(sZ * sR); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, R, &m->mu)); raw.mu = w; raw.b_mu = b;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->sig)); raw.sig = w; raw.b_sig = b;
         std::vector<float> z0(m->Zp, 0.f);
         std::memcpy(z0.data(), take(sZ), sizeof(float) * sZ);
         DKF_CHECK(upload(m, z0.data(), z0.size(), &m->z0));
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->gate1)); raw.gate1 = w;
-        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->gate2)); raw.gate2 = w;
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->prop1)); raw.prop1 = w;
-        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->prop2)); raw.prop2 = w;
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->lin)); raw.lin = w;
-        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->tscale)); raw.tscale = w;
-        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->emean1)); raw.emean1 = w;
-        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->emean2)); raw.emean2 = w;
-        w = take(sH * sN); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, N, &m->escale1)); raw.escale1 = w;
-        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2)); raw.escale2 = w;
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->gate1)); raw.gate1 = w; raw.b_gate1 = b;
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->gate2)); raw.gate2 = w; raw.b_gate2 = b;
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->prop1)); raw.prop1 = w; raw.b_prop1 = b;
+        w = take(sZ * sH); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, H, &m->prop2)); raw.prop2 = w; raw.b_prop2 = b;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->lin)); raw.lin = w; raw.b_lin = b;
+        w = take(sZ * sZ); b = take(sZ); DKF_CHECK(pack_layer(m, w, b, Z, Z, &m->tscale)); raw.tscale = w; raw.b_tscale = b;
+        w = take(sH * sZ); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, Z, &m->emean1)); raw.emean1 = w; raw.b_emean1 = b;
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->emean2)); raw.emean2 = w; raw.b_emean2 = b;
+        w = take(sH * sN); b = take(sH); DKF_CHECK(pack_layer(m, w, b, H, N, &m->escale1)); raw.escale1 = w; raw.b_escale1 = b;
+        w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2)); raw.escale2 = w; raw.b_escale2 = b;
     }
 
     m->use_chain = chain_supported(Z, R, H, L, N);

@@ -146,10 +146,6 @@ __device__ __forceinline__ void mma_narrow(Acc4 &acc, const f32x4 (&t)[GROUP], c
 }
 
 __device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
-__device__ __forceinline__ float fast_tanh(float v) {
-    // 1 - 2 / (exp(2v) + 1) with the hardware exp2 and reciprocal
-    return 1.0f - 2.0f * fast_rcp(__expf(2.0f * v) + 1.0f);
-}
 __device__ __forceinline__ float fast_softplus(float v) {
     return fmaxf(v, 0.f) + __logf(1.0f + __expf(-fabsf(v)));
 }
@@ -194,18 +190,19 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 #pragma unroll 8
         for (int i = 0; i < kCopies; ++i) gw[tid + i * kThreads] = src[tid + i * kThreads];
         for (int i = tid + kCopies * kThreads; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
-        for (int i = tid; i < a.L * R16; i += kThreads) {
-            const int t = i / R16, r = i % R16;
-            ctx[i] = a.ctx_f[(size_t)t * a.Rp + r] + a.ctx_b[(size_t)t * a.Rp + r];
+        // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
+        // with tanh written as 1 - 2 r
+        const int n4 = a.L * R16 / 4;
+        for (int i = tid; i < n4; i += kThreads) {
+            const int t = (i * 4) / R16, r = (i * 4) % R16;
+            const f32x4 f = *reinterpret_cast<const f32x4 *>(a.ctx_f + (size_t)t * a.Rp + r);
+            const f32x4 b = *reinterpret_cast<const f32x4 *>(a.ctx_b + (size_t)t * a.Rp + r);
+            reinterpret_cast<f32x4 *>(ctx)[i] = (f + b + splat(1.0f)) * (1.0f / 3.0f);
         }
-        auto copy = [&](float *dst, const float *srcb, int n) {
-            for (int i = tid; i < n; i += kThreads) dst[i] = srcb[i];
-        };
-        copy(lb_comb, a.b_comb, R16); copy(lb_mu, a.b_mu, Z16); copy(lb_sig, a.b_sig, Z16);
-        copy(lb_gate1, a.b_gate1, H16); copy(lb_gate2, a.b_gate2, Z16); copy(lb_prop1, a.b_prop1, H16);
-        copy(lb_prop2, a.b_prop2, Z16); copy(lb_lin, a.b_lin, Z16); copy(lb_tscale, a.b_tscale, Z16);
-        copy(lb_emean1, a.b_emean1, H16); copy(lb_escale1, a.b_escale1, H16);
-        copy(lb_emean2, a.b_emean2, N16); copy(lb_escale2, a.b_escale2, N16);
+        // all biases: one table, already in LDS order
+        const int b4 = (R16 + 6 * Z16 + 4 * H16 + 2 * N16) / 4;
+        const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(a.bias_table);
+        for (int i = tid; i < b4; i += kThreads) reinterpret_cast<f32x4 *>(bias)[i] = bsrc[i];
     }
     __syncthreads();
     auto bias4 = [&](const float *tab, int blk) { return *reinterpret_cast<const f32x4 *>(tab + blk * 16 + 4 * q); };
@@ -251,9 +248,10 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
             // comb tiles are stored [group of GO output blocks][input block][block in group]
             constexpr int GO = RB < 4 ? RB : 4;
             const float *ctx_t = ctx + t * R16 + 4 * q;
-            auto finish = [&](int ob) {  // h_out = (tanh(.) + h_left + h_right) / 3
-                const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + ob * 16);
-                h[ob] = (map4(h[ob], [](float v) { return fast_tanh(v); }) + c) * (1.0f / 3.0f);
+            auto finish = [&](int ob) {  // h_out = (tanh(v) + h_left + h_right) / 3, tanh(v) = 1 - 2 / (exp(2v) + 1)
+                const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + ob * 16);  // (1 + h_left + h_right) / 3
+                const f32x4 r = map4(h[ob], [](float v) { return fast_rcp(__expf(2.0f * v) + 1.0f); });
+                h[ob] = r * (-2.0f / 3.0f) + c;
             };
 #pragma unroll
             for (int ob = 0; ob < RB; ++ob) h[ob] = bias4(lb_comb, ob);

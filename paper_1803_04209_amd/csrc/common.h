@@ -144,8 +144,9 @@ struct ChainArgs {
     const float *stream_tiles;   // chunks of chain_chunk_tiles(HB) tiles in consumption order (pack_chain, api.hip)
     int stream_chunks;
     const float *z0;
-    const float *b_comb, *b_mu, *b_sig, *b_gate1, *b_gate2, *b_prop1, *b_prop2, *b_lin, *b_tscale;
-    const float *b_emean1, *b_emean2, *b_escale1, *b_escale2;  // zero padded to a multiple of 32
+    // biases, each zero padded to whole 16-blocks, in the order comb, mu, sig, gate1, gate2, prop1,
+    // prop2, lin, tscale, emean1, escale1, emean2, escale2
+    const float *bias_table;
     const float *eps_q, *eps_z, *eps_x;
     float *mean;  // [S][ld_mean] scratch, also the emission mean for inspection
     int ld_mean;
