@@ -166,13 +166,14 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes);
  * captured graph).  Stage ids: 0 filter (projection + RNN chains), 1 guide
  * chain + transition, 2 emission mean hidden layer, 3 emission mean, 4
  * emission scale hidden layer, 5 emission scale + draw, 6 row sort + rank
- * sums, 7 rank means + argmax.
+ * sums, 7 rank means + argmax, 8 the fused sampler (stages 1-5 in one kernel, used
+ * for the layer sizes it is built for; then stages 1-5 record nothing).
  * dkf_timing_enable(mask) starts recording for the stages in the bit mask (0
  * stops).  dkf_timing_read synchronises the device and returns, for one
  * stage, the number of launches recorded and their summed duration in
  * milliseconds, then clears that stage's records.  At most 4096 launches per
  * stage are kept between reads. */
-#define DKF_NUM_STAGES 8
+#define DKF_NUM_STAGES 9
 int dkf_timing_enable(uint32_t stage_mask);
 int dkf_timing_read(int32_t stage, int32_t *launches, double *total_ms);
 

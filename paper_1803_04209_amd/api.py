@@ -21,9 +21,9 @@ LIB_PATH = PKG / "libcutoff_dkf.so"
 DKF_OK, DKF_WARMUP, CUTOFF_NO_ELIGIBLE = 0, 1, 2
 DKF_EINVAL, DKF_ENOTREADY, DKF_EBADOBS, DKF_EHIP, DKF_ENOMEM, DKF_EBLOB, DKF_EUNSUPPORTED = -1, -2, -3, -4, -5, -6, -7
 DKF_DTYPE_F32, DKF_DTYPE_BF16 = 0, 1
-DKF_NUM_STAGES = 8
+DKF_NUM_STAGES = 9
 STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_scale_hidden",
-               "emit_scale_draw", "sort_rank_sums", "means_argmax"]
+               "emit_scale_draw", "sort_rank_sums", "means_argmax", "sampler_fused"]
 
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",

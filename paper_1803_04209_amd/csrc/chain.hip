@@ -544,7 +544,7 @@ bool chain_supported(int Z, int R, int H, int L, int N) {
 }
 
 int launch_chain(const ChainArgs &a, hipStream_t stream) {
-    StageTimer timer(kStageGuide, stream);
+    StageTimer timer(kStageSampler, stream);
     const int zb = (a.Z + 15) / 16, rb = (a.R + 15) / 16, hb = (a.H + 15) / 16;
     if (zb == 1 && rb == 2 && hb == 2) return launch_one<1, 2, 2>(a, stream);
     if (zb == 1 && rb == 8 && hb == 8) return launch_one<1, 8, 8>(a, stream);

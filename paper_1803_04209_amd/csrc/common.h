@@ -33,6 +33,7 @@ enum Stage : int {
     kStageEmitScaleDraw = 5,
     kStageSort = 6,
     kStageArgmax = 7,
+    kStageSampler = 8,  // guide + transition + emission in the register-chained kernel
 };
 
 // Records a start event in the constructor and a stop event in the destructor
