@@ -134,22 +134,37 @@ int upload(dkf_model *m, const float *src, size_t n, const float **out) {
     return DKF_OK;
 }
 
+// fp32 -> bf16, round to nearest even (the rounding v_cvt_pk_bf16_f32 applies on the device)
+uint16_t to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
 // Re-tile W[n_out][k_in] (row-major) for the MFMA B operand; see PackedLayer.
 int pack_layer(dkf_model *m, const float *w, const float *b, int n_out, int k_in, PackedLayer *out) {
+    const bool bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
     PackedLayer p;
     p.n_out = n_out;
     p.k_in = k_in;
     p.n_blocks = (n_out + 31) / 32;
-    p.k_groups = round_up(k_in, 32) / 8;
-    std::vector<float> tiles((size_t)p.n_blocks * p.k_groups * 256, 0.f);
+    p.k_groups = bf16 ? round_up(k_in, 64) / 16 : round_up(k_in, 32) / 8;
+    std::vector<float> tiles((size_t)p.n_blocks * p.k_groups * 256, 0.f);  // 64 lanes x 16 bytes per k-group
+    uint16_t *half = reinterpret_cast<uint16_t *>(tiles.data());
+    const int per_lane = bf16 ? 8 : 4;
     for (int nb = 0; nb < p.n_blocks; ++nb)
         for (int kg = 0; kg < p.k_groups; ++kg)
             for (int lane = 0; lane < 64; ++lane) {
                 const int n = nb * 32 + (lane & 31);
                 if (n >= n_out) continue;
-                for (int j = 0; j < 4; ++j) {
-                    const int k = kg * 8 + (lane >> 5) * 4 + j;
-                    if (k < k_in) tiles[(((size_t)nb * p.k_groups + kg) * 64 + lane) * 4 + j] = w[(size_t)n * k_in + k];
+                const size_t entry = ((size_t)nb * p.k_groups + kg) * 64 + lane;
+                for (int j = 0; j < per_lane; ++j) {
+                    const int k = kg * 2 * per_lane + (lane >> 5) * per_lane + j;
+                    if (k >= k_in) continue;
+                    if (bf16) half[entry * 8 + j] = to_bf16(w[(size_t)n * k_in + k]);
+                    else tiles[entry * 4 + j] = w[(size_t)n * k_in + k];
                 }
             }
     std::vector<float> bias((size_t)p.n_blocks * 32, 0.f);
@@ -349,11 +364,13 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
     g.z_next_dbg = st ? st->z_next : nullptr;
     g.z_next = m->z_next;
     g.S = S; g.L = m->L; g.Z = m->Z; g.Zp = m->Zp; g.R = m->R; g.Rp = m->Rp; g.H = m->H; g.Hp = m->Hp;
+    g.bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
     int rc = launch_guide(g, stream);
     if (rc != DKF_OK) return rc;
 
     GemmArgs e{};
     e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
+    e.bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
     // hidden layer of the mean
     e.A = m->z_next; e.lda = m->Zp; e.layer = m->emean1;
     e.epilogue = m->cfg.emit_mean_act ? kEpiBiasRelu : kEpiBias;
@@ -442,7 +459,6 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (!config_ok(cfg) || !blob) return DKF_EINVAL;
     if (cfg->n_workers > 4096 || cfg->z_dim > 1024 || cfg->hidden > 1024 || cfg->rnn_dim > 1024 || cfg->lag > 256)
         return DKF_EUNSUPPORTED;
-    if (cfg->mlp_dtype != DKF_DTYPE_F32) return DKF_EUNSUPPORTED;
     if (blob_bytes != dkf_blob_bytes(cfg)) return DKF_EBLOB;
     int32_t head[8];
     std::memcpy(head, blob, sizeof head);
@@ -455,13 +471,15 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     m->cfg = *cfg;
     const int N = m->N = cfg->n_workers, L = m->L = cfg->lag, Z = m->Z = cfg->z_dim, H = m->H = cfg->hidden,
               R = m->R = cfg->rnn_dim;
-    m->Np = round_up(N, 32); m->Zp = round_up(Z, 32); m->Hp = round_up(H, 32); m->Rp = round_up(R, 32);
+    const bool bf16 = cfg->mlp_dtype == DKF_DTYPE_BF16;
+    const int pad = bf16 ? 64 : 32;  // activation row padding = K granularity of the matrix kernels
+    m->Np = round_up(N, pad); m->Zp = round_up(Z, pad); m->Hp = round_up(H, pad); m->Rp = round_up(R, pad);
     const int Smax = cfg->max_samples;
     int rc = DKF_OK;
 #define DKF_CHECK(expr) do { rc = (expr); if (rc != DKF_OK) { dkf_free(m); return rc; } } while (0)
 #define DKF_CHECK_HIP(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { set_last_hip_error(e_); dkf_free(m); return DKF_EHIP; } } while (0)
 
-    DKF_CHECK(guide_prepare(m->Zp, m->Rp, m->Hp));
+    DKF_CHECK(guide_prepare(m->Zp, m->Rp, m->Hp, bf16));
 
     const float *p = reinterpret_cast<const float *>(static_cast<const char *>(blob) + 32);
     auto take = [&](size_t n) { const float *q = p; p += n; return q; };
@@ -495,7 +513,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
         w = take(sN * sH); b = take(sN); DKF_CHECK(pack_layer(m, w, b, N, H, &m->escale2)); raw.escale2 = w; raw.b_escale2 = b;
     }
 
-    m->use_chain = chain_supported(Z, R, H, L, N);
+    m->use_chain = !bf16 && chain_supported(Z, R, H, L, N);
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
 
     void *q = nullptr;

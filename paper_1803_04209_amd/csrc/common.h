@@ -65,15 +65,19 @@ struct Control {
     uint32_t seed_hi;
 };
 
-// Weights of one dense layer re-tiled for v_mfma_f32_32x32x2_f32:
-// tiles[nb][kg][lane][4] with n = nb*32 + lane%32, k = kg*8 + (lane/32)*4 + j;
-// zero outside [n_out) x [k_in).  bias is padded with zeros to n_blocks*32.
+// Weights of one dense layer re-tiled as the B operand of the 32x32 matrix instructions,
+// 16 bytes per lane and k-group, zero outside [n_out) x [k_in):
+//   fp32 (v_mfma_f32_32x32x2_f32):   tiles[nb][kg][lane][4 floats], n = nb*32 + lane%32,
+//                                    k = kg*8 + (lane/32)*4 + j;   k_groups = ceil32(k_in) / 8
+//   bf16 (v_mfma_f32_32x32x16_bf16): tiles[nb][kg][lane][8 bf16],  k = kg*16 + (lane/32)*8 + j;
+//                                    k_groups = ceil64(k_in) / 16
+// bias (fp32) is padded with zeros to n_blocks*32.
 struct PackedLayer {
-    const float *tiles = nullptr;
+    const float *tiles = nullptr;  // raw 16-byte entries
     const float *bias = nullptr;
     int n_out = 0, k_in = 0;
     int n_blocks = 0;  // ceil(n_out / 32)
-    int k_groups = 0;  // ceil32(k_in) / 8
+    int k_groups = 0;
 };
 
 // ---- launchers (each enqueues on `stream` and returns a DKF_* code) ------------
@@ -105,10 +109,11 @@ struct GuideArgs {
     float *z_next_dbg;           // [S][Z] or NULL
     float *z_next;               // [S][Zp] zero padded: input of the emission
     int S, L, Z, Zp, R, Rp, H, Hp;
+    bool bf16;  // layers packed as bf16 tiles
 };
 int launch_guide(const GuideArgs &a, hipStream_t stream);
-size_t guide_lds_bytes(int Zp, int Rp, int Hp);
-int guide_prepare(int Zp, int Rp, int Hp);  // raises the kernel's LDS limit once per size
+size_t guide_lds_bytes(int Zp, int Rp, int Hp, bool bf16);
+int guide_prepare(int Zp, int Rp, int Hp, bool bf16);  // raises the kernel's LDS limit once per size
 
 // mlp_gemm.hip
 enum Epilogue : int {
@@ -133,6 +138,7 @@ struct GemmArgs {
     float *out_mean_dbg;  // [S][N] or NULL
     float *out_sd_dbg;    // [S][N] or NULL
     int N;
+    bool bf16;  // layer packed as bf16 tiles: A is rounded to bf16 while it is staged
 };
 int launch_gemm(const GemmArgs &a, int stage, hipStream_t stream);
 

@@ -18,11 +18,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kTileM = 128;
 constexpr int kTileNB = 4;            // 32-column blocks per workgroup
-constexpr int kChunkKG = 4;           // k-groups (of 8) per LDS chunk: K chunk = 32
-constexpr int kLda = kTileM + 1;      // float4 plane stride
-constexpr int kPlanes = kChunkKG * 2; // float4 planes per chunk
+constexpr int kChunkKG = 4;           // k-groups per LDS chunk: K chunk = 32 columns in fp32, 64 in bf16
+constexpr int kLda = kTileM + 1;      // plane stride in 16-byte entries
+constexpr int kPlanes = kChunkKG * 2; // planes per chunk (4 fp32 or 8 bf16 columns each)
 
-template <int EPI>
+// BF16: the activation rows are read as fp32 and rounded to bf16 (nearest even) while they are
+// staged into LDS; the layer's tiles are bf16; accumulation and the epilogue stay fp32.
+template <int EPI, bool BF16>
 __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
     __shared__ f32x4 As[2][kPlanes * kLda];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -49,14 +51,26 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
     }
 
     // global -> LDS mapping of the activation chunk: plane q = tid % 8, rows tid/8 + 32 i
+    constexpr int kPlaneCols = BF16 ? 8 : 4;  // columns per plane
+    constexpr int kLoads = BF16 ? 2 : 1;      // float4 loads per plane entry
     const int lq = tid & 7, lrow = tid >> 3;
     const float *arow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int r = m0 + lrow + 32 * i;
         if (r >= a.S) r = a.S - 1;
-        arow[i] = a.A + (size_t)r * a.lda + lq * 4;
+        arow[i] = a.A + (size_t)r * a.lda + lq * kPlaneCols;
     }
+    auto stage = [](const f32x4 (&v)[kLoads]) {  // one 16-byte plane entry from kLoads float4
+        if constexpr (BF16) {
+            bf16x8 h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { h[e] = (__bf16)v[0][e]; h[4 + e] = (__bf16)v[1][e]; }
+            return __builtin_bit_cast(f32x4, h);
+        } else {
+            return v[0];
+        }
+    };
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -64,16 +78,18 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
 
-    f32x4 areg[4];
+    f32x4 areg[4][kLoads];
     f32x4 breg[2][kChunkKG];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) areg[i] = *reinterpret_cast<const f32x4 *>(arow[i]);
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int l = 0; l < kLoads; ++l) areg[i][l] = *reinterpret_cast<const f32x4 *>(arow[i] + 4 * l);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int g = 0; g < kChunkKG; ++g) breg[j][g] = bt[j][(size_t)g * 64];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) As[0][lq * kLda + lrow + 32 * i] = areg[i];
+    for (int i = 0; i < 4; ++i) As[0][lq * kLda + lrow + 32 * i] = stage(areg[i]);
     __syncthreads();
 
     const int r = lane & 31, half = lane >> 5;
@@ -88,7 +104,9 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
         if (more) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                areg[i] = *reinterpret_cast<const f32x4 *>(arow[i] + (size_t)(ch + 1) * kChunkKG * 8);
+#pragma unroll
+                for (int l = 0; l < kLoads; ++l)
+                    areg[i][l] = *reinterpret_cast<const f32x4 *>(arow[i] + (size_t)(ch + 1) * kPlanes * kPlaneCols + 4 * l);
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -99,17 +117,24 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
         for (int g = 0; g < kChunkKG; ++g) {
             const f32x4 a0 = As[cur][(g * 2 + half) * kLda + wr * 64 + r];
             const f32x4 a1 = As[cur][(g * 2 + half) * kLda + wr * 64 + 32 + r];
+            if constexpr (BF16) {
+                acc[0][0] = mfma32_bf16(a0, bcur[0][g], acc[0][0]);
+                acc[0][1] = mfma32_bf16(a0, bcur[1][g], acc[0][1]);
+                acc[1][0] = mfma32_bf16(a1, bcur[0][g], acc[1][0]);
+                acc[1][1] = mfma32_bf16(a1, bcur[1][g], acc[1][1]);
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc[0][0] = mfma32(a0[e], bcur[0][g][e], acc[0][0]);
-                acc[0][1] = mfma32(a0[e], bcur[1][g][e], acc[0][1]);
-                acc[1][0] = mfma32(a1[e], bcur[0][g][e], acc[1][0]);
-                acc[1][1] = mfma32(a1[e], bcur[1][g][e], acc[1][1]);
+                for (int e = 0; e < 4; ++e) {
+                    acc[0][0] = mfma32(a0[e], bcur[0][g][e], acc[0][0]);
+                    acc[0][1] = mfma32(a0[e], bcur[1][g][e], acc[0][1]);
+                    acc[1][0] = mfma32(a1[e], bcur[0][g][e], acc[1][0]);
+                    acc[1][1] = mfma32(a1[e], bcur[1][g][e], acc[1][1]);
+                }
             }
         }
         if (more) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) As[cur ^ 1][lq * kLda + lrow + 32 * i] = areg[i];
+            for (int i = 0; i < 4; ++i) As[cur ^ 1][lq * kLda + lrow + 32 * i] = stage(areg[i]);
         }
         __syncthreads();
     }
@@ -151,18 +176,23 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
 }  // namespace
 
 int launch_gemm(const GemmArgs &a, int stage, hipStream_t stream) {
-    if (a.layer.k_groups % kChunkKG != 0 || a.layer.k_groups * 8 > a.lda) return DKF_EINVAL;
+    if (a.layer.k_groups % kChunkKG != 0 || a.layer.k_groups * (a.bf16 ? 16 : 8) > a.lda) return DKF_EINVAL;
     StageTimer timer(stage, stream);
     const int row_tiles = (a.S + kTileM - 1) / kTileM;
     const int col_tiles = (a.layer.n_blocks + kTileNB - 1) / kTileNB;
     const int row_tiles8 = (row_tiles + 7) / 8 * 8;
     const dim3 grid(row_tiles8 * col_tiles);
+#define DKF_GEMM_LAUNCH(E_)                                                                       \
+    if (a.bf16) hipLaunchKernelGGL((mlp_gemm<E_, true>), grid, dim3(kThreads), 0, stream, a);    \
+    else hipLaunchKernelGGL((mlp_gemm<E_, false>), grid, dim3(kThreads), 0, stream, a);          \
+    break
     switch (a.epilogue) {
-        case kEpiBias: hipLaunchKernelGGL(mlp_gemm<kEpiBias>, grid, dim3(kThreads), 0, stream, a); break;
-        case kEpiBiasRelu: hipLaunchKernelGGL(mlp_gemm<kEpiBiasRelu>, grid, dim3(kThreads), 0, stream, a); break;
-        case kEpiScaleDraw: hipLaunchKernelGGL(mlp_gemm<kEpiScaleDraw>, grid, dim3(kThreads), 0, stream, a); break;
+        case kEpiBias: DKF_GEMM_LAUNCH(kEpiBias);
+        case kEpiBiasRelu: DKF_GEMM_LAUNCH(kEpiBiasRelu);
+        case kEpiScaleDraw: DKF_GEMM_LAUNCH(kEpiScaleDraw);
         default: return DKF_EINVAL;
     }
+#undef DKF_GEMM_LAUNCH
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
 }
