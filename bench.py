@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "contended", "replay"])
+    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "contended", "large_bf16", "replay"])
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
     args = ap.parse_args()
     if args.gpus != 1:

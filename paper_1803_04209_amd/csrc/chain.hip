@@ -145,16 +145,6 @@ __device__ __forceinline__ void mma_narrow(Acc4 &acc, const f32x4 (&t)[GROUP], c
         for (int e = 0; e < 4; ++e) acc.c[e] = mfma16(t[j][e], x[j][e], acc.c[e]);
 }
 
-__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
-__device__ __forceinline__ float fast_softplus(float v) {
-    return fmaxf(v, 0.f) + __logf(1.0f + __expf(-fabsf(v)));
-}
-__device__ __forceinline__ float fast_sigmoid(float v) {
-    const float e = __expf(-fabsf(v));
-    const float r = fast_rcp(1.0f + e);
-    return v >= 0.f ? r : e * r;
-}
-
 // VEC: N and Z are multiples of 4, so every per-lane load/store is one aligned float4 and the
 // hot loops are free of branches (dead lanes and pad columns are handled by clamped addresses,
 // selects and a sink buffer; control flow would force the compiler to drain all outstanding
@@ -228,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         return e;
     };
     auto relu4 = [](f32x4 v) { return map4(v, [](float u) { return fmaxf(u, 0.f); }); };
-    auto softplus4 = [](f32x4 v) { return map4(v, [](float u) { return fast_softplus(u); }); };
+    auto softplus4 = [](f32x4 v) { return map4(v, [](float u) { return softplus_f(u); }); };
 
     f32x4 z[ZB];
 #pragma unroll
@@ -371,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         small_layer(lin, lb_lin, z);
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) {
-            const f32x4 gate = map4(g[zb], [](float v) { return fast_sigmoid(v); });
+            const f32x4 gate = map4(g[zb], [](float v) { return sigmoid_f(v); });
             G[zb] = (splat(1.f) - gate) * lin[zb] + gate * prop[zb];
             rG[zb] = relu4(G[zb]);
         }

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a
 // ctx_dir[t][r] = h_t,  h_t = relu(proj[slot(t)][r] / s + b[r] + sum_k w_hh[r][k] h_prev[k])
 // grid: 2 (direction), block 1024; dynamic LDS: 2 * Rp floats.
 __global__ __launch_bounds__(kChainThreads) void encode_window(FilterArgs a) {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     const Control ctl = *a.ctl;
     if (ctl.count < a.L) return;  // still warming up: nothing to encode
     const int dir = blockIdx.x;
@@ -68,21 +68,54 @@ __global__ __launch_bounds__(kChainThreads) void encode_window(FilterArgs a) {
     __syncthreads();
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     constexpr int kWaves = kChainThreads / 64;
+    constexpr int kBatch = 8;  // rows per wavefront pass: 8 x (R/256) float4 loads in flight per lane
+    const bool vec = (R & 3) == 0;
     for (int step = 0; step < L; ++step) {
         const int t = dir ? L - 1 - step : step;
         int slot = ctl.oldest + t;
         if (slot >= L) slot -= L;
         const float *__restrict__ p = proj + (size_t)slot * R;
-        for (int r = wave; r < R; r += kWaves) {
-            const float *__restrict__ wr = w + (size_t)r * R;
-            float s = 0.f;
-            if (step > 0)
-                for (int k = lane; k < R; k += 64) s += wr[k] * h_prev[k];
-            s = wave_sum(s);
+        for (int r0 = wave * kBatch; r0 < R; r0 += kWaves * kBatch) {
+            float s[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) s[j] = 0.f;
+            if (step > 0) {
+                if (vec) {
+                    for (int k = lane * 4; k < R; k += 256) {
+                        const float4 hv = *reinterpret_cast<const float4 *>(h_prev + k);
+                        float4 wv[kBatch];
+#pragma unroll
+                        for (int j = 0; j < kBatch; ++j) {
+                            const int r = r0 + j < R ? r0 + j : R - 1;
+                            wv[j] = *reinterpret_cast<const float4 *>(w + (size_t)r * R + k);
+                        }
+#pragma unroll
+                        for (int j = 0; j < kBatch; ++j)
+                            s[j] += wv[j].x * hv.x + wv[j].y * hv.y + wv[j].z * hv.z + wv[j].w * hv.w;
+                    }
+                } else {
+                    for (int k = lane; k < R; k += 64) {
+                        const float hv = h_prev[k];
+#pragma unroll
+                        for (int j = 0; j < kBatch; ++j) {
+                            const int r = r0 + j < R ? r0 + j : R - 1;
+                            s[j] += w[(size_t)r * R + k] * hv;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) s[j] = wave_sum(s[j]);
             if (lane == 0) {
-                const float v = fmaxf(p[r] * ctl.inv_scale + bias[r] + s, 0.f);
-                h_next[r] = v;
-                ctx[(size_t)t * Rp + r] = v;
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const int r = r0 + j;
+                    if (r < R) {
+                        const float v = fmaxf(p[r] * ctl.inv_scale + bias[r] + s[j], 0.f);
+                        h_next[r] = v;
+                        ctx[(size_t)t * Rp + r] = v;
+                    }
+                }
             }
         }
         __syncthreads();
@@ -103,7 +136,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
     constexpr int ROWS = kChainThreads / TPR;
     static_assert(TPR * KPT == ROWS, "square tile");
     constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;  // 4 pad floats per column segment: conflict-free b128 reads
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     const Control ctl = *a.ctl;
     if (ctl.count < a.L) return;
     const int dir = blockIdx.x;

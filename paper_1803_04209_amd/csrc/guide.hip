@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void guide_transition(GuideArgs a) {
         const float *__restrict__ cf = a.ctx_f + (size_t)t * a.Rp;
         const float *__restrict__ cb = a.ctx_b + (size_t)t * a.Rp;
         wide_layer<BF16>(a.comb, s.zA, wave, lane, [&](int row, int col, float v) {
-            put(s.hA, row, col, (tanhf(v) + cf[col] + cb[col]) * (1.0f / 3.0f));
+            put(s.hA, row, col, (tanh_f(v) + cf[col] + cb[col]) * (1.0f / 3.0f));
         });
         __syncthreads();
         narrow_layer<BF16>(a.mu, s.hA, s.red, wave, lane, [&](int row, int col, float v) {

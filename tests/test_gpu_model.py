@@ -71,7 +71,8 @@ def custom(N=6, L=4, Z=3, H=5, R=7, S=64, idx=9):
 
 @pytest.mark.parametrize("cfg", [
     custom(), custom(N=33, L=1, Z=8, H=40, R=36, S=100), custom(N=70, L=7, Z=33, H=65, R=31, S=257),
-    custom(N=130, L=3, Z=70, H=129, R=200, S=33)], ids=["6", "33", "70", "130"])
+    custom(N=130, L=3, Z=70, H=129, R=200, S=33), custom(N=40, L=3, Z=8, H=16, R=301, S=32),
+    custom(N=24, L=4, Z=8, H=16, R=260, S=32)], ids=["6", "33", "70", "130", "wide-rnn-odd", "wide-rnn"])
 @pytest.mark.parametrize("act", [0, 1])
 def test_unaligned_sizes_every_stage(api, cfg, act):
     g, o, _ = make_pair(api, cfg, act=act, std=0.3)
