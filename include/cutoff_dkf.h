@@ -113,7 +113,10 @@ int dkf_filter_step(dkf_model *m, const float *x_obs, void *stream);
  * x_{T+1} ~ N(I(z_{T+1}), J(z_{T+1})) each, returned in seconds.
  *   eps_q [L][S][Z], eps_z [S][Z], eps_x [S][N]: dev, fp32 standard normals
  *     that drive the three reparameterised draws.  If all three are NULL the
- *     library draws them itself from `seed` with a counter-based generator.
+ *     library draws them itself: element i of tensor t (0 eps_q, 1 eps_z,
+ *     2 eps_x) is output i mod 4 of Box-Muller on Philox4x32-10 with counter
+ *     (i/4 low, i/4 high, t, 0) and key (seed low, seed high), the uniforms
+ *     being u1 = ((w >> 8) + 1) / 2^24 and u2 = (w >> 8) / 2^24.
  *   out_samples [S][N] dev, caller-owned; `stages` may be NULL.
  * Errors: DKF_EINVAL (S < 1, S > max_samples, some but not all eps NULL),
  * DKF_ENOTREADY (window not full), DKF_EHIP. */

@@ -8,6 +8,9 @@ from .binding import (  # noqa: F401
     OracleModel,
     build,
     cutoff_select,
+    fill_normal,
+    make_noise,
+    philox4x32_10,
     num_threads,
     set_threads,
     NO_ELIGIBLE,

@@ -57,6 +57,8 @@ def _load():
     lib.oracle_cutoff_select.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_cutoff_select_f32.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_predict_cutoff.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_double, ip]
+    lib.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.oracle_fill_normal.argtypes = [C.c_uint64, C.c_uint32, C.c_size_t, fp]
     lib.oracle_num_threads.restype = C.c_int
     lib.oracle_set_threads.argtypes = [C.c_int]
     _lib = lib
@@ -69,6 +71,29 @@ def num_threads() -> int:
 
 def set_threads(n: int) -> None:
     _load().oracle_set_threads(int(n))
+
+
+def philox4x32_10(ctr, key):
+    """Four output words of Philox4x32-10 for a 4-word counter and a 2-word key."""
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    out = (C.c_uint32 * 4)()
+    _load().oracle_philox4x32_10(c, k, out)
+    return [int(v) for v in out]
+
+
+def fill_normal(seed: int, tensor: int, shape) -> np.ndarray:
+    """The sampler's own noise stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x) for `seed`, fp32."""
+    out = np.empty(shape, dtype=np.float32)
+    _load().oracle_fill_normal(int(seed), int(tensor), out.size, _fp(out))
+    return out
+
+
+def make_noise(cfg, seed: int, samples=None):
+    """(eps_q, eps_z, eps_x) exactly as the library draws them for `seed`."""
+    S = int(samples if samples is not None else cfg.samples)
+    return (fill_normal(seed, 0, (cfg.lag, S, cfg.z_dim)), fill_normal(seed, 1, (S, cfg.z_dim)),
+            fill_normal(seed, 2, (S, cfg.n_workers)))
 
 
 def _dp(a):

@@ -329,6 +329,44 @@ int oracle_sample_runtimes(const oracle_model *m, int S, const int32_t *rows, in
     return ORACLE_OK;
 }
 
+/* ---- noise the sampler may draw itself ------------------------------------------
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) written from its published definition:
+ * ten rounds of  (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0))
+ * with M0 = 0xD2511F53, M1 = 0xCD9E8D57, the key raised by (0x9E3779B9, 0xBB67AE85) after
+ * every round.  READING (the paper does not say how its samples are drawn): element i of
+ * tensor t uses counter (i/4 low, i/4 high, t, 0) and key (seed low, seed high); the four
+ * output words give two Box-Muller pairs from 24-bit uniforms u1 = ((w>>8)+1)/2^24,
+ * u2 = (w>>8)/2^24. */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+void oracle_fill_normal(uint64_t seed, uint32_t tensor, size_t n, float *out) {
+    const double two_pi = 6.283185307179586476925286766559;
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (size_t g = 0; g * 4 < n; ++g) {
+        uint32_t ctr[4] = {(uint32_t)g, (uint32_t)((uint64_t)g >> 32), tensor, 0u}, w[4];
+        oracle_philox4x32_10(ctr, key, w);
+        double v[4];
+        for (int pair = 0; pair < 2; ++pair) {
+            double u1 = (double)((w[2 * pair] >> 8) + 1u) / 16777216.0;
+            double u2 = (double)(w[2 * pair + 1] >> 8) / 16777216.0;
+            double r = sqrt(-2.0 * log(u1));
+            v[2 * pair] = r * cos(two_pi * u2);
+            v[2 * pair + 1] = r * sin(two_pi * u2);
+        }
+        for (int j = 0; j < 4 && g * 4 + j < n; ++j) out[g * 4 + j] = (float)v[j];
+    }
+}
+
 /* ---- Monte-Carlo order statistics and the cutoff (Sec. 3; Sec. 3.1.1) ------ */
 
 typedef struct { double v; int32_t idx; } keyed;

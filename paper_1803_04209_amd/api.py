@@ -247,11 +247,12 @@ class Predictor:
     def filter_step(self, x_obs) -> int:
         return dkf_filter_step(self.handle, x_obs)
 
-    def sample_runtimes(self, eps_q, eps_z, eps_x, stages: bool = False, out=None):
+    def sample_runtimes(self, eps_q=None, eps_z=None, eps_x=None, stages: bool = False, out=None, S=None, seed=0):
+        """With the three noise tensors: use them.  With none: the library draws its own from `seed` for S samples."""
         torch = _torch()
         cfg = self.cfg
-        S = eps_z.shape[0]
-        dev = eps_z.device
+        S = int(eps_z.shape[0] if eps_z is not None else S)
+        dev = eps_z.device if eps_z is not None else torch.device("cuda")
         out = torch.empty((S, cfg.n_workers), dtype=torch.float32, device=dev) if out is None else out
         st, tensors = None, None
         if stages:
@@ -265,10 +266,10 @@ class Predictor:
             st = dkf_stage_outputs(tensors["ctx"].data_ptr(), tensors["z_T"].data_ptr(),
                                    tensors["z_next"].data_ptr(), tensors["emit_mean"].data_ptr(),
                                    tensors["emit_sd"].data_ptr())
-        dkf_sample_runtimes(self.handle, S, eps_q, eps_z, eps_x, 0, out, st)
+        dkf_sample_runtimes(self.handle, S, eps_q, eps_z, eps_x, seed, out, st)
         return (out, tensors) if stages else out
 
-    def decide(self, x_obs, S, eps_q, eps_z, eps_x, seed=0):
+    def decide(self, x_obs, S, eps_q=None, eps_z=None, eps_x=None, seed=0):
         return dkf_decide(self.handle, x_obs, S, eps_q, eps_z, eps_x, seed)
 
     def decide_samples(self, S):

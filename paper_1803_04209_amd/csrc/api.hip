@@ -97,6 +97,7 @@ struct dkf_model {
     size_t cutoff_ws_bytes = 0;
     int32_t *d_cstar = nullptr;
     float *sink = nullptr;  // scratch for masked-off lanes of the sampler
+    float *gen_q = nullptr, *gen_z = nullptr, *gen_x = nullptr;  // noise drawn by the library itself
 
     // captured decision graph
     hipStream_t own_stream = nullptr;
@@ -350,6 +351,14 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     return DKF_OK;
 }
 
+// Draw the three noise tensors for S samples into the model's own buffers.
+int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStream_t stream) {
+    int rc = launch_fill_normal(m->gen_q, (size_t)m->L * S * m->Z, 0, ctl, seed, stream);
+    if (rc == DKF_OK) rc = launch_fill_normal(m->gen_z, (size_t)S * m->Z, 1, ctl, seed, stream);
+    if (rc == DKF_OK) rc = launch_fill_normal(m->gen_x, (size_t)S * m->N, 2, ctl, seed, stream);
+    return rc;
+}
+
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
     if (m->use_chain) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
@@ -531,6 +540,9 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     DKF_CHECK(dev_alloc(m, m->cutoff_ws_bytes, &q, true)); m->cutoff_ws = q;
     DKF_CHECK(dev_alloc(m, 2 * sizeof(int32_t), &q, true)); m->d_cstar = static_cast<int32_t *>(q);
     DKF_CHECK(dev_alloc(m, 4096, &q, true)); m->sink = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)L * Smax * Z * 4, &q, false)); m->gen_q = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * Z * 4, &q, false)); m->gen_z = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, (size_t)Smax * N * 4, &q, false)); m->gen_x = static_cast<float *>(q);
 
     for (int i = 0; i < dkf_model::kStagingSlots + 1; ++i) {
         void *h = nullptr;
@@ -585,12 +597,15 @@ int dkf_filter_step(dkf_model *m, const float *x_obs, void *stream_) {
 
 int dkf_sample_runtimes(dkf_model *m, int32_t S, const float *eps_q, const float *eps_z, const float *eps_x,
                         uint64_t seed, float *out_samples, const dkf_stage_outputs *stages, void *stream_) {
-    (void)seed;
     if (!m || !out_samples || S < 1 || S > m->cfg.max_samples) return DKF_EINVAL;
     const int n_null = (eps_q == nullptr) + (eps_z == nullptr) + (eps_x == nullptr);
     if (n_null != 0 && n_null != 3) return DKF_EINVAL;
-    if (n_null == 3) return DKF_EUNSUPPORTED;  // built-in generator: not in this build
     if (m->pushes < m->L) return DKF_ENOTREADY;
+    if (n_null == 3) {
+        const int rc = enqueue_noise(m, S, nullptr, seed, static_cast<hipStream_t>(stream_));
+        if (rc != DKF_OK) return rc;
+        eps_q = m->gen_q; eps_z = m->gen_z; eps_x = m->gen_x;
+    }
     return enqueue_sample(m, S, eps_q, eps_z, eps_x, out_samples, stages, static_cast<hipStream_t>(stream_));
 }
 
@@ -608,7 +623,7 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
     if (!m || !x_obs || !cstar_host || S < 1 || S > m->cfg.max_samples) return DKF_EINVAL;
     const int n_null = (eps_q == nullptr) + (eps_z == nullptr) + (eps_x == nullptr);
     if (n_null != 0 && n_null != 3) return DKF_EINVAL;
-    if (n_null == 3) return DKF_EUNSUPPORTED;
+    const bool own_noise = n_null == 3;
     hipStream_t stream = stream_ ? static_cast<hipStream_t>(stream_) : m->own_stream;
     // the eager path may still own staging slots on another stream: drain it
     for (int i = 0; i < dkf_model::kStagingSlots; ++i)
@@ -634,7 +649,10 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         hipError_t e = hipMemcpyAsync(m->d_in, m->staging_graph, m->in_floats() * 4, hipMemcpyHostToDevice, stream);
         if (e != hipSuccess) { set_last_hip_error(e); rc = DKF_EHIP; }
         if (rc == DKF_OK) rc = launch_filter(filter_args(m), true, true, stream);
-        if (rc == DKF_OK) rc = enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
+        if (rc == DKF_OK && own_noise) rc = enqueue_noise(m, S, m->ctl_dev(), 0, stream);  // seed travels in the control block
+        if (rc == DKF_OK)
+            rc = own_noise ? enqueue_sample(m, S, m->gen_q, m->gen_z, m->gen_x, m->samples, nullptr, stream)
+                           : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
         if (rc == DKF_OK)
             rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
                                       m->d_cstar, m->cutoff_ws, m->cutoff_ws_bytes, stream);

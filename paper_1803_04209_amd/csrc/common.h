@@ -168,6 +168,10 @@ __host__ __device__ constexpr int chain_chunk_tiles(int hb) { return hb >= 8 ? 3
 bool chain_supported(int Z, int R, int H, int L, int N);
 int launch_chain(const ChainArgs &a, hipStream_t stream);
 
+// noise.hip: out[0..n) = standard normals of stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x); the seed
+// is read from `ctl` when that is not NULL (captured graphs), else taken from `seed`
+int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl, uint64_t seed, hipStream_t stream);
+
 // cutoff_select.hip
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,

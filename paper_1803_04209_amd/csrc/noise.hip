@@ -1,0 +1,72 @@
+// Built-in standard-normal noise for the three reparameterised draws of the sampler
+// (guide steps, transition, emission; Sec. 3.1.3), used when the caller supplies no tensors.
+//
+// Counter-based: element i of tensor t (0 = eps_q, 1 = eps_z, 2 = eps_x) is the (i mod 4)-th
+// output of Box-Muller applied to Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel random
+// numbers: as easy as 1, 2, 3", SC'11) with counter (i/4 low, i/4 high, t, 0) and key
+// (seed low, seed high).  Uniforms use the top 24 bits of each word, u1 = (w0 >> 8) + 1) / 2^24
+// in (0, 1], u2 = (w1 >> 8) / 2^24 in [0, 1), so both are exact in fp32:
+//   n0 = sqrt(-2 ln u1) cos(2 pi u2), n1 = sqrt(-2 ln u1) sin(2 pi u2); words 2, 3 give n2, n3.
+#include "common.h"
+
+namespace dkf {
+namespace {
+
+struct U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        c = U4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c;
+}
+
+__device__ __forceinline__ void box_muller(uint32_t w0, uint32_t w1, float &n0, float &n1) {
+    const float u1 = (float)((w0 >> 8) + 1u) * (1.0f / 16777216.0f);
+    const float u2 = (float)(w1 >> 8) * (1.0f / 16777216.0f);
+    const float r = sqrtf(-2.0f * logf(u1));
+    float s, c;
+    sincospif(2.0f * u2, &s, &c);
+    n0 = r * c;
+    n1 = r * s;
+}
+
+// out[i] for i in [0, n): one thread per group of four elements
+__global__ __launch_bounds__(256) void fill_normal(float *__restrict__ out, size_t n, uint32_t tensor,
+                                                   const Control *ctl, uint32_t seed_lo, uint32_t seed_hi) {
+    if (ctl) { seed_lo = ctl->seed_lo; seed_hi = ctl->seed_hi; }
+    const size_t groups = (n + 3) / 4;
+    for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += (size_t)gridDim.x * blockDim.x) {
+        const U4 r = philox4x32_10(U4{(uint32_t)g, (uint32_t)(g >> 32), tensor, 0u}, seed_lo, seed_hi);
+        float v[4];
+        box_muller(r.x, r.y, v[0], v[1]);
+        box_muller(r.z, r.w, v[2], v[3]);
+        const size_t i0 = g * 4;
+        if (i0 + 3 < n) {
+            *reinterpret_cast<float4 *>(out + i0) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (i0 + j < n) out[i0 + j] = v[j];
+        }
+    }
+}
+
+}  // namespace
+
+int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl, uint64_t seed, hipStream_t stream) {
+    if (n == 0) return DKF_OK;
+    const size_t groups = (n + 3) / 4;
+    size_t blocks = (groups + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(fill_normal, dim3((unsigned)blocks), dim3(256), 0, stream, out, n, tensor, ctl, (uint32_t)seed,
+                       (uint32_t)(seed >> 32));
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
+}  // namespace dkf

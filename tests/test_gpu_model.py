@@ -199,6 +199,47 @@ def torch_isfinite(t):
     return bool(torch.isfinite(t).all())
 
 
+@pytest.mark.parametrize("name", ["tiny", "medium", "odd"])
+def test_builtin_noise_matches_the_oracle_stream(api, name):
+    """No noise tensors: the library draws Philox4x32-10 / Box-Muller normals from the seed; the
+    oracle is fed the same stream from its own implementation of the published generator."""
+    cfg = custom(N=18, L=2, Z=10, H=31, R=30, S=70) if name == "odd" else synth.CONFIGS[name]
+    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2)
+    for seed in (0, 0x1234_5678_9ABC_DEF0):
+        x, st = g.sample_runtimes(S=cfg.samples, seed=seed, stages=True)
+        eq, ez, ex = oracle.make_noise(cfg, seed)
+        xo, so = o.sample_runtimes(eq, ez, ex, stages=True)
+        assert rel_err(st["z_T"].cpu().numpy(), so["z_T"]) <= TOL
+        assert rel_err(st["emit_mean"].cpu().numpy(), so["emit_mean"]) <= TOL
+        assert rel_err(x.cpu().numpy(), xo) <= TOL
+    x2 = g.sample_runtimes(S=cfg.samples, seed=1)
+    assert not np.allclose(x2.cpu().numpy(), x.cpu().numpy())
+    g.close()
+
+
+def test_decide_with_builtin_noise(api):
+    import torch
+
+    cfg = synth.CONFIGS["tiny"]
+    blob = synth.make_blob(cfg)
+    tr = synth.make_trace(cfg)
+    S = cfg.samples
+    graph, eager = api.Predictor(cfg, blob), api.Predictor(cfg, blob)
+    for t in range(cfg.lag + 8):
+        seed = 1000 + t
+        c, status = graph.decide(tr[t], S, seed=seed)
+        re = eager.filter_step(tr[t])
+        if t < cfg.lag - 1:
+            assert status == api.DKF_WARMUP == re
+            continue
+        x = eager.sample_runtimes(S=S, seed=seed)
+        res = api.select_cutoff(x)
+        assert (c, status) == (res["cstar"], res["status"])
+        assert torch.equal(graph.decide_samples(S), x)
+    graph.close()
+    eager.close()
+
+
 def test_warmup_errors_and_reset(api):
     import torch
 
@@ -228,8 +269,9 @@ def test_warmup_errors_and_reset(api):
     assert torch.equal(a, b)
     with pytest.raises(api.DkfError):
         api.dkf_sample_runtimes(g.handle, cfg.samples + 1, eq, ez, ex, 0, out)
-    with pytest.raises(api.DkfError):
-        api.dkf_sample_runtimes(g.handle, cfg.samples, eq, None, ex, 0, out)
+    with pytest.raises(api.DkfError) as e:
+        api.dkf_sample_runtimes(g.handle, cfg.samples, eq, None, ex, 0, out)  # some but not all tensors
+    assert e.value.code == api.DKF_EINVAL
     with pytest.raises(api.DkfError) as e:
         api.dkf_load_weights(api.make_config(cfg), blob[:-4])
     assert e.value.code == api.DKF_EBLOB
