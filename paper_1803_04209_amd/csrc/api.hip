@@ -281,16 +281,19 @@ bool config_ok(const dkf_config *c) {
            (c->emit_mean_act == 0 || c->emit_mean_act == 1);
 }
 
-FilterArgs filter_args(const dkf_model *m) {
+// `input`: where the step's observation + control block is read from (pinned host staging or d_in)
+FilterArgs filter_args(const dkf_model *m, const float *input) {
     FilterArgs a;
-    a.input = m->d_in;
+    a.input = input;
+    a.mirror = m->d_in;
     a.ctl = m->ctl_dev();
     a.proj_f = m->proj_f; a.proj_b = m->proj_b;
     a.ctx_f = m->ctx_f; a.ctx_b = m->ctx_b;
     a.w_ih_f = m->w_ih_f; a.w_ih_b = m->w_ih_b;
     a.w_hh_f = m->w_hh_f; a.w_hh_b = m->w_hh_b;
     a.bias_f = m->bias_f; a.bias_b = m->bias_b;
-    a.N = m->N; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
+    a.N = m->N; a.Np = m->Np; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
+    a.encode = true;
     return a;
 }
 
@@ -546,7 +549,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
 
     for (int i = 0; i < dkf_model::kStagingSlots + 1; ++i) {
         void *h = nullptr;
-        DKF_CHECK_HIP(hipHostMalloc(&h, m->in_floats() * 4, hipHostMallocDefault));
+        DKF_CHECK_HIP(hipHostMalloc(&h, m->in_floats() * 4, hipHostMallocMapped | hipHostMallocCoherent));
         m->host_allocs.push_back(h);
         if (i < dkf_model::kStagingSlots) {
             m->staging[i] = static_cast<float *>(h);
@@ -557,7 +560,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     }
     {
         void *h = nullptr;
-        DKF_CHECK_HIP(hipHostMalloc(&h, 2 * sizeof(int32_t), hipHostMallocDefault));
+        DKF_CHECK_HIP(hipHostMalloc(&h, 2 * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent));
         m->host_allocs.push_back(h);
         m->cstar_host = static_cast<int32_t *>(h);
     }
@@ -588,10 +591,10 @@ int dkf_filter_step(dkf_model *m, const float *x_obs, void *stream_) {
     const int status = stage_observation(m, x_obs, 0, m->staging[i]);
     if (status < 0) return status;
     m->staging_next = (i + 1) % dkf_model::kStagingSlots;
-    DKF_HIP_TRY(hipMemcpyAsync(m->d_in, m->staging[i], m->in_floats() * 4, hipMemcpyHostToDevice, stream));
+    // the first kernel reads the pinned staging slot directly (no copy node) and mirrors it to d_in
+    const int rc = launch_filter(filter_args(m, m->staging[i]), true, status == DKF_OK, stream);
     DKF_HIP_TRY(hipEventRecord(m->staging_done[i], stream));
     m->staging_used[i] = true;
-    const int rc = launch_filter(filter_args(m), true, status == DKF_OK, stream);
     return rc != DKF_OK ? rc : status;
 }
 
@@ -631,8 +634,7 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
     const int status = stage_observation(m, x_obs, seed, m->staging_graph);
     if (status < 0) return status;
     if (status == DKF_WARMUP) {
-        DKF_HIP_TRY(hipMemcpyAsync(m->d_in, m->staging_graph, m->in_floats() * 4, hipMemcpyHostToDevice, stream));
-        const int rc = launch_filter(filter_args(m), true, false, stream);
+        const int rc = launch_filter(filter_args(m, m->staging_graph), true, false, stream);
         if (rc != DKF_OK) return rc;
         DKF_HIP_TRY(hipStreamSynchronize(stream));
         *cstar_host = m->N;
@@ -645,21 +647,17 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         DKF_HIP_TRY(hipStreamSynchronize(stream));
         DKF_HIP_TRY(hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal));
         g_capturing++;
-        int rc = DKF_OK;
-        hipError_t e = hipMemcpyAsync(m->d_in, m->staging_graph, m->in_floats() * 4, hipMemcpyHostToDevice, stream);
-        if (e != hipSuccess) { set_last_hip_error(e); rc = DKF_EHIP; }
-        if (rc == DKF_OK) rc = launch_filter(filter_args(m), true, true, stream);
+        // kernels only: the first one reads the pinned staging buffer, the last one writes the
+        // decision into pinned host memory
+        int rc = launch_filter(filter_args(m, m->staging_graph), true, true, stream);
+        hipError_t e = hipSuccess;
         if (rc == DKF_OK && own_noise) rc = enqueue_noise(m, S, m->ctl_dev(), 0, stream);  // seed travels in the control block
         if (rc == DKF_OK)
             rc = own_noise ? enqueue_sample(m, S, m->gen_q, m->gen_z, m->gen_x, m->samples, nullptr, stream)
                            : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
         if (rc == DKF_OK)
             rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
-                                      m->d_cstar, m->cutoff_ws, m->cutoff_ws_bytes, stream);
-        if (rc == DKF_OK) {
-            e = hipMemcpyAsync(m->cstar_host, m->d_cstar, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream);
-            if (e != hipSuccess) { set_last_hip_error(e); rc = DKF_EHIP; }
-        }
+                                      m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream);
         g_capturing--;
         hipGraph_t graph = nullptr;
         e = hipStreamEndCapture(stream, &graph);
@@ -723,8 +721,7 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes) {
         c.scale = m->scale;
         c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
         std::memcpy(dst + m->Np, &c, sizeof c);
-        DKF_HIP_TRY(hipMemcpy(m->d_in, dst, m->in_floats() * 4, hipMemcpyHostToDevice));
-        const int rc = launch_filter(filter_args(m), true, slot == stored - 1 && stored == L, nullptr);
+        const int rc = launch_filter(filter_args(m, dst), true, slot == stored - 1 && stored == L, nullptr);
         if (rc != DKF_OK) return rc;
         DKF_HIP_TRY(hipDeviceSynchronize());
     }

@@ -84,14 +84,18 @@ struct PackedLayer {
 
 // filter.hip
 struct FilterArgs {
-    const float *input;    // dev: [N] new observation followed by a Control block
-    const Control *ctl;    // dev: = input + N
+    const float *input;    // [Np] new observation followed by a Control block; device memory or pinned
+                           // host memory (read once by the first kernel of the step)
+    float *mirror;         // dev copy of `input` written by that kernel (may equal input)
+    const Control *ctl;    // dev: = mirror + Np, what later kernels read
     float *proj_f, *proj_b;  // dev [L][R] raw input projections W_ih x (no bias, not normalised)
     float *ctx_f, *ctx_b;    // dev [L][Rp] encodings, window order, zero padded
     const float *w_ih_f, *w_ih_b;      // dev [R][N]
     const float *w_hh_f, *w_hh_b;      // dev [R][R]
     const float *bias_f, *bias_b;      // dev [R]: b_ih + b_hh
-    int N, L, R, Rp;
+    int N, Np, L, R, Rp;
+    bool project;  // (register-resident kernel) compute the new observation's projection in-kernel
+    bool encode;   // run the recurrences (after the projection) when the window is full
 };
 int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream);
 

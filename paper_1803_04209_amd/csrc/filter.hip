@@ -25,11 +25,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // proj_dir[slot][r] = sum_j w_ih_dir[r][j] * x[j]      grid: (ceil(R/16), 2)
 __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a) {
-    const Control ctl = *a.ctl;
+    const Control ctl = *reinterpret_cast<const Control *>(a.input + a.Np);
     const int dir = blockIdx.y;
     const float *__restrict__ w = dir ? a.w_ih_b : a.w_ih_f;
     float *__restrict__ proj = (dir ? a.proj_b : a.proj_f) + (size_t)ctl.slot * a.R;
     const float *__restrict__ x = a.input;
+    if (blockIdx.x == 0 && dir == 0 && a.mirror != a.input) {  // device copy for the kernels that follow
+        const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
+        for (int i = threadIdx.x; i < n; i += kProjThreads) a.mirror[i] = a.input[i];
+    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int N = a.N;
     for (int i = wave; i < kProjRowsPerBlock; i += kProjThreads / 64) {
@@ -137,19 +141,55 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
     static_assert(TPR * KPT == ROWS, "square tile");
     constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;  // 4 pad floats per column segment: conflict-free b128 reads
     extern __shared__ __align__(16) float lds[];
-    const Control ctl = *a.ctl;
-    if (ctl.count < a.L) return;
+    const Control ctl = a.project ? *reinterpret_cast<const Control *>(a.input + a.Np) : *a.ctl;
     const int dir = blockIdx.x;
-    const int R = a.R, L = a.L;
+    const int R = a.R, L = a.L, N = a.N;
     const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
     const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
-    const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
+    float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
     float *__restrict__ ctx = dir ? a.ctx_b : a.ctx_f;
     float *pre = lds;               // [L][ROWS] in chain order (step), input term of every position
     float *h0 = lds + L * ROWS;     // two state buffers, padded layout
     float *h1 = h0 + HSTRIDE;
+    float *xs = h1 + HSTRIDE;       // [Np] the new observation
+    float *newp = xs + a.Np;        // [ROWS] its input projection
     const int tid = threadIdx.x;
     const int row = tid / TPR, seg = tid % TPR, k0 = seg * KPT;
+
+    // the new observation (read straight from the caller-side staging buffer, which may be
+    // pinned host memory) -> LDS, and a device copy of it and of the control block
+    if (a.project) {
+        const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
+        for (int i = tid; i < n; i += kChainThreads) {
+            const float v = a.input[i];
+            if (i < a.Np) xs[i] = v;
+            if (dir == 0 && a.mirror != a.input) a.mirror[i] = v;
+        }
+    }
+    __syncthreads();
+    // input projection of the new observation: TPR lanes per row, interleaved float4 columns
+    if (a.project) {
+        const float *__restrict__ wi = (dir ? a.w_ih_b : a.w_ih_f) + (size_t)row * N;
+        float s = 0.f;
+        if (row < R) {
+            if ((N & 3) == 0) {
+                for (int j = seg * 4; j < N; j += TPR * 4) {
+                    const float4 wv = *reinterpret_cast<const float4 *>(wi + j);
+                    const float4 xv = *reinterpret_cast<const float4 *>(xs + j);
+                    s += wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
+                }
+            } else {
+                for (int j = seg; j < N; j += TPR) s += wi[j] * xs[j];
+            }
+        }
+#pragma unroll
+        for (int d = 1; d < TPR; d <<= 1) s += __shfl_xor(s, d, 64);
+        if (seg == 0) {
+            newp[row] = s;
+            if (row < R) proj[(size_t)ctl.slot * R + row] = s;
+        }
+    }
+    if (ctl.count < L || !a.encode) return;  // warming up, or only the projection was asked for
 
     float wreg[KPT];
     if (KPT >= 4 && (R & 3) == 0) {
@@ -169,9 +209,17 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
         const int t = dir ? L - 1 - step : step;
         int slot = ctl.oldest + t;
         if (slot >= L) slot -= L;
-        pre[i] = r < R ? proj[(size_t)slot * R + r] * ctl.inv_scale + bias[r] : 0.f;
+        const float pv = (a.project && slot == ctl.slot) ? 0.f : (r < R ? proj[(size_t)slot * R + r] : 0.f);  // new one: from LDS below
+        pre[i] = r < R ? pv * ctl.inv_scale + bias[r] : 0.f;
     }
     for (int i = tid; i < 2 * HSTRIDE; i += kChainThreads) h0[i] = 0.f;
+    __syncthreads();
+    if (a.project) {  // the new observation's term comes from LDS (its global copy is for later steps)
+        int t_new = ctl.slot - ctl.oldest;
+        if (t_new < 0) t_new += L;
+        const int step_new = dir ? L - 1 - t_new : t_new;
+        for (int r = tid; r < R; r += kChainThreads) pre[step_new * ROWS + r] = newp[r] * ctl.inv_scale + bias[r];
+    }
     __syncthreads();
 
     float *h_prev = h0, *h_next = h1;
@@ -206,7 +254,7 @@ template <int TPR, int KPT>
 int launch_encode_reg(const FilterArgs &a, hipStream_t stream) {
     constexpr int ROWS = kChainThreads / TPR;
     constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;
-    const size_t lds = ((size_t)a.L * ROWS + 2 * HSTRIDE) * sizeof(float);
+    const size_t lds = ((size_t)a.L * ROWS + 2 * HSTRIDE + a.Np + ROWS) * sizeof(float);
     if (lds > 64 * 1024) return DKF_EUNSUPPORTED;
     hipLaunchKernelGGL((encode_window_reg<TPR, KPT>), dim3(2), dim3(kChainThreads), lds, stream, a);
     DKF_HIP_TRY(hipGetLastError());
@@ -215,25 +263,45 @@ int launch_encode_reg(const FilterArgs &a, hipStream_t stream) {
 
 }  // namespace
 
-int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream) {
+int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t stream) {
     StageTimer timer(kStageFilter, stream);
-    if (project) {
+    FilterArgs a = args;
+    a.encode = encode;
+    a.project = false;
+    // Small encoders: projection and both recurrences in one launch of two workgroups.  A larger
+    // input matrix (measured: 256 x 512) is read faster by the many workgroups of the separate
+    // projection kernel than by those two.
+    const bool fuse = project && (size_t)a.R * a.N <= 32768;
+    if (!fuse && project) {
+        if (a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
+            const size_t bytes = a.Np * sizeof(float) + sizeof(Control);
+            DKF_HIP_TRY(hipMemcpyAsync(a.mirror, a.input, bytes, hipMemcpyHostToDevice, stream));
+            a.input = a.mirror;
+        }
         const dim3 pgrid((a.R + kProjRowsPerBlock - 1) / kProjRowsPerBlock, 2);
         hipLaunchKernelGGL(project_observation, pgrid, dim3(kProjThreads), 0, stream, a);
         DKF_HIP_TRY(hipGetLastError());
+        project = false;
     }
-    if (encode) {
+    if (fuse || encode) {
+        a.project = fuse;
         int rc = DKF_EUNSUPPORTED;
         if (a.R <= 32) rc = launch_encode_reg<32, 1>(a, stream);
         else if (a.R <= 64) rc = launch_encode_reg<16, 4>(a, stream);
         else if (a.R <= 128) rc = launch_encode_reg<8, 16>(a, stream);
         else if (a.R <= 256) rc = launch_encode_reg<4, 64>(a, stream);
-        if (rc == DKF_EUNSUPPORTED) {  // wide or long windows: matrix streamed from L2 every step
-            hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
-            DKF_HIP_TRY(hipGetLastError());
-        } else if (rc != DKF_OK) {
-            return rc;
-        }
+        if (rc != DKF_EUNSUPPORTED) return rc;
+    }
+    // wide encoders or long windows: the recurrences with the matrix streamed from L2 every step
+    a.project = false;
+    if (project) {  // the fused kernel did not fit
+        const dim3 pgrid((a.R + kProjRowsPerBlock - 1) / kProjRowsPerBlock, 2);
+        hipLaunchKernelGGL(project_observation, pgrid, dim3(kProjThreads), 0, stream, a);
+        DKF_HIP_TRY(hipGetLastError());
+    }
+    if (encode) {
+        hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
+        DKF_HIP_TRY(hipGetLastError());
     }
     return DKF_OK;
 }
