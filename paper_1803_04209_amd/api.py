@@ -28,7 +28,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
     "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "dkf_decide",
-    "dkf_decide_samples", "dkf_get_state", "dkf_set_state", "dkf_timing_enable", "dkf_timing_read",
+    "dkf_decide_samples", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
 
@@ -84,6 +84,7 @@ def _lib():
     lib.dkf_decide_samples.argtypes = [vp]
     lib.dkf_get_state.argtypes = [vp, vp, C.POINTER(sz)]
     lib.dkf_set_state.argtypes = [vp, vp, sz]
+    lib.dkf_set_sampler.argtypes = [C.c_void_p, C.c_int32]
     lib.dkf_timing_enable.argtypes = [C.c_uint32]
     lib.dkf_timing_read.argtypes = [i32, C.POINTER(i32), C.POINTER(C.c_double)]
     _handle = lib
@@ -209,6 +210,13 @@ def dkf_set_state(model: int, state: bytes) -> None:
     _check("dkf_set_state", _lib().dkf_set_state(model, state, len(state)))
 
 
+SAMPLER_AUTO, SAMPLER_WAVE16, SAMPLER_WAVE4, SAMPLER_STAGED = 0, 1, 2, 3
+
+
+def dkf_set_sampler(handle, variant: int) -> None:
+    _check("dkf_set_sampler", _lib().dkf_set_sampler(handle, variant))
+
+
 def dkf_timing_enable(stage_mask: int) -> None:
     _check("dkf_timing_enable", _lib().dkf_timing_enable(stage_mask))
 
@@ -240,6 +248,9 @@ class Predictor:
             self.close()
         except Exception:  # interpreter shutdown: the library may already be gone
             pass
+
+    def set_sampler(self, variant: int) -> None:
+        dkf_set_sampler(self.handle, variant)
 
     def reset(self):
         dkf_reset(self.handle)

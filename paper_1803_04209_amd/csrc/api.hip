@@ -73,6 +73,10 @@ struct dkf_model {
     bool use_chain = false;  // sizes covered by the register-chained sampler
     const float *chain_guide = nullptr, *chain_stream = nullptr, *chain_bias = nullptr;
     int chain_chunks = 0;
+    int sampler = DKF_SAMPLER_AUTO;  // dkf_set_sampler
+    bool use_quad = false;   // sizes covered by the four-samples-per-wavefront sampler (small S)
+    const float *quad_guide = nullptr, *quad_stream = nullptr, *quad_bias = nullptr;
+    int quad_chunks = 0;
 
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
@@ -281,6 +285,93 @@ bool config_ok(const dkf_config *c) {
            (c->emit_mean_act == 0 || c->emit_mean_act == 1);
 }
 
+// Tile streams of the four-samples-per-wavefront sampler (quad.hip).  A tile is 64 lanes x 4
+// floats; entry e of lane l is the B operand of the tile's e-th matrix instruction:
+//   wide layer, narrow input, tile (zq, kg):    W[64 og + l][16 zq + 4 kg + e]
+//   wide layer, wide input, tile (og, ig, b):   W[64 og + l][64 ig + 4 b + e]
+//   narrow layer, wide input, tile (zq, ig, q): W[16 zq + (l & 15)][64 ig + 16 (l >> 4) + 4 q + e]
+//   narrow layer, narrow input, tile (zo, zi):  W[16 zo + (l & 15)][16 zi + 4 (l >> 4) + e]
+// (zero outside the matrix).  Guide: comb [zq][kg][og], mu [zq][ig][q], sig [zo][zi].  Stream:
+// the transition layers and the emission's first layer at the positions of quad_plan(); then per
+// 64-worker group og the mean's second layer [ig][b] followed by that group's columns of the
+// scale network's first layer [b][hg]; then per group the scale network's second layer [ig][b].
+int pack_quad(dkf_model *m, const RawLayers &r) {
+    const int Z = m->Z, R = m->R, H = m->H, N = m->N;
+    const int ZQ = (Z + 15) / 16, RG = (R + 63) / 64, HG = (H + 63) / 64, NG = (N + 63) / 64;
+    const int CH = kQuadChunkTiles;
+    auto tile = [](std::vector<float> &dst, size_t at, const float *w, int n_out, int k_in, auto &&row, auto &&col) {
+        if (dst.size() < (at + 1) * 256) dst.resize((at + 1) * 256, 0.f);
+        for (int lane = 0; lane < 64; ++lane)
+            for (int e = 0; e < 4; ++e) {
+                const int n = row(lane), k = col(lane, e);
+                if (n < n_out && k < k_in) dst[at * 256 + lane * 4 + e] = w[(size_t)n * k_in + k];
+            }
+    };
+    auto wide_q = [&](std::vector<float> &dst, size_t at, const float *w, int n_out, int k_in, int groups) {  // [zq][kg][og]
+        for (int zq = 0; zq < ZQ; ++zq) for (int kg = 0; kg < 4; ++kg) for (int og = 0; og < groups; ++og)
+            tile(dst, at++, w, n_out, k_in, [&](int l) { return 64 * og + l; },
+                 [&](int, int e) { return 16 * zq + 4 * kg + e; });
+    };
+    auto narrow_a = [&](std::vector<float> &dst, size_t at, const float *w, int n_out, int k_in, int groups) {  // [zq][ig][q]
+        for (int zq = 0; zq < ZQ; ++zq) for (int ig = 0; ig < groups; ++ig) for (int q = 0; q < 4; ++q)
+            tile(dst, at++, w, n_out, k_in, [&](int l) { return 16 * zq + (l & 15); },
+                 [&](int l, int e) { return 64 * ig + 16 * (l >> 4) + 4 * q + e; });
+    };
+    auto narrow_q = [&](std::vector<float> &dst, size_t at, const float *w) {  // [zo][zi], Z x Z
+        for (int zo = 0; zo < ZQ; ++zo) for (int zi = 0; zi < ZQ; ++zi)
+            tile(dst, at++, w, Z, Z, [&](int l) { return 16 * zo + (l & 15); },
+                 [&](int l, int e) { return 16 * zi + 4 * (l >> 4) + e; });
+    };
+    std::vector<float> g, s;
+    wide_q(g, 0, r.comb, R, Z, RG);
+    narrow_a(g, (size_t)4 * ZQ * RG, r.mu, Z, R, RG);
+    narrow_q(g, (size_t)8 * ZQ * RG, r.sig);
+    const QuadPlan plan = quad_plan(ZQ, HG);
+    s.resize((size_t)plan.head_chunks * CH * 256, 0.f);
+    wide_q(s, plan.gate1, r.gate1, H, Z, HG);
+    wide_q(s, plan.prop1, r.prop1, H, Z, HG);
+    narrow_q(s, plan.lin, r.lin);
+    narrow_a(s, plan.gate2, r.gate2, Z, H, HG);
+    narrow_a(s, plan.prop2, r.prop2, Z, H, HG);
+    narrow_q(s, plan.tscale, r.tscale);
+    wide_q(s, plan.emean1, r.emean1, H, Z, HG);
+    size_t at = (size_t)plan.head_chunks * CH;
+    for (int og = 0; og < NG; ++og) {
+        for (int t = 0; t < 16 * HG; ++t) {  // mean, second layer: tile (ig, b)
+            const int ig = t / 16, b = t % 16;
+            tile(s, at++, r.emean2, N, H, [&](int l) { return 64 * og + l; }, [&](int, int e) { return 64 * ig + 4 * b + e; });
+        }
+        for (int t = 0; t < 16 * HG; ++t) {  // scale network, first layer, input columns of group og: tile (b, hg)
+            const int b = t / HG, hg = t % HG;
+            tile(s, at++, r.escale1, H, N, [&](int l) { return 64 * hg + l; }, [&](int, int e) { return 64 * og + 4 * b + e; });
+        }
+    }
+    for (int og = 0; og < NG; ++og) {
+        for (int t = 0; t < 16 * HG; ++t) {
+            const int ig = t / 16, b = t % 16;
+            tile(s, at++, r.escale2, N, H, [&](int l) { return 64 * og + l; }, [&](int, int e) { return 64 * ig + 4 * b + e; });
+        }
+        at = (at + CH - 1) / CH * CH;  // a group starts on a chunk
+    }
+    s.resize(at * 256, 0.f);
+    m->quad_chunks = (int)(at / CH);
+    std::vector<float> bt;
+    auto add_bias = [&](const float *b, int n, int padded) {
+        const size_t base = bt.size();
+        bt.resize(base + (size_t)padded, 0.f);
+        for (int i = 0; i < n; ++i) bt[base + i] = b[i];
+    };
+    const int Z16 = 16 * ZQ, R64 = 64 * RG, H64 = 64 * HG, N64 = 64 * NG;
+    add_bias(r.b_comb, R, R64); add_bias(r.b_mu, Z, Z16); add_bias(r.b_sig, Z, Z16);
+    add_bias(r.b_gate1, H, H64); add_bias(r.b_gate2, Z, Z16); add_bias(r.b_prop1, H, H64); add_bias(r.b_prop2, Z, Z16);
+    add_bias(r.b_lin, Z, Z16); add_bias(r.b_tscale, Z, Z16); add_bias(r.b_emean1, H, H64); add_bias(r.b_escale1, H, H64);
+    add_bias(r.b_emean2, N, N64); add_bias(r.b_escale2, N, N64);
+    int rc = upload(m, bt.data(), bt.size(), &m->quad_bias);
+    if (rc == DKF_OK) rc = upload(m, g.data(), g.size(), &m->quad_guide);
+    if (rc == DKF_OK) rc = upload(m, s.data(), s.size(), &m->quad_stream);
+    return rc;
+}
+
 // `input`: where the step's observation + control block is read from (pinned host staging or d_in)
 FilterArgs filter_args(const dkf_model *m, const float *input) {
     FilterArgs a;
@@ -330,14 +421,26 @@ int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *ds
 
 int copy_ctx(dkf_model *m, float *dst, hipStream_t stream);
 
+// Up to this many samples the four-per-wavefront sampler is used where both are available (at
+// 16 per wavefront, 16384 samples are what fills every SIMD of the chip once).
+constexpr int kQuadMaxSamples = 8192;
+
 int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
+    // few samples: four per wavefront, so that they still spread over the whole chip
+    const bool quad = m->sampler == DKF_SAMPLER_WAVE4 ||
+                      (m->sampler == DKF_SAMPLER_AUTO && m->use_quad && (S <= kQuadMaxSamples || !m->use_chain));
     ChainArgs c{};
     c.ctl = m->ctl_dev();
     c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
-    c.guide_tiles = m->chain_guide; c.stream_tiles = m->chain_stream; c.stream_chunks = m->chain_chunks;
+    if (quad) {
+        c.guide_tiles = m->quad_guide; c.stream_tiles = m->quad_stream; c.stream_chunks = m->quad_chunks;
+        c.bias_table = m->quad_bias;
+    } else {
+        c.guide_tiles = m->chain_guide; c.stream_tiles = m->chain_stream; c.stream_chunks = m->chain_chunks;
+        c.bias_table = m->chain_bias;
+    }
     c.z0 = m->z0;
-    c.bias_table = m->chain_bias;
     c.eps_q = eps_q; c.eps_z = eps_z; c.eps_x = eps_x;
     c.mean = m->mean; c.ld_mean = m->Np;
     c.out_samples = out_samples;
@@ -348,7 +451,7 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.out_sd_dbg = st ? st->emit_sd : nullptr;
     c.S = S; c.L = m->L; c.Z = m->Z; c.R = m->R; c.H = m->H; c.N = m->N; c.NB = (m->N + 15) / 16;
     c.emit_mean_act = m->cfg.emit_mean_act;
-    const int rc = launch_chain(c, stream);
+    const int rc = quad ? launch_quad(c, stream) : launch_chain(c, stream);
     if (rc != DKF_OK) return rc;
     if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
     return DKF_OK;
@@ -364,7 +467,7 @@ int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStr
 
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
-    if (m->use_chain) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
+    if (m->sampler != DKF_SAMPLER_STAGED && (m->use_chain || m->use_quad)) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
     GuideArgs g;
     g.ctl = m->ctl_dev();
     g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
@@ -527,6 +630,8 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
 
     m->use_chain = !bf16 && chain_supported(Z, R, H, L, N);
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
+    m->use_quad = !bf16 && quad_supported(Z, R, H, L, N);
+    if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
 
     void *q = nullptr;
     DKF_CHECK(dev_alloc(m, m->in_floats() * 4, &q, true)); m->d_in = static_cast<float *>(q);
@@ -725,6 +830,15 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes) {
         if (rc != DKF_OK) return rc;
         DKF_HIP_TRY(hipDeviceSynchronize());
     }
+    return DKF_OK;
+}
+
+int dkf_set_sampler(dkf_model *m, int32_t variant) {
+    if (!m || variant < DKF_SAMPLER_AUTO || variant > DKF_SAMPLER_STAGED) return DKF_EINVAL;
+    if (variant == DKF_SAMPLER_WAVE16 && !m->use_chain) return DKF_EUNSUPPORTED;
+    if (variant == DKF_SAMPLER_WAVE4 && !m->use_quad) return DKF_EUNSUPPORTED;
+    if (variant != m->sampler) m->graph_S = 0;  // a captured decision graph holds the old kernels
+    m->sampler = variant;
     return DKF_OK;
 }
 

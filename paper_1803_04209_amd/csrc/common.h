@@ -172,6 +172,31 @@ __host__ __device__ constexpr int chain_chunk_tiles(int hb) { return hb >= 8 ? 3
 bool chain_supported(int Z, int R, int H, int L, int N);
 int launch_chain(const ChainArgs &a, hipStream_t stream);
 
+// quad.hip: the same chain with four samples per wavefront (small sample counts).  Same
+// arguments; guide_tiles / stream_tiles / bias_table are the quad packing (pack_quad, api.hip):
+// 1 KiB tiles of 64 lanes x float4; biases padded to 64 (R, H, N wide) or 16 (Z wide) per block.
+constexpr int kQuadChunkTiles = 32;
+// Tile positions of the transition layers and of the emission's first layer in the stream.  A
+// layer never straddles a chunk; Z -> Z layers take at least four tiles.
+struct QuadPlan {
+    int gate1, prop1, lin, gate2, prop2, tscale, emean1;
+    int head_chunks;  // chunks before the emission's N-wide layers
+};
+__host__ __device__ constexpr QuadPlan quad_plan(int zq, int hg) {
+    const int big = 4 * zq * hg, small = zq * zq < 4 ? 4 : zq * zq;
+    const int sizes[7] = {big, big, small, big, big, small, big};
+    int at[7] = {0, 0, 0, 0, 0, 0, 0};
+    int pos = 0;
+    for (int i = 0; i < 7; ++i) {
+        if (pos % kQuadChunkTiles + sizes[i] > kQuadChunkTiles) pos = (pos / kQuadChunkTiles + 1) * kQuadChunkTiles;
+        at[i] = pos;
+        pos += sizes[i];
+    }
+    return QuadPlan{at[0], at[1], at[2], at[3], at[4], at[5], at[6], (pos + kQuadChunkTiles - 1) / kQuadChunkTiles};
+}
+bool quad_supported(int Z, int R, int H, int L, int N);
+int launch_quad(const ChainArgs &a, hipStream_t stream);
+
 // noise.hip: out[0..n) = standard normals of stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x); the seed
 // is read from `ctl` when that is not NULL (captured graphs), else taken from `seed`
 int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl, uint64_t seed, hipStream_t stream);

@@ -32,10 +32,15 @@ def cuda(*arrays):
     return [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in arrays]
 
 
-def make_pair(api, cfg, weights=None, act=0, pushes=None, std=0.1, mlp_dtype=None):
+# kernel variants of the sampling stage (dkf_set_sampler): every one must meet the same tolerance
+WAVE16, WAVE4, STAGED = 1, 2, 3
+
+
+def make_pair(api, cfg, weights=None, act=0, pushes=None, std=0.1, mlp_dtype=None, sampler=0):
     w = synth.make_weights(cfg, std) if weights is None else weights
     blob = synth.pack_blob(cfg, w)
     g = api.Predictor(cfg, blob, emit_mean_act=act, mlp_dtype=mlp_dtype)
+    g.set_sampler(sampler)
     o = oracle.OracleModel(cfg, blob, emit_mean_act=act)
     tr = synth.make_trace(cfg)
     n = cfg.lag if pushes is None else pushes
@@ -85,9 +90,10 @@ def test_unaligned_sizes_every_stage(api, cfg, act):
     custom(N=100, L=4, Z=16, H=128, R=128, S=130), custom(N=1000, L=3, Z=32, H=256, R=256, S=40),
     custom(N=36, L=5, Z=8, H=20, R=24, S=16)], ids=["vec-tail", "scalar", "medium-like", "contended-like", "one-wave"])
 @pytest.mark.parametrize("act", [0, 1])
-def test_register_chained_sampler_tails(api, cfg, act):
-    """Sizes that take the fused sampler kernel with ragged worker blocks, pad features and partial waves."""
-    g, o, _ = make_pair(api, cfg, act=act, std=0.3)
+@pytest.mark.parametrize("sampler", [WAVE16, WAVE4, STAGED], ids=["wave16", "wave4", "staged"])
+def test_fused_sampler_tails(api, cfg, act, sampler):
+    """Sizes that the fused sampler kernels cover, with ragged worker blocks, pad features and partial waves."""
+    g, o, _ = make_pair(api, cfg, act=act, std=0.3, sampler=sampler)
     compare_stages(api, cfg, g, o)
     eq, ez, ex = synth.make_noise(cfg)
     x_plain = g.sample_runtimes(*cuda(eq, ez, ex))  # variant without the per-stage outputs
@@ -107,17 +113,19 @@ def test_tiny_preset_every_decision_position(api):
     g.close()
 
 
-def test_medium_preset_full_size(api):
+@pytest.mark.parametrize("sampler", [WAVE16, WAVE4], ids=["wave16", "wave4"])
+def test_medium_preset_full_size(api, sampler):
     cfg = synth.CONFIGS["medium"]
-    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 3)
+    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 3, sampler=sampler)
     compare_stages(api, cfg, g, o, rows=np.arange(0, cfg.samples, 8, dtype=np.int32))
     g.close()
 
 
 @pytest.mark.parametrize("name", ["contended", "replay"])
-def test_large_fp32_presets_sampled_rows(api, name):
+@pytest.mark.parametrize("sampler", [WAVE16, WAVE4], ids=["wave16", "wave4"])
+def test_large_fp32_presets_sampled_rows(api, name, sampler):
     cfg = synth.CONFIGS[name]
-    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2)
+    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2, sampler=sampler)
     rows = np.sort(np.random.default_rng(3).choice(cfg.samples, 192, replace=False)).astype(np.int32)
     rows[0], rows[-1] = 0, cfg.samples - 1
     x, errs = compare_stages(api, cfg, g, o, rows=rows)
@@ -333,3 +341,16 @@ def test_decide_graph_replays_match_eager(api, name):
             torch.cuda.synchronize()
     graph.close()
     eager.close()
+
+
+def test_sampler_variant_selection(api):
+    """A variant the model's sizes rule out is refused and the current one stays."""
+    cfg = custom(N=130, L=3, Z=70, H=129, R=200, S=33)  # latent too wide for both fused kernels
+    g = api.Predictor(cfg, synth.make_blob(cfg))
+    for v in (WAVE16, WAVE4):
+        with pytest.raises(api.DkfError):
+            g.set_sampler(v)
+    g.set_sampler(STAGED)
+    with pytest.raises(api.DkfError):
+        g.set_sampler(7)
+    g.close()
