@@ -61,36 +61,43 @@ __device__ __forceinline__ void static_for(F &&f) {
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 __device__ __forceinline__ f32x4 splat(float v) { f32x4 r = {v, v, v, v}; return r; }
 
+// A dependent v_mfma_f32_4x4x1 issues half a pass late (measured: 12.3 instead of 8.2 clocks), so
+// every product runs on two accumulators that take turns; the caller adds them at the end.
+struct Acc2 {
+    f32x4 a, b;
+    __device__ __forceinline__ void init(float first) { a = splat(first); b = splat(0.f); }
+    __device__ __forceinline__ f32x4 sum() const { return a + b; }
+};
 // one weight tile, wide layer, narrow (Q) input: input features 4*KG .. 4*KG+3 of the register
 template <int KG>
-__device__ __forceinline__ void tile_wide_q(f32x4 &acc, float q, f32x4 w) {
-    acc = mfma4<4, 4 * KG + 0>(q, w.x, acc);
-    acc = mfma4<4, 4 * KG + 1>(q, w.y, acc);
-    acc = mfma4<4, 4 * KG + 2>(q, w.z, acc);
-    acc = mfma4<4, 4 * KG + 3>(q, w.w, acc);
+__device__ __forceinline__ void tile_wide_q(Acc2 &acc, float q, f32x4 w) {
+    acc.a = mfma4<4, 4 * KG + 0>(q, w.x, acc.a);
+    acc.b = mfma4<4, 4 * KG + 1>(q, w.y, acc.b);
+    acc.a = mfma4<4, 4 * KG + 2>(q, w.z, acc.a);
+    acc.b = mfma4<4, 4 * KG + 3>(q, w.w, acc.b);
 }
 // one weight tile, wide layer, wide (A) input: features 4*B .. 4*B+3 of the 64-group
 template <int B>
-__device__ __forceinline__ void tile_wide_a(f32x4 &acc, f32x4 a, f32x4 w) {
-    acc = mfma4<4, B>(a.x, w.x, acc);
-    acc = mfma4<4, B>(a.y, w.y, acc);
-    acc = mfma4<4, B>(a.z, w.z, acc);
-    acc = mfma4<4, B>(a.w, w.w, acc);
+__device__ __forceinline__ void tile_wide_a(Acc2 &acc, f32x4 a, f32x4 w) {
+    acc.a = mfma4<4, B>(a.x, w.x, acc.a);
+    acc.b = mfma4<4, B>(a.y, w.y, acc.b);
+    acc.a = mfma4<4, B>(a.z, w.z, acc.a);
+    acc.b = mfma4<4, B>(a.w, w.w, acc.b);
 }
 // one weight tile, narrow layer, wide (A) input: group g covers features 16g + 4*QQ .. +3
 template <int QQ>
-__device__ __forceinline__ void tile_narrow_a(f32x4 &acc, f32x4 a, f32x4 w) {
-    acc = mfma4<2, QQ>(a.x, w.x, acc);
-    acc = mfma4<2, QQ>(a.y, w.y, acc);
-    acc = mfma4<2, QQ>(a.z, w.z, acc);
-    acc = mfma4<2, QQ>(a.w, w.w, acc);
+__device__ __forceinline__ void tile_narrow_a(Acc2 &acc, f32x4 a, f32x4 w) {
+    acc.a = mfma4<2, QQ>(a.x, w.x, acc.a);
+    acc.b = mfma4<2, QQ>(a.y, w.y, acc.b);
+    acc.a = mfma4<2, QQ>(a.z, w.z, acc.a);
+    acc.b = mfma4<2, QQ>(a.w, w.w, acc.b);
 }
 // one weight tile, narrow layer, narrow (Q) input: all 16 features (group g: 4g .. 4g+3)
-__device__ __forceinline__ void tile_narrow_q(f32x4 &acc, float q, f32x4 w) {
-    acc = mfma4<2, 0>(q, w.x, acc);
-    acc = mfma4<2, 1>(q, w.y, acc);
-    acc = mfma4<2, 2>(q, w.z, acc);
-    acc = mfma4<2, 3>(q, w.w, acc);
+__device__ __forceinline__ void tile_narrow_q(Acc2 &acc, float q, f32x4 w) {
+    acc.a = mfma4<2, 0>(q, w.x, acc.a);
+    acc.b = mfma4<2, 1>(q, w.y, acc.b);
+    acc.a = mfma4<2, 2>(q, w.z, acc.a);
+    acc.b = mfma4<2, 3>(q, w.w, acc.b);
 }
 
 __device__ __forceinline__ float dpp_xor1(float v) {  // quad_perm [1, 0, 3, 2]
@@ -134,15 +141,15 @@ struct QuadStream {
     typedef float Regs __attribute__((ext_vector_type(4 * kPerThread)));
     const f32x4 *src;
     f32x4 *buf;
-    int total, cur_chunk, cur_buf, tid;
-    Regs regs;
+    int total, cur_chunk, cur_buf, tid, rot;
+    Regs regs, first[NBUF - 1];  // `first` only lives from start_fetch() to start_commit()
 
     __device__ __forceinline__ Regs fetch(int chunk) const {
         if (chunk >= total) chunk = total - 1;  // past the end: refetch the last chunk (never used)
         Regs r;
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
-            const f32x4 t = src[(size_t)chunk * kChunkF4 + tid + i * kThreads];
+            const f32x4 t = src[(size_t)chunk * kChunkF4 + tid + ((i + rot) & (kPerThread - 1)) * kThreads];
             r[4 * i] = t.x; r[4 * i + 1] = t.y; r[4 * i + 2] = t.z; r[4 * i + 3] = t.w;
         }
         return r;
@@ -151,21 +158,22 @@ struct QuadStream {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const f32x4 t = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            buf[b * kChunkF4 + tid + i * kThreads] = t;
+            buf[b * kChunkF4 + tid + ((i + rot) & (kPerThread - 1)) * kThreads] = t;
         }
     }
-    __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int t) {
-        src = s; buf = b; total = n; tid = t; cur_chunk = 0; cur_buf = 0;
-        regs = fetch(0);
-        commit(regs, 0);
-        if constexpr (NBUF == 3) {
-            regs = fetch(1);
-            commit(regs, 1);
-            regs = fetch(2);
-        } else {
-            regs = fetch(1);
-        }
-        __syncthreads();
+    // The first NBUF chunks are requested together at the very start of the kernel (one L2 round
+    // trip, hidden behind the set-up of the other LDS tables) and land in LDS before the guide loop.
+    // Workgroups walk a chunk's 4 KiB slabs in rotated order so that the compute units of one XCD
+    // do not all ask the same L2 channel for the same lines at the same moment.
+    __device__ __forceinline__ void start_fetch(const f32x4 *s, f32x4 *b, int n, int t, int rotation) {
+        src = s; buf = b; total = n; tid = t; cur_chunk = 0; cur_buf = 0; rot = rotation & (kPerThread - 1);
+#pragma unroll
+        for (int c = 0; c < NBUF - 1; ++c) first[c] = fetch(c);
+        regs = fetch(NBUF - 1);
+    }
+    __device__ __forceinline__ void start_commit() {  // caller synchronises the workgroup afterwards
+#pragma unroll
+        for (int c = 0; c < NBUF - 1; ++c) commit(first[c], c);
     }
     __device__ __forceinline__ void advance() {
         ++cur_chunk;
@@ -180,27 +188,56 @@ struct QuadStream {
         }
         __syncthreads();
     }
+    // The same hand-over in eight pieces, one per 4 KiB slab, for callers that spread it over a
+    // chunk's matrix work: slab(i) for every i in 0..7 (any order), then advance_light().
+    __device__ __forceinline__ void slab(int i) {
+        const int target = cur_buf + NBUF - 1 >= NBUF ? cur_buf - 1 : cur_buf + NBUF - 1;
+        const int at = tid + ((i + rot) & (kPerThread - 1)) * kThreads;
+        const f32x4 t = {regs[4 * i], regs[4 * i + 1], regs[4 * i + 2], regs[4 * i + 3]};
+        buf[target * kChunkF4 + at] = t;
+        int chunk = cur_chunk + NBUF;
+        if (chunk >= total) chunk = total - 1;
+        const f32x4 n = src[(size_t)chunk * kChunkF4 + at];
+        regs[4 * i] = n.x; regs[4 * i + 1] = n.y; regs[4 * i + 2] = n.z; regs[4 * i + 3] = n.w;
+    }
+    __device__ __forceinline__ void advance_light() {
+        ++cur_chunk;
+        cur_buf = cur_buf + 1 == NBUF ? 0 : cur_buf + 1;
+        __syncthreads();
+    }
     __device__ __forceinline__ f32x4 tile(int t, int lane) const { return buf[cur_buf * kChunkF4 + t * kTileF4 + lane]; }
 };
 
-// use(ic<g>, tiles[4]) for every group of four consecutive tiles; the next group's tiles are
-// read from LDS while the current group feeds the matrix cores.
-template <int COUNT, typename LoadF, typename UseG>
-__device__ __forceinline__ void for_tile_quads(LoadF &&load, UseG &&use) {
+// use(ic<g>, tiles[4]) for every group of four consecutive tiles.  A SIMD receives LDS data at
+// 32 bytes per clock, i.e. one 1 KiB tile in the time its four matrix instructions take, so the
+// reads must never be waited for: the tiles of group g+2 are requested (and the request pinned
+// in place by scheduling fences) before group g is used -- two groups = 256 clocks of cover.
+template <int COUNT, typename LoadF, typename UseG, typename PreG>
+__device__ __forceinline__ void for_tile_quads(LoadF &&load, UseG &&use, PreG &&pre) {
     static_assert(COUNT % 4 == 0, "whole groups of four tiles");
     constexpr int kGroups = COUNT / 4;
-    f32x4 buf[2][4];
+    f32x4 buf[3][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) buf[0][j] = load(j);
+    if constexpr (kGroups > 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) buf[1][j] = load(4 + j);
+    }
     static_for<0, kGroups>([&](auto gc) {
         constexpr int g = decltype(gc)::value;
-        if constexpr (g + 1 < kGroups) {
+        if constexpr (g + 2 < kGroups) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) buf[(g + 1) & 1][j] = load((g + 1) * 4 + j);
+            for (int j = 0; j < 4; ++j) buf[(g + 2) % 3][j] = load((g + 2) * 4 + j);
         }
-        use(gc, buf[g & 1]);
+        pre(gc);
+        sched_fence();
+        use(gc, buf[g % 3]);
         sched_fence();
     });
+}
+template <int COUNT, typename LoadF, typename UseG>
+__device__ __forceinline__ void for_tile_quads(LoadF &&load, UseG &&use) {
+    for_tile_quads<COUNT>(load, use, [](auto) {});
 }
 
 template <int ZQ, int RG, int HG, int NBUF, bool DBG>
@@ -240,25 +277,76 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) d_sc[i] = s0 + i < S ? s0 + i : S - 1;
 
-    // guide weights, encodings and all biases -> LDS
+    QuadStream<NBUF> ws;
+    ws.start_fetch(reinterpret_cast<const f32x4 *>(a.stream_tiles), ring, a.stream_chunks, tid, blockIdx.x >> 3);
+    // Guide weights: small sets stay in registers for all L steps (every wavefront holds all of
+    // them: a SIMD receives LDS data no faster than its matrix pipe consumes it, so operands that
+    // are reused L times should not come from LDS); larger sets go to LDS.
+    constexpr bool kGuideRegs = kGuideTiles <= 20;
+    f32x4 gr[kGuideRegs ? kGuideTiles : 1];
+    if constexpr (kGuideRegs) {
+#pragma unroll
+        for (int i = 0; i < kGuideTiles; ++i) gr[i] = reinterpret_cast<const f32x4 *>(a.guide_tiles)[i * kTileF4 + lane];
+    }
+    // encodings and all biases (and the larger guide weight sets) -> LDS; loads are issued in
+    // batches ahead of the stores so that the memory round trips overlap
     {
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(a.guide_tiles);
-        for (int i = tid; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
+        if constexpr (!kGuideRegs) {
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(a.guide_tiles);
+            constexpr int n = kGuideTiles * kTileF4;
+            for (int base = 0; base < n; base += 8 * kThreads) {
+                f32x4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = base + tid + u * kThreads;
+                    v[u] = src[i < n ? i : n - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = base + tid + u * kThreads;
+                    if (i < n) gw[i] = v[u];
+                }
+            }
+        }
         // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
         // with tanh written as 1 - 2 r; features past R read as (1 + 0 + 0) / 3, which makes their
         // h_out exactly 0 (tanh(0) = 0)
-        for (int i = tid; i < a.L * R64; i += kThreads) {
-            const int t = i / R64, r = i % R64;
-            const float f = r < a.R ? a.ctx_f[(size_t)t * a.Rp + r] + a.ctx_b[(size_t)t * a.Rp + r] : 0.f;
-            ctx[i] = (f + 1.0f) * (1.0f / 3.0f);
+        const int nc = a.L * R64;
+        for (int base = 0; base < nc; base += 4 * kThreads) {
+            float f[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + tid + u * kThreads;
+                const int ic = i < nc ? i : nc - 1;
+                const int t = ic / R64, r = ic % R64, rc = r < a.R ? r : a.R - 1;
+                f[u] = a.ctx_f[(size_t)t * a.Rp + rc];
+                b[u] = a.ctx_b[(size_t)t * a.Rp + rc];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + tid + u * kThreads;
+                if (i < nc) ctx[i] = ((i % R64 < a.R ? f[u] + b[u] : 0.f) + 1.0f) * (1.0f / 3.0f);
+            }
         }
         const int nb = R64 + 6 * Z16 + 4 * H64 + 2 * N64;
-        for (int i = tid; i < nb; i += kThreads) bias[i] = a.bias_table[i];
+        for (int base = 0; base < nb; base += 4 * kThreads) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + tid + u * kThreads;
+                v[u] = a.bias_table[i < nb ? i : nb - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + tid + u * kThreads;
+                if (i < nb) bias[i] = v[u];
+            }
+        }
     }
+    ws.start_commit();
     __syncthreads();
-    const f32x4 *w_comb = gw;                 // [zq][kg][og]
-    const f32x4 *w_mu = gw + kCombTiles * kTileF4;  // [zq][ig][q]
-    const f32x4 *w_sig = w_mu + kMuTiles * kTileF4; // [zo][zi]
+    // guide tile t: comb [zq][kg][og] at 0, mu [zq][ig][q] at kCombTiles, sig [zo][zi] after that
+    auto gtile = [&](int t) { return kGuideRegs ? gr[kGuideRegs ? t : 0] : gw[t * kTileF4 + lane]; };
 
     auto load_p_noise = [&](const float *base, int zq) {  // base -> [S][Z]
         const int f = zq * 16 + pk;
@@ -293,50 +381,53 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
 #pragma unroll
         for (int zq = 0; zq < ZQ; ++zq) eps_next[zq] = load_p_noise(a.eps_q + (size_t)tn * S * Z, zq);
         // combiner: h_out = (tanh(W_c z + b) + h_left + h_right) / 3, tiles [zq][kg][og]
-        f32x4 acc[RG];
+        Acc2 acc[RG];
 #pragma unroll
-        for (int og = 0; og < RG; ++og) acc[og] = splat(b_comb[og]);
+        for (int og = 0; og < RG; ++og) acc[og].init(b_comb[og]);
         static_for<0, ZQ>([&](auto zc) {
             constexpr int zq = decltype(zc)::value;
             static_for<0, 4>([&](auto kc) {
                 constexpr int kg = decltype(kc)::value;
 #pragma unroll
                 for (int og = 0; og < RG; ++og)
-                    tile_wide_q<kg>(acc[og], zQ[zq], w_comb[((zq * 4 + kg) * RG + og) * kTileF4 + lane]);
+                    tile_wide_q<kg>(acc[og], zQ[zq], gtile((zq * 4 + kg) * RG + og));
             });
         });
         f32x4 hA[RG];
 #pragma unroll
         for (int og = 0; og < RG; ++og) {
             const float c = ctx[t * R64 + og * 64 + lane];
+            const f32x4 v = acc[og].sum();
             f32x4 h;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[i] = fast_rcp(__expf(2.0f * acc[og][i]) + 1.0f) * (-2.0f / 3.0f) + c;
+            for (int i = 0; i < 4; ++i) h[i] = fast_rcp(__expf(2.0f * v[i]) + 1.0f) * (-2.0f / 3.0f) + c;
             hA[og] = quad_transpose(h, odd1, odd2);
         }
         // mu = W_mu h_out + b, tiles [zq][ig][q]; two accumulators in turn
         float muP[ZQ], muQ[ZQ];
         static_for<0, ZQ>([&](auto zc) {
             constexpr int zq = decltype(zc)::value;
-            f32x4 n0 = splat(0.f), n1 = splat(0.f);
+            Acc2 n;
+            n.init(0.f);
             static_for<0, RG>([&](auto ic) {
                 constexpr int ig = decltype(ic)::value;
-                const f32x4 *w = w_mu + ((zq * RG + ig) * 4) * kTileF4 + lane;
-                tile_narrow_a<0>(n0, hA[ig], w[0 * kTileF4]);
-                tile_narrow_a<1>(n1, hA[ig], w[1 * kTileF4]);
-                tile_narrow_a<2>(n0, hA[ig], w[2 * kTileF4]);
-                tile_narrow_a<3>(n1, hA[ig], w[3 * kTileF4]);
+                constexpr int w = kCombTiles + (zq * RG + ig) * 4;
+                tile_narrow_a<0>(n, hA[ig], gtile(w + 0));
+                tile_narrow_a<1>(n, hA[ig], gtile(w + 1));
+                tile_narrow_a<2>(n, hA[ig], gtile(w + 2));
+                tile_narrow_a<3>(n, hA[ig], gtile(w + 3));
             });
-            muP[zq] = reduce_to_p(n0 + n1) + b_mu[zq];
+            muP[zq] = reduce_to_p(n.sum()) + b_mu[zq];
             muQ[zq] = to_q(muP[zq]);
         });
         // sigma = softplus(W_sigma mu + b), z = mu + sigma eps, tiles [zo][zi]
 #pragma unroll
         for (int zo = 0; zo < ZQ; ++zo) {
-            f32x4 n = splat(0.f);
+            Acc2 n;
+            n.init(0.f);
 #pragma unroll
-            for (int zi = 0; zi < ZQ; ++zi) tile_narrow_q(n, muQ[zi], w_sig[(zo * ZQ + zi) * kTileF4 + lane]);
-            const float pre = reduce_to_p(n) + b_sig[zo];
+            for (int zi = 0; zi < ZQ; ++zi) tile_narrow_q(n, muQ[zi], gtile(kCombTiles + kMuTiles + zo * ZQ + zi));
+            const float pre = reduce_to_p(n.sum()) + b_sig[zo];
             zP[zo] = muP[zo] + softplus_f(pre) * eps[zo];
             eps[zo] = eps_next[zo];
         }
@@ -347,8 +438,6 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
     for (int zq = 0; zq < ZQ; ++zq) store_p(a.z_last, zq, zP[zq]);
 
     // ---- streamed part: transition, then emission --------------------------------
-    QuadStream<NBUF> ws;
-    ws.start(reinterpret_cast<const f32x4 *>(a.stream_tiles), ring, a.stream_chunks, tid);
     int chunk_now = 0;  // compile-time after unrolling: chunk the stream is positioned at
     auto seek = [&](int chunk) {  // layers are laid out so that none straddles a chunk
         while (chunk_now < chunk) { ws.advance(); ++chunk_now; }
@@ -358,8 +447,9 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
     auto wide_from_q = [&](f32x4(&out)[HG], const float *tab, const float(&x)[ZQ], int pos) {
         seek(pos / CH);
         const int base = pos % CH;
+        Acc2 acc[HG];
 #pragma unroll
-        for (int og = 0; og < HG; ++og) out[og] = splat(tab[og * 64 + lane]);
+        for (int og = 0; og < HG; ++og) acc[og].init(tab[og * 64 + lane]);
         // groups of four tiles: (zq, kg) major, og minor
         for_tile_quads<4 * ZQ * HG>([&](int i) { return ws.tile(base + i, lane); },
                                     [&](auto gc, const f32x4(&tl)[4]) {
@@ -367,28 +457,30 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
                                         static_for<0, 4>([&](auto jc) {
                                             constexpr int idx = g * 4 + decltype(jc)::value;
                                             constexpr int og = idx % HG, kk = idx / HG;  // kk = zq * 4 + kg
-                                            tile_wide_q<kk % 4>(out[og], x[kk / 4], tl[decltype(jc)::value]);
+                                            tile_wide_q<kk % 4>(acc[og], x[kk / 4], tl[decltype(jc)::value]);
                                         });
                                     });
+#pragma unroll
+        for (int og = 0; og < HG; ++og) out[og] = acc[og].sum();
     };
     // out (P, per zq) = W h + b for a wide -> narrow layer, tiles [zq][ig][q]
     auto narrow_from_a = [&](float(&out)[ZQ], const float *tab, const f32x4(&x)[HG], int pos) {
         seek(pos / CH);
         const int base = pos % CH;
-        f32x4 n0[ZQ], n1[ZQ];
+        Acc2 n[ZQ];
 #pragma unroll
-        for (int zq = 0; zq < ZQ; ++zq) n0[zq] = n1[zq] = splat(0.f);
+        for (int zq = 0; zq < ZQ; ++zq) n[zq].init(0.f);
         for_tile_quads<4 * ZQ * HG>([&](int i) { return ws.tile(base + i, lane); },
                                     [&](auto gc, const f32x4(&tl)[4]) {
                                         constexpr int g = decltype(gc)::value;
                                         constexpr int zq = g / HG, ig = g % HG;
-                                        tile_narrow_a<0>(n0[zq], x[ig], tl[0]);
-                                        tile_narrow_a<1>(n1[zq], x[ig], tl[1]);
-                                        tile_narrow_a<2>(n0[zq], x[ig], tl[2]);
-                                        tile_narrow_a<3>(n1[zq], x[ig], tl[3]);
+                                        tile_narrow_a<0>(n[zq], x[ig], tl[0]);
+                                        tile_narrow_a<1>(n[zq], x[ig], tl[1]);
+                                        tile_narrow_a<2>(n[zq], x[ig], tl[2]);
+                                        tile_narrow_a<3>(n[zq], x[ig], tl[3]);
                                     });
 #pragma unroll
-        for (int zq = 0; zq < ZQ; ++zq) out[zq] = reduce_to_p(n0[zq] + n1[zq]) + tab[zq * 16 + pk];
+        for (int zq = 0; zq < ZQ; ++zq) out[zq] = reduce_to_p(n[zq].sum()) + tab[zq * 16 + pk];
     };
     // out (P) = W x + b for a narrow -> narrow layer, tiles [zo][zi] (padded to a multiple of four)
     auto small_layer = [&](float(&out)[ZQ], const float *tab, const float(&x)[ZQ], int pos) {
@@ -396,10 +488,11 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
         const int base = pos % CH;
 #pragma unroll
         for (int zo = 0; zo < ZQ; ++zo) {
-            f32x4 n = splat(0.f);
+            Acc2 n;
+            n.init(0.f);
 #pragma unroll
             for (int zi = 0; zi < ZQ; ++zi) tile_narrow_q(n, x[zi], ws.tile(base + zo * ZQ + zi, lane));
-            out[zo] = reduce_to_p(n) + tab[zo * 16 + pk];
+            out[zo] = reduce_to_p(n.sum()) + tab[zo * 16 + pk];
         }
     };
     auto to_a = [&](f32x4(&dst)[HG], const f32x4(&src)[HG], bool relu) {
@@ -456,26 +549,28 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
     // HG*16 tiles of the scale network's first layer (column group og)
     constexpr int kSegs = HG < 2 ? 1 : HG / 2;  // 32-tile chunks per 16*HG tiles
     constexpr int kSegTiles = HG < 2 ? 16 : 32;
-    f32x4 h2[HG];
+    Acc2 h2[HG];
 #pragma unroll
-    for (int hg = 0; hg < HG; ++hg) h2[hg] = splat(lb_escale1[hg * 64 + lane]);
+    for (int hg = 0; hg < HG; ++hg) h2[hg].init(lb_escale1[hg * 64 + lane]);
     float *sink = a.sink + tid;
     for (int og = 0; og < NG; ++og) {
         const int col = og * 64 + lane;
-        f32x4 m0 = splat(lb_emean2[col]), m1 = splat(0.f);
+        Acc2 macc;
+        macc.init(lb_emean2[col]);
         static_for<0, kSegs>([&](auto sc) {
             constexpr int seg = decltype(sc)::value;
             for_tile_quads<kSegTiles>([&](int i) { return ws.tile(i, lane); },
                                       [&](auto gc, const f32x4(&tl)[4]) {
                                           constexpr int t0 = seg * kSegTiles + decltype(gc)::value * 4;  // tile = ig*16 + b
-                                          tile_wide_a<(t0 + 0) % 16>(m0, h1A[(t0 + 0) / 16], tl[0]);
-                                          tile_wide_a<(t0 + 1) % 16>(m1, h1A[(t0 + 1) / 16], tl[1]);
-                                          tile_wide_a<(t0 + 2) % 16>(m0, h1A[(t0 + 2) / 16], tl[2]);
-                                          tile_wide_a<(t0 + 3) % 16>(m1, h1A[(t0 + 3) / 16], tl[3]);
-                                      });
-            if constexpr (HG >= 2) ws.advance();
+                                          tile_wide_a<(t0 + 0) % 16>(macc, h1A[(t0 + 0) / 16], tl[0]);
+                                          tile_wide_a<(t0 + 1) % 16>(macc, h1A[(t0 + 1) / 16], tl[1]);
+                                          tile_wide_a<(t0 + 2) % 16>(macc, h1A[(t0 + 2) / 16], tl[2]);
+                                          tile_wide_a<(t0 + 3) % 16>(macc, h1A[(t0 + 3) / 16], tl[3]);
+                                      },
+                                      [&](auto gc) { ws.slab(decltype(gc)::value); });  // HG = 1: slabs 0..3
+            if constexpr (HG >= 2) ws.advance_light();
         });
-        const f32x4 mean = m0 + m1;
+        const f32x4 mean = macc.sum();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float *dst = col < N ? a.mean + (size_t)d_sc[i] * a.ld_mean + col : sink;
@@ -493,13 +588,19 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
                                           tile_wide_a<(t0 + 1) / HG>(h2[(t0 + 1) % HG], mA, tl[1]);
                                           tile_wide_a<(t0 + 2) / HG>(h2[(t0 + 2) % HG], mA, tl[2]);
                                           tile_wide_a<(t0 + 3) / HG>(h2[(t0 + 3) % HG], mA, tl[3]);
-                                      });
-            if constexpr (HG >= 2) ws.advance();
+                                      },
+                                      [&](auto gc) { ws.slab((HG < 2 ? 4 : 0) + decltype(gc)::value); });
+            if constexpr (HG >= 2) ws.advance_light();
         });
-        if constexpr (HG < 2) ws.advance();
+        if constexpr (HG < 2) ws.advance_light();
     }
     f32x4 h2A[HG];
-    to_a(h2A, h2, true);
+    {
+        f32x4 d[HG];
+#pragma unroll
+        for (int hg = 0; hg < HG; ++hg) d[hg] = h2[hg].sum();
+        to_a(h2A, d, true);
+    }
 
     // scale, draw, back to seconds: per group og HG*16 tiles of the scale network's second layer
     const float scale = a.ctl->scale;
@@ -512,20 +613,26 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
             e[i] = a.eps_x[(size_t)d_sc[i] * N + colc];
             m[i] = a.mean[(size_t)d_sc[i] * a.ld_mean + colc];
         }
-        f32x4 p0 = splat(lb_escale2[col]), p1 = splat(0.f);
+        Acc2 pacc;
+        pacc.init(lb_escale2[col]);
         static_for<0, kSegs>([&](auto sc) {
             constexpr int seg = decltype(sc)::value;
             for_tile_quads<kSegTiles>([&](int i) { return ws.tile(i, lane); },
                                       [&](auto gc, const f32x4(&tl)[4]) {
                                           constexpr int t0 = seg * kSegTiles + decltype(gc)::value * 4;
-                                          tile_wide_a<(t0 + 0) % 16>(p0, h2A[(t0 + 0) / 16], tl[0]);
-                                          tile_wide_a<(t0 + 1) % 16>(p1, h2A[(t0 + 1) / 16], tl[1]);
-                                          tile_wide_a<(t0 + 2) % 16>(p0, h2A[(t0 + 2) / 16], tl[2]);
-                                          tile_wide_a<(t0 + 3) % 16>(p1, h2A[(t0 + 3) / 16], tl[3]);
+                                          tile_wide_a<(t0 + 0) % 16>(pacc, h2A[(t0 + 0) / 16], tl[0]);
+                                          tile_wide_a<(t0 + 1) % 16>(pacc, h2A[(t0 + 1) / 16], tl[1]);
+                                          tile_wide_a<(t0 + 2) % 16>(pacc, h2A[(t0 + 2) / 16], tl[2]);
+                                          tile_wide_a<(t0 + 3) % 16>(pacc, h2A[(t0 + 3) / 16], tl[3]);
+                                      },
+                                      [&](auto gc) {
+                                          constexpr int g = decltype(gc)::value;
+                                          if constexpr (HG < 2) { ws.slab(2 * g); ws.slab(2 * g + 1); }  // 4 groups per chunk
+                                          else ws.slab(g);
                                       });
-            ws.advance();
+            ws.advance_light();
         });
-        const f32x4 pre = p0 + p1;
+        const f32x4 pre = pacc.sum();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float sd = softplus_f(pre[i]);
