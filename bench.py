@@ -42,7 +42,7 @@ def stage_work(cfg):
 
 # Sources whose change invalidates stored hardware-counter readings of a stage's kernel.
 STAGE_SOURCES = {
-    "sampler_fused": ["chain.hip", "common.h", "mfma_tile.h"],
+    "sampler_fused": ["chain.hip", "quad.hip", "common.h", "mfma_tile.h"],
     "sort_rank_sums": ["cutoff_select.hip", "common.h"],
 }
 

@@ -263,40 +263,45 @@ constexpr int kMeanParts = 16;  // second-level partial sums per rank
 
 // part2[p][c] = sum over blocks b = 4p + sub (mod 64) of partial[b][c], fp64, fixed order.
 // grid: (ceil(N/64), kMeanParts); 64 ranks x 4 interleaved block subsets per workgroup.
+// sum over blocks b = first, first + 64, ... of partial[b][col]
+__device__ __forceinline__ double block_subset_sum(const float *__restrict__ partial, int blocks, int npad, int col,
+                                                   int first) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    const int stride = kMeanParts * 4;
+    int b = first;
+    for (; b + 3 * stride < blocks; b += 4 * stride) {  // four independent loads in flight
+        const float v0 = partial[(size_t)b * npad + col];
+        const float v1 = partial[(size_t)(b + stride) * npad + col];
+        const float v2 = partial[(size_t)(b + 2 * stride) * npad + col];
+        const float v3 = partial[(size_t)(b + 3 * stride) * npad + col];
+        s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
+    }
+    for (; b < blocks; b += stride) s0 += (double)partial[(size_t)b * npad + col];
+    return (s0 + s1) + (s2 + s3);
+}
+
 __global__ __launch_bounds__(256) void rank_partial_sums(const float *__restrict__ partial, int blocks, int npad,
                                                          int N, double *__restrict__ part2) {
     __shared__ double red[4][64];
     const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6;
     const int col = blockIdx.x * 64 + lane;
     const int first = blockIdx.y * 4 + sub;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    if (col < N) {
-        const int stride = kMeanParts * 4;
-        int b = first;
-        for (; b + 3 * stride < blocks; b += 4 * stride) {  // four independent loads in flight
-            const float v0 = partial[(size_t)b * npad + col];
-            const float v1 = partial[(size_t)(b + stride) * npad + col];
-            const float v2 = partial[(size_t)(b + 2 * stride) * npad + col];
-            const float v3 = partial[(size_t)(b + 3 * stride) * npad + col];
-            s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
-        }
-        for (; b < blocks; b += stride) s0 += (double)partial[(size_t)b * npad + col];
-    }
-    red[sub][lane] = (s0 + s1) + (s2 + s3);
+    red[sub][lane] = col < N ? block_subset_sum(partial, blocks, npad, col, first) : 0.0;
     __syncthreads();
     if (sub == 0 && col < N)
         part2[(size_t)blockIdx.y * N + col] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
 }
 
-// Omega(c) = c / mean[c] where eligible; c* = largest maximiser.
-__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ part2, int N, int S, int c_min,
-                                                    int c_max, float t_floor, float *__restrict__ out_mean,
-                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar) {
-    __shared__ double best_v[256];
-    __shared__ int best_c[256];
+// Omega(c) = c / mean[c] where eligible; c* = largest maximiser.  One workgroup of THREADS
+// threads; part2 may live in global memory or in LDS.
+template <int THREADS>
+__device__ __forceinline__ void omega_argmax_body(const double *part2, int N, int S, int c_min, int c_max,
+                                                  float t_floor, float *__restrict__ out_mean,
+                                                  float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
+                                                  double *best_v, int *best_c) {
     double bv = -INFINITY;
     int bc = 0;
-    for (int c = threadIdx.x + 1; c <= N; c += 256) {
+    for (int c = threadIdx.x + 1; c <= N; c += THREADS) {
         double sum = 0.0;
 #pragma unroll
         for (int p = 0; p < kMeanParts; ++p) sum += part2[(size_t)p * N + c - 1];
@@ -310,7 +315,7 @@ __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ p
     best_v[threadIdx.x] = bv;
     best_c[threadIdx.x] = bc;
     __syncthreads();
-    for (int d = 128; d > 0; d >>= 1) {
+    for (int d = THREADS / 2; d > 0; d >>= 1) {
         if ((int)threadIdx.x < d) {
             const double ov = best_v[threadIdx.x + d];
             const int oc = best_c[threadIdx.x + d];
@@ -326,6 +331,41 @@ __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ p
         out_cstar[0] = none ? c_max : best_c[0];
         out_cstar[1] = none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
     }
+}
+
+__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ part2, int N, int S, int c_min,
+                                                    int c_max, float t_floor, float *__restrict__ out_mean,
+                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar) {
+    __shared__ double best_v[256];
+    __shared__ int best_c[256];
+    omega_argmax_body<256>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v, best_c);
+}
+
+// Both reduction levels and the argmax in one workgroup, for the smallest problems (a few KiB of
+// per-block sums): the same sums in the same order as the two kernels above.  (A single launch
+// in which the last workgroup to finish does the argmax was measured slower at every size: making
+// one workgroup's sums visible to another inside a kernel costs a write-back of the XCD's L2.)
+constexpr int kFusedMeansMaxN = 128;
+constexpr int kFusedThreads = 1024;
+__global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *__restrict__ partial, int blocks,
+                                                                   int npad, int N, int S, int c_min, int c_max,
+                                                                   float t_floor, float *__restrict__ out_mean,
+                                                                   float *__restrict__ out_omega,
+                                                                   int32_t *__restrict__ out_cstar) {
+    __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N]
+    __shared__ double best_v[kFusedThreads];
+    __shared__ int best_c[kFusedThreads];
+    for (int i = threadIdx.x; i < kMeanParts * N; i += kFusedThreads) {
+        const int col = i % N, p = i / N;
+        const double r0 = block_subset_sum(partial, blocks, npad, col, 4 * p + 0);
+        const double r1 = block_subset_sum(partial, blocks, npad, col, 4 * p + 1);
+        const double r2 = block_subset_sum(partial, blocks, npad, col, 4 * p + 2);
+        const double r3 = block_subset_sum(partial, blocks, npad, col, 4 * p + 3);
+        part2[i] = ((r0 + r1) + r2) + r3;
+    }
+    __syncthreads();
+    omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
+                                     best_c);
 }
 
 struct SortPlan {
@@ -412,12 +452,18 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     }
     {
         StageTimer timer(kStageArgmax, stream);
-        hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
-                           p.blocks, p.npad, N, part2);
-        DKF_HIP_TRY(hipGetLastError());
-        hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, part2, N, S, c_min, c_max, t_floor, out_mean,
-                           out_omega, out_cstar);
-        DKF_HIP_TRY(hipGetLastError());
+        if (N <= kFusedMeansMaxN && (size_t)p.blocks * N <= 8192) {
+            hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
+                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar);
+            DKF_HIP_TRY(hipGetLastError());
+        } else {
+            hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
+                               p.blocks, p.npad, N, part2);
+            DKF_HIP_TRY(hipGetLastError());
+            hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, part2, N, S, c_min, c_max, t_floor,
+                               out_mean, out_omega, out_cstar);
+            DKF_HIP_TRY(hipGetLastError());
+        }
     }
     return DKF_OK;
 }
