@@ -345,7 +345,9 @@ __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ p
 // per-block sums): the same sums in the same order as the two kernels above.  (A single launch
 // in which the last workgroup to finish does the argmax was measured slower at every size: making
 // one workgroup's sums visible to another inside a kernel costs a write-back of the XCD's L2.)
-constexpr int kFusedMeansMaxN = 128;
+constexpr int kFusedMeansMaxN = 128;          // widest row the one-workgroup reduction takes
+constexpr int kFusedMeansMaxSums = 8192;      // most per-block sums it takes (blocks x N)
+
 constexpr int kFusedThreads = 1024;
 __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *__restrict__ partial, int blocks,
                                                                    int npad, int N, int S, int c_min, int c_max,
@@ -452,7 +454,7 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     }
     {
         StageTimer timer(kStageArgmax, stream);
-        if (N <= kFusedMeansMaxN && (size_t)p.blocks * N <= 8192) {
+        if (N <= kFusedMeansMaxN && p.blocks * N <= kFusedMeansMaxSums) {
             hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
                                p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar);
             DKF_HIP_TRY(hipGetLastError());

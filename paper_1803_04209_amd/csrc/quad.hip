@@ -277,6 +277,17 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) d_sc[i] = s0 + i < S ? s0 + i : S - 1;
 
+    // everything the first guide step needs from global memory is requested up front, together
+    // with the weight stream's first chunks, so that the round trips overlap
+    float zQ[ZQ], eps[ZQ];
+#pragma unroll
+    for (int zq = 0; zq < ZQ; ++zq) {
+        const int fq = zq * 16 + qk, fp = zq * 16 + pk;
+        const float z0v = a.z0[fq < Z ? fq : Z - 1];
+        const float ev = a.eps_q[(size_t)p_sc * Z + (fp < Z ? fp : Z - 1)];
+        zQ[zq] = fq < Z ? z0v : 0.f;
+        eps[zq] = fp < Z ? ev : 0.f;
+    }
     QuadStream<NBUF> ws;
     ws.start_fetch(reinterpret_cast<const f32x4 *>(a.stream_tiles), ring, a.stream_chunks, tid, blockIdx.x >> 3);
     // Guide weights: small sets stay in registers for all L steps (every wavefront holds all of
@@ -312,35 +323,54 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
         // with tanh written as 1 - 2 r; features past R read as (1 + 0 + 0) / 3, which makes their
         // h_out exactly 0 (tanh(0) = 0)
         const int nc = a.L * R64;
-        for (int base = 0; base < nc; base += 4 * kThreads) {
-            float f[4], b[4];
+        const int nb = R64 + 6 * Z16 + 4 * H64 + 2 * N64;
+        auto load_ctx = [&](int base, float(&f)[8], float(&b)[8]) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const int i = base + tid + u * kThreads;
                 const int ic = i < nc ? i : nc - 1;
                 const int t = ic / R64, r = ic % R64, rc = r < a.R ? r : a.R - 1;
                 f[u] = a.ctx_f[(size_t)t * a.Rp + rc];
                 b[u] = a.ctx_b[(size_t)t * a.Rp + rc];
             }
+        };
+        auto store_ctx = [&](int base, const float(&f)[8], const float(&b)[8]) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const int i = base + tid + u * kThreads;
                 if (i < nc) ctx[i] = ((i % R64 < a.R ? f[u] + b[u] : 0.f) + 1.0f) * (1.0f / 3.0f);
             }
-        }
-        const int nb = R64 + 6 * Z16 + 4 * H64 + 2 * N64;
-        for (int base = 0; base < nb; base += 4 * kThreads) {
-            float v[4];
+        };
+        auto load_bias = [&](int base, float(&v)[4]) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int i = base + tid + u * kThreads;
                 v[u] = a.bias_table[i < nb ? i : nb - 1];
             }
+        };
+        auto store_bias = [&](int base, const float(&v)[4]) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int i = base + tid + u * kThreads;
                 if (i < nb) bias[i] = v[u];
             }
+        };
+        {   // first batch of both tables in one round trip; the common sizes need no second
+            float f[8], b[8], v[4];
+            load_ctx(0, f, b);
+            load_bias(0, v);
+            store_ctx(0, f, b);
+            store_bias(0, v);
+        }
+        for (int base = 8 * kThreads; base < nc; base += 8 * kThreads) {
+            float f[8], b[8];
+            load_ctx(base, f, b);
+            store_ctx(base, f, b);
+        }
+        for (int base = 4 * kThreads; base < nb; base += 4 * kThreads) {
+            float v[4];
+            load_bias(base, v);
+            store_bias(base, v);
         }
     }
     ws.start_commit();
@@ -359,12 +389,6 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
         if (p_smp < S && f < Z) dst[(size_t)p_smp * Z + f] = v;
     };
 
-    float zQ[ZQ];
-#pragma unroll
-    for (int zq = 0; zq < ZQ; ++zq) {
-        const int f = zq * 16 + qk;
-        zQ[zq] = f < Z ? a.z0[f] : 0.f;
-    }
     float b_comb[RG], b_mu[ZQ], b_sig[ZQ];
 #pragma unroll
     for (int og = 0; og < RG; ++og) b_comb[og] = lb_comb[og * 64 + lane];
@@ -372,9 +396,9 @@ __global__ __launch_bounds__(kThreads) void sample_quad(ChainArgs a) {
     for (int zq = 0; zq < ZQ; ++zq) { b_mu[zq] = lb_mu[zq * 16 + pk]; b_sig[zq] = lb_sig[zq * 16 + pk]; }
 
     // ---- guide chain ------------------------------------------------------------
-    float zP[ZQ], eps[ZQ];
+    float zP[ZQ];
 #pragma unroll
-    for (int zq = 0; zq < ZQ; ++zq) { eps[zq] = load_p_noise(a.eps_q, zq); zP[zq] = 0.f; }
+    for (int zq = 0; zq < ZQ; ++zq) zP[zq] = 0.f;
     for (int t = 0; t < a.L; ++t) {
         float eps_next[ZQ];  // next step's noise is fetched while this step computes
         const int tn = t + 1 < a.L ? t + 1 : t;
