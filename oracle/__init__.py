@@ -7,12 +7,16 @@ this package; the GPU library never does.
 from .binding import (  # noqa: F401
     OracleModel,
     build,
+    cutoff_elfving,
     cutoff_select,
+    elfving_mean,
     fill_normal,
+    impute_censored,
     make_noise,
     philox4x32_10,
     num_threads,
     set_threads,
+    trace_throughput,
     NO_ELIGIBLE,
     OK,
     WARMUP,

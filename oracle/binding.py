@@ -59,6 +59,12 @@ def _load():
     lib.oracle_predict_cutoff.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_double, ip]
     lib.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     lib.oracle_fill_normal.argtypes = [C.c_uint64, C.c_uint32, C.c_size_t, fp]
+    u8 = C.POINTER(C.c_uint8)
+    lib.oracle_impute_censored.argtypes = [fp, C.c_int, C.c_int, fp, u8, C.c_float, fp, fp, ip]
+    lib.oracle_elfving_mean.restype = C.c_double
+    lib.oracle_elfving_mean.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double]
+    lib.oracle_cutoff_elfving.argtypes = [C.c_int, C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, dp, dp, ip]
+    lib.oracle_trace_throughput.argtypes = [dp, C.c_int, C.c_int, ip, dp]
     lib.oracle_num_threads.restype = C.c_int
     lib.oracle_set_threads.argtypes = [C.c_int]
     _lib = lib
@@ -209,3 +215,47 @@ def cutoff_select(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=True, w
     if rc < 0:
         raise ValueError(f"oracle_cutoff_select: error {rc}")
     return dict(status=rc, cstar=int(cstar[0]), mean=mean, omega=omega, sorted=srt, perm=perm)
+
+
+def impute_censored(samples, x_obs, censored, tau, u):
+    """Fill in the run-times of dropped workers from the draws that exceed the censoring time.
+    Returns (x_full float32[N], n_exceed int32[N])."""
+    a = np.ascontiguousarray(samples, dtype=np.float32)
+    S, N = a.shape
+    xo = np.ascontiguousarray(x_obs, dtype=np.float32)
+    cm = np.ascontiguousarray(censored, dtype=np.uint8)
+    uu = np.ascontiguousarray(u, dtype=np.float32)
+    out = np.empty(N, dtype=np.float32)
+    cnt = np.empty(N, dtype=np.int32)
+    rc = _load().oracle_impute_censored(_fp(a), S, N, _fp(xo), cm.ctypes.data_as(C.POINTER(C.c_uint8)), float(tau),
+                                        _fp(uu), _fp(out), _ip(cnt))
+    if rc < 0:
+        raise ValueError(f"oracle_impute_censored: error {rc}")
+    return out, cnt
+
+
+def elfving_mean(j: int, n: int, mu: float, sigma: float) -> float:
+    return float(_load().oracle_elfving_mean(j, n, mu, sigma))
+
+
+def cutoff_elfving(n, mu, sigma, c_min=1, c_max=None, t_floor=0.0):
+    c_max = n if c_max is None else c_max
+    mean, omega = np.empty(n), np.empty(n)
+    cstar = np.zeros(1, dtype=np.int32)
+    rc = _load().oracle_cutoff_elfving(n, float(mu), float(sigma), c_min, c_max, float(t_floor), _dp(mean), _dp(omega),
+                                       _ip(cstar))
+    if rc < 0:
+        raise ValueError(f"oracle_cutoff_elfving: error {rc}")
+    return dict(status=rc, cstar=int(cstar[0]), mean=mean, omega=omega)
+
+
+def trace_throughput(trace, cutoffs):
+    """(achieved, full-sync, hindsight-best) gradients per second over a trace [T][N]."""
+    tr = np.ascontiguousarray(trace, dtype=np.float64)
+    T, N = tr.shape
+    cs = np.ascontiguousarray(cutoffs, dtype=np.int32)
+    out = np.empty(3)
+    rc = _load().oracle_trace_throughput(_dp(tr), T, N, _ip(cs), _dp(out))
+    if rc < 0:
+        raise ValueError(f"oracle_trace_throughput: error {rc}")
+    return tuple(float(v) for v in out)

@@ -448,3 +448,130 @@ int oracle_predict_cutoff(const oracle_model *m, int S, const float *eps_q, cons
     free(x);
     return rc;
 }
+
+/* ---------------------------------------------------------------------------
+ * Censored run-times (Sec. 4.2, "Handling Censored Run-times").
+ *
+ * After a cutoff the server has killed the stragglers, so their run-times are
+ * only known to exceed the censoring time tau = the c-th arrival.  The filter
+ * needs a full vector, so every dropped worker gets a value drawn from its
+ * predictive run-time distribution left-truncated at tau (the display of
+ * Sec. 4.2).
+ * READING: the predictive distribution of worker w is represented by the S
+ * Monte-Carlo draws samples[.][w] made for this iteration; the truncated
+ * distribution is therefore the empirical distribution of the draws that
+ * exceed tau, and one of them is picked with the supplied uniform number:
+ * the floor(u * m)-th in sample order, m = number of exceeding draws.
+ * READING: if no draw exceeds tau the smallest value consistent with the
+ * censoring, tau itself, is used.
+ * Observed workers keep their observed value.  n_exceed (optional) receives
+ * m for dropped workers and -1 for observed ones.
+ */
+int oracle_impute_censored(const float *samples, int S, int N, const float *x_obs, const uint8_t *censored,
+                           float tau, const float *u, float *x_full, int32_t *n_exceed) {
+    if (!samples || !x_obs || !censored || !u || !x_full || S < 1 || N < 1) return ORACLE_EINVAL;
+    for (int w = 0; w < N; ++w) {
+        if (!censored[w]) {
+            x_full[w] = x_obs[w];
+            if (n_exceed) n_exceed[w] = -1;
+            continue;
+        }
+        if (!(u[w] >= 0.0f && u[w] < 1.0f)) return ORACLE_EINVAL;
+        int m = 0;
+        for (int k = 0; k < S; ++k)
+            if (samples[(size_t)k * N + w] > tau) ++m;
+        if (n_exceed) n_exceed[w] = m;
+        if (m == 0) { x_full[w] = tau; continue; }
+        long pick = (long)floor((double)u[w] * (double)m);
+        if (pick > m - 1) pick = m - 1;
+        long seen = 0;
+        for (int k = 0; k < S; ++k) {
+            float v = samples[(size_t)k * N + w];
+            if (v > tau) {
+                if (seen == pick) { x_full[w] = v; break; }
+                ++seen;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ---------------------------------------------------------------------------
+ * Comparison cutoffs (Sec. 3.1.1 and Sec. 4).
+ *
+ * Standard normal quantile by bisection on the distribution function
+ * Phi(x) = erfc(-x / sqrt 2) / 2: slow and obviously right. */
+static double normal_quantile(double p) {
+    if (!(p > 0.0)) return -INFINITY;
+    if (!(p < 1.0)) return INFINITY;
+    double lo = -40.0, hi = 40.0;
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        double cdf = 0.5 * erfc(-mid / sqrt(2.0));
+        if (cdf < p) lo = mid; else hi = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+/* Elfving's approximation of the expected j-th of n iid normal order
+ * statistics (eq. 4):  mu + sigma * Phi^-1((j - pi/8) / (n - pi/4 + 1)).
+ * READING: the fraction is printed upside down in eq. 4; this is the form of
+ * the cited source, and the only one that reproduces the value the paper
+ * computes with it in Sec. 4.1. */
+double oracle_elfving_mean(int j, int n, double mu, double sigma) {
+    const double pi = 3.14159265358979323846;
+    return mu + sigma * normal_quantile(((double)j - pi / 8.0) / ((double)n - pi / 4.0 + 1.0));
+}
+
+/* The "order" baseline of Sec. 4: the cutoff that maximises c / E[x_(c)] when
+ * the order statistics are those of n iid normal run-times (Elfving).  Same
+ * range, floor and tie rules as oracle_cutoff_select. */
+int oracle_cutoff_elfving(int n, double mu, double sigma, int c_min, int c_max, double t_floor,
+                          double *out_mean, double *out_omega, int32_t *out_cstar) {
+    if (!out_cstar || n < 1 || c_min < 1 || c_max > n || c_min > c_max || !(sigma >= 0.0)) return ORACLE_EINVAL;
+    int best = -1;
+    double best_omega = -INFINITY;
+    for (int c = 1; c <= n; ++c) {
+        double mean = oracle_elfving_mean(c, n, mu, sigma);
+        double omega = -INFINITY;
+        if (c >= c_min && c <= c_max && mean > t_floor) omega = (double)c / mean;
+        if (out_mean) out_mean[c - 1] = mean;
+        if (out_omega) out_omega[c - 1] = omega;
+        if (omega > -INFINITY && omega >= best_omega) { best_omega = omega; best = c; }
+    }
+    if (best < 0) { *out_cstar = c_max; return ORACLE_NO_ELIGIBLE; }
+    *out_cstar = best;
+    return ORACLE_OK;
+}
+
+static int dbl_cmp(const void *a, const void *b) {
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/* Gradient throughput of a run over a recorded trace (Sec. 3, Omega; Fig. 2):
+ * with cutoff c_t at iteration t the server waits for the c_t-th fastest
+ * worker, so the run computes sum_t c_t gradients in sum_t x_{t,(c_t)} seconds.
+ *   out[0] = that ratio for the given cutoffs,
+ *   out[1] = full synchronisation, c_t = N,
+ *   out[2] = the best cutoff in hindsight at every iteration, c_t = argmax_c c / x_{t,(c)}
+ *            (the "maximum" curve of Fig. 2). */
+int oracle_trace_throughput(const double *trace, int T, int N, const int32_t *cutoffs, double *out) {
+    if (!trace || !cutoffs || !out || T < 1 || N < 1) return ORACLE_EINVAL;
+    double *row = (double *)malloc(sizeof(double) * N);
+    double g_cut = 0, t_cut = 0, g_sync = 0, t_sync = 0, g_best = 0, t_best = 0;
+    for (int t = 0; t < T; ++t) {
+        if (cutoffs[t] < 1 || cutoffs[t] > N) { free(row); return ORACLE_EINVAL; }
+        memcpy(row, trace + (size_t)t * N, sizeof(double) * N);
+        qsort(row, N, sizeof(double), dbl_cmp);
+        g_cut += cutoffs[t];  t_cut += row[cutoffs[t] - 1];
+        g_sync += N;          t_sync += row[N - 1];
+        int best = 1;
+        for (int c = 2; c <= N; ++c)
+            if ((double)c / row[c - 1] >= (double)best / row[best - 1]) best = c;
+        g_best += best;       t_best += row[best - 1];
+    }
+    free(row);
+    out[0] = g_cut / t_cut; out[1] = g_sync / t_sync; out[2] = g_best / t_best;
+    return ORACLE_OK;
+}
