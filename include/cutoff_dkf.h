@@ -158,6 +158,28 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
  * next call on the model). */
 const float *dkf_decide_samples(const dkf_model *m);
 
+/* Censored run-times (Sec. 4.2): once the server has stopped waiting at time
+ * tau (the c-th arrival) the workers still running are killed and their
+ * run-times are unknown, but the filter needs a full vector.  Every dropped
+ * worker w gets a draw from its predictive run-time distribution
+ * left-truncated at tau.  That distribution is represented by column w of
+ * the [S][N] sample matrix the decision was taken from (dkf_decide_samples, or
+ * the output of dkf_sample_runtimes), so the draw is: of the m entries of
+ * column w that are > tau, taken in sample order, entry floor(u[w] * m);
+ * tau itself when m = 0.  Observed workers keep x_obs[w].
+ *   samples [S][N], x_obs [N] (entries of dropped workers are ignored),
+ *   censored [N] uint8 (non-zero = dropped), u [N] uniform numbers in [0, 1)
+ *   (read for dropped workers only; the caller draws them), x_full [N] out,
+ *   n_exceed [N] int32 out or NULL (m for dropped workers, -1 for observed):
+ *   all dev.  workspace: dev, at least dkf_impute_workspace(S, N) bytes,
+ *   4-byte aligned, contents are scratch.
+ * Errors: DKF_EINVAL (NULL, S or N < 1, tau NaN, workspace too small),
+ * DKF_EUNSUPPORTED (more than 2^40 entries), DKF_EHIP. */
+int dkf_impute_censored(const float *samples, int32_t S, int32_t N, const float *x_obs, const uint8_t *censored,
+                        float tau, const float *u, float *x_full, int32_t *n_exceed, void *workspace,
+                        size_t workspace_bytes, void *stream);
+size_t dkf_impute_workspace(int32_t S, int32_t N);
+
 /* Filter state (window, normaliser, counters) as an opaque blob, so that a
  * run can be resumed.  get: *bytes in = capacity, out = size needed/written
  * (buf may be NULL to query).  Both synchronise the device. */

@@ -28,7 +28,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
     "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "dkf_decide",
-    "dkf_decide_samples", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
+    "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
 
@@ -82,6 +82,9 @@ def _lib():
     lib.dkf_decide.argtypes = [vp, vp, i32, vp, vp, vp, u64, C.POINTER(i32), vp]
     lib.dkf_decide_samples.restype = vp
     lib.dkf_decide_samples.argtypes = [vp]
+    lib.dkf_impute_censored.argtypes = [vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, sz, vp]
+    lib.dkf_impute_workspace.restype = sz
+    lib.dkf_impute_workspace.argtypes = [i32, i32]
     lib.dkf_get_state.argtypes = [vp, vp, C.POINTER(sz)]
     lib.dkf_set_state.argtypes = [vp, vp, sz]
     lib.dkf_set_sampler.argtypes = [C.c_void_p, C.c_int32]
@@ -198,6 +201,21 @@ def dkf_decide(model: int, x_obs: np.ndarray, S: int, eps_q, eps_z, eps_x, seed:
     return int(c.value), rc
 
 
+def dkf_impute_workspace(S: int, N: int) -> int:
+    return int(_lib().dkf_impute_workspace(S, N))
+
+
+def dkf_impute_censored(samples, x_obs, censored, tau: float, u, x_full, n_exceed, workspace, stream=None) -> int:
+    torch = _torch()
+    S, N = samples.shape
+    f = torch.float32
+    return _check("dkf_impute_censored", _lib().dkf_impute_censored(
+        _dev(samples, f, name="samples"), S, N, _dev(x_obs, f, (N,), "x_obs"),
+        _dev(censored, torch.uint8, (N,), "censored"), float(tau), _dev(u, f, (N,), "u"),
+        _dev(x_full, f, (N,), "x_full"), _dev(n_exceed, torch.int32, (N,), "n_exceed"),
+        _dev(workspace, torch.uint8, name="workspace"), workspace.numel(), _stream_ptr(stream)))
+
+
 def dkf_get_state(model: int) -> bytes:
     n = C.c_size_t(0)
     _check("dkf_get_state", _lib().dkf_get_state(model, None, C.byref(n)))
@@ -300,6 +318,18 @@ class Predictor:
 
     def set_state(self, state: bytes):
         dkf_set_state(self.handle, state)
+
+
+def impute_censored(samples, x_obs, censored, tau, u):
+    """Allocate outputs + workspace, call dkf_impute_censored, return (x_full, n_exceed) tensors."""
+    torch = _torch()
+    S, N = samples.shape
+    dev = samples.device
+    ws = torch.empty(dkf_impute_workspace(S, N), dtype=torch.uint8, device=dev)
+    x_full = torch.empty(N, dtype=torch.float32, device=dev)
+    n_exceed = torch.empty(N, dtype=torch.int32, device=dev)
+    dkf_impute_censored(samples, x_obs, censored, tau, u, x_full, n_exceed, ws)
+    return x_full, n_exceed
 
 
 def select_cutoff(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=False, want_perm=False):

@@ -1,7 +1,6 @@
 // C ABI of libcutoff_dkf.so: model object, host-side window bookkeeping,
 // weight re-tiling, stream/graph orchestration.  All arithmetic of the
-// predictor runs in the kernels of filter.hip, guide.hip, mlp_gemm.hip and
-// cutoff_select.hip; this file only moves data and launches them.
+// predictor runs in the kernels of the other .hip files; this file only moves data and launches them.
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -780,6 +779,15 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
 }
 
 const float *dkf_decide_samples(const dkf_model *m) { return m ? m->samples : nullptr; }
+
+size_t dkf_impute_workspace(int32_t S, int32_t N) { return impute_workspace_bytes(S, N); }
+
+int dkf_impute_censored(const float *samples, int32_t S, int32_t N, const float *x_obs, const uint8_t *censored,
+                        float tau, const float *u, float *x_full, int32_t *n_exceed, void *workspace,
+                        size_t workspace_bytes, void *stream) {
+    return launch_impute_censored(samples, S, N, x_obs, censored, tau, u, x_full, n_exceed, workspace,
+                                  workspace_bytes, static_cast<hipStream_t>(stream));
+}
 
 // state blob: int64 {magic, N, L, pushes}, float scale, float pad, then the ring [L][N]
 int dkf_get_state(const dkf_model *m, void *buf, size_t *bytes) {

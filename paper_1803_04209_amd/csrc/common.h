@@ -207,4 +207,10 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream);
 size_t cutoff_workspace_bytes(int S, int N);
 
+// impute.hip
+int launch_impute_censored(const float *samples, int S, int N, const float *x_obs, const uint8_t *censored,
+                           float tau, const float *u, float *x_full, int32_t *n_exceed, void *workspace,
+                           size_t workspace_bytes, hipStream_t stream);
+size_t impute_workspace_bytes(int S, int N);
+
 }  // namespace dkf
