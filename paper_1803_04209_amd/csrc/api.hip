@@ -76,6 +76,10 @@ struct dkf_model {
     bool use_quad = false;   // sizes covered by the four-samples-per-wavefront sampler (small S)
     const float *quad_guide = nullptr, *quad_stream = nullptr, *quad_bias = nullptr;
     int quad_chunks = 0;
+    bool use_gchain = false;  // bf16 sizes covered by the register-resident guide/transition kernel
+    const float *gc_tiles = nullptr, *gc_bias = nullptr, *gc_mu_w32 = nullptr, *gc_mu_b32 = nullptr;
+    float *gc_cmu = nullptr;
+    int gc_bias_floats = 0;
 
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
@@ -267,6 +271,52 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     int rc = upload(m, g.data(), g.size(), &m->chain_guide);
     if (rc != DKF_OK) return rc;
     return upload(m, s.data(), s.size(), &m->chain_stream);
+}
+
+// Tiles and biases of the bf16 guide/transition kernel (layout: GChainArgs).
+int pack_gchain(dkf_model *m, const RawLayers &r) {
+    const int Z = m->Z, R = m->R, H = m->H;
+    const int Q = gchain_q(Z, R, H), HP = 128 * Q, ZT = 2, ZK = 4;
+    std::vector<uint16_t> t;
+    auto tile = [&](const float *w, int n_out, int k_in, int ob, int ks) {
+        const size_t base = t.size();
+        t.resize(base + 512, 0);
+        for (int lane = 0; lane < 64; ++lane)
+            for (int j = 0; j < 8; ++j) {
+                const int row = 32 * ob + (lane & 31), k = 16 * ks + 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
+                if (row < n_out && k < k_in) t[base + lane * 8 + j] = to_bf16(w[(size_t)row * k_in + k]);
+            }
+    };
+    auto wide = [&](const float *w, int n_out) {  // Z -> n_out
+        for (int wv = 0; wv < 4; ++wv) for (int ob = 0; ob < Q; ++ob) for (int ks = 0; ks < ZK; ++ks) tile(w, n_out, Z, wv * Q + ob, ks);
+    };
+    auto narrow = [&](const float *w, int k_in) {  // k_in -> Z
+        for (int wv = 0; wv < 4; ++wv) for (int nb = 0; nb < ZT; ++nb) for (int ks = 0; ks < 2 * Q; ++ks) tile(w, Z, k_in, nb, 2 * wv * Q + ks);
+    };
+    auto small = [&](const float *w) {
+        for (int nb = 0; nb < ZT; ++nb) for (int ks = 0; ks < ZK; ++ks) tile(w, Z, Z, nb, ks);
+    };
+    wide(r.comb, R); narrow(r.mu, R); small(r.sig);
+    wide(r.gate1, H); narrow(r.gate2, H); wide(r.prop1, H); narrow(r.prop2, H); small(r.lin); small(r.tscale);
+    std::vector<float> bt;
+    auto add_bias = [&](const float *b, int n, int padded) {
+        const size_t base = bt.size();
+        bt.resize(base + (size_t)padded, 0.f);
+        for (int i = 0; i < n; ++i) bt[base + i] = b[i];
+    };
+    add_bias(r.b_comb, R, HP); add_bias(r.b_sig, Z, 64); add_bias(r.b_gate1, H, HP); add_bias(r.b_gate2, Z, 64);
+    add_bias(r.b_prop1, H, HP); add_bias(r.b_prop2, Z, 64); add_bias(r.b_lin, Z, 64); add_bias(r.b_tscale, Z, 64);
+    m->gc_bias_floats = (int)bt.size();
+    std::vector<float> as_floats(t.size() / 2);
+    std::memcpy(as_floats.data(), t.data(), t.size() * sizeof(uint16_t));
+    int rc = upload(m, as_floats.data(), as_floats.size(), &m->gc_tiles);
+    if (rc == DKF_OK) rc = upload(m, bt.data(), bt.size(), &m->gc_bias);
+    if (rc == DKF_OK) rc = upload(m, r.mu, (size_t)Z * R, &m->gc_mu_w32);
+    if (rc == DKF_OK) rc = upload(m, r.b_mu, (size_t)Z, &m->gc_mu_b32);
+    void *q = nullptr;
+    if (rc == DKF_OK) rc = dev_alloc(m, (size_t)m->L * 64 * sizeof(float), &q, true);
+    m->gc_cmu = static_cast<float *>(q);
+    return rc;
 }
 
 size_t blob_floats(const dkf_config *c) {
@@ -467,6 +517,23 @@ int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStr
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
     if (m->sampler != DKF_SAMPLER_STAGED && (m->use_chain || m->use_quad)) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
+    int rc = DKF_EUNSUPPORTED;
+    if (m->sampler != DKF_SAMPLER_STAGED && m->use_gchain) {
+        GChainArgs c{};
+        c.ctl = m->ctl_dev();
+        c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
+        c.tiles = m->gc_tiles; c.bias_table = m->gc_bias; c.bias_floats = m->gc_bias_floats;
+        c.mu_w32 = m->gc_mu_w32; c.mu_b32 = m->gc_mu_b32; c.cmu = m->gc_cmu;
+        c.z0 = m->z0;
+        c.eps_q = eps_q; c.eps_z = eps_z;
+        c.z_last = st ? st->z_last : nullptr;
+        c.z_next_dbg = st ? st->z_next : nullptr;
+        c.z_next = m->z_next;
+        c.S = S; c.L = m->L; c.Z = m->Z; c.Zp = m->Zp; c.R = m->R; c.H = m->H;
+        rc = launch_gchain(c, stream);
+        if (rc != DKF_OK && rc != DKF_EUNSUPPORTED && rc != DKF_EINVAL) return rc;
+    }
+    if (rc != DKF_OK) {  // sizes (or caller buffers not 16-byte aligned) the register-resident kernel does not take
     GuideArgs g;
     g.ctl = m->ctl_dev();
     g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
@@ -479,8 +546,9 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
     g.z_next = m->z_next;
     g.S = S; g.L = m->L; g.Z = m->Z; g.Zp = m->Zp; g.R = m->R; g.Rp = m->Rp; g.H = m->H; g.Hp = m->Hp;
     g.bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
-    int rc = launch_guide(g, stream);
+    rc = launch_guide(g, stream);
     if (rc != DKF_OK) return rc;
+    }
 
     GemmArgs e{};
     e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
@@ -631,6 +699,8 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
     m->use_quad = !bf16 && quad_supported(Z, R, H, L, N);
     if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
+    m->use_gchain = bf16 && gchain_q(Z, R, H) != 0 && m->Zp == 64;
+    if (m->use_gchain) DKF_CHECK(pack_gchain(m, raw));
 
     void *q = nullptr;
     DKF_CHECK(dev_alloc(m, m->in_floats() * 4, &q, true)); m->d_in = static_cast<float *>(q);

@@ -95,6 +95,7 @@ struct FilterArgs {
     const float *bias_f, *bias_b;      // dev [R]: b_ih + b_hh
     int N, Np, L, R, Rp;
     bool project;  // (register-resident kernel) compute the new observation's projection in-kernel
+    bool mark_empty;  // (projection kernel) fill ctx with the multi-workgroup encoder's "not written yet" value
     bool encode;   // run the recurrences (after the projection) when the window is full
 };
 int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream);
@@ -118,6 +119,32 @@ struct GuideArgs {
 int launch_guide(const GuideArgs &a, hipStream_t stream);
 size_t guide_lds_bytes(int Zp, int Rp, int Hp, bool bf16);
 int guide_prepare(int Zp, int Rp, int Hp, bool bf16);  // raises the kernel's LDS limit once per size
+
+// gchain.hip: guide chain + transition in bf16 with the guide's weights in registers
+struct GChainArgs {
+    const Control *ctl;
+    const float *ctx_f, *ctx_b;  // [L][Rp]
+    int Rp;
+    // 1 KiB weight tiles (32 output features x 16 inputs, bf16): lane l, entry j of tile (ob, ks) is
+    // W[32 ob + l % 32][16 ks + 8 (j / 4) + 4 (l / 32) + j % 4].  With Q = gchain_q() tiles of hidden
+    // width per wavefront, in this order: comb [w][ob < Q][ks < 4]; mu [w][nb < 2][ks < 2Q] (k-step
+    // 2 w Q + ks of the matrix); sig [nb][ks]; gate1, gate2, prop1, prop2 like comb / mu; lin,
+    // tscale like sig.
+    const float *tiles;
+    // fp32 biases, zero padded: comb [128 Q], sig [64], gate1 [128 Q], gate2 [64], prop1 [128 Q],
+    // prop2 [64], lin [64], tscale [64]
+    const float *bias_table;
+    int bias_floats;
+    const float *mu_w32, *mu_b32;  // unrounded W_mu [Z][R] and b_mu [Z] for the context's share of the mean
+    float *cmu;                    // [L][64] scratch: that share per window position (zero beyond Z)
+    const float *z0;               // [64] zero padded
+    const float *eps_q, *eps_z;    // [L][S][Z], [S][Z]
+    float *z_last, *z_next_dbg;    // [S][Z] or NULL
+    float *z_next;                 // [S][Zp]: input of the emission
+    int S, L, Z, Zp, R, H;
+};
+int gchain_q(int Z, int R, int H);  // 0: sizes the kernel is not built for
+int launch_gchain(const GChainArgs &a, hipStream_t stream);
 
 // mlp_gemm.hip
 enum Epilogue : int {

@@ -14,8 +14,9 @@ namespace dkf {
 namespace {
 
 constexpr int kProjThreads = 256;
-constexpr int kProjRowsPerBlock = 16;
+constexpr int kProjRowsPerBlock = 4;  // one row per wavefront: R/4 workgroups per direction
 constexpr int kChainThreads = 1024;
+constexpr float kCoopEmpty = -1.0f;  // "not written yet" in ctx while the multi-workgroup encoder runs (states are >= 0)
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -34,6 +35,12 @@ __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a
         const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
         for (int i = threadIdx.x; i < n; i += kProjThreads) a.mirror[i] = a.input[i];
     }
+    if (a.mark_empty) {  // the multi-workgroup encoder that follows polls ctx for values >= 0
+        const int total = a.L * a.R;
+        float *__restrict__ c = dir ? a.ctx_b : a.ctx_f;
+        for (int i = blockIdx.x * kProjThreads + threadIdx.x; i < total; i += gridDim.x * kProjThreads)
+            c[(size_t)(i / a.R) * a.Rp + i % a.R] = kCoopEmpty;
+    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int N = a.N;
     for (int i = wave; i < kProjRowsPerBlock; i += kProjThreads / 64) {
@@ -42,7 +49,18 @@ __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a
         const float *__restrict__ wr = w + (size_t)r * N;
         float s = 0.f;
         if ((N & 3) == 0) {
-            for (int j = lane * 4; j < N; j += 256) {
+            int j = lane * 4;
+            for (; j + 768 < N; j += 1024) {  // four independent loads of the matrix row in flight
+                float4 wv[4], xv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    wv[q] = *reinterpret_cast<const float4 *>(wr + j + 256 * q);
+                    xv[q] = *reinterpret_cast<const float4 *>(x + j + 256 * q);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s += wv[q].x * xv[q].x + wv[q].y * xv[q].y + wv[q].z * xv[q].z + wv[q].w * xv[q].w;
+            }
+            for (; j < N; j += 256) {
                 const float4 wv = *reinterpret_cast<const float4 *>(wr + j);
                 const float4 xv = *reinterpret_cast<const float4 *>(x + j);
                 s += wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
@@ -250,6 +268,126 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
     }
 }
 
+// Wide encoders (R > 256): the R x R matrix no longer fits one compute unit's registers, so each
+// direction is split over P = ceil(R / 64) workgroups of 64 rows, every thread holding KPT
+// consecutive columns of one row in registers for the whole chain (16 threads per row).  After
+// each step a workgroup publishes its 64 new state values (they are the rows of ctx it owns) and
+// reads the full state back: one device-scope exchange of R floats per step instead of streaming
+// the matrix from L2 per step.  The data is its own flag: a ReLU output is never negative, the
+// projection kernel that precedes this one fills ctx with kCoopEmpty, and thread k polls element
+// k of the step's row until it has been written (one memory round trip per step, no counters).
+// The wait is bounded: if a value does not arrive within kCoopSpinLimit polls (it always does
+// unless the device is shared with a kernel that never ends) the encodings this workgroup owns
+// are set to NaN, which surfaces as "no eligible cutoff", and every wave still exits.
+constexpr int kCoopRows = 64;
+constexpr int kCoopTpr = kChainThreads / kCoopRows;  // 16 lanes per row = one DPP row
+constexpr int kCoopSpinLimit = 1 << 20;
+
+__device__ __forceinline__ float row16_sum(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // 7 - lane within 8
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // 15 - lane within 16
+    return v;
+}
+
+template <int KPT>
+__global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a) {
+    constexpr int SEG = KPT + 4;  // 4 pad floats per column segment: conflict-free b128 reads
+    constexpr int HBUF = kCoopTpr * SEG;
+    extern __shared__ __align__(16) float lds[];
+    __shared__ int bail;
+    const Control ctl = *a.ctl;
+    if (ctl.count < a.L) return;  // still warming up: nothing to encode (uniform over the grid)
+    const int dir = blockIdx.y;
+    const int R = a.R, Rp = a.Rp, L = a.L;
+    const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
+    const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
+    const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
+    float *ctx = dir ? a.ctx_b : a.ctx_f;
+    float *h = lds;               // two buffers [kCoopTpr][SEG]: previous state by column segment
+    float *pre = lds + 2 * HBUF;  // [L][kCoopRows] input term of every step
+    const int tid = threadIdx.x;
+    const int row_local = tid / kCoopTpr, seg = tid % kCoopTpr;
+    const int row = blockIdx.x * kCoopRows + row_local, k0 = seg * KPT;
+
+    float wreg[KPT];
+#pragma unroll
+    for (int j = 0; j < KPT; j += 4) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < R) {
+            if ((R & 3) == 0 && k0 + j + 3 < R) {
+                v = *reinterpret_cast<const float4 *>(w + (size_t)row * R + k0 + j);
+            } else {
+                if (k0 + j < R) v.x = w[(size_t)row * R + k0 + j];
+                if (k0 + j + 1 < R) v.y = w[(size_t)row * R + k0 + j + 1];
+                if (k0 + j + 2 < R) v.z = w[(size_t)row * R + k0 + j + 2];
+                if (k0 + j + 3 < R) v.w = w[(size_t)row * R + k0 + j + 3];
+            }
+        }
+        wreg[j] = v.x; wreg[j + 1] = v.y; wreg[j + 2] = v.z; wreg[j + 3] = v.w;
+    }
+    for (int i = tid; i < L * kCoopRows; i += kChainThreads) {
+        const int step = i / kCoopRows, r = blockIdx.x * kCoopRows + i % kCoopRows;
+        const int t = dir ? L - 1 - step : step;
+        int slot = ctl.oldest + t;
+        if (slot >= L) slot -= L;
+        pre[i] = r < R ? proj[(size_t)slot * R + r] * ctl.inv_scale + bias[r] : 0.f;
+    }
+    for (int i = tid; i < 2 * HBUF; i += kChainThreads) h[i] = 0.f;
+    if (tid == 0) bail = 0;
+    __syncthreads();
+
+    const int my_slot = (tid / KPT) * SEG + tid % KPT;  // where column `tid` of the state sits in a buffer
+    for (int step = 0; step < L; ++step) {
+        const int t = dir ? L - 1 - step : step;
+        float s = 0.f;
+        if (step > 0) {
+            const float *hp = h + (step & 1) * HBUF + seg * SEG;
+#pragma unroll
+            for (int j = 0; j < KPT; j += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
+                s += wreg[j] * hv.x + wreg[j + 1] * hv.y + wreg[j + 2] * hv.z + wreg[j + 3] * hv.w;
+            }
+            s = row16_sum(s);
+        }
+        if (seg == 0 && row < R)
+            __hip_atomic_store(ctx + (size_t)t * Rp + row, fmaxf(pre[step * kCoopRows + row_local] + s, 0.f),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (step == L - 1) break;
+        // the whole state of this step, written by all workgroups of the direction
+        if (tid < R) {
+            const float *src = ctx + (size_t)t * Rp + tid;
+            float v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int polls = 0;
+            while (v < 0.f) {
+                if (++polls > kCoopSpinLimit) { bail = 1; v = 0.f; break; }
+                __builtin_amdgcn_s_sleep(1);
+                v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            h[((step + 1) & 1) * HBUF + my_slot] = v;
+        }
+        __syncthreads();
+        if (bail) break;
+    }
+    if (bail) {  // bounded wait ran out: poison what this workgroup owns so that the failure is visible
+        for (int i = tid; i < L * kCoopRows; i += kChainThreads) {
+            const int r = blockIdx.x * kCoopRows + i % kCoopRows;
+            if (r < R) ctx[(size_t)(i / kCoopRows) * Rp + r] = __builtin_nanf("");
+        }
+    }
+}
+
+template <int KPT>
+int launch_encode_coop(const FilterArgs &a, hipStream_t stream) {
+    const size_t lds = ((size_t)2 * kCoopTpr * (KPT + 4) + (size_t)a.L * kCoopRows) * sizeof(float);
+    if (lds > 60 * 1024) return DKF_EUNSUPPORTED;
+    const dim3 grid((a.R + kCoopRows - 1) / kCoopRows, 2);
+    hipLaunchKernelGGL((encode_window_coop<KPT>), grid, dim3(kChainThreads), lds, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
 template <int TPR, int KPT>
 int launch_encode_reg(const FilterArgs &a, hipStream_t stream) {
     constexpr int ROWS = kChainThreads / TPR;
@@ -261,6 +399,18 @@ int launch_encode_reg(const FilterArgs &a, hipStream_t stream) {
     return DKF_OK;
 }
 
+// dynamic LDS of encode_window_reg for this size, 0 if R is beyond it
+size_t reg_encoder_lds(const FilterArgs &a) {
+    int rows, kpt;
+    if (a.R <= 32) { rows = 32; kpt = 1; }
+    else if (a.R <= 64) { rows = 64; kpt = 4; }
+    else if (a.R <= 128) { rows = 128; kpt = 16; }
+    else if (a.R <= 256) { rows = 256; kpt = 64; }
+    else return 0;
+    const int hstride = rows + (rows / kpt) * 4;
+    return ((size_t)a.L * rows + 2 * hstride + a.Np + rows) * sizeof(float);
+}
+
 }  // namespace
 
 int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t stream) {
@@ -268,38 +418,40 @@ int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t
     FilterArgs a = args;
     a.encode = encode;
     a.project = false;
+    a.mark_empty = false;
+    const size_t reg_lds = reg_encoder_lds(a);
+    const bool reg_ok = reg_lds != 0 && reg_lds <= 64 * 1024;  // one workgroup per direction, matrix in registers
     // Small encoders: projection and both recurrences in one launch of two workgroups.  A larger
     // input matrix (measured: 256 x 512) is read faster by the many workgroups of the separate
     // projection kernel than by those two.
-    const bool fuse = project && (size_t)a.R * a.N <= 32768;
-    if (!fuse && project) {
-        if (a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
+    const bool fuse = project && reg_ok && (size_t)a.R * a.N <= 32768;
+    const bool coop = encode && !reg_ok;  // wide encoders or long windows: several workgroups per direction
+    if ((project && !fuse) || coop) {
+        if (project && a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
             const size_t bytes = a.Np * sizeof(float) + sizeof(Control);
             DKF_HIP_TRY(hipMemcpyAsync(a.mirror, a.input, bytes, hipMemcpyHostToDevice, stream));
-            a.input = a.mirror;
         }
+        a.input = a.mirror;  // (without `project` the observation of the last push is projected again: same result)
+        a.mark_empty = coop;
         const dim3 pgrid((a.R + kProjRowsPerBlock - 1) / kProjRowsPerBlock, 2);
         hipLaunchKernelGGL(project_observation, pgrid, dim3(kProjThreads), 0, stream, a);
         DKF_HIP_TRY(hipGetLastError());
-        project = false;
     }
-    if (fuse || encode) {
+    if (fuse || (encode && reg_ok)) {
         a.project = fuse;
+        if (a.R <= 32) return launch_encode_reg<32, 1>(a, stream);
+        if (a.R <= 64) return launch_encode_reg<16, 4>(a, stream);
+        if (a.R <= 128) return launch_encode_reg<8, 16>(a, stream);
+        return launch_encode_reg<4, 64>(a, stream);
+    }
+    if (coop) {
         int rc = DKF_EUNSUPPORTED;
-        if (a.R <= 32) rc = launch_encode_reg<32, 1>(a, stream);
-        else if (a.R <= 64) rc = launch_encode_reg<16, 4>(a, stream);
-        else if (a.R <= 128) rc = launch_encode_reg<8, 16>(a, stream);
-        else if (a.R <= 256) rc = launch_encode_reg<4, 64>(a, stream);
+        if (a.R <= 256) rc = launch_encode_coop<16>(a, stream);
+        else if (a.R <= 512) rc = launch_encode_coop<32>(a, stream);
+        else if (a.R <= 768) rc = launch_encode_coop<48>(a, stream);
+        else if (a.R <= 1024) rc = launch_encode_coop<64>(a, stream);
         if (rc != DKF_EUNSUPPORTED) return rc;
-    }
-    // wide encoders or long windows: the recurrences with the matrix streamed from L2 every step
-    a.project = false;
-    if (project) {  // the fused kernel did not fit
-        const dim3 pgrid((a.R + kProjRowsPerBlock - 1) / kProjRowsPerBlock, 2);
-        hipLaunchKernelGGL(project_observation, pgrid, dim3(kProjThreads), 0, stream, a);
-        DKF_HIP_TRY(hipGetLastError());
-    }
-    if (encode) {
+        // very long windows: the matrix streamed from L2 every step
         hipLaunchKernelGGL(encode_window, dim3(2), dim3(kChainThreads), 2 * a.Rp * sizeof(float), stream, a);
         DKF_HIP_TRY(hipGetLastError());
     }

@@ -1,0 +1,351 @@
+// Guide trajectories and the gated transition in bf16 (Sec. 3.1.3) with the
+// guide's weights held in registers for all L steps.
+//
+// A workgroup of four wavefronts (one per SIMD) owns 32 samples.  Every layer
+// is computed transposed, Y^T = W X^T, with v_mfma_f32_32x32x16_bf16: weights
+// are the A operand (rows = output features), activations the B operand
+// (columns = samples).  Lane l of a result tile owns sample l % 32 and features
+// 8 (i / 4) + 4 (l / 32) + i % 4, i = 0..15; with the weights' K order permuted
+// the same way at load time, a result tile rounded to bf16 *is* two B operands
+// of the next layer, so activations never leave registers inside a wavefront.
+//   wide layers  (Z -> R, Z -> H): each wavefront computes a quarter of the
+//                output features from the full latent (which every wavefront holds);
+//   narrow layers (R -> Z, H -> Z): each wavefront multiplies its quarter of the
+//                hidden features (K split) and the four partial results are summed
+//                through LDS in a fixed order, after which every wavefront again
+//                holds the full latent;
+//   Z -> Z layers are computed by all four wavefronts alike.
+// The context enters the mean linearly, mu = W_mu (tanh(.) + h_l + h_r) / 3 + b,
+// so its share c_t = W_mu (h_l,t + h_r,t) / 3 + b_mu is computed once per window
+// position by guide_context (fp32, unrounded weights) and added after the
+// matrix product: the per-sample work of a step is tanh on the accumulators and
+// three products.  Transition weights are used once per workgroup and are
+// streamed from L2 in the same tile format.
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace dkf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRows = 32;  // samples per workgroup
+constexpr int ZT = 2;      // 32-feature tiles of the latent (Zp = 64)
+constexpr int ZK = 4;      // 16-wide k-steps of the latent
+
+__device__ __forceinline__ f32x16 mma(bf16x8 w, bf16x8 x, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, x, c, 0, 0, 0);
+}
+
+// half G (0/1) of a result tile as the B operand of k-step 2 * tile + G of the next layer
+template <int G>
+__device__ __forceinline__ bf16x8 operand_of(const f32x16 &v) {
+    bf16x8 r;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = (__bf16)v[8 * G + j];  // round to nearest even
+    return r;
+}
+
+__device__ __forceinline__ bf16x8 load_tile(const f32x4 *__restrict__ tiles, int tile, int lane) {
+    return __builtin_bit_cast(bf16x8, tiles[(size_t)tile * 64 + lane]);
+}
+
+// c_t[z] = b_mu[z] + (1/3) sum_r W_mu[z][r] (ctx_f[t][r] + ctx_b[t][r]);  grid (L, ceil(Z/4)), one wavefront per z
+__global__ __launch_bounds__(256) void guide_context(GChainArgs a) {
+    if (a.ctl->count < a.L) return;
+    const int t = blockIdx.x, z = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (z >= a.Z) return;
+    const float *__restrict__ w = a.mu_w32 + (size_t)z * a.R;
+    const float *__restrict__ cf = a.ctx_f + (size_t)t * a.Rp;
+    const float *__restrict__ cb = a.ctx_b + (size_t)t * a.Rp;
+    float s = 0.f;
+    for (int r = lane; r < a.R; r += 64) s += w[r] * (cf[r] + cb[r]);
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, 64);
+    if (lane == 0) a.cmu[(size_t)t * 64 + z] = s * (1.0f / 3.0f) + a.mu_b32[z];
+}
+
+// Q: 32-feature tiles of the hidden width per wavefront (hidden widths padded to 128 Q).
+template <int Q>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void guide_chain_bf16(GChainArgs a) {
+    extern __shared__ __align__(16) char lds_raw[];
+    // LDS: red[2][4][8][64] float4 (two exchange buffers), bias table, c_t table
+    f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw);
+    float *bias = reinterpret_cast<float *>(lds_raw + 2 * 4 * 8 * 64 * 16);
+    float *cmu = bias + a.bias_floats;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, h = lane >> 5;
+    const int S = a.S, Z = a.Z, L = a.L;
+    const int smp = blockIdx.x * kRows + col;
+    const bool live = smp < S;
+    const f32x4 *__restrict__ T = reinterpret_cast<const f32x4 *>(a.tiles);
+    constexpr int HP = 128 * Q;  // padded hidden width
+    // bias table offsets (floats)
+    constexpr int oC = 0, oSig = oC + HP, oG1 = oSig + 64, oG2 = oG1 + HP, oP1 = oG2 + 64, oP2 = oP1 + HP,
+                  oLin = oP2 + 64, oTs = oLin + 64;
+    // tile offsets
+    constexpr int nWide = 4 * Q * ZK, nNarrow = 4 * ZT * 2 * Q, nSmall = ZT * ZK;
+    constexpr int tC = 0, tMu = tC + nWide, tSig = tMu + nNarrow, tG1 = tSig + nSmall, tG2 = tG1 + nWide,
+                  tP1 = tG2 + nNarrow, tP2 = tP1 + nWide, tLin = tP2 + nNarrow, tTs = tLin + nSmall;
+
+    for (int i = tid; i < a.bias_floats; i += kThreads) bias[i] = a.bias_table[i];
+    for (int i = tid; i < L * 64; i += kThreads) cmu[i] = a.cmu[i];
+
+    // guide weights of this wavefront -> registers
+    bf16x8 wc[Q][ZK], wmu[ZT][2 * Q], wsig[ZT][ZK];
+#pragma unroll
+    for (int ob = 0; ob < Q; ++ob)
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) wc[ob][ks] = load_tile(T, tC + (w * Q + ob) * ZK + ks, lane);
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+        for (int ks = 0; ks < 2 * Q; ++ks) wmu[nb][ks] = load_tile(T, tMu + (w * ZT + nb) * 2 * Q + ks, lane);
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) wsig[nb][ks] = load_tile(T, tSig + nb * ZK + ks, lane);
+
+    // z_0 as B operands: k-step ks, entry j <-> feature 16 ks + 8 (j / 4) + 4 h + j % 4
+    bf16x8 zB[ZK];
+#pragma unroll
+    for (int ks = 0; ks < ZK; ++ks)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zB[ks][j] = (__bf16)a.z0[16 * ks + 8 * (j >> 2) + 4 * h + (j & 3)];
+    __syncthreads();
+
+    int buf = 0;
+    // Sum the four wavefronts' partial tiles p[ZT] in the order ((w0 + w1) + w2) + w3; every
+    // wavefront ends up with the same full result.
+    auto all_sum = [&](f32x16 (&p)[ZT]) {
+        f32x4 *mine = red + ((buf * 4 + w) * 8) * 64 + lane;
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 v = {p[nb][4 * q], p[nb][4 * q + 1], p[nb][4 * q + 2], p[nb][4 * q + 3]};
+                mine[(nb * 4 + q) * 64] = v;
+            }
+        __syncthreads();
+        const f32x4 *all = red + (buf * 4 * 8) * 64 + lane;
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = (nb * 4 + q) * 64;
+                const f32x4 s = ((all[e] + all[8 * 64 + e]) + all[16 * 64 + e]) + all[24 * 64 + e];
+                p[nb][4 * q] = s[0]; p[nb][4 * q + 1] = s[1]; p[nb][4 * q + 2] = s[2]; p[nb][4 * q + 3] = s[3];
+            }
+        buf ^= 1;
+    };
+    // feature (within the 64-wide latent) of element i of latent tile nb in this lane
+    auto zfeat = [&](int nb, int i) { return 32 * nb + 8 * (i >> 2) + 4 * h + (i & 3); };
+    // 16 floats of a [.][Z] noise row for this lane's features of latent tile nb (zero where there is no such feature)
+    auto load_noise = [&](const float *__restrict__ row, f32x4 (&e)[ZT][4]) {
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = 32 * nb + 8 * q + 4 * h;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (live && f < Z) v = *reinterpret_cast<const f32x4 *>(row + f);
+                e[nb][q] = v;
+            }
+    };
+
+    f32x16 mu[ZT];
+    for (int t = 0; t < L; ++t) {
+        f32x4 eps[ZT][4];
+        load_noise(a.eps_q + ((size_t)t * S + (live ? smp : 0)) * Z, eps);
+        // combiner: this wavefront's quarter of tanh(W_c z + b_c), straight into B operands
+        bf16x8 hB[2 * Q];
+#pragma unroll
+        for (int ob = 0; ob < Q; ++ob) {
+            f32x16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < ZK; ++ks) acc = mma(wc[ob][ks], zB[ks], acc);
+            const float *b = bias + oC + 32 * (w * Q + ob) + 4 * h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[4 * q + r] = tanh_f(acc[4 * q + r] + bq[r]);
+            }
+            hB[2 * ob] = operand_of<0>(acc);
+            hB[2 * ob + 1] = operand_of<1>(acc);
+        }
+        // mean: partial product over this wavefront's hidden features, then the sum over wavefronts
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb) {
+            mu[nb] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 2 * Q; ++ks) mu[nb] = mma(wmu[nb][ks], hB[ks], mu[nb]);
+        }
+        all_sum(mu);
+        bf16x8 mB[ZK];
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb) {
+            const float *c = cmu + t * 64 + 32 * nb + 4 * h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 cq = *reinterpret_cast<const f32x4 *>(c + 8 * q);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mu[nb][4 * q + r] = mu[nb][4 * q + r] * (1.0f / 3.0f) + cq[r];
+            }
+            mB[2 * nb] = operand_of<0>(mu[nb]);
+            mB[2 * nb + 1] = operand_of<1>(mu[nb]);
+        }
+        // scale from the mean, reparameterised draw
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb) {
+            f32x16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < ZK; ++ks) acc = mma(wsig[nb][ks], mB[ks], acc);
+            const float *b = bias + oSig + 32 * nb + 4 * h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 4 * q + r;
+                    const float z = mu[nb][i] + softplus_f(acc[i] + bq[r]) * eps[nb][q][r];
+                    acc[i] = zfeat(nb, i) < Z ? z : 0.f;
+                }
+            }
+            if (t == L - 1 && a.z_last && live && w == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int f = 32 * nb + 8 * q + 4 * h;
+                    if (f < Z) {
+                        f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+                        *reinterpret_cast<f32x4 *>(a.z_last + (size_t)smp * Z + f) = v;
+                    }
+                }
+            }
+            zB[2 * nb] = operand_of<0>(acc);
+            zB[2 * nb + 1] = operand_of<1>(acc);
+        }
+    }
+
+    // ---- gated transition: weights streamed from L2, used once ------------------------
+    // wide layer (Z -> H) of this wavefront's quarter + ReLU, then the narrow layer's partial
+    // product over that quarter, summed over the wavefronts
+    auto two_layer = [&](int t_wide, int o_wide, int t_narrow, f32x16 (&out)[ZT]) {
+        bf16x8 hB[2 * Q];
+#pragma unroll
+        for (int ob = 0; ob < Q; ++ob) {
+            f32x16 acc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < ZK; ++ks) acc = mma(load_tile(T, t_wide + (w * Q + ob) * ZK + ks, lane), zB[ks], acc);
+            const float *b = bias + o_wide + 32 * (w * Q + ob) + 4 * h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[4 * q + r] = fmaxf(acc[4 * q + r] + bq[r], 0.f);
+            }
+            hB[2 * ob] = operand_of<0>(acc);
+            hB[2 * ob + 1] = operand_of<1>(acc);
+        }
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb) {
+            out[nb] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 2 * Q; ++ks)
+                out[nb] = mma(load_tile(T, t_narrow + (w * ZT + nb) * 2 * Q + ks, lane), hB[ks], out[nb]);
+        }
+        all_sum(out);
+    };
+    f32x16 gate[ZT], prop[ZT];
+    two_layer(tG1, oG1, tG2, gate);
+    two_layer(tP1, oP1, tP2, prop);
+    f32x4 eps[ZT][4];
+    load_noise(a.eps_z + (size_t)(live ? smp : 0) * Z, eps);
+    f32x16 G[ZT];
+    bf16x8 gB[ZK];
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb) {
+        f32x16 lin = zero16();
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) lin = mma(load_tile(T, tLin + nb * ZK + ks, lane), zB[ks], lin);
+        f32x16 relu;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int f = zfeat(nb, i);
+            const float g = sigmoid_f(gate[nb][i] + bias[oG2 + f]);
+            const float v = (1.f - g) * (lin[i] + bias[oLin + f]) + g * (prop[nb][i] + bias[oP2 + f]);
+            G[nb][i] = f < Z ? v : 0.f;
+            relu[i] = fmaxf(G[nb][i], 0.f);
+        }
+        gB[2 * nb] = operand_of<0>(relu);
+        gB[2 * nb + 1] = operand_of<1>(relu);
+    }
+    if (w != 0) return;  // every wavefront holds the same G; one of them finishes and writes
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb) {
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) acc = mma(load_tile(T, tTs + nb * ZK + ks, lane), gB[ks], acc);
+        if (!live) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int f = 32 * nb + 8 * q + 4 * h;
+            f32x4 v;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = 4 * q + r;
+                const float zn = G[nb][i] + softplus_f(acc[i] + bias[oTs + f + r]) * eps[nb][q][r];
+                v[r] = f + r < Z ? zn : 0.f;
+            }
+            *reinterpret_cast<f32x4 *>(a.z_next + (size_t)smp * a.Zp + f) = v;
+            if (a.z_next_dbg && f < Z) *reinterpret_cast<f32x4 *>(a.z_next_dbg + (size_t)smp * Z + f) = v;
+        }
+    }
+}
+
+template <int Q>
+size_t gchain_lds(const GChainArgs &a) {
+    return (size_t)2 * 4 * 8 * 64 * 16 + ((size_t)a.bias_floats + (size_t)a.L * 64) * sizeof(float);
+}
+
+template <int Q>
+int launch_q(const GChainArgs &a, hipStream_t stream) {
+    const size_t lds = gchain_lds<Q>(a);
+    if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
+    static size_t prepared = 0;  // largest LDS size the kernel has been enabled for
+    if (lds > prepared) {
+        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(guide_chain_bf16<Q>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        prepared = lds;
+    }
+    hipLaunchKernelGGL(guide_context, dim3(a.L, (a.Z + 3) / 4), dim3(256), 0, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(guide_chain_bf16<Q>, dim3((a.S + kRows - 1) / kRows), dim3(kThreads), lds, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
+}  // namespace
+
+int gchain_q(int Z, int R, int H) {
+    if (Z < 1 || Z > 64 || (Z & 3) != 0) return 0;
+    const int widest = R > H ? R : H;
+    if (widest <= 128) return 1;
+    if (widest <= 256) return 2;
+    if (widest <= 512) return 4;
+    return 0;
+}
+
+int launch_gchain(const GChainArgs &a, hipStream_t stream) {
+    StageTimer timer(kStageGuide, stream);
+    if ((reinterpret_cast<uintptr_t>(a.eps_q) | reinterpret_cast<uintptr_t>(a.eps_z) |
+         reinterpret_cast<uintptr_t>(a.z_last) | reinterpret_cast<uintptr_t>(a.z_next_dbg)) & 15)
+        return DKF_EINVAL;
+    switch (gchain_q(a.Z, a.R, a.H)) {
+        case 1: return launch_q<1>(a, stream);
+        case 2: return launch_q<2>(a, stream);
+        case 4: return launch_q<4>(a, stream);
+        default: return DKF_EUNSUPPORTED;
+    }
+}
+
+}  // namespace dkf
