@@ -152,33 +152,43 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             }
     };
 
-    f32x16 mu[ZT];
+    // accumulator tile that starts at the bias of this lane's 16 features (read from the LDS table)
+    auto bias_tile = [&](const float *b) {  // b: table entry of the tile's first feature + 4 h
+        f32x16 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+            v[4 * q] = bq[0]; v[4 * q + 1] = bq[1]; v[4 * q + 2] = bq[2]; v[4 * q + 3] = bq[3];
+        }
+        return v;
+    };
+
+    f32x16 mu[ZT], zf[ZT];
     for (int t = 0; t < L; ++t) {
         f32x4 eps[ZT][4];
         load_noise(a.eps_q + ((size_t)t * S + (live ? smp : 0)) * Z, eps);
-        // combiner: this wavefront's quarter of tanh(W_c z + b_c), straight into B operands
-        bf16x8 hB[2 * Q];
+        // combiner: this wavefront's quarter of W_c z + b_c, all products issued before the first tanh
+        f32x16 pre[Q];
 #pragma unroll
         for (int ob = 0; ob < Q; ++ob) {
-            f32x16 acc = zero16();
+            pre[ob] = bias_tile(bias + oC + 32 * (w * Q + ob) + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) acc = mma(wc[ob][ks], zB[ks], acc);
-            const float *b = bias + oC + 32 * (w * Q + ob) + 4 * h;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[4 * q + r] = tanh_f(acc[4 * q + r] + bq[r]);
-            }
-            hB[2 * ob] = operand_of<0>(acc);
-            hB[2 * ob + 1] = operand_of<1>(acc);
+            for (int ks = 0; ks < ZK; ++ks) pre[ob] = mma(wc[ob][ks], zB[ks], pre[ob]);
         }
-        // mean: partial product over this wavefront's hidden features, then the sum over wavefronts
+        // tanh tile by tile, each straight into two B operands of the mean's partial product over
+        // this wavefront's hidden features
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) {
-            mu[nb] = zero16();
+        for (int nb = 0; nb < ZT; ++nb) mu[nb] = zero16();
 #pragma unroll
-            for (int ks = 0; ks < 2 * Q; ++ks) mu[nb] = mma(wmu[nb][ks], hB[ks], mu[nb]);
+        for (int ob = 0; ob < Q; ++ob) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) pre[ob][i] = tanh_f(pre[ob][i]);
+            const bf16x8 h0 = operand_of<0>(pre[ob]), h1 = operand_of<1>(pre[ob]);
+#pragma unroll
+            for (int nb = 0; nb < ZT; ++nb) {
+                mu[nb] = mma(wmu[nb][2 * ob], h0, mu[nb]);
+                mu[nb] = mma(wmu[nb][2 * ob + 1], h1, mu[nb]);
+            }
         }
         all_sum(mu);
         bf16x8 mB[ZK];
@@ -194,97 +204,109 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             mB[2 * nb] = operand_of<0>(mu[nb]);
             mB[2 * nb + 1] = operand_of<1>(mu[nb]);
         }
-        // scale from the mean, reparameterised draw
+        // scale from the mean, reparameterised draw.  Pad features need no masking: their mean is 0
+        // (zero weight rows, zero c_t) and their noise was loaded as 0.
 #pragma unroll
         for (int nb = 0; nb < ZT; ++nb) {
-            f32x16 acc = zero16();
+            zf[nb] = bias_tile(bias + oSig + 32 * nb + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) acc = mma(wsig[nb][ks], mB[ks], acc);
-            const float *b = bias + oSig + 32 * nb + 4 * h;
+            for (int ks = 0; ks < ZK; ++ks) zf[nb] = mma(wsig[nb][ks], mB[ks], zf[nb]);
+        }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+        for (int nb = 0; nb < ZT; ++nb) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = 4 * q + r;
-                    const float z = mu[nb][i] + softplus_f(acc[i] + bq[r]) * eps[nb][q][r];
-                    acc[i] = zfeat(nb, i) < Z ? z : 0.f;
-                }
-            }
-            if (t == L - 1 && a.z_last && live && w == 0) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int f = 32 * nb + 8 * q + 4 * h;
-                    if (f < Z) {
-                        f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-                        *reinterpret_cast<f32x4 *>(a.z_last + (size_t)smp * Z + f) = v;
-                    }
-                }
-            }
-            zB[2 * nb] = operand_of<0>(acc);
-            zB[2 * nb + 1] = operand_of<1>(acc);
+            for (int i = 0; i < 16; ++i) zf[nb][i] = mu[nb][i] + softplus_f(zf[nb][i]) * eps[nb][i >> 2][i & 3];
+            zB[2 * nb] = operand_of<0>(zf[nb]);
+            zB[2 * nb + 1] = operand_of<1>(zf[nb]);
         }
     }
+    if (a.z_last && live && w == 0) {
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int f = 32 * nb + 8 * q + 4 * h;
+                if (f < Z) {
+                    f32x4 v = {zf[nb][4 * q], zf[nb][4 * q + 1], zf[nb][4 * q + 2], zf[nb][4 * q + 3]};
+                    *reinterpret_cast<f32x4 *>(a.z_last + (size_t)smp * Z + f) = v;
+                }
+            }
+    }
 
-    // ---- gated transition: weights streamed from L2, used once ------------------------
+    // ---- gated transition: weights used once per workgroup, fetched from L2 into the registers
+    // the guide's weights occupied ------------------------------------------------------------
     // wide layer (Z -> H) of this wavefront's quarter + ReLU, then the narrow layer's partial
     // product over that quarter, summed over the wavefronts
     auto two_layer = [&](int t_wide, int o_wide, int t_narrow, f32x16 (&out)[ZT]) {
-        bf16x8 hB[2 * Q];
+        bf16x8 ww[Q][ZK], wn[ZT][2 * Q];
+#pragma unroll
+        for (int ob = 0; ob < Q; ++ob)
+#pragma unroll
+            for (int ks = 0; ks < ZK; ++ks) ww[ob][ks] = load_tile(T, t_wide + (w * Q + ob) * ZK + ks, lane);
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < 2 * Q; ++ks) wn[nb][ks] = load_tile(T, t_narrow + (w * ZT + nb) * 2 * Q + ks, lane);
+        f32x16 pre[Q];
 #pragma unroll
         for (int ob = 0; ob < Q; ++ob) {
-            f32x16 acc = zero16();
+            pre[ob] = bias_tile(bias + o_wide + 32 * (w * Q + ob) + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) acc = mma(load_tile(T, t_wide + (w * Q + ob) * ZK + ks, lane), zB[ks], acc);
-            const float *b = bias + o_wide + 32 * (w * Q + ob) + 4 * h;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[4 * q + r] = fmaxf(acc[4 * q + r] + bq[r], 0.f);
-            }
-            hB[2 * ob] = operand_of<0>(acc);
-            hB[2 * ob + 1] = operand_of<1>(acc);
+            for (int ks = 0; ks < ZK; ++ks) pre[ob] = mma(ww[ob][ks], zB[ks], pre[ob]);
         }
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) {
-            out[nb] = zero16();
+        for (int nb = 0; nb < ZT; ++nb) out[nb] = zero16();
 #pragma unroll
-            for (int ks = 0; ks < 2 * Q; ++ks)
-                out[nb] = mma(load_tile(T, t_narrow + (w * ZT + nb) * 2 * Q + ks, lane), hB[ks], out[nb]);
+        for (int ob = 0; ob < Q; ++ob) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) pre[ob][i] = fmaxf(pre[ob][i], 0.f);
+            const bf16x8 h0 = operand_of<0>(pre[ob]), h1 = operand_of<1>(pre[ob]);
+#pragma unroll
+            for (int nb = 0; nb < ZT; ++nb) {
+                out[nb] = mma(wn[nb][2 * ob], h0, out[nb]);
+                out[nb] = mma(wn[nb][2 * ob + 1], h1, out[nb]);
+            }
         }
         all_sum(out);
     };
     f32x16 gate[ZT], prop[ZT];
     two_layer(tG1, oG1, tG2, gate);
     two_layer(tP1, oP1, tP2, prop);
+    if (w != 0) return;  // every wavefront now holds the same sums; one of them finishes and writes
     f32x4 eps[ZT][4];
     load_noise(a.eps_z + (size_t)(live ? smp : 0) * Z, eps);
+    bf16x8 wl[ZT][ZK], wt[ZT][ZK];
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) {
+            wl[nb][ks] = load_tile(T, tLin + nb * ZK + ks, lane);
+            wt[nb][ks] = load_tile(T, tTs + nb * ZK + ks, lane);
+        }
     f32x16 G[ZT];
     bf16x8 gB[ZK];
 #pragma unroll
     for (int nb = 0; nb < ZT; ++nb) {
-        f32x16 lin = zero16();
+        f32x16 lin = bias_tile(bias + oLin + 32 * nb + 4 * h);
 #pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) lin = mma(load_tile(T, tLin + nb * ZK + ks, lane), zB[ks], lin);
+        for (int ks = 0; ks < ZK; ++ks) lin = mma(wl[nb][ks], zB[ks], lin);
         f32x16 relu;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int f = zfeat(nb, i);
             const float g = sigmoid_f(gate[nb][i] + bias[oG2 + f]);
-            const float v = (1.f - g) * (lin[i] + bias[oLin + f]) + g * (prop[nb][i] + bias[oP2 + f]);
+            const float v = (1.f - g) * lin[i] + g * (prop[nb][i] + bias[oP2 + f]);
             G[nb][i] = f < Z ? v : 0.f;
             relu[i] = fmaxf(G[nb][i], 0.f);
         }
         gB[2 * nb] = operand_of<0>(relu);
         gB[2 * nb + 1] = operand_of<1>(relu);
     }
-    if (w != 0) return;  // every wavefront holds the same G; one of them finishes and writes
 #pragma unroll
     for (int nb = 0; nb < ZT; ++nb) {
-        f32x16 acc = zero16();
+        f32x16 acc = bias_tile(bias + oTs + 32 * nb + 4 * h);
 #pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) acc = mma(load_tile(T, tTs + nb * ZK + ks, lane), gB[ks], acc);
+        for (int ks = 0; ks < ZK; ++ks) acc = mma(wt[nb][ks], gB[ks], acc);
         if (!live) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -293,7 +315,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int i = 4 * q + r;
-                const float zn = G[nb][i] + softplus_f(acc[i] + bias[oTs + f + r]) * eps[nb][q][r];
+                const float zn = G[nb][i] + softplus_f(acc[i]) * eps[nb][q][r];
                 v[r] = f + r < Z ? zn : 0.f;
             }
             *reinterpret_cast<f32x4 *>(a.z_next + (size_t)smp * a.Zp + f) = v;

@@ -74,14 +74,20 @@ __device__ __forceinline__ void mma_block(f32x16 &acc, const f32x4 *A, int lda, 
 }
 
 // Nonlinearities on the hardware exp2 / log2 / reciprocal units (about 1 ulp each; the absolute
-// error of every function below stays under 3e-7 of its range).
+// error of every function below stays under 3e-7 of its range).  The raw instructions are used:
+// exp2 of a large negative argument flushes to zero, which is the right limit here, and the
+// logarithm's argument lies in [1, 2], so neither needs the library's denormal handling.
 __device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+__device__ __forceinline__ float exp_f(float v) { return __builtin_amdgcn_exp2f(v * 1.44269504088896341f); }
 __device__ __forceinline__ float tanh_f(float v) {  // 1 - 2 / (exp(2v) + 1)
-    return 1.0f - 2.0f * fast_rcp(__expf(2.0f * v) + 1.0f);
+    return 1.0f - 2.0f * fast_rcp(__builtin_amdgcn_exp2f(v * 2.88539008177792681f) + 1.0f);
 }
-__device__ __forceinline__ float softplus_f(float v) { return fmaxf(v, 0.f) + __logf(1.0f + __expf(-fabsf(v))); }
+__device__ __forceinline__ float softplus_f(float v) {  // max(v, 0) + ln(1 + exp(-|v|))
+    const float e = __builtin_amdgcn_exp2f(fabsf(v) * -1.44269504088896341f);
+    return fmaxf(v, 0.f) + 0.693147180559945309f * __builtin_amdgcn_logf(1.0f + e);
+}
 __device__ __forceinline__ float sigmoid_f(float v) {
-    const float e = __expf(-fabsf(v));
+    const float e = __builtin_amdgcn_exp2f(fabsf(v) * -1.44269504088896341f);
     const float r = fast_rcp(1.0f + e);
     return v >= 0.f ? r : e * r;
 }
