@@ -80,6 +80,10 @@ struct dkf_model {
     const float *gc_tiles = nullptr, *gc_bias = nullptr, *gc_mu_w32 = nullptr, *gc_mu_b32 = nullptr;
     float *gc_cmu = nullptr;
     int gc_bias_floats = 0;
+    // emission layers and activations in fragment order (egemm.hip), bf16 models with use_gchain
+    const float *ef_w[4] = {}, *ef_b[4] = {};  // emean1, emean2, escale1, escale2
+    int ef_Hp = 0, ef_Np = 0, ef_samp_tiles = 0;
+    float *zfrag = nullptr, *h1frag = nullptr, *h2frag = nullptr, *meanfrag = nullptr, *mean_tiles = nullptr;
 
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
@@ -319,6 +323,80 @@ int pack_gchain(dkf_model *m, const RawLayers &r) {
     return rc;
 }
 
+// One dense layer as weight fragments [m_pad / 32][k_pad / 16] (same tile format as pack_gchain) + padded bias.
+int pack_frag_layer(dkf_model *m, const float *w, const float *b, int n_out, int k_in, int m_pad, int k_pad,
+                    const float **tiles_out, const float **bias_out) {
+    std::vector<uint16_t> t((size_t)(m_pad / 32) * (k_pad / 16) * 512, 0);
+    for (int ob = 0; ob < m_pad / 32; ++ob)
+        for (int ks = 0; ks < k_pad / 16; ++ks) {
+            uint16_t *dst = t.data() + ((size_t)ob * (k_pad / 16) + ks) * 512;
+            for (int lane = 0; lane < 64; ++lane)
+                for (int j = 0; j < 8; ++j) {
+                    const int row = 32 * ob + (lane & 31), k = 16 * ks + 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
+                    if (row < n_out && k < k_in) dst[lane * 8 + j] = to_bf16(w[(size_t)row * k_in + k]);
+                }
+        }
+    std::vector<float> as_floats(t.size() / 2);
+    std::memcpy(as_floats.data(), t.data(), t.size() * sizeof(uint16_t));
+    std::vector<float> bias(m_pad, 0.f);
+    for (int i = 0; i < n_out; ++i) bias[i] = b[i];
+    int rc = upload(m, as_floats.data(), as_floats.size(), tiles_out);
+    if (rc == DKF_OK) rc = upload(m, bias.data(), bias.size(), bias_out);
+    return rc;
+}
+
+int pack_emission_frags(dkf_model *m, const RawLayers &r) {
+    const int Hp = round_up(m->H, 128), Np = round_up(m->N, 128);
+    m->ef_Hp = Hp; m->ef_Np = Np;
+    m->ef_samp_tiles = (m->cfg.max_samples + 127) / 128;
+    int rc = pack_frag_layer(m, r.emean1, r.b_emean1, m->H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, r.emean2, r.b_emean2, m->N, m->H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale1, r.b_escale1, m->H, m->N, Hp, Np, &m->ef_w[2], &m->ef_b[2]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale2, r.b_escale2, m->N, m->H, Np, Hp, &m->ef_w[3], &m->ef_b[3]);
+    const size_t blocks = (size_t)m->ef_samp_tiles * 4;  // 32-sample blocks
+    void *q = nullptr;
+    if (rc == DKF_OK) rc = dev_alloc(m, blocks * 4 * 1024, &q, true);
+    m->zfrag = static_cast<float *>(q);
+    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Hp / 16) * 1024, &q, true);
+    m->h1frag = static_cast<float *>(q);
+    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Hp / 16) * 1024, &q, true);
+    m->h2frag = static_cast<float *>(q);
+    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Np / 16) * 1024, &q, true);
+    m->meanfrag = static_cast<float *>(q);
+    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Np / 32) * 4096, &q, true);
+    m->mean_tiles = static_cast<float *>(q);
+    return rc;
+}
+
+// The four emission layers on fragments; z_{T+1} fragments come from the guide/transition kernel.
+int enqueue_emission_frags(dkf_model *m, int S, const float *eps_x, float *out_samples, const dkf_stage_outputs *st,
+                           hipStream_t stream) {
+    FragGemmArgs e{};
+    e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
+    const int Hp = m->ef_Hp, Np = m->ef_Np;
+    const int st128 = (S + 127) / 128;
+    auto wide_tiles = [&] { e.tile = 2; e.feat_tiles = Np / 128; e.samp_tiles = st128; };
+    auto narrow_tiles = [&] { e.tile = 2; e.feat_tiles = Hp / 128; e.samp_tiles = st128; };
+    int rc;
+    e.wfrag = m->ef_w[0]; e.bias = m->ef_b[0]; e.xfrag = m->zfrag; e.k_steps = 4; narrow_tiles();
+    e.epilogue = m->cfg.emit_mean_act ? kFragRelu : kFragIdentity;
+    e.out_frag = m->h1frag; e.out_k_steps = Hp / 16;
+    if ((rc = launch_frag_gemm(e, kStageEmitHidden, stream)) != DKF_OK) return rc;
+    e.wfrag = m->ef_w[1]; e.bias = m->ef_b[1]; e.xfrag = m->h1frag; e.k_steps = Hp / 16; wide_tiles();
+    e.epilogue = kFragMean; e.out_frag = m->meanfrag; e.out_k_steps = Np / 16;
+    e.mean_tiles = m->mean_tiles; e.mean_blocks = Np / 32;
+    if ((rc = launch_frag_gemm(e, kStageEmitMean, stream)) != DKF_OK) return rc;
+    e.wfrag = m->ef_w[2]; e.bias = m->ef_b[2]; e.xfrag = m->meanfrag; e.k_steps = Np / 16; narrow_tiles();
+    e.epilogue = kFragRelu; e.out_frag = m->h2frag; e.out_k_steps = Hp / 16;
+    if ((rc = launch_frag_gemm(e, kStageEmitScaleHidden, stream)) != DKF_OK) return rc;
+    e.wfrag = m->ef_w[3]; e.bias = m->ef_b[3]; e.xfrag = m->h2frag; e.k_steps = Hp / 16; wide_tiles();
+    e.epilogue = kFragDraw; e.out_frag = nullptr; e.out_k_steps = 0;
+    e.eps_x = eps_x; e.out_samples = out_samples;
+    e.out_mean_dbg = st ? st->emit_mean : nullptr;
+    e.out_sd_dbg = st ? st->emit_sd : nullptr;
+    return launch_frag_gemm(e, kStageEmitScaleDraw, stream);
+}
+
 size_t blob_floats(const dkf_config *c) {
     const size_t N = c->n_workers, Z = c->z_dim, H = c->hidden, R = c->rnn_dim;
     const size_t rnn = 2 * (R * N + R + R * R + R);
@@ -528,10 +606,19 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
         c.eps_q = eps_q; c.eps_z = eps_z;
         c.z_last = st ? st->z_last : nullptr;
         c.z_next_dbg = st ? st->z_next : nullptr;
-        c.z_next = m->z_next;
+        c.z_next = nullptr;
+        c.zfrag = m->zfrag;
         c.S = S; c.L = m->L; c.Z = m->Z; c.Zp = m->Zp; c.R = m->R; c.H = m->H;
-        rc = launch_gchain(c, stream);
-        if (rc != DKF_OK && rc != DKF_EUNSUPPORTED && rc != DKF_EINVAL) return rc;
+        const bool aligned = ((reinterpret_cast<uintptr_t>(eps_x) | reinterpret_cast<uintptr_t>(out_samples) |
+                               (st ? reinterpret_cast<uintptr_t>(st->emit_mean) | reinterpret_cast<uintptr_t>(st->emit_sd) : 0)) & 15) == 0;
+        if (aligned) rc = launch_gchain(c, stream);
+        if (rc == DKF_OK) {
+            rc = enqueue_emission_frags(m, S, eps_x, out_samples, st, stream);
+            if (rc != DKF_OK) return rc;
+            if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
+            return DKF_OK;
+        }
+        if (rc != DKF_EUNSUPPORTED && rc != DKF_EINVAL) return rc;
     }
     if (rc != DKF_OK) {  // sizes (or caller buffers not 16-byte aligned) the register-resident kernel does not take
     GuideArgs g;
@@ -701,6 +788,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
     m->use_gchain = bf16 && gchain_q(Z, R, H) != 0 && m->Zp == 64;
     if (m->use_gchain) DKF_CHECK(pack_gchain(m, raw));
+    if (m->use_gchain) DKF_CHECK(pack_emission_frags(m, raw));
 
     void *q = nullptr;
     DKF_CHECK(dev_alloc(m, m->in_floats() * 4, &q, true)); m->d_in = static_cast<float *>(q);

@@ -140,11 +140,37 @@ struct GChainArgs {
     const float *z0;               // [64] zero padded
     const float *eps_q, *eps_z;    // [L][S][Z], [S][Z]
     float *z_last, *z_next_dbg;    // [S][Z] or NULL
-    float *z_next;                 // [S][Zp]: input of the emission
+    float *z_next;                 // [S][Zp] fp32 rows or NULL
+    float *zfrag;                  // [ceil(S/32)][4][64 lanes][16 B] z_{T+1} as bf16 B fragments, or NULL
     int S, L, Z, Zp, R, H;
 };
 int gchain_q(int Z, int R, int H);  // 0: sizes the kernel is not built for
 int launch_gchain(const GChainArgs &a, hipStream_t stream);
+
+// egemm.hip: one dense layer on operands in fragment order (1 KiB = 32 rows x 16 k, bf16, the
+// k order of GChainArgs::tiles): out^T = epilogue(W x^T + b)
+enum FragEpilogue : int {
+    kFragIdentity = 0,  // y -> bf16 fragments
+    kFragRelu = 1,      // relu(y) -> bf16 fragments
+    kFragMean = 2,      // y -> bf16 fragments and fp32 result tiles
+    kFragDraw = 3,      // sd = softplus(y); x = s * (mean + sd * eps) -> [S][N] rows
+};
+struct FragGemmArgs {
+    int tile;            // 2: workgroups of 128 features x 128 samples (the only size built)
+    const float *wfrag;  // [32-feature block][k_steps][64][16 B], feat_tiles * 2 * tile blocks
+    const float *xfrag;  // [32-sample block][k_steps][64][16 B], samp_tiles * 2 * tile blocks
+    const float *bias;   // fp32 per feature, zero padded
+    int k_steps, feat_tiles, samp_tiles, epilogue;
+    float *out_frag;     // [32-sample block][out_k_steps][64][16 B], out_k_steps = padded features / 16
+    int out_k_steps;
+    float *mean_tiles;   // kFragMean: out, kFragDraw: in; [32-sample block][mean_blocks][4][64] float4
+    int mean_blocks;     // padded N / 32
+    const Control *ctl;  // kFragDraw: the normaliser
+    const float *eps_x;  // [S][N]
+    float *out_samples, *out_mean_dbg, *out_sd_dbg;  // [S][N]
+    int S, N;
+};
+int launch_frag_gemm(const FragGemmArgs &a, int stage, hipStream_t stream);
 
 // mlp_gemm.hip
 enum Epilogue : int {

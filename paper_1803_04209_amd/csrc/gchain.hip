@@ -307,18 +307,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         f32x16 acc = bias_tile(bias + oTs + 32 * nb + 4 * h);
 #pragma unroll
         for (int ks = 0; ks < ZK; ++ks) acc = mma(wt[nb][ks], gB[ks], acc);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float zn = G[nb][i] + softplus_f(acc[i]) * eps[nb][i >> 2][i & 3];
+            acc[i] = zfeat(nb, i) < Z ? zn : 0.f;
+        }
+        if (a.zfrag) {  // B fragments of the emission's first layer (all 32 lanes: rows beyond S are finite padding)
+            f32x4 *out = reinterpret_cast<f32x4 *>(a.zfrag) + ((size_t)blockIdx.x * ZK + 2 * nb) * 64 + lane;
+            out[0] = __builtin_bit_cast(f32x4, operand_of<0>(acc));
+            out[64] = __builtin_bit_cast(f32x4, operand_of<1>(acc));
+        }
         if (!live) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int f = 32 * nb + 8 * q + 4 * h;
-            f32x4 v;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = 4 * q + r;
-                const float zn = G[nb][i] + softplus_f(acc[i]) * eps[nb][q][r];
-                v[r] = f + r < Z ? zn : 0.f;
-            }
-            *reinterpret_cast<f32x4 *>(a.z_next + (size_t)smp * a.Zp + f) = v;
+            const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            if (a.z_next) *reinterpret_cast<f32x4 *>(a.z_next + (size_t)smp * a.Zp + f) = v;
             if (a.z_next_dbg && f < Z) *reinterpret_cast<f32x4 *>(a.z_next_dbg + (size_t)smp * Z + f) = v;
         }
     }
