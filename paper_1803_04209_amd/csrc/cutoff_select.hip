@@ -68,6 +68,35 @@ __device__ __forceinline__ T tmin(T a, T b) { return a < b ? a : b; }
 template <typename T>
 __device__ __forceinline__ T tmax(T a, T b) { return a < b ? b : a; }
 
+// ---- cross-lane exchanges of 32-bit keys without the LDS crossbar where possible ---------
+// DPP moves reach lane ^ 1, ^ 2, ^ 8 and the mirror images inside 4, 8 and 16 lanes directly and
+// lane ^ 4 as two mirrors; only distances 16 and 32 go through ds_bpermute.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+// value of lane ^ LM for LM = 2^k, or of lane ^ LM for LM = 2^k - 1 (mirror inside 2^k lanes)
+template <int LM>
+__device__ __forceinline__ uint32_t from_lane_xor(uint32_t x) {
+    if constexpr (LM == 1) return dpp_mov<0xB1>(x);                      // quad_perm [1,0,3,2]
+    else if constexpr (LM == 2) return dpp_mov<0x4E>(x);                 // quad_perm [2,3,0,1]
+    else if constexpr (LM == 3) return dpp_mov<0x1B>(x);                 // quad_perm [3,2,1,0]
+    else if constexpr (LM == 4) return dpp_mov<0x1B>(dpp_mov<0x141>(x)); // (l ^ 7) ^ 3
+    else if constexpr (LM == 7) return dpp_mov<0x141>(x);                // row_half_mirror
+    else if constexpr (LM == 8) return dpp_mov<0x128>(x);                // row_ror:8
+    else if constexpr (LM == 15) return dpp_mov<0x140>(x);               // row_mirror
+    else return (uint32_t)__shfl_xor((int)x, LM, 64);
+}
+// median of three: with c = 0 it is min(a, b), with c = 0xFFFFFFFF it is max(a, b), so one
+// instruction serves the lanes that keep the smaller key and those that keep the larger one
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+// 0 in lanes whose group-lane bit `bit` is clear (they keep the minimum), all ones in the others
+__device__ __forceinline__ uint32_t keep_mask(int g, int bit) { return (g >> bit) & 1 ? 0xFFFFFFFFu : 0u; }
+
 // Compare-exchange across element bit B (partner = i ^ 2^B); the element whose
 // bit B is clear keeps the smaller key.
 template <typename T, int E, int LG, int B>
@@ -75,11 +104,17 @@ __device__ __forceinline__ void xor_stage(T (&v)[E], int g) {
     using Lay = Layout<E, LG>;
     if constexpr (Lay::is_lane_bit(B)) {
         constexpr int lm = 1 << Lay::lane_bit(B);
-        const bool keep_min = (g & lm) == 0;
+        if constexpr (sizeof(T) == 4) {
+            const uint32_t sel = keep_mask(g, Lay::lane_bit(B));
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            T p = __shfl_xor(v[e], lm, 64);
-            v[e] = keep_min ? tmin(v[e], p) : tmax(v[e], p);
+            for (int e = 0; e < E; ++e) v[e] = umed3(v[e], from_lane_xor<lm>(v[e]), sel);
+        } else {
+            const bool keep_min = (g & lm) == 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                T p = __shfl_xor(v[e], lm, 64);
+                v[e] = keep_min ? tmin(v[e], p) : tmax(v[e], p);
+            }
         }
     } else {
         constexpr int rm = 1 << Lay::reg_bit(B);
@@ -113,12 +148,23 @@ __device__ __forceinline__ void flip_stage(T (&v)[E], int g) {
         }
     } else {
         T p[E];
+        if constexpr (sizeof(T) == 4) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) p[e] = __shfl_xor(v[e ^ rm], lm, 64);
+            for (int e = 0; e < E; ++e) p[e] = from_lane_xor<lm>(v[e ^ rm]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) p[e] = __shfl_xor(v[e ^ rm], lm, 64);
+        }
         if constexpr (Lay::is_lane_bit(top)) {
-            const bool keep_min = (g & (1 << Lay::lane_bit(top))) == 0;
+            if constexpr (sizeof(T) == 4) {
+                const uint32_t sel = keep_mask(g, Lay::lane_bit(top));
 #pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = keep_min ? tmin(v[e], p[e]) : tmax(v[e], p[e]);
+                for (int e = 0; e < E; ++e) v[e] = umed3(v[e], p[e], sel);
+            } else {
+                const bool keep_min = (g & (1 << Lay::lane_bit(top))) == 0;
+#pragma unroll
+                for (int e = 0; e < E; ++e) v[e] = keep_min ? tmin(v[e], p[e]) : tmax(v[e], p[e]);
+            }
         } else {
             constexpr int tb = 1 << Lay::reg_bit(top);
 #pragma unroll
