@@ -387,12 +387,14 @@ __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ p
     omega_argmax_body<256>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v, best_c);
 }
 
-// Both reduction levels and the argmax in one workgroup, for the smallest problems (a few KiB of
-// per-block sums): the same sums in the same order as the two kernels above.  (A single launch
-// in which the last workgroup to finish does the argmax was measured slower at every size: making
-// one workgroup's sums visible to another inside a kernel costs a write-back of the XCD's L2.)
+// Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
+// enough (a few thousand per thread at most) that one launch beats two: thread (part, col) adds
+// the blocks part, part + P, ... of one rank with eight loads in flight, the P parts of a rank are
+// added in order from LDS.  (A single launch in which the last workgroup of the sort does the
+// argmax was measured slower at every size: making one workgroup's sums visible to another
+// inside a kernel costs a write-back of the XCD's L2.)
 constexpr int kFusedMeansMaxN = 128;          // widest row the one-workgroup reduction takes
-constexpr int kFusedMeansMaxSums = 8192;      // most per-block sums it takes (blocks x N)
+constexpr int kFusedMeansMaxSums = 32768;     // most per-block sums it takes (blocks x N)
 
 constexpr int kFusedThreads = 1024;
 __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *__restrict__ partial, int blocks,
@@ -400,16 +402,28 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
                                                                    float t_floor, float *__restrict__ out_mean,
                                                                    float *__restrict__ out_omega,
                                                                    int32_t *__restrict__ out_cstar) {
-    __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N]
+    __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N], unused parts are zero
     __shared__ double best_v[kFusedThreads];
     __shared__ int best_c[kFusedThreads];
-    for (int i = threadIdx.x; i < kMeanParts * N; i += kFusedThreads) {
-        const int col = i % N, p = i / N;
-        const double r0 = block_subset_sum(partial, blocks, npad, col, 4 * p + 0);
-        const double r1 = block_subset_sum(partial, blocks, npad, col, 4 * p + 1);
-        const double r2 = block_subset_sum(partial, blocks, npad, col, 4 * p + 2);
-        const double r3 = block_subset_sum(partial, blocks, npad, col, 4 * p + 3);
-        part2[i] = ((r0 + r1) + r2) + r3;
+    int cols = 1;
+    while (cols < N) cols <<= 1;               // threads per part (a power of two >= N)
+    int P = kFusedThreads / cols;              // parts
+    if (P > kMeanParts) P = kMeanParts;
+    const int col = threadIdx.x % cols, part = threadIdx.x / cols;
+    for (int i = threadIdx.x; i < kMeanParts * N; i += kFusedThreads) part2[i] = 0.0;
+    __syncthreads();
+    if (col < N && part < P) {
+        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int b = part;
+        for (; b + 7 * P < blocks; b += 8 * P) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = partial[(size_t)(b + j * P) * npad + col];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s[j] += (double)v[j];
+        }
+        for (int j = 0; b < blocks; b += P, ++j) s[j] += (double)partial[(size_t)b * npad + col];
+        part2[part * N + col] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
     }
     __syncthreads();
     omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
@@ -433,7 +447,7 @@ SortPlan plan_for(int S, int N) {
     p.npad = npad;
     const int rows_per_block = kThreads / g;
     int blocks = (S + rows_per_block - 1) / rows_per_block;
-    const int cap = 1024;  // a few blocks per compute unit; more rows per group beyond that
+    const int cap = 2048;  // up to eight blocks per compute unit (measured best); more rows per group beyond that
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     p.blocks = blocks;
