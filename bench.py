@@ -44,6 +44,11 @@ def stage_work(cfg):
 STAGE_SOURCES = {
     "sampler_fused": ["chain.hip", "quad.hip", "common.h", "mfma_tile.h"],
     "sort_rank_sums": ["cutoff_select.hip", "common.h"],
+    "guide_transition": ["gchain.hip", "guide.hip", "common.h", "mfma_tile.h"],
+    "emit_hidden": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
+    "emit_mean": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
+    "emit_scale_hidden": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
+    "emit_scale_draw": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
 }
 
 
@@ -147,6 +152,7 @@ def main():
     torch.cuda.synchronize()
     lat = np.empty(K)
     cuts = np.empty(K, dtype=np.int64)
+    first_timed = t_idx
     t_start = time.perf_counter()
     for i in range(K):
         t0 = time.perf_counter()
@@ -206,6 +212,18 @@ def main():
         "frac": achieved / peak, "traffic": stored_traffic(cfg.name, api.STAGE_NAMES[dominant]), "launches": n_launch, "avg_launch_us": kernel_s * 1e6,
         "work_per_launch": amount,
     }
+    # Gradients per second the chosen cutoffs would have achieved on the iterations that followed
+    # each decision (Fig. 2's three curves: chosen, wait for all, best cutoff in hindsight).
+    nxt = np.sort(trace[first_timed + 1:first_timed + 1 + K].astype(np.float64), axis=1)
+    rank = np.arange(1, N + 1)
+    best = np.argmax((rank / nxt)[:, ::-1], axis=1)
+    best = N - 1 - best
+    implied = {
+        "chosen_cutoffs": float(cuts.sum() / nxt[np.arange(K), cuts - 1].sum()),
+        "full_sync": float(K * N / nxt[:, -1].sum()),
+        "hindsight_best": float((best + 1).sum() / nxt[np.arange(K), best].sum()),
+        "note": "seed-initialised (untrained) weights: says nothing about forecast quality",
+    }
     mlp_flops = sum(v for s, (b, v) in work.items() if b == "mfma")
     mlp_us = sum(stage_us[s] for s, (b, _) in work.items() if b == "mfma")
 
@@ -218,6 +236,7 @@ def main():
         "decisions_per_s": K / wall,
         "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3)},
         "mean_cutoff": float(cuts.mean()),
+        "implied_gradients_per_s": implied,
         "eager_pipelined": {"vectors_per_s": S * K / eager_wall, "ms_per_step": eager_wall / K * 1e3},
         "stage_us": {api.STAGE_NAMES[s]: round(stage_us[s], 2) for s in range(api.DKF_NUM_STAGES)},
         "mlp_stages": {"flops": mlp_flops, "us": mlp_us, "tflops": mlp_flops / (mlp_us * 1e-6) / 1e12,
