@@ -148,7 +148,11 @@ size_t cutoff_select_workspace(int32_t S, int32_t N);
  * 0, replayed from a captured HIP graph after the first call with a given S.
  * Noise comes from the caller's tensors (eps_* as in dkf_sample_runtimes, read
  * at every call from the same addresses) or, if they are NULL, from `seed`.
- * Synchronises the stream and writes c* to *cstar_host.
+ * Blocks until the decision has arrived and writes c* to *cstar_host.  (The
+ * last kernel of the graph stores the decision and a per-call ticket in pinned
+ * host memory, which the call watches; every kernel of the decision has
+ * finished by then, but the stream may report busy for a few microseconds
+ * more.  If the ticket does not arrive the stream is synchronised instead.)
  * Returns DKF_OK, DKF_WARMUP (then *cstar_host = N), CUTOFF_NO_ELIGIBLE, or
  * an error. */
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,

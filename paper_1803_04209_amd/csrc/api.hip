@@ -99,7 +99,8 @@ struct dkf_model {
     bool staging_used[kStagingSlots] = {};
     int staging_next = 0;
     float *staging_graph = nullptr;
-    int32_t *cstar_host = nullptr;  // pinned int32[2]
+    int32_t *cstar_host = nullptr;  // pinned int32[4]: c*, status, ticket of the decision they belong to
+    int32_t ticket = 0;             // sequence number of the last decision handed to the GPU
 
     // workspace
     float *z_next = nullptr, *hid1 = nullptr, *mean = nullptr, *hid2 = nullptr;
@@ -537,7 +538,7 @@ int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *ds
     c.slot = slot;
     c.count = count;
     c.oldest = count < L ? 0 : (slot + 1) % L;
-    c.reserved0 = 0;
+    c.ticket = 0;
     c.scale = m->scale;
     c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
     c.seed_lo = (uint32_t)seed;
@@ -547,6 +548,10 @@ int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *ds
 }
 
 int copy_ctx(dkf_model *m, float *dst, hipStream_t stream);
+
+// Host polls of the decision's ticket before falling back to a stream synchronisation (a few
+// hundred milliseconds: far beyond any decision this library takes).
+constexpr long kTicketSpins = 50L * 1000 * 1000;
 
 // Up to this many samples the four-per-wavefront sampler is used where both are available (at
 // 16 per wavefront, 16384 samples are what fills every SIMD of the chip once).
@@ -822,9 +827,10 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     }
     {
         void *h = nullptr;
-        DKF_CHECK_HIP(hipHostMalloc(&h, 2 * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent));
+        DKF_CHECK_HIP(hipHostMalloc(&h, 4 * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent));
         m->host_allocs.push_back(h);
         m->cstar_host = static_cast<int32_t *>(h);
+        std::memset(h, 0, 4 * sizeof(int32_t));
     }
     DKF_CHECK_HIP(hipStreamCreateWithFlags(&m->own_stream, hipStreamNonBlocking));
     m->window.assign((size_t)L * N, 0.f);
@@ -895,6 +901,8 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         if (m->staging_used[i]) { DKF_HIP_TRY(hipEventSynchronize(m->staging_done[i])); m->staging_used[i] = false; }
     const int status = stage_observation(m, x_obs, seed, m->staging_graph);
     if (status < 0) return status;
+    const int32_t ticket = m->ticket = m->ticket == INT32_MAX ? 1 : m->ticket + 1;
+    reinterpret_cast<Control *>(m->staging_graph + m->Np)->ticket = ticket;
     if (status == DKF_WARMUP) {
         const int rc = launch_filter(filter_args(m, m->staging_graph), true, false, stream);
         if (rc != DKF_OK) return rc;
@@ -919,7 +927,7 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
                            : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
         if (rc == DKF_OK)
             rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
-                                      m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream);
+                                      m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream, &m->ctl_dev()->ticket);
         g_capturing--;
         hipGraph_t graph = nullptr;
         e = hipStreamEndCapture(stream, &graph);
@@ -931,9 +939,20 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         m->graph_eps[0] = eps_q; m->graph_eps[1] = eps_z; m->graph_eps[2] = eps_x;
     }
     DKF_HIP_TRY(hipGraphLaunch(m->graph_exec, stream));
-    DKF_HIP_TRY(hipStreamSynchronize(stream));
-    *cstar_host = m->cstar_host[0];
-    return m->cstar_host[1];
+    // The last kernel stores {c*, status} and then this decision's ticket into pinned host memory.
+    // Watching for the ticket returns the decision a few microseconds before the runtime's own
+    // completion path would; the stream is synchronised as well if the ticket does not show up.
+    volatile int32_t *box = m->cstar_host;
+    bool seen = false;
+    for (long spin = 0; spin < kTicketSpins; ++spin) {
+        if (box[2] == ticket) { seen = true; break; }
+        __builtin_ia32_pause();
+    }
+    if (!seen) DKF_HIP_TRY(hipStreamSynchronize(stream));
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    if (box[2] != ticket) return DKF_EHIP;
+    *cstar_host = box[0];
+    return box[1];
 }
 
 const float *dkf_decide_samples(const dkf_model *m) { return m ? m->samples : nullptr; }

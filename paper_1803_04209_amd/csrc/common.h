@@ -58,7 +58,7 @@ struct Control {
     int32_t slot;       // ring slot the new observation goes to
     int32_t count;      // observations in the window after this push (<= L)
     int32_t oldest;     // ring slot of the oldest observation in the window
-    int32_t reserved0;
+    int32_t ticket;     // sequence number of the decision this block belongs to (0: none); echoed next to c*
     float scale;        // normaliser s (0 while warming up)
     float inv_scale;    // 1/s
     uint32_t seed_lo;   // seed of the built-in generator for this step
@@ -257,7 +257,8 @@ int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl
 // cutoff_select.hip
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
-                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream);
+                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
+                         const int32_t *ticket = nullptr);  // dev: if set, *ticket is stored to out_cstar[2] after c*
 size_t cutoff_workspace_bytes(int S, int N);
 
 // impute.hip

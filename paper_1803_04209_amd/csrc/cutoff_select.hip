@@ -344,7 +344,7 @@ template <int THREADS>
 __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, int S, int c_min, int c_max,
                                                   float t_floor, float *__restrict__ out_mean,
                                                   float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
-                                                  double *best_v, int *best_c) {
+                                                  double *best_v, int *best_c, const int32_t *ticket) {
     double bv = -INFINITY;
     int bc = 0;
     for (int c = threadIdx.x + 1; c <= N; c += THREADS) {
@@ -376,15 +376,20 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
         const bool none = best_c[0] == 0;
         out_cstar[0] = none ? c_max : best_c[0];
         out_cstar[1] = none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
+        if (ticket) {  // a host polling out_cstar[2] (pinned memory) must see the decision first
+            __threadfence_system();
+            __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
 __global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ part2, int N, int S, int c_min,
                                                     int c_max, float t_floor, float *__restrict__ out_mean,
-                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar) {
+                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
+                                                    const int32_t *ticket) {
     __shared__ double best_v[256];
     __shared__ int best_c[256];
-    omega_argmax_body<256>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v, best_c);
+    omega_argmax_body<256>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v, best_c, ticket);
 }
 
 // Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
@@ -401,7 +406,8 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
                                                                    int npad, int N, int S, int c_min, int c_max,
                                                                    float t_floor, float *__restrict__ out_mean,
                                                                    float *__restrict__ out_omega,
-                                                                   int32_t *__restrict__ out_cstar) {
+                                                                   int32_t *__restrict__ out_cstar,
+                                                                   const int32_t *ticket) {
     __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N], unused parts are zero
     __shared__ double best_v[kFusedThreads];
     __shared__ int best_c[kFusedThreads];
@@ -427,7 +433,7 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
     }
     __syncthreads();
     omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                     best_c);
+                                     best_c, ticket);
 }
 
 struct SortPlan {
@@ -475,7 +481,8 @@ size_t cutoff_workspace_bytes(int S, int N) {
 
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
-                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream) {
+                         int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
+                         const int32_t *ticket) {
     if (!samples || !out_cstar || !workspace) return DKF_EINVAL;
     if (S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return DKF_EINVAL;
     if (t_floor != t_floor) return DKF_EINVAL;
@@ -516,14 +523,14 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
         StageTimer timer(kStageArgmax, stream);
         if (N <= kFusedMeansMaxN && p.blocks * N <= kFusedMeansMaxSums) {
             hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
-                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar);
+                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket);
             DKF_HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
                                p.blocks, p.npad, N, part2);
             DKF_HIP_TRY(hipGetLastError());
             hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, part2, N, S, c_min, c_max, t_floor,
-                               out_mean, out_omega, out_cstar);
+                               out_mean, out_omega, out_cstar, ticket);
             DKF_HIP_TRY(hipGetLastError());
         }
     }
