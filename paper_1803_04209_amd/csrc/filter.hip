@@ -18,6 +18,24 @@ constexpr int kProjRowsPerBlock = 4;  // one row per wavefront: R/4 workgroups p
 constexpr int kChainThreads = 1024;
 constexpr float kCoopEmpty = -1.0f;  // "not written yet" in ctx while the multi-workgroup encoder runs (states are >= 0)
 
+// Sum over aligned groups of TPR lanes (TPR a power of two <= 64); every lane of a group gets the
+// total.  Up to 16 lanes the partners come by DPP moves (lane ^ 1, lane ^ 2, mirror inside 8, mirror
+// inside 16: any pairing across the halves does for a sum), beyond that through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int TPR>
+__device__ __forceinline__ float group_sum(float v) {
+    if constexpr (TPR >= 2) v += dpp_f<0xB1>(v);
+    if constexpr (TPR >= 4) v += dpp_f<0x4E>(v);
+    if constexpr (TPR >= 8) v += dpp_f<0x141>(v);
+    if constexpr (TPR >= 16) v += dpp_f<0x140>(v);
+    if constexpr (TPR >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (TPR >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
@@ -200,8 +218,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
                 for (int j = seg; j < N; j += TPR) s += wi[j] * xs[j];
             }
         }
-#pragma unroll
-        for (int d = 1; d < TPR; d <<= 1) s += __shfl_xor(s, d, 64);
+        s = group_sum<TPR>(s);
         if (seg == 0) {
             newp[row] = s;
             if (row < R) proj[(size_t)ctl.slot * R + row] = s;
@@ -222,13 +239,25 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
 #pragma unroll
         for (int j = 0; j < KPT; ++j) wreg[j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
     }
-    for (int i = tid; i < L * ROWS; i += kChainThreads) {
-        const int step = i / ROWS, r = i % ROWS;
-        const int t = dir ? L - 1 - step : step;
-        int slot = ctl.oldest + t;
-        if (slot >= L) slot -= L;
-        const float pv = (a.project && slot == ctl.slot) ? 0.f : (r < R ? proj[(size_t)slot * R + r] : 0.f);  // new one: from LDS below
-        pre[i] = r < R ? pv * ctl.inv_scale + bias[r] : 0.f;
+    for (int i0 = tid; i0 < L * ROWS; i0 += 4 * kChainThreads) {  // four loads in flight per thread
+        float pv[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            const int step = i / ROWS, r = i % ROWS;
+            const int t = dir ? L - 1 - step : step;
+            int slot = ctl.oldest + t;
+            if (slot >= L) slot -= L;
+            const bool ok = i < L * ROWS && r < R;
+            // (the new observation's term comes from LDS below)
+            pv[u] = (ok && !(a.project && slot == ctl.slot)) ? proj[(size_t)slot * R + r] : 0.f;
+            bv[u] = ok ? bias[r] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            if (i < L * ROWS) pre[i] = pv[u] * ctl.inv_scale + bv[u];
+        }
     }
     for (int i = tid; i < 2 * HSTRIDE; i += kChainThreads) h0[i] = 0.f;
     __syncthreads();
@@ -246,18 +275,21 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
         float s = 0.f;
         const float *hp = h_prev + k0 + seg * 4;
         if (KPT >= 4) {
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;  // four chains instead of one of KPT dependent adds
 #pragma unroll
             for (int j = 0; j < KPT; j += 4) {
                 const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
-                s += wreg[j] * hv.x + wreg[j + 1 < KPT ? j + 1 : j] * hv.y + wreg[j + 2 < KPT ? j + 2 : j] * hv.z +
-                     wreg[j + 3 < KPT ? j + 3 : j] * hv.w;
+                s0 += wreg[j] * hv.x;
+                s1 += wreg[j + 1 < KPT ? j + 1 : j] * hv.y;
+                s2 += wreg[j + 2 < KPT ? j + 2 : j] * hv.z;
+                s3 += wreg[j + 3 < KPT ? j + 3 : j] * hv.w;
             }
+            s = (s0 + s1) + (s2 + s3);
         } else {
 #pragma unroll
             for (int j = 0; j < KPT; ++j) s += wreg[j] * hp[j];
         }
-#pragma unroll
-        for (int d = 1; d < TPR; d <<= 1) s += __shfl_xor(s, d, 64);
+        s = group_sum<TPR>(s);
         if (seg == 0) {
             const float v = fmaxf(pre[step * ROWS + row] + s, 0.f);
             h_next[row + (row / KPT) * 4] = v;
@@ -265,6 +297,95 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
         }
         __syncthreads();
         float *tmp = h_prev; h_prev = h_next; h_next = tmp;
+    }
+}
+
+// The same recurrence for 128 < R <= 256 with four rows per thread: thread (row group, segment) holds
+// a 4 x 16 block of the matrix, so a step reads only 16 state values per thread from LDS (a quarter
+// of what one row x 64 columns per thread reads: that variant is bound by LDS bandwidth) at the
+// price of four 16-lane reductions.  No fused projection: the input terms come from the ring.
+// Dynamic LDS: (L * 256 + 2 * 320) floats.
+__global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a) {
+    constexpr int ROWS = 256, TPR = 16, KPT = 16, RPT = 4, SEG = KPT + 4, HBUF = TPR * SEG;
+    extern __shared__ __align__(16) float lds[];
+    const Control ctl = *a.ctl;
+    const int dir = blockIdx.x;
+    const int R = a.R, L = a.L;
+    if (ctl.count < L) return;
+    const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
+    const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
+    const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
+    float *__restrict__ ctx = dir ? a.ctx_b : a.ctx_f;
+    float *pre = lds;             // [L][ROWS] input term of every step
+    float *h = lds + L * ROWS;    // two buffers [TPR][SEG]
+    const int tid = threadIdx.x;
+    const int rg = tid / TPR, seg = tid % TPR, k0 = seg * KPT;
+
+    // input terms of every step first (their loads are then in flight together with the matrix's)
+    for (int i0 = tid; i0 < L * ROWS; i0 += 4 * kChainThreads) {
+        float pv[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            const int step = i / ROWS, r = i % ROWS;
+            const int t = dir ? L - 1 - step : step;
+            int slot = ctl.oldest + t;
+            if (slot >= L) slot -= L;
+            const bool ok = i < L * ROWS && r < R;
+            pv[u] = ok ? proj[(size_t)slot * R + r] : 0.f;
+            bv[u] = ok ? bias[r] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            if (i < L * ROWS) pre[i] = pv[u] * ctl.inv_scale + bv[u];
+        }
+    }
+    float wreg[RPT][KPT];
+    if (R == ROWS) {  // the whole tile is inside the matrix: plain 16-byte loads
+#pragma unroll
+        for (int i = 0; i < RPT; ++i)
+#pragma unroll
+            for (int j = 0; j < KPT; j += 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(w + (size_t)(rg * RPT + i) * ROWS + k0 + j);
+                wreg[i][j] = v.x; wreg[i][j + 1] = v.y; wreg[i][j + 2] = v.z; wreg[i][j + 3] = v.w;
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+            const int row = rg * RPT + i;
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) wreg[i][j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
+        }
+    }
+    for (int i = tid; i < 2 * HBUF; i += kChainThreads) h[i] = 0.f;
+    __syncthreads();
+
+    const int my_row = rg * RPT + (seg & (RPT - 1));  // lanes 0..3 of a row group write one row each
+    for (int step = 0; step < L; ++step) {
+        const int t = dir ? L - 1 - step : step;
+        float s[RPT] = {0.f, 0.f, 0.f, 0.f};
+        if (step > 0) {
+            const float *hp = h + (step & 1) * HBUF + seg * SEG;
+#pragma unroll
+            for (int j = 0; j < KPT; j += 4) {
+                const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
+#pragma unroll
+                for (int i = 0; i < RPT; ++i)
+                    s[i] += (wreg[i][j] * hv.x + wreg[i][j + 1] * hv.y) + (wreg[i][j + 2] * hv.z + wreg[i][j + 3] * hv.w);
+            }
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) s[i] = group_sum<TPR>(s[i]);
+        }
+        float mine = s[0];
+#pragma unroll
+        for (int i = 1; i < RPT; ++i) mine = (seg & (RPT - 1)) == i ? s[i] : mine;
+        if (seg < RPT) {
+            const float v = fmaxf(pre[step * ROWS + my_row] + mine, 0.f);
+            h[((step + 1) & 1) * HBUF + (my_row / KPT) * SEG + my_row % KPT] = v;
+            if (my_row < R) ctx[(size_t)t * a.Rp + my_row] = v;
+        }
+        __syncthreads();
     }
 }
 
@@ -282,14 +403,6 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
 constexpr int kCoopRows = 64;
 constexpr int kCoopTpr = kChainThreads / kCoopRows;  // 16 lanes per row = one DPP row
 constexpr int kCoopSpinLimit = 1 << 20;
-
-__device__ __forceinline__ float row16_sum(float v) {
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // 7 - lane within 8
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // 15 - lane within 16
-    return v;
-}
 
 template <int KPT>
 __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a) {
@@ -312,6 +425,13 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
     const int row = blockIdx.x * kCoopRows + row_local, k0 = seg * KPT;
 
     float wreg[KPT];
+    if (R == kCoopTpr * KPT && (R % kCoopRows) == 0) {  // the whole tile is inside the matrix: plain 16-byte loads
+#pragma unroll
+        for (int j = 0; j < KPT; j += 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(w + (size_t)row * R + k0 + j);
+            wreg[j] = v.x; wreg[j + 1] = v.y; wreg[j + 2] = v.z; wreg[j + 3] = v.w;
+        }
+    } else
 #pragma unroll
     for (int j = 0; j < KPT; j += 4) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -327,12 +447,24 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
         }
         wreg[j] = v.x; wreg[j + 1] = v.y; wreg[j + 2] = v.z; wreg[j + 3] = v.w;
     }
-    for (int i = tid; i < L * kCoopRows; i += kChainThreads) {
-        const int step = i / kCoopRows, r = blockIdx.x * kCoopRows + i % kCoopRows;
-        const int t = dir ? L - 1 - step : step;
-        int slot = ctl.oldest + t;
-        if (slot >= L) slot -= L;
-        pre[i] = r < R ? proj[(size_t)slot * R + r] * ctl.inv_scale + bias[r] : 0.f;
+    for (int i0 = tid; i0 < L * kCoopRows; i0 += 4 * kChainThreads) {  // four loads in flight per thread
+        float pv[4], bv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            const int step = i / kCoopRows, r = blockIdx.x * kCoopRows + i % kCoopRows;
+            const int t = dir ? L - 1 - step : step;
+            int slot = ctl.oldest + t;
+            if (slot >= L) slot -= L;
+            const bool ok = i < L * kCoopRows && r < R;
+            pv[u] = ok ? proj[(size_t)slot * R + r] : 0.f;
+            bv[u] = ok ? bias[r] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * kChainThreads;
+            if (i < L * kCoopRows) pre[i] = pv[u] * ctl.inv_scale + bv[u];
+        }
     }
     for (int i = tid; i < 2 * HBUF; i += kChainThreads) h[i] = 0.f;
     if (tid == 0) bail = 0;
@@ -349,7 +481,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
                 const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
                 s += wreg[j] * hv.x + wreg[j + 1] * hv.y + wreg[j + 2] * hv.z + wreg[j + 3] * hv.w;
             }
-            s = row16_sum(s);
+            s = group_sum<kCoopTpr>(s);
         }
         if (seg == 0 && row < R)
             __hip_atomic_store(ctx + (size_t)t * Rp + row, fmaxf(pre[step * kCoopRows + row_local] + s, 0.f),
@@ -442,6 +574,12 @@ int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t
         if (a.R <= 32) return launch_encode_reg<32, 1>(a, stream);
         if (a.R <= 64) return launch_encode_reg<16, 4>(a, stream);
         if (a.R <= 128) return launch_encode_reg<8, 16>(a, stream);
+        if (!fuse) {  // four rows per thread: a quarter of the LDS reads per step
+            const size_t lds = ((size_t)a.L * 256 + 2 * 16 * 20) * sizeof(float);
+            hipLaunchKernelGGL(encode_window_reg4, dim3(2), dim3(kChainThreads), lds, stream, a);
+            DKF_HIP_TRY(hipGetLastError());
+            return DKF_OK;
+        }
         return launch_encode_reg<4, 64>(a, stream);
     }
     if (coop) {
