@@ -106,8 +106,13 @@ __device__ __forceinline__ void xor_stage(T (&v)[E], int g) {
         constexpr int lm = 1 << Lay::lane_bit(B);
         if constexpr (sizeof(T) == 4) {
             const uint32_t sel = keep_mask(g, Lay::lane_bit(B));
+            // all moves first, then all medians: a DPP move that reads a register the instruction
+            // just before it wrote costs wait states
+            uint32_t p[E];
 #pragma unroll
-            for (int e = 0; e < E; ++e) v[e] = umed3(v[e], from_lane_xor<lm>(v[e]), sel);
+            for (int e = 0; e < E; ++e) p[e] = from_lane_xor<lm>(v[e]);
+#pragma unroll
+            for (int e = 0; e < E; ++e) v[e] = umed3(v[e], p[e], sel);
         } else {
             const bool keep_min = (g & lm) == 0;
 #pragma unroll

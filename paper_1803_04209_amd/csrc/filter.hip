@@ -166,66 +166,63 @@ __global__ __launch_bounds__(kChainThreads) void encode_window(FilterArgs a) {
 // Same recurrence with the R x R matrix held in registers for the whole chain:
 // 1024 threads, TPR threads per row, each owning KPT consecutive columns
 // (TPR * KPT = rows covered = 1024 / TPR).  A step is KPT fused multiply-adds
-// per thread against the previous state in LDS, a log2(TPR)-step shuffle
-// reduction and one barrier.  The input term (W_ih x_t)/s + b_ih + b_hh of
-// every window position is staged in LDS before the loop, so the loop itself
-// touches no global memory except the ctx stores.
-// Dynamic LDS: (L * ROWS + 2 * HSTRIDE) floats.
+// per thread against the previous state in LDS, a log2(TPR)-step lane
+// reduction and one barrier.
+// With `project` the kernel is the first of a decision: it reads the new observation and the
+// control block straight from the caller-side staging buffer (pinned host memory: a PCIe round
+// trip of about 3 us).  Everything that does not depend on them -- this thread's share of the
+// input matrix row, its block of the recurrent matrix, the ring of cached projections -- is
+// requested first, so that those loads are in flight during that round trip.
+// Dynamic LDS: (L * ROWS + 2 * HSTRIDE + Np + ROWS) floats.
 template <int TPR, int KPT>
 __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a) {
     constexpr int ROWS = kChainThreads / TPR;
     static_assert(TPR * KPT == ROWS, "square tile");
     constexpr int HSTRIDE = ROWS + (ROWS / KPT) * 4;  // 4 pad floats per column segment: conflict-free b128 reads
+    constexpr int kMaxIn = 8;  // float4 of an input-matrix row per thread: N <= 32 TPR (the fused path's limit)
     extern __shared__ __align__(16) float lds[];
-    const Control ctl = a.project ? *reinterpret_cast<const Control *>(a.input + a.Np) : *a.ctl;
     const int dir = blockIdx.x;
     const int R = a.R, L = a.L, N = a.N;
     const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
     const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
     float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
     float *__restrict__ ctx = dir ? a.ctx_b : a.ctx_f;
-    float *pre = lds;               // [L][ROWS] in chain order (step), input term of every position
+    float *ring = lds;              // [L][ROWS] cached projections by ring slot (zero beyond R)
     float *h0 = lds + L * ROWS;     // two state buffers, padded layout
     float *h1 = h0 + HSTRIDE;
     float *xs = h1 + HSTRIDE;       // [Np] the new observation
-    float *newp = xs + a.Np;        // [ROWS] its input projection
     const int tid = threadIdx.x;
     const int row = tid / TPR, seg = tid % TPR, k0 = seg * KPT;
 
-    // the new observation (read straight from the caller-side staging buffer, which may be
-    // pinned host memory) -> LDS, and a device copy of it and of the control block
+    // 1. the observation and the control block (host memory when `project`)
+    const int n_in = a.Np + (int)(sizeof(Control) / sizeof(float));
+    float in0 = 0.f, in1 = 0.f;  // elements tid and tid + 1024 (Np + 8 <= 2048 on this path)
     if (a.project) {
-        const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
-        for (int i = tid; i < n; i += kChainThreads) {
-            const float v = a.input[i];
-            if (i < a.Np) xs[i] = v;
-            if (dir == 0 && a.mirror != a.input) a.mirror[i] = v;
-        }
+        if (tid < n_in) in0 = a.input[tid];
+        if (tid + kChainThreads < n_in) in1 = a.input[tid + kChainThreads];
     }
-    __syncthreads();
-    // input projection of the new observation: TPR lanes per row, interleaved float4 columns
+    // 2. device memory: input-matrix row share, recurrent block, projection ring, bias
+    const bool vec_in = (N & 3) == 0;
+    float4 wi[kMaxIn];
     if (a.project) {
-        const float *__restrict__ wi = (dir ? a.w_ih_b : a.w_ih_f) + (size_t)row * N;
-        float s = 0.f;
-        if (row < R) {
-            if ((N & 3) == 0) {
-                for (int j = seg * 4; j < N; j += TPR * 4) {
-                    const float4 wv = *reinterpret_cast<const float4 *>(wi + j);
-                    const float4 xv = *reinterpret_cast<const float4 *>(xs + j);
-                    s += wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
+        const float *__restrict__ wrow = (dir ? a.w_ih_b : a.w_ih_f) + (size_t)row * N;
+#pragma unroll
+        for (int q = 0; q < kMaxIn; ++q) {
+            wi[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < R) {
+                if (vec_in) {
+                    const int j = (q * TPR + seg) * 4;
+                    if (j < N) wi[q] = *reinterpret_cast<const float4 *>(wrow + j);
+                } else {  // element (4 q + e) * TPR + seg
+                    const int j = 4 * q * TPR + seg;
+                    if (j < N) wi[q].x = wrow[j];
+                    if (j + TPR < N) wi[q].y = wrow[j + TPR];
+                    if (j + 2 * TPR < N) wi[q].z = wrow[j + 2 * TPR];
+                    if (j + 3 * TPR < N) wi[q].w = wrow[j + 3 * TPR];
                 }
-            } else {
-                for (int j = seg; j < N; j += TPR) s += wi[j] * xs[j];
             }
         }
-        s = group_sum<TPR>(s);
-        if (seg == 0) {
-            newp[row] = s;
-            if (row < R) proj[(size_t)ctl.slot * R + row] = s;
-        }
     }
-    if (ctl.count < L || !a.encode) return;  // warming up, or only the projection was asked for
-
     float wreg[KPT];
     if (KPT >= 4 && (R & 3) == 0) {
 #pragma unroll
@@ -240,38 +237,73 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
         for (int j = 0; j < KPT; ++j) wreg[j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
     }
     for (int i0 = tid; i0 < L * ROWS; i0 += 4 * kChainThreads) {  // four loads in flight per thread
-        float pv[4], bv[4];
+        float pv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * kChainThreads;
-            const int step = i / ROWS, r = i % ROWS;
-            const int t = dir ? L - 1 - step : step;
-            int slot = ctl.oldest + t;
-            if (slot >= L) slot -= L;
-            const bool ok = i < L * ROWS && r < R;
-            // (the new observation's term comes from LDS below)
-            pv[u] = (ok && !(a.project && slot == ctl.slot)) ? proj[(size_t)slot * R + r] : 0.f;
-            bv[u] = ok ? bias[r] : 0.f;
+            const int slot = i / ROWS, r = i % ROWS;
+            pv[u] = (i < L * ROWS && r < R) ? proj[(size_t)slot * R + r] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * kChainThreads;
-            if (i < L * ROWS) pre[i] = pv[u] * ctl.inv_scale + bv[u];
+            if (i < L * ROWS) ring[i] = pv[u];
         }
     }
+    const float my_bias = (seg == 0 && row < R) ? bias[row] : 0.f;
     for (int i = tid; i < 2 * HSTRIDE; i += kChainThreads) h0[i] = 0.f;
-    __syncthreads();
-    if (a.project) {  // the new observation's term comes from LDS (its global copy is for later steps)
-        int t_new = ctl.slot - ctl.oldest;
-        if (t_new < 0) t_new += L;
-        const int step_new = dir ? L - 1 - t_new : t_new;
-        for (int r = tid; r < R; r += kChainThreads) pre[step_new * ROWS + r] = newp[r] * ctl.inv_scale + bias[r];
+
+    // 3. the observation has arrived: LDS copy, device mirror, control block
+    if (a.project) {
+        if (tid < a.Np) xs[tid] = in0;
+        if (tid + kChainThreads < a.Np) xs[tid + kChainThreads] = in1;
+        if (dir == 0 && a.mirror != a.input) {
+            if (tid < n_in) a.mirror[tid] = in0;
+            if (tid + kChainThreads < n_in) a.mirror[tid + kChainThreads] = in1;
+        }
+        // control block: floats Np .. Np + 7 of the input, via LDS to every thread
+        float *cl = xs + a.Np;
+        if (tid >= a.Np && tid < n_in) cl[tid - a.Np] = in0;
+        if (tid + kChainThreads >= a.Np && tid + kChainThreads < n_in) cl[tid + kChainThreads - a.Np] = in1;
     }
+    __syncthreads();
+    Control ctl;
+    if (a.project) ctl = *reinterpret_cast<const Control *>(xs + a.Np);
+    else ctl = *a.ctl;
+
+    // 4. input projection of the new observation into its ring slot
+    if (a.project) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < kMaxIn; ++q) {
+            if (vec_in) {
+                const int j = (q * TPR + seg) * 4;
+                if (j < N) {
+                    const float4 xv = *reinterpret_cast<const float4 *>(xs + j);
+                    s += wi[q].x * xv.x + wi[q].y * xv.y + wi[q].z * xv.z + wi[q].w * xv.w;
+                }
+            } else {
+                const int j = 4 * q * TPR + seg;
+                if (j < N) s += wi[q].x * xs[j];
+                if (j + TPR < N) s += wi[q].y * xs[j + TPR];
+                if (j + 2 * TPR < N) s += wi[q].z * xs[j + 2 * TPR];
+                if (j + 3 * TPR < N) s += wi[q].w * xs[j + 3 * TPR];
+            }
+        }
+        s = group_sum<TPR>(s);
+        if (seg == 0) {
+            ring[ctl.slot * ROWS + row] = row < R ? s : 0.f;
+            if (row < R) proj[(size_t)ctl.slot * R + row] = s;
+        }
+    }
+    if (ctl.count < L || !a.encode) return;  // warming up, or only the projection was asked for
     __syncthreads();
 
     float *h_prev = h0, *h_next = h1;
     for (int step = 0; step < L; ++step) {
         const int t = dir ? L - 1 - step : step;
+        int slot = ctl.oldest + t;
+        if (slot >= L) slot -= L;
         float s = 0.f;
         const float *hp = h_prev + k0 + seg * 4;
         if (KPT >= 4) {
@@ -291,7 +323,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
         }
         s = group_sum<TPR>(s);
         if (seg == 0) {
-            const float v = fmaxf(pre[step * ROWS + row] + s, 0.f);
+            const float v = fmaxf(ring[slot * ROWS + row] * ctl.inv_scale + my_bias + s, 0.f);
             h_next[row + (row / KPT) * 4] = v;
             if (row < R) ctx[(size_t)t * a.Rp + row] = v;
         }
@@ -556,7 +588,8 @@ int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t
     // Small encoders: projection and both recurrences in one launch of two workgroups.  A larger
     // input matrix (measured: 256 x 512) is read faster by the many workgroups of the separate
     // projection kernel than by those two.
-    const bool fuse = project && reg_ok && (size_t)a.R * a.N <= 32768;
+    const int reg_rows = a.R <= 32 ? 32 : a.R <= 64 ? 64 : a.R <= 128 ? 128 : 256;  // rows the register kernel covers
+    const bool fuse = project && reg_ok && (size_t)reg_rows * a.N <= 32768;
     const bool coop = encode && !reg_ok;  // wide encoders or long windows: several workgroups per direction
     if ((project && !fuse) || coop) {
         if (project && a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
