@@ -22,6 +22,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kChunkFrags = 32;               // fragments per LDS chunk = 32 KiB
 constexpr int kFragsPerWave = kChunkFrags / 4;
+constexpr int kMeanStride = 36;               // floats per row of the epilogue's transposition tile (16-byte aligned rows)
 
 template <int G>
 __device__ __forceinline__ f32x4 pack_half(const f32x16 &v) {  // half G of a result tile as a B fragment
@@ -67,16 +68,26 @@ __global__ __launch_bounds__(kThreads, 2) void frag_gemm(FragGemmArgs a) {
         }
     }
 
+    // The last layer's result is not an operand of anything, so it is computed the other way round
+    // (activations as the A operand): a lane then owns one feature and 16 samples, and the noise
+    // reads and sample writes of its epilogue are 128 contiguous bytes per row.
+    constexpr bool kRowsAreSamples = EPI == kFragDraw;
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int mb = feat_tile * kFeatBlocks + wf * TM + i;
-        const float *b = a.bias + 32 * mb + 4 * (lane >> 5);
         f32x16 v;
+        if constexpr (kRowsAreSamples) {
+            const float b = a.bias[32 * mb + (lane & 31)];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
-            v[4 * q] = bq[0]; v[4 * q + 1] = bq[1]; v[4 * q + 2] = bq[2]; v[4 * q + 3] = bq[3];
+            for (int e = 0; e < 16; ++e) v[e] = b;
+        } else {
+            const float *b = a.bias + 32 * mb + 4 * (lane >> 5);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bq = *reinterpret_cast<const f32x4 *>(b + 8 * q);
+                v[4 * q] = bq[0]; v[4 * q + 1] = bq[1]; v[4 * q + 2] = bq[2]; v[4 * q + 3] = bq[3];
+            }
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = v;
@@ -127,7 +138,9 @@ __global__ __launch_bounds__(kThreads, 2) void frag_gemm(FragGemmArgs a) {
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[i], xb[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = kRowsAreSamples
+                                        ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(xb[j], wa[i], acc[i][j], 0, 0, 0)
+                                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[i], xb[j], acc[i][j], 0, 0, 0);
             }
             // the next chunk has been in registers for kDepth - 1 chunks of work
             to_lds((d + 1) % kDepth, (d + 1) & 1);
@@ -165,43 +178,33 @@ __global__ __launch_bounds__(kThreads, 2) void frag_gemm(FragGemmArgs a) {
                 }
             }
             if constexpr (EPI == kFragDraw) {
-                const int smp = sb * 32 + (lane & 31);
+                // the mean's tile is stored with lanes along samples: turn it through a wavefront-private
+                // LDS tile (the staging buffers are free by now) so that m[e] belongs to acc element e
+                float *tile = reinterpret_cast<float *>(&lds[0][0]) + wave * (32 * kMeanStride);
                 const f32x4 *mt = reinterpret_cast<const f32x4 *>(a.mean_tiles) + ((size_t)sb * a.mean_blocks + mb) * 4 * 64 + lane;
-                const int N = a.N;
-                const bool vec = (N & 3) == 0;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int f = 32 * mb + 8 * q + 4 * h;
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<f32x4 *>(tile + (lane & 31) * kMeanStride + 8 * q + 4 * h) = mt[q * 64];
+                float m[16];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) m[e] = tile[(8 * (e >> 2) + 4 * h + (e & 3)) * kMeanStride + (lane & 31)];
+                const int N = a.N, f = 32 * mb + (lane & 31);
+                const float *__restrict__ eps_x = a.eps_x;
+                float eps[16];  // all of the tile's noise requested before the first store
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int smp = sb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+                    eps[e] = (smp < a.S && f < N) ? eps_x[(size_t)smp * N + f] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int smp = sb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
                     if (smp >= a.S || f >= N) continue;
-                    const f32x4 m = mt[q * 64];
                     const size_t at = (size_t)smp * N + f;
-                    f32x4 e = {0.f, 0.f, 0.f, 0.f};
-                    if (vec) {
-                        e = *reinterpret_cast<const f32x4 *>(a.eps_x + at);
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (f + r < N) e[r] = a.eps_x[at + r];
-                    }
-                    f32x4 sd, x;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        sd[r] = softplus_f(v[4 * q + r]);
-                        x[r] = scale * (m[r] + sd[r] * e[r]);
-                    }
-                    if (vec) {
-                        *reinterpret_cast<f32x4 *>(a.out_samples + at) = x;
-                        if (a.out_mean_dbg) *reinterpret_cast<f32x4 *>(a.out_mean_dbg + at) = m;
-                        if (a.out_sd_dbg) *reinterpret_cast<f32x4 *>(a.out_sd_dbg + at) = sd;
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (f + r >= N) continue;
-                            a.out_samples[at + r] = x[r];
-                            if (a.out_mean_dbg) a.out_mean_dbg[at + r] = m[r];
-                            if (a.out_sd_dbg) a.out_sd_dbg[at + r] = sd[r];
-                        }
-                    }
+                    const float sd = softplus_f(v[e]);
+                    a.out_samples[at] = scale * (m[e] + sd * eps[e]);
+                    if (a.out_mean_dbg) a.out_mean_dbg[at] = m[e];
+                    if (a.out_sd_dbg) a.out_sd_dbg[at] = sd;
                 }
             }
         }

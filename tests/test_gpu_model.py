@@ -315,9 +315,10 @@ def test_state_roundtrip_resumes_bit_exactly(api):
     b.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "medium"])
+@pytest.mark.parametrize("name", ["tiny", "medium", "contended", "replay", "large_bf16"])
 def test_decide_graph_replays_match_eager(api, name):
-    """Every replay of the captured decision graph is checked against the eager calls."""
+    """Every replay of the captured decision graph (the path the benchmark times, at the presets' full
+    sizes) is checked against the eager calls, and its decision against the oracle's rule."""
     import torch
 
     cfg = synth.CONFIGS[name]
@@ -326,11 +327,9 @@ def test_decide_graph_replays_match_eager(api, name):
     S = cfg.samples
     eq, ez, ex = cuda(*synth.make_noise(cfg))
     graph, eager = api.Predictor(cfg, blob), api.Predictor(cfg, blob)
-    ref = oracle.OracleModel(cfg, blob)
-    for t in range(cfg.lag + 12):
+    for t in range(cfg.lag + (12 if cfg.samples * cfg.n_workers <= 1 << 20 else 4)):
         c, status = graph.decide(tr[t], S, eq, ez, ex)
         re = eager.filter_step(tr[t])
-        ref.filter_step(tr[t])
         if t < cfg.lag - 1:
             assert status == api.DKF_WARMUP == re and c == cfg.n_workers
             continue
