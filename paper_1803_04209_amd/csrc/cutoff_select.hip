@@ -35,17 +35,21 @@ __device__ __forceinline__ float value_of(uint32_t k) {
 
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 
-// Element index i of a row is split over a lane group of G = 2^LG lanes with E
-// keys each:  bits 0-1 -> key bits 0-1, next LG bits -> lane, rest -> key bits
-// 2.., so that one float4 load per (lane, e/4) is fully coalesced.
+// A row is held by a lane group of G = 2^LG lanes with E keys each.  Position p = e + E * g of
+// the sorting network belongs to key register e of lane g: the low log2(E) bits of a position are
+// register bits, so the network's stages on those bits -- the ones that occur most often -- are
+// compare-exchanges between registers of one lane, and only the stages on the high bits cross
+// lanes.  Where a key sits when it is loaded does not matter to a sort, so the row is read with
+// whichever pattern coalesces best (load_index: one float4 per lane and instruction, consecutive
+// lanes on consecutive 16 bytes); after the network position p holds rank p.
 template <int E, int LG>
 struct Layout {
     static constexpr int kLgE = ilog2(E);
     static constexpr int kLgN = kLgE + LG;
-    __host__ __device__ static constexpr bool is_lane_bit(int b) { return b >= 2 && b < 2 + LG; }
-    __host__ __device__ static constexpr int reg_bit(int b) { return b < 2 ? b : b - LG; }
-    __host__ __device__ static constexpr int lane_bit(int b) { return b - 2; }
-    // masks of the low m element bits, split into key-register and lane parts
+    __host__ __device__ static constexpr bool is_lane_bit(int b) { return b >= kLgE; }
+    __host__ __device__ static constexpr int reg_bit(int b) { return b; }
+    __host__ __device__ static constexpr int lane_bit(int b) { return b - kLgE; }
+    // masks of the low m position bits, split into key-register and lane parts
     __host__ __device__ static constexpr int reg_mask(int m) {
         int r = 0;
         for (int b = 0; b < m; ++b)
@@ -58,9 +62,12 @@ struct Layout {
             if (is_lane_bit(b)) r |= 1 << lane_bit(b);
         return r;
     }
-    __device__ static __forceinline__ int element(int g, int e) {
+    // index in the row of the key that register e of lane g loads
+    __device__ static __forceinline__ int load_index(int g, int e) {
         return (e & 3) | (g << 2) | ((e >> 2) << (2 + LG));
     }
+    // rank held by register e of lane g after the network
+    __device__ static __forceinline__ int rank(int g, int e) { return e | (g << kLgE); }
 };
 
 template <typename T>
@@ -226,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
         T v[E];
 #pragma unroll
         for (int q = 0; q < E / 4; ++q) {
-            const int i0 = Lay::element(g, q * 4);
+            const int i0 = Lay::load_index(g, q * 4);
             float f[4];
             if (vec_ok && valid && i0 + 3 < N) {
                 const float4 t = *reinterpret_cast<const float4 *>(src + i0);
@@ -250,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
 
 #pragma unroll
         for (int q = 0; q < E / 4; ++q) {
-            const int i0 = Lay::element(g, q * 4);
+            const int i0 = Lay::rank(g, q * 4);
             float f[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -303,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
             float s = red[0][idx / G][gg];
 #pragma unroll
             for (int w = 1; w < kWaves; ++w) s += red[w][idx / G][gg];
-            const int i = Lay::element(gg, e);
+            const int i = Lay::rank(gg, e);
             partial[(size_t)blockIdx.x * NPAD + i] = s;
         }
         __syncthreads();
@@ -451,6 +458,8 @@ SortPlan plan_for(int S, int N) {
     int npad = 8;
     while (npad < N) npad <<= 1;
     SortPlan p;
+    // eight keys per lane while a row fits one wavefront (more keys per lane keep more stages inside
+    // registers but leave fewer rows in flight: measured no faster at N = 512)
     p.e = npad / 64 > 8 ? npad / 64 : 8;
     int g = npad / p.e;
     p.lg = 0;
