@@ -112,7 +112,7 @@ def cpu_baseline(cfg, blob, trace, noise, budget_s):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--steps", type=int, default=None, help="timed decisions (default 300; 1000 for replay)")
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "contended", "large_bf16", "replay"])
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
@@ -136,7 +136,8 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
     S, N = cfg.samples, cfg.n_workers
-    K, W = args.steps, args.warmup
+    K = args.steps if args.steps is not None else (1000 if args.workload == "replay" else 300)
+    W = args.warmup
     blob = synth.make_blob(cfg)
     trace = synth.make_trace(cfg, max(cfg.trace_len, cfg.lag + 2 * (K + W) + 64))
     noise = synth.make_noise(cfg)
@@ -218,8 +219,20 @@ def main():
     rank = np.arange(1, N + 1)
     best = np.argmax((rank / nxt)[:, ::-1], axis=1)
     best = N - 1 - best
+    # the "order" baseline of Sec. 4: iid-normal run-times with the mean and spread of the last L
+    # observed vectors, expected order statistics by Elfving's formula (eq. 4), same argmax rule
+    from scipy.stats import norm
+
+    quant = norm.ppf((rank - np.pi / 8) / (N - np.pi / 4 + 1))
+    order_cuts = np.empty(K, dtype=np.int64)
+    for i in range(K):
+        win = trace[first_timed + i + 1 - cfg.lag:first_timed + i + 1].astype(np.float64)
+        mean = win.mean() + win.std() * quant
+        om = np.where(mean > 0, rank / np.where(mean > 0, mean, 1.0), -np.inf)
+        order_cuts[i] = N - np.argmax(om[::-1])
     implied = {
         "chosen_cutoffs": float(cuts.sum() / nxt[np.arange(K), cuts - 1].sum()),
+        "order_baseline": float(order_cuts.sum() / nxt[np.arange(K), order_cuts - 1].sum()),
         "full_sync": float(K * N / nxt[:, -1].sum()),
         "hindsight_best": float((best + 1).sum() / nxt[np.arange(K), best].sum()),
         "note": "seed-initialised (untrained) weights: says nothing about forecast quality",

@@ -87,8 +87,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     constexpr int tC = 0, tMu = tC + nWide, tSig = tMu + nNarrow, tG1 = tSig + nSmall, tG2 = tG1 + nWide,
                   tP1 = tG2 + nNarrow, tP2 = tP1 + nWide, tLin = tP2 + nNarrow, tTs = tLin + nSmall;
 
-    for (int i = tid; i < a.bias_floats; i += kThreads) bias[i] = a.bias_table[i];
-    for (int i = tid; i < L * 64; i += kThreads) cmu[i] = a.cmu[i];
+    // tables -> LDS, eight loads in flight per thread (a load-store loop would pay one memory round
+    // trip per iteration)
+    auto stage_table = [&](float *dst, const float *__restrict__ src, int n) {
+        for (int i0 = tid; i0 < n; i0 += 8 * kThreads) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i0 + u * kThreads < n ? src[i0 + u * kThreads] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + u * kThreads < n) dst[i0 + u * kThreads] = v[u];
+        }
+    };
+    stage_table(bias, a.bias_table, a.bias_floats);
+    stage_table(cmu, a.cmu, L * 64);
 
     // guide weights of this wavefront -> registers
     bf16x8 wc[Q][ZK], wmu[ZT][2 * Q], wsig[ZT][ZK];
