@@ -347,7 +347,7 @@ int pack_frag_layer(dkf_model *m, const float *w, const float *b, int n_out, int
 }
 
 int pack_emission_frags(dkf_model *m, const RawLayers &r) {
-    const int Hp = round_up(m->H, 128), Np = round_up(m->N, 128);
+    const int Hp = round_up(m->H, 128), Np = round_up(m->N, 256);  // N-wide layers may run in 256-feature tiles
     m->ef_Hp = Hp; m->ef_Np = Np;
     m->ef_samp_tiles = (m->cfg.max_samples + 127) / 128;
     int rc = pack_frag_layer(m, r.emean1, r.b_emean1, m->H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
@@ -376,7 +376,9 @@ int enqueue_emission_frags(dkf_model *m, int S, const float *eps_x, float *out_s
     e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
     const int Hp = m->ef_Hp, Np = m->ef_Np;
     const int st128 = (S + 127) / 128;
-    auto wide_tiles = [&] { e.tile = 2; e.feat_tiles = Np / 128; e.samp_tiles = st128; };
+    // N-wide layers: 256-feature tiles once that still gives every compute unit about two workgroups
+    const bool big = (Np / 256) * st128 >= 384;
+    auto wide_tiles = [&] { e.tile = big ? 4 : 2; e.feat_tiles = big ? Np / 256 : Np / 128; e.samp_tiles = st128; };
     auto narrow_tiles = [&] { e.tile = 2; e.feat_tiles = Hp / 128; e.samp_tiles = st128; };
     int rc;
     e.wfrag = m->ef_w[0]; e.bias = m->ef_b[0]; e.xfrag = m->zfrag; e.k_steps = 4; narrow_tiles();

@@ -156,7 +156,7 @@ enum FragEpilogue : int {
     kFragDraw = 3,      // sd = softplus(y); x = s * (mean + sd * eps) -> [S][N] rows
 };
 struct FragGemmArgs {
-    int tile;            // 2: workgroups of 128 features x 128 samples (the only size built)
+    int tile;            // workgroups of 64 * tile features x 128 samples: 2 or 4
     const float *wfrag;  // [32-feature block][k_steps][64][16 B], feat_tiles * 2 * tile blocks
     const float *xfrag;  // [32-sample block][k_steps][64][16 B], samp_tiles * 2 * tile blocks
     const float *bias;   // fp32 per feature, zero padded

@@ -20,8 +20,6 @@ namespace dkf {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kChunkFrags = 32;               // fragments per LDS chunk = 32 KiB
-constexpr int kFragsPerWave = kChunkFrags / 4;
 constexpr int kMeanStride = 36;               // floats per row of the epilogue's transposition tile (16-byte aligned rows)
 
 template <int G>
@@ -32,16 +30,23 @@ __device__ __forceinline__ f32x4 pack_half(const f32x16 &v) {  // half G of a re
     return __builtin_bit_cast(f32x4, r);
 }
 
-// T x T tiles of 32 x 32 per wavefront (features x samples), so a workgroup owns 64 T features x
-// 64 T samples; a chunk is KC = 8 / T k-steps; kDepth chunks in flight in registers (even).
-// Built for T = 2 (128 x 128, two workgroups per compute unit).  T = 4 would halve the L2 traffic
-// per flop, but its 256 accumulator registers per lane leave hipcc spilling inside the main loop
-// (measured 6x slower), so it is not instantiated.
-template <int EPI, int T>
+// TM x 2 tiles of 32 x 32 per wavefront (features x samples), 2 x 2 wavefronts: a workgroup owns
+// 64 TM features x 128 samples.  What bounds the main loop is LDS read bandwidth (measured: with the
+// global loads and LDS writes taken out the 2 x 2 variant still runs at 38 % of the matrix rate):
+// every 32 x 32 x 16 instruction consumes two 1 KiB fragments, and a wavefront with TM x TN tiles
+// reads TM + TN fragments per TM * TN instructions -- 32 bytes per clock at 2 x 2, which for four
+// SIMDs is all the LDS has; 4 x 2 needs 24 (and a quarter less from L2).
+//   TM = 2: the H-wide layers (a 4 x 2 tiling would leave half the compute units without work there)
+//   TM = 4: the N-wide layers
+// A chunk is KC k-steps = 32 (TM = 2) or 24 (TM = 4) fragments; kDepth chunks are in flight in
+// registers.  (4 x 4 tiles would halve the LDS reads again, but their 256 accumulator registers per
+// lane leave hipcc spilling inside the main loop: measured 6x slower.)
+template <int EPI, int TM>
 __global__ __launch_bounds__(kThreads, 2) void frag_gemm(FragGemmArgs a) {
-    constexpr int TM = T, TN = T, kFeatBlocks = 2 * T, kSampBlocks = 2 * T, KC = 8 / T;
-    constexpr int kDepth = 4;
-    static_assert((kFeatBlocks + kSampBlocks) * KC == kChunkFrags, "chunk size");
+    constexpr int TN = 2, kFeatBlocks = 2 * TM, kSampBlocks = 2 * TN, KC = TM == 2 ? 4 : 2;
+    constexpr int kChunkFrags = (kFeatBlocks + kSampBlocks) * KC, kFragsPerWave = kChunkFrags / 4;
+    constexpr int kDepth = TM == 2 ? 4 : 2;
+    static_assert(kChunkFrags % 4 == 0 && 4 * 32 * kMeanStride * 4 <= kChunkFrags * 1024, "chunk size");
     __shared__ f32x4 lds[2][kChunkFrags * 64];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wf = wave >> 1, ws = wave & 1;
@@ -211,21 +216,21 @@ __global__ __launch_bounds__(kThreads, 2) void frag_gemm(FragGemmArgs a) {
     }
 }
 
-template <int T>
+template <int TM>
 void launch_t(const FragGemmArgs &a, dim3 grid, hipStream_t stream) {
     switch (a.epilogue) {
-        case kFragIdentity: hipLaunchKernelGGL((frag_gemm<kFragIdentity, T>), grid, dim3(kThreads), 0, stream, a); break;
-        case kFragRelu: hipLaunchKernelGGL((frag_gemm<kFragRelu, T>), grid, dim3(kThreads), 0, stream, a); break;
-        case kFragMean: hipLaunchKernelGGL((frag_gemm<kFragMean, T>), grid, dim3(kThreads), 0, stream, a); break;
-        default: hipLaunchKernelGGL((frag_gemm<kFragDraw, T>), grid, dim3(kThreads), 0, stream, a); break;
+        case kFragIdentity: hipLaunchKernelGGL((frag_gemm<kFragIdentity, TM>), grid, dim3(kThreads), 0, stream, a); break;
+        case kFragRelu: hipLaunchKernelGGL((frag_gemm<kFragRelu, TM>), grid, dim3(kThreads), 0, stream, a); break;
+        case kFragMean: hipLaunchKernelGGL((frag_gemm<kFragMean, TM>), grid, dim3(kThreads), 0, stream, a); break;
+        default: hipLaunchKernelGGL((frag_gemm<kFragDraw, TM>), grid, dim3(kThreads), 0, stream, a); break;
     }
 }
 
 }  // namespace
 
-// feat_tiles / samp_tiles count tiles of 64 * a.tile features / samples
+// feat_tiles counts tiles of 64 * a.tile features, samp_tiles tiles of 128 samples
 int launch_frag_gemm(const FragGemmArgs &a, int stage, hipStream_t stream) {
-    if (a.tile != 2) return DKF_EUNSUPPORTED;
+    if (a.tile != 2 && a.tile != 4) return DKF_EUNSUPPORTED;
     if (a.epilogue < kFragIdentity || a.epilogue > kFragDraw) return DKF_EINVAL;
     if (a.k_steps < 4 || a.k_steps % 4 != 0 || a.feat_tiles < 1 || a.samp_tiles < 1) return DKF_EINVAL;
     if (a.epilogue == kFragDraw &&
@@ -235,7 +240,8 @@ int launch_frag_gemm(const FragGemmArgs &a, int stage, hipStream_t stream) {
     StageTimer timer(stage, stream);
     const int samp_tiles8 = (a.samp_tiles + 7) / 8 * 8;
     const dim3 grid(samp_tiles8 * a.feat_tiles);
-    launch_t<2>(a, grid, stream);
+    if (a.tile == 2) launch_t<2>(a, grid, stream);
+    else launch_t<4>(a, grid, stream);
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
 }

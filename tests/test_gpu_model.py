@@ -162,6 +162,21 @@ def test_bf16_every_stage(api, cfg, act, sampler):
     g.close()
 
 
+def test_bf16_2175_workers_ragged_wide_tiles(api):
+    """The paper's larger cluster size (2175 workers: not a multiple of anything), enough samples for
+    the N-wide emission layers to take their 256-feature tiling, ragged last sample tile."""
+    cfg = custom(N=2175, L=2, Z=16, H=128, R=128, S=5603)
+    g, o, _ = make_pair(api, cfg, std=0.05, mlp_dtype=api.DKF_DTYPE_BF16)
+    rows = np.sort(np.random.default_rng(7).choice(cfg.samples, 48, replace=False)).astype(np.int32)
+    rows[0], rows[-1] = 0, cfg.samples - 1
+    x, errs = compare_stages(api, cfg, g, o, rows=rows, tol=TOL_BF16)
+    print("bf16 N=2175 stage errors", {k: f"{v:.1e}" for k, v in errs.items()})
+    res = api.select_cutoff(x)
+    ref = oracle.cutoff_select(x.cpu().numpy(), want_sorted=False, want_perm=False)
+    assert res["status"] == ref["status"] and cstar_in_tie_band(res["cstar"], ref)
+    g.close()
+
+
 def elementwise_rel(got, ref):
     ref = np.asarray(ref, dtype=np.float64)
     rms = np.sqrt(np.mean(ref ** 2))
