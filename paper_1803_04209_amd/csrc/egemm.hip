@@ -9,10 +9,10 @@
 // transposed on the way:
 //   weights      wfrag[feature block of 32][k-step of 16][lane]
 //   activations  xfrag[sample block of 32][k-step of 16][lane]
-// A workgroup of four wavefronts (2 x 2) owns 128 features x 128 samples; fragments of a chunk of
-// four k-steps are staged once per workgroup in LDS (double buffered) and each wavefront
-// multiplies its 2 x 2 tiles from there.  The emission mean is kept twice: as bf16 fragments
-// (input of the scale network) and in fp32 in result-tile order (for the draw).
+// A workgroup of four wavefronts (2 x 2) owns 128 or 256 features x 128 samples; fragments of a
+// chunk of k-steps are staged once per workgroup in LDS (double buffered) and each wavefront
+// multiplies its 2 x 2 or 4 x 2 tiles from there.  The emission mean is kept twice: as bf16
+// fragments (input of the scale network) and in fp32 in result-tile order (for the draw).
 #include "common.h"
 #include "mfma_tile.h"
 

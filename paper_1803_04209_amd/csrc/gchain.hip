@@ -340,14 +340,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
 }
 
-template <int Q>
 size_t gchain_lds(const GChainArgs &a) {
     return (size_t)2 * 4 * 8 * 64 * 16 + ((size_t)a.bias_floats + (size_t)a.L * 64) * sizeof(float);
 }
 
 template <int Q>
 int launch_q(const GChainArgs &a, hipStream_t stream) {
-    const size_t lds = gchain_lds<Q>(a);
+    const size_t lds = gchain_lds(a);
     if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
     static size_t prepared = 0;  // largest LDS size the kernel has been enabled for
     if (lds > prepared) {

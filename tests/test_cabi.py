@@ -47,6 +47,9 @@ def test_host_only_calls_work_without_a_gpu():
     assert api.dkf_blob_bytes(c) == synth.make_blob(cfg).size
     assert api.cutoff_select_workspace(256, 16) > 0
     assert api.cutoff_select_workspace(256, 5000) == 0  # beyond the supported width
+    # imputation workspace: one int32 count per 64-row segment and worker, rounded up to 256 bytes
+    assert api.dkf_impute_workspace(4096, 128) == 64 * 128 * 4
+    assert api.dkf_impute_workspace(65, 3) == 256 and api.dkf_impute_workspace(0, 3) == 0
     bad = api.make_config(cfg)
     bad.lag = 0
     assert api.dkf_blob_bytes(bad) == 0
