@@ -395,13 +395,17 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
     }
 }
 
-__global__ __launch_bounds__(256) void omega_argmax(const double *__restrict__ part2, int N, int S, int c_min,
-                                                    int c_max, float t_floor, float *__restrict__ out_mean,
-                                                    float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
-                                                    const int32_t *ticket) {
-    __shared__ double best_v[256];
-    __shared__ int best_c[256];
-    omega_argmax_body<256>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v, best_c, ticket);
+constexpr int kArgmaxThreads = 1024;  // one workgroup; a rank's 16 partial sums are 16 dependent-free loads per thread
+__global__ __launch_bounds__(kArgmaxThreads) void omega_argmax(const double *__restrict__ part2, int N, int S,
+                                                               int c_min, int c_max, float t_floor,
+                                                               float *__restrict__ out_mean,
+                                                               float *__restrict__ out_omega,
+                                                               int32_t *__restrict__ out_cstar,
+                                                               const int32_t *ticket) {
+    __shared__ double best_v[kArgmaxThreads];
+    __shared__ int best_c[kArgmaxThreads];
+    omega_argmax_body<kArgmaxThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
+                                      best_c, ticket);
 }
 
 // Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
@@ -543,7 +547,7 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
             hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
                                p.blocks, p.npad, N, part2);
             DKF_HIP_TRY(hipGetLastError());
-            hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(256), 0, stream, part2, N, S, c_min, c_max, t_floor,
+            hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(kArgmaxThreads), 0, stream, part2, N, S, c_min, c_max, t_floor,
                                out_mean, out_omega, out_cstar, ticket);
             DKF_HIP_TRY(hipGetLastError());
         }
