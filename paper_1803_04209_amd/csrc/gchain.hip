@@ -180,13 +180,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         f32x4 eps[ZT][4];
         load_noise(a.eps_q + ((size_t)t * S + (live ? smp : 0)) * Z, eps);
         // combiner: this wavefront's quarter of W_c z + b_c, all products issued before the first tanh
+        // (k-step outermost: consecutive matrix instructions then belong to different accumulators;
+        // one that continues the accumulator of the instruction just before it waits out its latency)
         f32x16 pre[Q];
 #pragma unroll
-        for (int ob = 0; ob < Q; ++ob) {
-            pre[ob] = bias_tile(bias + oC + 32 * (w * Q + ob) + 4 * h);
+        for (int ob = 0; ob < Q; ++ob) pre[ob] = bias_tile(bias + oC + 32 * (w * Q + ob) + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) pre[ob] = mma(wc[ob][ks], zB[ks], pre[ob]);
-        }
+        for (int ks = 0; ks < ZK; ++ks)
+#pragma unroll
+            for (int ob = 0; ob < Q; ++ob) pre[ob] = mma(wc[ob][ks], zB[ks], pre[ob]);
         // tanh tile by tile, each straight into two B operands of the mean's partial product over
         // this wavefront's hidden features
 #pragma unroll
@@ -197,10 +199,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int i = 0; i < 16; ++i) pre[ob][i] = tanh_f(pre[ob][i]);
             const bf16x8 h0 = operand_of<0>(pre[ob]), h1 = operand_of<1>(pre[ob]);
 #pragma unroll
-            for (int nb = 0; nb < ZT; ++nb) {
-                mu[nb] = mma(wmu[nb][2 * ob], h0, mu[nb]);
-                mu[nb] = mma(wmu[nb][2 * ob + 1], h1, mu[nb]);
-            }
+            for (int nb = 0; nb < ZT; ++nb) mu[nb] = mma(wmu[nb][2 * ob], h0, mu[nb]);
+#pragma unroll
+            for (int nb = 0; nb < ZT; ++nb) mu[nb] = mma(wmu[nb][2 * ob + 1], h1, mu[nb]);
         }
         all_sum(mu);
         bf16x8 mB[ZK];
@@ -219,11 +220,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         // scale from the mean, reparameterised draw.  Pad features need no masking: their mean is 0
         // (zero weight rows, zero c_t) and their noise was loaded as 0.
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) {
-            zf[nb] = bias_tile(bias + oSig + 32 * nb + 4 * h);
+        for (int nb = 0; nb < ZT; ++nb) zf[nb] = bias_tile(bias + oSig + 32 * nb + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) zf[nb] = mma(wsig[nb][ks], mB[ks], zf[nb]);
-        }
+        for (int ks = 0; ks < ZK; ++ks)
+#pragma unroll
+            for (int nb = 0; nb < ZT; ++nb) zf[nb] = mma(wsig[nb][ks], mB[ks], zf[nb]);
 #pragma unroll
         for (int nb = 0; nb < ZT; ++nb) {
 #pragma unroll
@@ -261,11 +262,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int ks = 0; ks < 2 * Q; ++ks) wn[nb][ks] = load_tile(T, t_narrow + (w * ZT + nb) * 2 * Q + ks, lane);
         f32x16 pre[Q];
 #pragma unroll
-        for (int ob = 0; ob < Q; ++ob) {
-            pre[ob] = bias_tile(bias + o_wide + 32 * (w * Q + ob) + 4 * h);
+        for (int ob = 0; ob < Q; ++ob) pre[ob] = bias_tile(bias + o_wide + 32 * (w * Q + ob) + 4 * h);
 #pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) pre[ob] = mma(ww[ob][ks], zB[ks], pre[ob]);
-        }
+        for (int ks = 0; ks < ZK; ++ks)
+#pragma unroll
+            for (int ob = 0; ob < Q; ++ob) pre[ob] = mma(ww[ob][ks], zB[ks], pre[ob]);
 #pragma unroll
         for (int nb = 0; nb < ZT; ++nb) out[nb] = zero16();
 #pragma unroll
@@ -274,10 +275,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int i = 0; i < 16; ++i) pre[ob][i] = fmaxf(pre[ob][i], 0.f);
             const bf16x8 h0 = operand_of<0>(pre[ob]), h1 = operand_of<1>(pre[ob]);
 #pragma unroll
-            for (int nb = 0; nb < ZT; ++nb) {
-                out[nb] = mma(wn[nb][2 * ob], h0, out[nb]);
-                out[nb] = mma(wn[nb][2 * ob + 1], h1, out[nb]);
-            }
+            for (int nb = 0; nb < ZT; ++nb) out[nb] = mma(wn[nb][2 * ob], h0, out[nb]);
+#pragma unroll
+            for (int nb = 0; nb < ZT; ++nb) out[nb] = mma(wn[nb][2 * ob + 1], h1, out[nb]);
         }
         all_sum(out);
     };
