@@ -139,7 +139,7 @@ def main():
     K = args.steps if args.steps is not None else (1000 if args.workload == "replay" else 300)
     W = args.warmup
     blob = synth.make_blob(cfg)
-    trace = synth.make_trace(cfg, max(cfg.trace_len, cfg.lag + 2 * (K + W) + 64))
+    trace = synth.make_trace(cfg, max(cfg.trace_len, cfg.lag + 2 * (K + W) + 200))  # both timed regions, their warm-ups, the per-stage pass
     noise = synth.make_noise(cfg)
     eq, ez, ex = (torch.from_numpy(a).cuda() for a in noise)
     pred = api.Predictor(cfg, blob)
