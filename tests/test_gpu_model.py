@@ -229,19 +229,22 @@ def torch_isfinite(t):
     return bool(torch.isfinite(t).all())
 
 
-@pytest.mark.parametrize("name", ["tiny", "medium", "odd"])
+@pytest.mark.parametrize("name", ["tiny", "medium", "odd", "bf16"])
 def test_builtin_noise_matches_the_oracle_stream(api, name):
     """No noise tensors: the library draws Philox4x32-10 / Box-Muller normals from the seed; the
     oracle is fed the same stream from its own implementation of the published generator."""
-    cfg = custom(N=18, L=2, Z=10, H=31, R=30, S=70) if name == "odd" else synth.CONFIGS[name]
-    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2)
+    bf16 = name == "bf16"
+    cfg = (custom(N=18, L=2, Z=10, H=31, R=30, S=70) if name == "odd" else
+           custom(N=64, L=3, Z=16, H=128, R=128, S=100) if bf16 else synth.CONFIGS[name])
+    tol = TOL_BF16 if bf16 else TOL
+    g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2, mlp_dtype=api.DKF_DTYPE_BF16 if bf16 else None)
     for seed in (0, 0x1234_5678_9ABC_DEF0):
         x, st = g.sample_runtimes(S=cfg.samples, seed=seed, stages=True)
         eq, ez, ex = oracle.make_noise(cfg, seed)
         xo, so = o.sample_runtimes(eq, ez, ex, stages=True)
-        assert rel_err(st["z_T"].cpu().numpy(), so["z_T"]) <= TOL
-        assert rel_err(st["emit_mean"].cpu().numpy(), so["emit_mean"]) <= TOL
-        assert rel_err(x.cpu().numpy(), xo) <= TOL
+        assert rel_err(st["z_T"].cpu().numpy(), so["z_T"]) <= tol
+        assert rel_err(st["emit_mean"].cpu().numpy(), so["emit_mean"]) <= tol
+        assert rel_err(x.cpu().numpy(), xo) <= tol
     x2 = g.sample_runtimes(S=cfg.samples, seed=1)
     assert not np.allclose(x2.cpu().numpy(), x.cpu().numpy())
     g.close()
