@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     impute_censored,
     make_noise,
     philox4x32_10,
+    rank_spread,
     num_threads,
     set_threads,
     trace_throughput,

@@ -65,6 +65,7 @@ def _load():
     lib.oracle_elfving_mean.argtypes = [C.c_int, C.c_int, C.c_double, C.c_double]
     lib.oracle_cutoff_elfving.argtypes = [C.c_int, C.c_double, C.c_double, C.c_int, C.c_int, C.c_double, dp, dp, ip]
     lib.oracle_trace_throughput.argtypes = [dp, C.c_int, C.c_int, ip, dp]
+    lib.oracle_rank_spread.argtypes = [dp, C.c_int, C.c_int, dp, dp]
     lib.oracle_num_threads.restype = C.c_int
     lib.oracle_set_threads.argtypes = [C.c_int]
     _lib = lib
@@ -259,3 +260,16 @@ def trace_throughput(trace, cutoffs):
     if rc < 0:
         raise ValueError(f"oracle_trace_throughput: error {rc}")
     return tuple(float(v) for v in out)
+
+
+def rank_spread(samples):
+    """(mean [N], sd [N]) of every order statistic over the rows of samples [S][N] (divisor S)."""
+    a = np.ascontiguousarray(samples, dtype=np.float64)
+    if a.ndim != 2:
+        raise ValueError("samples must be [S][N]")
+    S, N = a.shape
+    mean, sd = np.empty(N), np.empty(N)
+    rc = _load().oracle_rank_spread(_dp(a), S, N, _dp(mean), _dp(sd))
+    if rc < 0:
+        raise ValueError(f"oracle_rank_spread: error {rc}")
+    return mean, sd

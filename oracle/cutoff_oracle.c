@@ -575,3 +575,31 @@ int oracle_trace_throughput(const double *trace, int T, int N, const int32_t *cu
     out[0] = g_cut / t_cut; out[1] = g_sync / t_sync; out[2] = g_best / t_best;
     return ORACLE_OK;
 }
+
+/* Spread of the predicted order statistics (Fig. 3 draws every predicted
+ * order statistic with a band of two standard deviations): sort every row of
+ * samples [S][N] ascending; for each rank c the mean over the S rows and
+ *   sd(c) = sqrt( (1/S) sum_k (x_(c),k - mean(c))^2 ).
+ * READING: the paper does not say which normalisation its bands use; the plain
+ * second moment about the Monte-Carlo mean (divisor S) is taken, the same
+ * divisor as the mean itself. */
+int oracle_rank_spread(const double *samples, int S, int N, double *out_mean, double *out_sd) {
+    if (!samples || !out_mean || !out_sd || S < 1 || N < 1) return ORACLE_EINVAL;
+    double *srt = (double *)malloc(sizeof(double) * (size_t)S * N);
+    if (!srt) return ORACLE_EINVAL;
+    memcpy(srt, samples, sizeof(double) * (size_t)S * N);
+    for (int k = 0; k < S; ++k) qsort(srt + (size_t)k * N, N, sizeof(double), dbl_cmp);
+    for (int c = 0; c < N; ++c) {
+        double sum = 0.0;
+        for (int k = 0; k < S; ++k) sum += srt[(size_t)k * N + c];
+        double mean = sum / (double)S, dev = 0.0;
+        for (int k = 0; k < S; ++k) {
+            double d = srt[(size_t)k * N + c] - mean;
+            dev += d * d;
+        }
+        out_mean[c] = mean;
+        out_sd[c] = sqrt(dev / (double)S);
+    }
+    free(srt);
+    return ORACLE_OK;
+}
