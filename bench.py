@@ -109,6 +109,42 @@ def cpu_baseline(cfg, blob, trace, noise, budget_s):
     }
 
 
+def aux_entry_points(api, torch, np, samples, x_next, calls):
+    """Average GPU time per call (events around `calls` back-to-back calls, so launch gaps count where
+    the kernels are shorter than a launch) of the entry points that run around a decision, on the
+    sample matrix the last decision drew: imputation of the run-times a cutoff at the median worker
+    would censor (Sec. 4.2), and the spread of the predicted order statistics (Fig. 3's bands)."""
+    S, N = samples.shape
+    order = np.argsort(x_next, kind="stable")
+    cens = np.ones(N, np.uint8)
+    cens[order[:N // 2]] = 0
+    tau = float(x_next[order[N // 2 - 1]]) if N > 1 else float(x_next[0])
+    d_obs = torch.from_numpy(np.ascontiguousarray(x_next)).cuda()
+    d_cens = torch.from_numpy(cens).cuda()
+    u = torch.rand(N, device="cuda")
+    x_full = torch.empty(N, device="cuda")
+    ws_i = torch.empty(max(api.dkf_impute_workspace(S, N), 256), dtype=torch.uint8, device="cuda")
+    res = api.select_cutoff(samples, want_sorted=True)
+    sd = torch.empty(N, device="cuda")
+    ws_s = torch.empty(max(api.cutoff_rank_spread_workspace(S, N), 256), dtype=torch.uint8, device="cuda")
+    legs = {
+        "impute_censored": lambda: api.dkf_impute_censored(samples, d_obs, d_cens, tau, u, x_full, None, ws_i),
+        "rank_spread": lambda: api.cutoff_rank_spread(res["sorted"], res["mean"], sd, ws_s),
+    }
+    out = {}
+    for name, call in legs.items():
+        for _ in range(5):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(calls):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) * 1e3 / calls
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +155,9 @@ def main():
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times (the known-size "
                          "kernel that hardware-counter readings are scaled by)")
+    ap.add_argument("--aux", type=int, default=0, metavar="CALLS",
+                    help="also time this many calls of the entry points around the decision (censored-run-time "
+                         "imputation, spread of the rank means) on the workload's own sample matrix")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -256,6 +295,8 @@ def main():
                        "frac_of_peak": mlp_flops / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype]},
         "roofline": roofline,
     }
+    if args.aux > 0:
+        result["aux_us_per_call"] = aux_entry_points(api, torch, np, out, trace[t_idx], args.aux)
     pred.close()
     if args.calibration_copy > 0:
         src = torch.ones(args.calibration_copy << 18, dtype=torch.float32, device="cuda")

@@ -143,6 +143,22 @@ int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int
                   void *workspace, size_t workspace_bytes, void *stream);
 size_t cutoff_select_workspace(int32_t S, int32_t N);
 
+/* Spread of the predicted order statistics (Fig. 3 draws every predicted
+ * order statistic with a band of two standard deviations): for each rank c,
+ *   out_sd[c-1] = sqrt( (1/S) sum_k (sorted[k][c-1] - mean[c-1])^2 ).
+ *   sorted [S][N] dev fp32: rows ascending, the out_sorted of cutoff_select;
+ *   mean [N] dev fp32: the out_mean of the same call;  out_sd [N] dev fp32.
+ *   (Nothing here depends on the rows being sorted: it is the spread of every
+ *   column about the given centre, divisor S.)
+ *   workspace: dev, at least cutoff_rank_spread_workspace(S, N) bytes, 4-byte
+ *     aligned; contents are scratch.  All buffers caller-owned.
+ * Sums run in a fixed order: the result does not depend on scheduling.
+ * Errors: DKF_EINVAL (null or misaligned pointer, S < 1, N < 1, workspace too
+ * small), DKF_EUNSUPPORTED (S * N > 2^40), DKF_EHIP. */
+int cutoff_rank_spread(const float *sorted, int32_t S, int32_t N, const float *mean, float *out_sd, void *workspace,
+                       size_t workspace_bytes, void *stream);
+size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
+
 /* One whole decision (the predict_cutoff call of Alg. 1): filter_step,
  * sample_runtimes with S samples and cutoff_select over c in [1, N] with floor
  * 0, replayed from a captured HIP graph after the first call with a given S.

@@ -28,7 +28,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
     "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "dkf_decide",
-    "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
+    "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
 
@@ -85,6 +85,9 @@ def _lib():
     lib.dkf_impute_censored.argtypes = [vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, sz, vp]
     lib.dkf_impute_workspace.restype = sz
     lib.dkf_impute_workspace.argtypes = [i32, i32]
+    lib.cutoff_rank_spread.argtypes = [vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.cutoff_rank_spread_workspace.restype = sz
+    lib.cutoff_rank_spread_workspace.argtypes = [i32, i32]
     lib.dkf_get_state.argtypes = [vp, vp, C.POINTER(sz)]
     lib.dkf_set_state.argtypes = [vp, vp, sz]
     lib.dkf_set_sampler.argtypes = [C.c_void_p, C.c_int32]
@@ -185,6 +188,19 @@ def cutoff_select(samples, c_min: int, c_max: int, t_floor: float, out_sorted, o
         _dev(out_sorted, torch.float32, (S, N), "out_sorted"), _dev(out_perm, torch.int32, (S, N), "out_perm"),
         _dev(out_mean, torch.float32, (N,), "out_mean"), _dev(out_omega, torch.float32, (N,), "out_omega"),
         _dev(out_cstar, torch.int32, (2,), "out_cstar"), _dev(workspace, torch.uint8, name="workspace"),
+        workspace.numel(), _stream_ptr(stream)))
+
+
+def cutoff_rank_spread_workspace(S: int, N: int) -> int:
+    return int(_lib().cutoff_rank_spread_workspace(S, N))
+
+
+def cutoff_rank_spread(sorted_rows, mean, out_sd, workspace, stream=None) -> int:
+    torch = _torch()
+    S, N = sorted_rows.shape
+    return _check("cutoff_rank_spread", _lib().cutoff_rank_spread(
+        _dev(sorted_rows, torch.float32, name="sorted"), S, N, _dev(mean, torch.float32, (N,), "mean"),
+        _dev(out_sd, torch.float32, (N,), "out_sd"), _dev(workspace, torch.uint8, name="workspace"),
         workspace.numel(), _stream_ptr(stream)))
 
 
@@ -330,6 +346,16 @@ def impute_censored(samples, x_obs, censored, tau, u):
     n_exceed = torch.empty(N, dtype=torch.int32, device=dev)
     dkf_impute_censored(samples, x_obs, censored, tau, u, x_full, n_exceed, ws)
     return x_full, n_exceed
+
+
+def rank_spread(sorted_rows, mean):
+    """Allocate output + workspace, call cutoff_rank_spread, return the sd tensor [N]."""
+    torch = _torch()
+    S, N = sorted_rows.shape
+    ws = torch.empty(max(cutoff_rank_spread_workspace(S, N), 256), dtype=torch.uint8, device=sorted_rows.device)
+    sd = torch.empty(N, dtype=torch.float32, device=sorted_rows.device)
+    cutoff_rank_spread(sorted_rows, mean, sd, ws)
+    return sd
 
 
 def select_cutoff(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=False, want_perm=False):

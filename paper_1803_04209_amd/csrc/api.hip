@@ -968,6 +968,14 @@ int dkf_impute_censored(const float *samples, int32_t S, int32_t N, const float 
                                   workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+size_t cutoff_rank_spread_workspace(int32_t S, int32_t N) { return rank_spread_workspace_bytes(S, N); }
+
+int cutoff_rank_spread(const float *sorted, int32_t S, int32_t N, const float *mean, float *out_sd, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+    return launch_rank_spread(sorted, S, N, mean, out_sd, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
 // state blob: int64 {magic, N, L, pushes}, float scale, float pad, then the ring [L][N]
 int dkf_get_state(const dkf_model *m, void *buf, size_t *bytes) {
     if (!m || !bytes) return DKF_EINVAL;

@@ -267,4 +267,9 @@ int launch_impute_censored(const float *samples, int S, int N, const float *x_ob
                            size_t workspace_bytes, hipStream_t stream);
 size_t impute_workspace_bytes(int S, int N);
 
+// spread.hip
+int launch_rank_spread(const float *sorted, int S, int N, const float *mean, float *out_sd, void *workspace,
+                       size_t workspace_bytes, hipStream_t stream);
+size_t rank_spread_workspace_bytes(int S, int N);
+
 }  // namespace dkf

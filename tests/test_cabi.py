@@ -50,6 +50,9 @@ def test_host_only_calls_work_without_a_gpu():
     # imputation workspace: one int32 count per 64-row segment and worker, rounded up to 256 bytes
     assert api.dkf_impute_workspace(4096, 128) == 64 * 128 * 4
     assert api.dkf_impute_workspace(65, 3) == 256 and api.dkf_impute_workspace(0, 3) == 0
+    # spread workspace: one fp32 partial per 256-row segment and rank
+    assert api.cutoff_rank_spread_workspace(16384, 512) == 64 * 512 * 4
+    assert api.cutoff_rank_spread_workspace(1, 1) == 256 and api.cutoff_rank_spread_workspace(5, 0) == 0
     bad = api.make_config(cfg)
     bad.lag = 0
     assert api.dkf_blob_bytes(bad) == 0
