@@ -170,7 +170,10 @@ size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
  * finished by then, but the stream may report busy for a few microseconds
  * more.  If the ticket does not arrive the stream is synchronised instead.)
  * Returns DKF_OK, DKF_WARMUP (then *cstar_host = N), CUTOFF_NO_ELIGIBLE, or
- * an error. */
+ * an error.  DKF_EINVAL and DKF_EBADOBS leave the model untouched; after any
+ * other error the observation has already entered the window but the
+ * decision is lost: restore the window (dkf_set_state) or start over
+ * (dkf_reset) before deciding again. */
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
                const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream);
 

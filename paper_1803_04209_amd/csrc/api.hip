@@ -628,20 +628,20 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
         if (rc != DKF_EUNSUPPORTED && rc != DKF_EINVAL) return rc;
     }
     if (rc != DKF_OK) {  // sizes (or caller buffers not 16-byte aligned) the register-resident kernel does not take
-    GuideArgs g;
-    g.ctl = m->ctl_dev();
-    g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
-    g.comb = m->comb; g.mu = m->mu; g.sig = m->sig; g.z0 = m->z0;
-    g.gate1 = m->gate1; g.prop1 = m->prop1; g.gate2 = m->gate2; g.prop2 = m->prop2;
-    g.lin = m->lin; g.tscale = m->tscale;
-    g.eps_q = eps_q; g.eps_z = eps_z;
-    g.z_last = st ? st->z_last : nullptr;
-    g.z_next_dbg = st ? st->z_next : nullptr;
-    g.z_next = m->z_next;
-    g.S = S; g.L = m->L; g.Z = m->Z; g.Zp = m->Zp; g.R = m->R; g.Rp = m->Rp; g.H = m->H; g.Hp = m->Hp;
-    g.bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
-    rc = launch_guide(g, stream);
-    if (rc != DKF_OK) return rc;
+        GuideArgs g;
+        g.ctl = m->ctl_dev();
+        g.ctx_f = m->ctx_f; g.ctx_b = m->ctx_b;
+        g.comb = m->comb; g.mu = m->mu; g.sig = m->sig; g.z0 = m->z0;
+        g.gate1 = m->gate1; g.prop1 = m->prop1; g.gate2 = m->gate2; g.prop2 = m->prop2;
+        g.lin = m->lin; g.tscale = m->tscale;
+        g.eps_q = eps_q; g.eps_z = eps_z;
+        g.z_last = st ? st->z_last : nullptr;
+        g.z_next_dbg = st ? st->z_next : nullptr;
+        g.z_next = m->z_next;
+        g.S = S; g.L = m->L; g.Z = m->Z; g.Zp = m->Zp; g.R = m->R; g.Rp = m->Rp; g.H = m->H; g.Hp = m->Hp;
+        g.bf16 = m->cfg.mlp_dtype == DKF_DTYPE_BF16;
+        rc = launch_guide(g, stream);
+        if (rc != DKF_OK) return rc;
     }
 
     GemmArgs e{};
