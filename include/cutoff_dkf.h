@@ -90,7 +90,12 @@ size_t dkf_blob_bytes(const dkf_config *cfg);
  * cores, converted to bf16 where cfg->mlp_dtype asks for it), allocates the
  * window and a workspace for cfg->max_samples samples.  `blob` is host memory
  * and may be released on return (the call synchronises `stream`).
- * Limits: 1 <= N <= 4096; Z, H, R <= 1024; L <= 256.
+ * Limits: 1 <= N <= 4096; Z, H, R <= 1024; L <= 256; and one workgroup's
+ * share of the guide chain must fit the 160 KB of LDS: with Zp, Hp, Rp the
+ * sizes rounded up to a multiple of 32 (fp32) or 64 (bf16),
+ *   fp32: 648 Zp + 132 max(Rp, Hp) <= 147456   (Z = 64 with H, R <= 800; Z = H = R <= 160)
+ *   bf16: 516 Zp +  66 max(Rp, Hp) <= 147456   (Z = 64 with H, R <= 1024; Z = H = R <= 192)
+ * Anything beyond returns DKF_EUNSUPPORTED; there is no slower fall-back.
  * Errors: DKF_EINVAL, DKF_EBLOB, DKF_EUNSUPPORTED, DKF_ENOMEM, DKF_EHIP. */
 int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes, void *stream, dkf_model **out);
 
