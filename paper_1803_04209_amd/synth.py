@@ -128,17 +128,30 @@ def _streams(cfg: ClusterConfig):
     return [np.random.Generator(np.random.PCG64(s)) for s in ss]
 
 
-def make_weights(cfg: ClusterConfig, std: float = 0.1) -> Dict[str, np.ndarray]:
-    """Every tensor, biases and z0 included, iid N(0, std^2) in fp32."""
+def make_weights(cfg: ClusterConfig, std: float = 0.1, calibrated: bool = False) -> Dict[str, np.ndarray]:
+    """Every tensor, biases and z0 included, iid N(0, std^2) in fp32.
+
+    `calibrated` adds fixed offsets to the output biases of the emission networks so that the
+    predicted run-times sit near 0.5 in units of the normaliser (where real run-times sit, the
+    normaliser being twice their mean) with a spread of 0.05 for the small presets (wide hidden
+    layers add to it), instead of scattering around zero."""
     g = _streams(cfg)[0]
-    return {
+    w = {
         name: (std * g.standard_normal(shape)).astype(np.float32)
         for name, shape in blob_layout(cfg)
     }
+    if calibrated:
+        w["emean2_b"] = (w["emean2_b"] + np.float32(0.5)).astype(np.float32)
+        w["escale2_b"] = (w["escale2_b"] + np.float32(CALIBRATED_SCALE_BIAS)).astype(np.float32)
+    return w
 
 
-def make_blob(cfg: ClusterConfig, std: float = 0.1) -> np.ndarray:
-    return pack_blob(cfg, make_weights(cfg, std))
+# softplus(-2.97) = 0.050
+CALIBRATED_SCALE_BIAS = -2.97
+
+
+def make_blob(cfg: ClusterConfig, std: float = 0.1, calibrated: bool = False) -> np.ndarray:
+    return pack_blob(cfg, make_weights(cfg, std, calibrated))
 
 
 def _markov_groups(g, T: int, groups: int, stay: float, slow: float) -> np.ndarray:

@@ -223,6 +223,23 @@ def test_large_bf16_preset_raw_weights(api):
     g.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "medium", "replay", "large_bf16"])
+def test_calibrated_weights(api, name):
+    """Emission biases shifted so that predictions sit where normalised run-times do (mean 0.5, small
+    spread): few samples are negative, so nearly every rank is eligible in the cutoff rule."""
+    cfg = synth.CONFIGS[name]
+    bf16 = cfg.mlp_dtype == "bf16"
+    std = 0.03 if bf16 else 0.1   # the large preset's recurrences amplify at 0.1 (see its own tests)
+    g, o, _ = make_pair(api, cfg, weights=synth.make_weights(cfg, std, calibrated=True), pushes=cfg.lag + 1)
+    rows = np.arange(0, cfg.samples, max(1, cfg.samples // 256), dtype=np.int32)
+    x, errs = compare_stages(api, cfg, g, o, rows=rows, tol=TOL_BF16 if bf16 else TOL)
+    res = api.select_cutoff(x)
+    ref = oracle.cutoff_select(x.cpu().numpy(), want_sorted=False, want_perm=False)
+    assert res["status"] == ref["status"] == api.DKF_OK and cstar_in_tie_band(res["cstar"], ref)
+    assert np.isfinite(ref["omega"]).sum() >= 0.5 * cfg.n_workers
+    g.close()
+
+
 def torch_isfinite(t):
     import torch
 
