@@ -231,6 +231,26 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
         const bool valid = row < S;
         const float *src = x + (size_t)(valid ? row : 0) * N;
         T v[E];
+        if (vec_ok && N == NPAD) {
+            // the row fills the network exactly: every 16-byte load of the row is issued before the
+            // first key is formed (an out-of-range group reads row 0 and discards it)
+            float4 t[E / 4];
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) t[q] = *reinterpret_cast<const float4 *>(src + Lay::load_index(g, q * 4));
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) {
+                const int i0 = Lay::load_index(g, q * 4);
+                const float f[4] = {t[q].x, t[q].y, t[q].z, t[q].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t k = valid ? key_of(f[j]) : kPadKey;
+                    if constexpr (WITH_PERM)
+                        v[q * 4 + j] = ((uint64_t)k << 32) | (uint32_t)(i0 + j);
+                    else
+                        v[q * 4 + j] = k;
+                }
+            }
+        } else {
 #pragma unroll
         for (int q = 0; q < E / 4; ++q) {
             const int i0 = Lay::load_index(g, q * 4);
@@ -251,6 +271,7 @@ __global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restri
                 else
                     v[q * 4 + j] = k;
             }
+        }
         }
 
         merge_up<T, E, LG, 1>(v, g);
