@@ -348,7 +348,16 @@ __device__ __forceinline__ double block_subset_sum(const float *__restrict__ par
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
     const int stride = kMeanParts * 4;
     int b = first;
-    for (; b + 3 * stride < blocks; b += 4 * stride) {  // four independent loads in flight
+    for (; b + 15 * stride < blocks; b += 16 * stride) {  // sixteen independent loads in flight
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)(b + u * stride) * npad + col];
+#pragma unroll
+        for (int u = 0; u < 16; u += 4) {  // same order of additions as four rounds of four
+            s0 += (double)v[u]; s1 += (double)v[u + 1]; s2 += (double)v[u + 2]; s3 += (double)v[u + 3];
+        }
+    }
+    for (; b + 3 * stride < blocks; b += 4 * stride) {
         const float v0 = partial[(size_t)b * npad + col];
         const float v1 = partial[(size_t)(b + stride) * npad + col];
         const float v2 = partial[(size_t)(b + 2 * stride) * npad + col];
@@ -458,6 +467,13 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
     if (col < N && part < P) {
         double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         int b = part;
+        for (; b + 31 * P < blocks; b += 32 * P) {  // thirty-two loads in flight, added as four rounds of eight
+            float v[32];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) v[j] = partial[(size_t)(b + j * P) * npad + col];
+#pragma unroll
+            for (int j = 0; j < 32; ++j) s[j & 7] += (double)v[j];
+        }
         for (; b + 7 * P < blocks; b += 8 * P) {
             float v[8];
 #pragma unroll
