@@ -7,7 +7,9 @@ values a deployed predictor has.  Then, on the held-out part of the trace:
   * every stage of the GPU path agrees with the oracle to the fp32 tolerance,
   * each GPU decision equals the oracle's rule applied to the GPU's own samples,
   * the cutoffs the GPU path chooses give more gradients per second than waiting for everyone
-    (the claim of Sec. 4.1, on synthetic data standing in for the paper's cluster traces).
+    (the claim of Sec. 4.1, on synthetic data standing in for the paper's cluster traces),
+  * most of the order statistics observed next lie inside the predicted mean +- 2 standard
+    deviations (the bands of Fig. 3, from cutoff_rank_spread).
 """
 from dataclasses import replace
 
@@ -43,7 +45,7 @@ def test_fitted_weights_parity_and_decisions(fitted):
     N, S = cfg.n_workers, cfg.samples
     g = api.Predictor(cfg, blob)
     o = oracle.OracleModel(cfg, blob)
-    chosen, steps, differ = [], [], 0
+    chosen, steps, differ, inside = [], [], 0, []
     for t in range(TOTAL - 1):
         assert g.filter_step(trace[t]) == o.filter_step(trace[t])
         if t < TRAIN:
@@ -64,9 +66,13 @@ def test_fitted_weights_parity_and_decisions(fitted):
             assert all(e <= 1e-4 for e in errs.values()), (t, errs)
         else:
             x = g.sample_runtimes(deq, dez, dex)
-        res = api.select_cutoff(x)
+        res = api.select_cutoff(x, want_sorted=True)
         ref = oracle.cutoff_select(x.cpu().numpy(), want_sorted=False, want_perm=False)
         assert res["status"] == ref["status"] and cstar_in_tie_band(res["cstar"], ref), t
+        # Fig. 3: the order statistics that were then observed, against the predicted ones +- 2 sd
+        sd = api.rank_spread(res["sorted"], res["mean"]).cpu().numpy()
+        actual = np.sort(trace[t + 1])
+        inside.append(np.abs(actual - res["mean"].cpu().numpy()) <= 2.0 * sd)
         # and against the oracle's decision from its OWN fp64 samples: the GPU's choice is as good to 1e-3
         own = oracle.cutoff_select(o.sample_runtimes(eq, ez, ex), want_sorted=False, want_perm=False)
         assert cstar_in_tie_band(res["cstar"], own, rel=1e-3), (t, res["cstar"], own["cstar"])
@@ -80,6 +86,9 @@ def test_fitted_weights_parity_and_decisions(fitted):
           f"{differ} of {len(c)} decisions differ from the fp64 oracle's own")
     assert got > 1.01 * full
     assert c.min() < N      # the predictor does drop stragglers
+    coverage = float(np.mean(inside))
+    print(f"observed order statistics inside the predicted mean +- 2 sd: {coverage:.3f}")
+    assert coverage > 0.6   # 0.24 with the unfitted weights
 
 
 class GpuPredictorPolicy:
