@@ -593,10 +593,8 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
 
 // Draw the three noise tensors for S samples into the model's own buffers.
 int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStream_t stream) {
-    int rc = launch_fill_normal(m->gen_q, (size_t)m->L * S * m->Z, 0, ctl, seed, stream);
-    if (rc == DKF_OK) rc = launch_fill_normal(m->gen_z, (size_t)S * m->Z, 1, ctl, seed, stream);
-    if (rc == DKF_OK) rc = launch_fill_normal(m->gen_x, (size_t)S * m->N, 2, ctl, seed, stream);
-    return rc;
+    return launch_fill_normal3(m->gen_q, (size_t)m->L * S * m->Z, m->gen_z, (size_t)S * m->Z, m->gen_x,
+                               (size_t)S * m->N, ctl, seed, stream);
 }
 
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,

@@ -252,7 +252,8 @@ int launch_quad(const ChainArgs &a, hipStream_t stream);
 
 // noise.hip: out[0..n) = standard normals of stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x); the seed
 // is read from `ctl` when that is not NULL (captured graphs), else taken from `seed`
-int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl, uint64_t seed, hipStream_t stream);
+int launch_fill_normal3(float *out0, size_t n0, float *out1, size_t n1, float *out2, size_t n2, const Control *ctl,
+                        uint64_t seed, hipStream_t stream);  // tensors 0, 1, 2 in one launch
 
 // cutoff_select.hip
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,

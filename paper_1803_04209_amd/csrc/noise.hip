@@ -36,35 +36,47 @@ __device__ __forceinline__ void box_muller(uint32_t w0, uint32_t w1, float &n0, 
     n1 = r * s;
 }
 
-// out[i] for i in [0, n): one thread per group of four elements
-__global__ __launch_bounds__(256) void fill_normal(float *__restrict__ out, size_t n, uint32_t tensor,
-                                                   const Control *ctl, uint32_t seed_lo, uint32_t seed_hi) {
+// four consecutive elements 4g .. 4g+3 of tensor `tensor`
+__device__ __forceinline__ void fill_group(float *__restrict__ out, size_t n, uint32_t tensor, size_t g,
+                                           uint32_t seed_lo, uint32_t seed_hi) {
+    const U4 r = philox4x32_10(U4{(uint32_t)g, (uint32_t)(g >> 32), tensor, 0u}, seed_lo, seed_hi);
+    float v[4];
+    box_muller(r.x, r.y, v[0], v[1]);
+    box_muller(r.z, r.w, v[2], v[3]);
+    const size_t i0 = g * 4;
+    if (i0 + 3 < n) {
+        *reinterpret_cast<float4 *>(out + i0) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        for (int j = 0; j < 4; ++j)
+            if (i0 + j < n) out[i0 + j] = v[j];
+    }
+}
+
+// Tensors 0, 1, 2 in one launch, one thread per group of four elements; the groups of the three
+// tensors are numbered one after the other.
+__global__ __launch_bounds__(256) void fill_normal3(float *__restrict__ out0, size_t n0, float *__restrict__ out1,
+                                                    size_t n1, float *__restrict__ out2, size_t n2,
+                                                    const Control *ctl, uint32_t seed_lo, uint32_t seed_hi) {
     if (ctl) { seed_lo = ctl->seed_lo; seed_hi = ctl->seed_hi; }
-    const size_t groups = (n + 3) / 4;
-    for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += (size_t)gridDim.x * blockDim.x) {
-        const U4 r = philox4x32_10(U4{(uint32_t)g, (uint32_t)(g >> 32), tensor, 0u}, seed_lo, seed_hi);
-        float v[4];
-        box_muller(r.x, r.y, v[0], v[1]);
-        box_muller(r.z, r.w, v[2], v[3]);
-        const size_t i0 = g * 4;
-        if (i0 + 3 < n) {
-            *reinterpret_cast<float4 *>(out + i0) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (i0 + j < n) out[i0 + j] = v[j];
-        }
+    const size_t g0 = (n0 + 3) / 4, g1 = (n1 + 3) / 4, g2 = (n2 + 3) / 4;
+    for (size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x; g < g0 + g1 + g2; g += (size_t)gridDim.x * blockDim.x) {
+        if (g < g0) fill_group(out0, n0, 0u, g, seed_lo, seed_hi);
+        else if (g < g0 + g1) fill_group(out1, n1, 1u, g - g0, seed_lo, seed_hi);
+        else fill_group(out2, n2, 2u, g - g0 - g1, seed_lo, seed_hi);
     }
 }
 
 }  // namespace
 
-int launch_fill_normal(float *out, size_t n, uint32_t tensor, const Control *ctl, uint64_t seed, hipStream_t stream) {
-    if (n == 0) return DKF_OK;
-    const size_t groups = (n + 3) / 4;
+int launch_fill_normal3(float *out0, size_t n0, float *out1, size_t n1, float *out2, size_t n2, const Control *ctl,
+                        uint64_t seed, hipStream_t stream) {
+    if (!out0 || !out1 || !out2) return DKF_EINVAL;
+    const size_t groups = (n0 + 3) / 4 + (n1 + 3) / 4 + (n2 + 3) / 4;
+    if (groups == 0) return DKF_OK;
     size_t blocks = (groups + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(fill_normal, dim3((unsigned)blocks), dim3(256), 0, stream, out, n, tensor, ctl, (uint32_t)seed,
-                       (uint32_t)(seed >> 32));
+    hipLaunchKernelGGL(fill_normal3, dim3((unsigned)blocks), dim3(256), 0, stream, out0, n0, out1, n1, out2, n2, ctl,
+                       (uint32_t)seed, (uint32_t)(seed >> 32));
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
 }
