@@ -148,6 +148,27 @@ int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int
                   void *workspace, size_t workspace_bytes, void *stream);
 size_t cutoff_select_workspace(int32_t S, int32_t N);
 
+/* cutoff_select for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and error codes as
+ * cutoff_select, without the workspace: the per-block rank sums live in a
+ * fixed array of cutoff_select_static_max_workspace() bytes (17 MiB) of device
+ * memory that belongs to the library; each GPU the library runs on holds its
+ * own copy until the process ends.  The call allocates and frees nothing (its
+ * first call on a device looks the array's address up, so make that call
+ * outside a capture).
+ *   Limit: cutoff_select_workspace(S, N) <= cutoff_select_static_max_workspace()
+ *   (every N <= 2048 with any S; N <= 4096 with S <= 4096), otherwise
+ *   DKF_EUNSUPPORTED and nothing is launched.
+ *   All calls on one GPU share the array: calls that overlap in time on one
+ *   GPU (different streams, different threads) race and give wrong results;
+ *   calls ordered on one stream are safe.  The array keeps the last call's
+ *   contents; nothing in it needs clearing between calls. */
+int cutoff_select_static(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                         float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                         int32_t *out_cstar, void *stream);
+size_t cutoff_select_static_max_workspace(void);
+
 /* Spread of the predicted order statistics (Fig. 3 draws every predicted
  * order statistic with a band of two standard deviations): for each rank c,
  *   out_sd[c-1] = sqrt( (1/S) sum_k (sorted[k][c-1] - mean[c-1])^2 ).

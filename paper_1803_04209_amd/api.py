@@ -27,7 +27,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
-    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "dkf_decide",
+    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
     "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
@@ -79,6 +79,9 @@ def _lib():
     lib.cutoff_select.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cutoff_select_workspace.restype = sz
     lib.cutoff_select_workspace.argtypes = [i32, i32]
+    lib.cutoff_select_static.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
+    lib.cutoff_select_static_max_workspace.restype = sz
+    lib.cutoff_select_static_max_workspace.argtypes = []
     lib.dkf_decide.argtypes = [vp, vp, i32, vp, vp, vp, u64, C.POINTER(i32), vp]
     lib.dkf_decide_samples.restype = vp
     lib.dkf_decide_samples.argtypes = [vp]
@@ -189,6 +192,21 @@ def cutoff_select(samples, c_min: int, c_max: int, t_floor: float, out_sorted, o
         _dev(out_mean, torch.float32, (N,), "out_mean"), _dev(out_omega, torch.float32, (N,), "out_omega"),
         _dev(out_cstar, torch.int32, (2,), "out_cstar"), _dev(workspace, torch.uint8, name="workspace"),
         workspace.numel(), _stream_ptr(stream)))
+
+
+def cutoff_select_static_max_workspace() -> int:
+    return int(_lib().cutoff_select_static_max_workspace())
+
+
+def cutoff_select_static(samples, c_min: int, c_max: int, t_floor: float, out_sorted, out_perm, out_mean, out_omega,
+                         out_cstar, stream=None) -> int:
+    torch = _torch()
+    S, N = samples.shape
+    return _check("cutoff_select_static", _lib().cutoff_select_static(
+        _dev(samples, torch.float32, name="samples"), S, N, c_min, c_max, float(t_floor),
+        _dev(out_sorted, torch.float32, (S, N), "out_sorted"), _dev(out_perm, torch.int32, (S, N), "out_perm"),
+        _dev(out_mean, torch.float32, (N,), "out_mean"), _dev(out_omega, torch.float32, (N,), "out_omega"),
+        _dev(out_cstar, torch.int32, (2,), "out_cstar"), _stream_ptr(stream)))
 
 
 def cutoff_rank_spread_workspace(S: int, N: int) -> int:

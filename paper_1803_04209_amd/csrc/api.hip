@@ -889,6 +889,15 @@ int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int
                                 out_cstar, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+int cutoff_select_static(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                         float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                         int32_t *out_cstar, void *stream) {
+    return launch_cutoff_select_static(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean,
+                                       out_omega, out_cstar, static_cast<hipStream_t>(stream));
+}
+
+size_t cutoff_select_static_max_workspace(void) { return cutoff_static_scratch_bytes(); }
+
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
                const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream_) {
     if (!m || !x_obs || !cstar_host || S < 1 || S > m->cfg.max_samples) return DKF_EINVAL;

@@ -261,6 +261,11 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
                          const int32_t *ticket = nullptr);  // dev: if set, *ticket is stored to out_cstar[2] after c*
 size_t cutoff_workspace_bytes(int S, int N);
+// the same with the workspace in a fixed device array of the library (no allocation anywhere)
+int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
+                                float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                                int32_t *out_cstar, hipStream_t stream);
+size_t cutoff_static_scratch_bytes();
 
 // impute.hip
 int launch_impute_censored(const float *samples, int S, int N, const float *x_obs, const uint8_t *censored,

@@ -1,8 +1,8 @@
 // Monte-Carlo order statistics and the cutoff decision on gfx950.
 //
-// "Sample, sort, record the values of all n sorted samples, repeat"
-// (Sec. 3.1.1, last paragraph), then Omega(c) = c / mean x_(c) and its argmax
-// (Sec. 3).  Three kernels:
+// Monte-Carlo estimate of the expected order statistics (Sec. 3.1.1, last
+// paragraph), then Omega(c) = c / mean x_(c) and its argmax (Sec. 3).  Three
+// kernels:
 //   sort_rank_sums : every row of the [S][N] sample matrix is sorted by a
 //                    bitonic network held in registers (several keys per lane,
 //                    cross-lane exchanges inside one wavefront), and each rank's
@@ -12,6 +12,8 @@
 // Keys are the order-preserving uint32 image of the fp32 bits, so all compares
 // are integer min/max; with a permutation requested the worker index rides in
 // the low half of a 64-bit key and breaks ties.
+#include <mutex>
+
 #include "common.h"
 
 namespace dkf {
@@ -590,6 +592,53 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
         }
     }
     return DKF_OK;
+}
+
+// ---- the same call for callers that cannot allocate ------------------------------------------
+// The per-block rank sums and the second-level sums live in a fixed array of device memory that
+// is part of the loaded code object, so the call needs no workspace from anybody.  Every GPU has
+// its own copy at its own address; the address is looked up once per device.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)17 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void **out) {
+    int dev = -1;
+    DKF_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DKF_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        DKF_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255) != 0) return DKF_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DKF_OK;
+}
+}  // namespace
+
+size_t cutoff_static_scratch_bytes() { return kStaticScratchBytes; }
+
+int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
+                                float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
+                                int32_t *out_cstar, hipStream_t stream) {
+    if (S < 1 || N < 1) return DKF_EINVAL;
+    if (N > 4096) return DKF_EUNSUPPORTED;
+    if (cutoff_workspace_bytes(S, N) > kStaticScratchBytes) return DKF_EUNSUPPORTED;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != DKF_OK) return rc;
+    // every word of the scratch the kernels read has been written earlier in the same call, so
+    // nothing is cleared; what the previous call left behind is never looked at
+    return launch_cutoff_select(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean, out_omega,
+                                out_cstar, ws, kStaticScratchBytes, stream, nullptr);
 }
 
 }  // namespace dkf
