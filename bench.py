@@ -182,7 +182,8 @@ def main():
     import numpy as np
     import torch
 
-    from paper_1803_04209_amd import api, synth
+    from paper_1803_04209_amd import api
+    import cluster_synth as synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -54,6 +54,7 @@ def _load():
     lib.oracle_filter_step.argtypes = [C.c_void_p, dp]
     lib.oracle_encode_window.argtypes = [C.c_void_p, dp, dp]
     lib.oracle_sample_runtimes.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp]
+    lib.oracle_transition_terms.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp, dp, dp]
     lib.oracle_cutoff_select.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_cutoff_select_f32.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_predict_cutoff.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_double, ip]
@@ -182,6 +183,24 @@ class OracleModel:
         if stages:
             return x, dict(z_T=zT, z_next=zn, emit_mean=mean, emit_sd=sd)
         return x
+
+    def transition_terms(self, eps_q, eps_z, eps_x, rows=None):
+        """Inside of the gated transition per sample: gate_hidden [n][H] (before its ReLU), gate_pre
+        (argument of the sigmoid), gate, lin, prop, G, Hs, each [n][Z]."""
+        cfg = self.cfg
+        eps_q, eps_z, eps_x = _f32(eps_q), _f32(eps_z), _f32(eps_x)
+        S = eps_z.shape[0]
+        assert eps_q.shape == (cfg.lag, S, cfg.z_dim) and eps_z.shape == (S, cfg.z_dim)
+        r = None if rows is None else np.ascontiguousarray(rows, dtype=np.int32)
+        n = S if r is None else r.size
+        out = dict(gate_hidden=np.empty((n, cfg.hidden)))
+        for k in ("gate_pre", "gate", "lin", "prop", "G", "Hs"):
+            out[k] = np.empty((n, cfg.z_dim))
+        rc = _load().oracle_transition_terms(self._h, S, _ip(r), n, _fp(eps_q), _fp(eps_z), _fp(eps_x),
+                                             *[_dp(out[k]) for k in ("gate_hidden", "gate_pre", "gate", "lin", "prop", "G", "Hs")])
+        if rc < 0:
+            raise RuntimeError(f"oracle_transition_terms: error {rc}")
+        return out
 
     def predict_cutoff(self, eps_q, eps_z, eps_x, c_min=1, c_max=None, t_floor=0.0):
         eps_q, eps_z, eps_x = _f32(eps_q), _f32(eps_z), _f32(eps_x)

@@ -17,8 +17,10 @@
  * Parity pins (tests, CPU only): closed-form order statistics of iid
  * uniform / exponential / normal rows, brute-force argmax on tiny N, the
  * paper's 10 s / 8 s example, degenerate-weight cases that collapse the
- * network to closed forms, and an independent numpy float64 transcription of
- * the equations.  The trained-model behaviour of the whole pipeline (the
+ * network to closed forms, hand-worked small cases with literal expected
+ * values for the gate and the combiner at ordinary values, the all-widths-one
+ * chain worked as scalar arithmetic by a math-only script, and an independent
+ * numpy float64 transcription of the equations (an index check, not a pin).  The trained-model behaviour of the whole pipeline (the
  * paper's Fig. 2/3) is "parity unpinned": no trained weights, traces or
  * printed predictions exist to compare with.
  */
@@ -244,9 +246,21 @@ static void scratch_free(scratch *s) {
     free(s->g); free(s->h); free(s->lin); free(s->G); free(s->mean); free(s->sd);
 }
 
+/* Optional taps on the inside of the gated transition of one sample (any may be NULL). */
+typedef struct {
+    double *gate_hidden; /* [H] W_g1 z_T + b, before the ReLU */
+    double *gate_pre;    /* [Z] argument of the sigmoid */
+    double *gate;        /* [Z] g */
+    double *lin;         /* [Z] W_l z_T + b_l */
+    double *prop;        /* [Z] proposed mean h */
+    double *G;           /* [Z] transition mean */
+    double *Hs;          /* [Z] transition scale */
+} transition_taps;
+
 static void sample_one(const oracle_model *m, const double *hl, const double *hr, int S, int k,
                        const float *eps_q, const float *eps_z, const float *eps_x, scratch *w,
-                       double *x_out, double *zT_out, double *zn_out, double *mean_out, double *sd_out) {
+                       double *x_out, double *zT_out, double *zn_out, double *mean_out, double *sd_out,
+                       const transition_taps *tap) {
     int N = m->cfg.n_workers, L = m->cfg.lag, Z = m->cfg.z_dim, H = m->cfg.hidden, R = m->cfg.rnn_dim;
     /* Guide chain: z_t ~ N(mu_q, sigma_q) for t = 1..L, sequential in t.
      * READING: the latent before the window is a learned vector z0. */
@@ -266,8 +280,10 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
     if (zT_out) memcpy(zT_out, w->z, sizeof(double) * Z);
     /* Gated transition z_{T+1} ~ N(G(z_T), H(z_T)) */
     affine(m->gate1_w, m->gate1_b, w->z, Z, H, w->hid);
+    if (tap && tap->gate_hidden) memcpy(tap->gate_hidden, w->hid, sizeof(double) * H);
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
     affine(m->gate2_w, m->gate2_b, w->hid, H, Z, w->g);
+    if (tap && tap->gate_pre) memcpy(tap->gate_pre, w->g, sizeof(double) * Z);
     for (int i = 0; i < Z; ++i) w->g[i] = sigmoid(w->g[i]);
     affine(m->prop1_w, m->prop1_b, w->z, Z, H, w->hid);
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
@@ -276,9 +292,16 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
     for (int i = 0; i < Z; ++i) w->G[i] = (1.0 - w->g[i]) * w->lin[i] + w->g[i] * w->h[i];
     for (int i = 0; i < Z; ++i) w->mu[i] = relu(w->G[i]);
     affine(m->tscale_w, m->tscale_b, w->mu, Z, Z, w->pre);
-    for (int i = 0; i < Z; ++i)
-        w->zn[i] = w->G[i] + softplus(w->pre[i]) * (double)eps_z[(size_t)k * Z + i];
+    for (int i = 0; i < Z; ++i) w->pre[i] = softplus(w->pre[i]);
+    for (int i = 0; i < Z; ++i) w->zn[i] = w->G[i] + w->pre[i] * (double)eps_z[(size_t)k * Z + i];
     if (zn_out) memcpy(zn_out, w->zn, sizeof(double) * Z);
+    if (tap) {
+        if (tap->gate) memcpy(tap->gate, w->g, sizeof(double) * Z);
+        if (tap->lin) memcpy(tap->lin, w->lin, sizeof(double) * Z);
+        if (tap->prop) memcpy(tap->prop, w->h, sizeof(double) * Z);
+        if (tap->G) memcpy(tap->G, w->G, sizeof(double) * Z);
+        if (tap->Hs) memcpy(tap->Hs, w->pre, sizeof(double) * Z);
+    }
     /* Emission x_{T+1} ~ N(I(z_{T+1}), J(z_{T+1})), J fed by I's output */
     affine(m->emean1_w, m->emean1_b, w->zn, Z, H, w->hid);
     if (m->cfg.emit_mean_act == 1)
@@ -321,8 +344,48 @@ int oracle_sample_runtimes(const oracle_model *m, int S, const int32_t *rows, in
             int k = rows ? rows[i] : i;
             sample_one(m, hl, hr, S, k, eps_q, eps_z, eps_x, &w, out_samples + (size_t)i * N,
                        out_zT ? out_zT + (size_t)i * Z : NULL, out_znext ? out_znext + (size_t)i * Z : NULL,
-                       out_mean ? out_mean + (size_t)i * N : NULL, out_sd ? out_sd + (size_t)i * N : NULL);
+                       out_mean ? out_mean + (size_t)i * N : NULL, out_sd ? out_sd + (size_t)i * N : NULL, NULL);
         }
+        scratch_free(&w);
+    }
+    free(hl); free(hr);
+    return ORACLE_OK;
+}
+
+/* The inside of the gated transition (Sec. 3.1.3: g, h, G, H of the transition display) for the
+ * samples listed in `rows` (all S when rows == NULL): the same sample_one as above with its taps
+ * switched on.  Outputs [n_out][H] (gate_hidden) or [n_out][Z]; any may be NULL. */
+int oracle_transition_terms(const oracle_model *m, int S, const int32_t *rows, int n_rows,
+                            const float *eps_q, const float *eps_z, const float *eps_x,
+                            double *out_gate_hidden, double *out_gate_pre, double *out_gate,
+                            double *out_lin, double *out_prop, double *out_G, double *out_Hs) {
+    int N = m->cfg.n_workers, L = m->cfg.lag, Z = m->cfg.z_dim, H = m->cfg.hidden, R = m->cfg.rnn_dim;
+    if (S < 1 || !eps_q || !eps_z || !eps_x) return ORACLE_EINVAL;
+    if (m->count < L) return ORACLE_ENOTREADY;
+    int n_out = rows ? n_rows : S;
+    for (int i = 0; rows && i < n_rows; ++i)
+        if (rows[i] < 0 || rows[i] >= S) return ORACLE_EINVAL;
+    double *hl = (double *)malloc(sizeof(double) * (size_t)L * R);
+    double *hr = (double *)malloc(sizeof(double) * (size_t)L * R);
+    oracle_encode_window(m, hl, hr);
+#pragma omp parallel
+    {
+        scratch w = scratch_new(&m->cfg);
+        double *x = (double *)malloc(sizeof(double) * N);
+#pragma omp for schedule(static)
+        for (int i = 0; i < n_out; ++i) {
+            int k = rows ? rows[i] : i;
+            transition_taps tap;
+            tap.gate_hidden = out_gate_hidden ? out_gate_hidden + (size_t)i * H : NULL;
+            tap.gate_pre = out_gate_pre ? out_gate_pre + (size_t)i * Z : NULL;
+            tap.gate = out_gate ? out_gate + (size_t)i * Z : NULL;
+            tap.lin = out_lin ? out_lin + (size_t)i * Z : NULL;
+            tap.prop = out_prop ? out_prop + (size_t)i * Z : NULL;
+            tap.G = out_G ? out_G + (size_t)i * Z : NULL;
+            tap.Hs = out_Hs ? out_Hs + (size_t)i * Z : NULL;
+            sample_one(m, hl, hr, S, k, eps_q, eps_z, eps_x, &w, x, NULL, NULL, NULL, NULL, &tap);
+        }
+        free(x);
         scratch_free(&w);
     }
     free(hl); free(hr);
@@ -386,7 +449,7 @@ static int keyed_cmp(const void *pa, const void *pb) {
     return (a->idx > b->idx) - (a->idx < b->idx);
 }
 
-/* samples [S][N]: sort every row ascending ("sample, sort, record"), average
+/* samples [S][N]: sort every row ascending (Monte-Carlo order statistics, Sec. 3.1.1 last paragraph), average
  * each rank over the S rows, form Omega(c) = c / mean x_(c) and return the
  * maximiser, 1-based.  READING: only c in [c_min, c_max] whose mean exceeds
  * t_floor are eligible; ties go to the largest c; with nothing eligible the

@@ -28,7 +28,7 @@ import numpy as np
 import torch
 import torch.nn.functional as F
 
-from paper_1803_04209_amd import synth  # blob layout and seeded traces only
+import cluster_synth as synth
 
 DT = torch.float64
 

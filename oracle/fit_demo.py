@@ -14,7 +14,7 @@ import time
 
 import numpy as np
 
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 from . import binding, elbo
 

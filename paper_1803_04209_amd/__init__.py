@@ -1,12 +1,10 @@
 """MI355X-native Cutoff-SGD run-time predictor (hand-written HIP behind a C ABI).
 
-`synth` (seeded synthetic inputs) imports without the compiled library; the
-binding in `api` loads `libcutoff_dkf.so` on first use and raises if it is
+The binding in `api` loads `libcutoff_dkf.so` on first use and raises if it is
 missing: there is no CPU fallback.
 """
-from . import synth  # noqa: F401
 
-__all__ = ["synth", "api"]
+__all__ = ["api"]
 
 
 def __getattr__(name):

@@ -132,7 +132,7 @@ def _check(fn: str, rc: int) -> int:
 
 
 def make_config(cfg, max_samples=None, emit_mean_act=0, mlp_dtype=None) -> dkf_config:
-    """dkf_config from a synth.ClusterConfig-like object."""
+    """dkf_config from an object with n_workers, lag, z_dim, hidden, rnn_dim, samples, mlp_dtype attributes."""
     if mlp_dtype is None:
         mlp_dtype = DKF_DTYPE_BF16 if getattr(cfg, "mlp_dtype", "f32") == "bf16" else DKF_DTYPE_F32
     return dkf_config(cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim, int(mlp_dtype),

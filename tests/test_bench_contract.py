@@ -15,7 +15,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_stage_work_matches_the_layer_sizes():
     sys.path.insert(0, str(ROOT))
     import bench
-    from paper_1803_04209_amd import synth
+    import cluster_synth as synth
 
     cfg = synth.CONFIGS["medium"]
     w = bench.stage_work(cfg)

@@ -38,7 +38,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_host_only_calls_work_without_a_gpu():
-    from paper_1803_04209_amd import api, synth
+    from paper_1803_04209_amd import api
+    import cluster_synth as synth
 
     lib = api._lib()
     assert lib.dkf_strerror(api.DKF_EBADOBS).decode().startswith("observation")
@@ -63,3 +64,12 @@ def test_product_code_never_touches_the_oracle():
         if path.is_file() and path.suffix in {".py", ".hip", ".h", ".cpp"}:
             text = path.read_text()
             assert "import oracle" not in text and "from oracle" not in text and "cutoff_oracle" not in text, path
+
+
+def test_oracle_never_imports_the_product():
+    for path in (ROOT / "oracle").rglob("*"):
+        if path.is_file() and path.suffix in {".py", ".c", ".h"}:
+            text = path.read_text()
+            assert "paper_1803_04209_amd" not in text and "cutoff_dkf" not in text, path
+    text = (ROOT / "cluster_synth.py").read_text()
+    assert "import oracle" not in text and "paper_1803_04209_amd" not in text

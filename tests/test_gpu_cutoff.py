@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 from gpu_util import cstar_in_tie_band
 
 pytestmark = pytest.mark.gpu

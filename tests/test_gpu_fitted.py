@@ -18,7 +18,7 @@ import pytest
 
 import oracle
 from oracle import elbo
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 from gpu_util import cstar_in_tie_band, rel_err
 
 pytestmark = pytest.mark.gpu

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 pytestmark = pytest.mark.gpu
 

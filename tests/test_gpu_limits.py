@@ -11,7 +11,7 @@ from dataclasses import replace
 import numpy as np
 import pytest
 
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 from test_gpu_model import TOL, TOL_BF16, api, compare_stages, custom, make_pair  # noqa: F401
 
 pytestmark = pytest.mark.gpu

@@ -13,7 +13,7 @@ import pytest
 from scipy import integrate, stats
 
 import oracle
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 
 def read_golden(path):

@@ -18,7 +18,7 @@ from scipy.stats import multivariate_normal
 
 import oracle
 from oracle import elbo as E
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 
 def softplus_inv(y):

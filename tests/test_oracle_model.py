@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 
 def custom(N=6, L=4, Z=3, H=5, R=7, S=64, idx=9):

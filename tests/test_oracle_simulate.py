@@ -10,7 +10,7 @@ import pytest
 
 import oracle
 from oracle import simulate as sim
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 
 def test_full_sync_and_static_cutoffs_are_sums_of_order_statistics():

@@ -9,7 +9,7 @@ the array must be refused.
 import numpy as np
 import pytest
 
-from paper_1803_04209_amd import synth
+import cluster_synth as synth
 
 pytestmark = pytest.mark.gpu
 
