@@ -4,14 +4,18 @@
 A step is one whole decision: push one observed run-time vector (host -> GPU),
 re-encode the window, draw S joint run-time vectors, sort them, average the
 ranks, pick c*, and bring c* back (GPU -> host), i.e. one `dkf_decide` call.
-Prints ONE JSON line; see the design doc for how the figures are defined.
+Prints ONE JSON line.  The headline fields (value, ms_per_step, roofline,
+cpu_baseline) are those of --workload (default: `contended`, the largest
+fp32 workload); `workloads` carries the same measurements for the workloads
+listed in --also (default: large_bf16 and replay).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload medium|contended|replay|tiny]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--also a,b|none]
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import sys
 import time
 from pathlib import Path
@@ -23,6 +27,20 @@ if str(ROOT) not in sys.path:
 METRIC = "sampled N-worker run-time vectors/sec + cutoff decisions/sec (p50 latency)"
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}  # MI355X dense MFMA
 PEAK_HBM_GBS = 8000.0
+# 256 compute units x 64 vector lanes per clock x 2.4 GHz 32-bit integer operations per second; a
+# compare-exchange of two keys is one minimum and one maximum
+PEAK_VALU_OPS = 256 * 64 * 2.4e9
+PEAK_CMPEX = PEAK_VALU_OPS / 2.0
+LATENCY_DECISIONS = 1000  # fewest decisions the latency percentiles are taken from
+
+
+def sort_compare_exchanges(S, N):
+    """Compare-exchanges of the bitonic networks that sort S rows of N keys (rows padded to a power of two >= 8)."""
+    npad = 8
+    while npad < N:
+        npad *= 2
+    p = int(math.log2(npad))
+    return S * (npad // 2) * (p * (p + 1) // 2)
 
 
 def stage_work(cfg):
@@ -62,8 +80,8 @@ def kernel_sources_digest(stage_name):
 
 
 def stored_traffic(workload, stage_name):
-    """HBM bytes per launch from the committed FETCH_SIZE / WRITE_SIZE counter summary of this
-    workload's dominant kernel; None when there is none or the kernel's sources changed since."""
+    """HBM bytes per launch of one stage's kernel from the committed FETCH_SIZE / WRITE_SIZE counter
+    summary of this workload; None when there is none or the kernel's sources changed since."""
     path = ROOT / "profiles" / f"pmc_traffic_{workload}.txt"
     if not path.exists():
         return None
@@ -72,9 +90,10 @@ def stored_traffic(workload, stage_name):
         if line.startswith("@"):
             k, _, v = line[1:].partition("=")
             kv[k.strip()] = v.strip()
-    if kv.get("stage") != stage_name or kv.get("sources_sha256") != kernel_sources_digest(stage_name):
+    if kv.get(f"{stage_name}.sources_sha256") != kernel_sources_digest(stage_name):
         return None
-    return float(kv["traffic_bytes_per_launch"])
+    v = kv.get(f"{stage_name}.traffic_bytes_per_launch")
+    return float(v) if v is not None else None
 
 
 def cpu_baseline(cfg, blob, trace, noise, budget_s):
@@ -157,44 +176,22 @@ def aux_entry_points(api, torch, np, samples, x_next, calls):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed decisions (default 300; 1000 for replay)")
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="medium", choices=["tiny", "medium", "contended", "large_bf16", "replay"])
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
-    ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
-                    help="also run a plain device-to-device copy of this many MiB three times (the known-size "
-                         "kernel that hardware-counter readings are scaled by)")
-    ap.add_argument("--weights", default="raw", choices=["raw", "calibrated"],
-                    help="raw: every tensor N(0, 0.1^2) as the workloads are defined; calibrated: the same plus "
-                         "emission biases that put predictions where normalised run-times sit")
-    ap.add_argument("--aux", type=int, default=0, metavar="CALLS",
-                    help="also time this many calls of the entry points around the decision (censored-run-time "
-                         "imputation, spread of the rank means) on the workload's own sample matrix")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(args, name, K, W, headline):
+    """Every measurement of one workload; returns a dict (the headline workload's becomes the JSON line's top level)."""
     import numpy as np
     import torch
 
     from paper_1803_04209_amd import api
     import cluster_synth as synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.workload]
+    cfg = synth.CONFIGS[name]
     S, N = cfg.samples, cfg.n_workers
-    K = args.steps if args.steps is not None else (1000 if args.workload == "replay" else 300)
-    W = args.warmup
+    KL = max(LATENCY_DECISIONS, K)          # decisions behind the latency percentiles
+    K_own = min(K, 300)                     # decisions of the built-in-noise region
+    K_eager = min(K, 200)                   # eager steps behind the per-kernel times
     blob = synth.make_blob(cfg, calibrated=args.weights == "calibrated")
-    trace = synth.make_trace(cfg, max(cfg.trace_len, cfg.lag + 3 * (K + W) + 200))  # both timed regions, their warm-ups, the per-stage pass
+    need = cfg.lag + (W + K) + (W + KL) + (W + K_own) + 3 * (K_eager + 25) + 16
+    trace = synth.make_trace(cfg, max(cfg.trace_len, need))
     noise = synth.make_noise(cfg)
     eq, ez, ex = (torch.from_numpy(a).cuda() for a in noise)
     pred = api.Predictor(cfg, blob)
@@ -202,36 +199,43 @@ def main():
     for _ in range(cfg.lag - 1):  # fill the window (untimed); the next push completes it
         pred.filter_step(trace[t_idx]); t_idx += 1
 
-    # ---- region 1: synchronous decisions through the captured graph ----------------
+    # ---- region 1: K synchronous decisions through the captured graph (value, ms_per_step) ---------
     for _ in range(W):
         pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
     torch.cuda.synchronize()
-    lat = np.empty(K)
     cuts = np.empty(K, dtype=np.int64)
     first_timed = t_idx
     t_start = time.perf_counter()
     for i in range(K):
-        t0 = time.perf_counter()
         cuts[i], _ = pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
-        lat[i] = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
-    ms_per_step = wall / K * 1e3
 
-    # ---- region 1b: the same, the library drawing its own noise (counter-based generator) ----
+    # ---- region 1a: latency of single decisions, at least LATENCY_DECISIONS of them -----------------
+    for _ in range(W):
+        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+    torch.cuda.synchronize()
+    lat = np.empty(KL)
+    for i in range(KL):
+        t0 = time.perf_counter()
+        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+        lat[i] = time.perf_counter() - t0
+    torch.cuda.synchronize()
+
+    # ---- region 1b: the same path, the library drawing its own noise (counter-based generator) ------
     for i in range(W):
         pred.decide(trace[t_idx], S, seed=i); t_idx += 1
     torch.cuda.synchronize()
-    lat_own = np.empty(K)
+    lat_own = np.empty(K_own)
     t_start = time.perf_counter()
-    for i in range(K):
+    for i in range(K_own):
         t0 = time.perf_counter()
         pred.decide(trace[t_idx], S, seed=W + i); t_idx += 1
         lat_own[i] = time.perf_counter() - t0
     torch.cuda.synchronize()
     wall_own = time.perf_counter() - t_start
 
-    # ---- region 2: the same steps enqueued eagerly, HIP events around each stage -----
+    # ---- region 2: the same steps enqueued eagerly, one HIP event pair around every kernel launch ---
     out = torch.empty((S, N), dtype=torch.float32, device="cuda")
     ws = torch.empty(api.cutoff_select_workspace(S, N), dtype=torch.uint8, device="cuda")
     cst = torch.zeros(2, dtype=torch.int32, device="cuda")
@@ -245,42 +249,56 @@ def main():
 
     work = stage_work(cfg)
     api.dkf_timing_enable((1 << api.DKF_NUM_STAGES) - 1)
-    eager_steps(min(W, 20) + 1)
+    eager_steps(21)
     for s in range(api.DKF_NUM_STAGES):
         api.dkf_timing_read(s)
-    eager_steps(min(K, 50))
-    stage_us = {}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eager_steps(K_eager)
+    torch.cuda.synchronize()
+    eager_wall = time.perf_counter() - t0
+    stage_us, stage_n = {}, {}
     for s in range(api.DKF_NUM_STAGES):
         n, ms = api.dkf_timing_read(s)
-        stage_us[s] = ms / max(n, 1) * 1e3
+        stage_us[s], stage_n[s] = ms / max(n, 1) * 1e3, n
+    api.dkf_timing_enable(0)
     fused = stage_us[8] > 0  # stages 1-5 ran as one kernel
     if fused:
         work = {s: w for s, w in work.items() if s in (6, 8)}
     else:
         del work[8]
+
+    def roofline_of(s):
+        bound, amount = work[s]
+        secs = stage_us[s] * 1e-6
+        if bound == "mfma":
+            achieved, peak, unit = amount / secs / 1e12, PEAK_TFLOPS[cfg.mlp_dtype], "TFLOP/s"
+        else:
+            achieved, peak, unit = amount / secs / 1e9, PEAK_HBM_GBS, "GB/s"
+        return {"kernel": api.STAGE_NAMES[s], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": stored_traffic(cfg.name, api.STAGE_NAMES[s]),
+                "launches": stage_n[s], "avg_launch_us": stage_us[s], "work_per_launch": amount,
+                "timing": "mean of HIP-event pairs around each launch on the launch stream, host running ahead "
+                          "(the pair also brackets the dispatch of the launch, a few microseconds)"}
+
     dominant = max(work, key=lambda s: stage_us[s])
-    # dominant kernel alone: one event pair per launch, host running ahead of the GPU
-    api.dkf_timing_enable(1 << dominant)
-    eager_steps(min(W, 20) + 1)
-    api.dkf_timing_read(dominant)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    eager_steps(K)
-    torch.cuda.synchronize()
-    eager_wall = time.perf_counter() - t0
-    n_launch, total_ms = api.dkf_timing_read(dominant)
-    api.dkf_timing_enable(0)
-    kernel_s = total_ms / max(n_launch, 1) * 1e-3
-    bound, amount = work[dominant]
-    if bound == "mfma":
-        achieved, peak, unit = amount / kernel_s / 1e12, PEAK_TFLOPS[cfg.mlp_dtype], "TFLOP/s"
-    else:
-        achieved, peak, unit = amount / kernel_s / 1e9, PEAK_HBM_GBS, "GB/s"
-    roofline = {
-        "kernel": api.STAGE_NAMES[dominant], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-        "frac": achieved / peak, "traffic": stored_traffic(cfg.name, api.STAGE_NAMES[dominant]), "launches": n_launch, "avg_launch_us": kernel_s * 1e6,
-        "work_per_launch": amount,
+    stages = [roofline_of(s) for s in sorted(work)]
+    # the row sort: against HBM (the sample matrix read once) and against the vector ALU (its compare-exchanges)
+    sort_s = stage_us[6] * 1e-6
+    cmpex = sort_compare_exchanges(S, N)
+    hbm_frac = 4.0 * S * N / sort_s / 1e9 / PEAK_HBM_GBS
+    valu_frac = cmpex / sort_s / PEAK_CMPEX
+    sort_block = {
+        "kernel": "sort_rank_sums", "avg_launch_us": stage_us[6], "bytes": 4.0 * S * N,
+        "hbm": {"achieved": 4.0 * S * N / sort_s / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": hbm_frac},
+        "valu": {"compare_exchanges": cmpex, "achieved": cmpex / sort_s / 1e12, "peak": PEAK_CMPEX / 1e12,
+                 "unit": "T compare-exchanges/s", "frac": valu_frac},
+        "binds": "valu" if valu_frac > hbm_frac else "hbm",
+        "traffic": stored_traffic(cfg.name, "sort_rank_sums"),
     }
+    mlp_flops = sum(v for s, (b, v) in work.items() if b == "mfma")
+    mlp_us = sum(stage_us[s] for s, (b, _) in work.items() if b == "mfma")
+
     # Gradients per second the chosen cutoffs would have achieved on the iterations that followed
     # each decision (Fig. 2's three curves: chosen, wait for all, best cutoff in hindsight).
     nxt = np.sort(trace[first_timed + 1:first_timed + 1 + K].astype(np.float64), axis=1)
@@ -305,32 +323,87 @@ def main():
         "hindsight_best": float((best + 1).sum() / nxt[np.arange(K), best].sum()),
         "note": f"seed-initialised (untrained, {args.weights}) weights: says nothing about forecast quality",
     }
-    mlp_flops = sum(v for s, (b, v) in work.items() if b == "mfma")
-    mlp_us = sum(stage_us[s] for s, (b, _) in work.items() if b == "mfma")
-
     result = {
-        "metric": METRIC, "value": S * K / wall, "unit": "vectors/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.mlp_dtype, "data": "synthetic",
+        "value": S * K / wall, "unit": "vectors/s", "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
+        "dtype": cfg.mlp_dtype,
         "config": {"workload": f"{cfg.name}: N={N} L={cfg.lag} Z={cfg.z_dim} H={cfg.hidden} S={S}",
                    "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay)",
                    "weights": args.weights},
         "decisions_per_s": K / wall,
-        "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3)},
+        "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3),
+                       "decisions": KL},
         "mean_cutoff": float(cuts.mean()),
         "implied_gradients_per_s": implied,
-        "builtin_noise": {"vectors_per_s": S * K / wall_own, "ms_per_step": wall_own / K * 1e3,
-                          "p50_ms": float(np.median(lat_own) * 1e3),
+        "builtin_noise": {"vectors_per_s": S * K_own / wall_own, "ms_per_step": wall_own / K_own * 1e3,
+                          "p50_ms": float(np.median(lat_own) * 1e3), "decisions": K_own,
                           "note": "same graph path, eps tensors drawn per decision by the library (Philox4x32-10)"},
-        "eager_pipelined": {"vectors_per_s": S * K / eager_wall, "ms_per_step": eager_wall / K * 1e3},
+        "eager_pipelined": {"vectors_per_s": S * K_eager / eager_wall, "ms_per_step": eager_wall / K_eager * 1e3},
         "stage_us": {api.STAGE_NAMES[s]: round(stage_us[s], 2) for s in range(api.DKF_NUM_STAGES)},
         "mlp_stages": {"flops": mlp_flops, "us": mlp_us, "tflops": mlp_flops / (mlp_us * 1e-6) / 1e12,
                        "frac_of_peak": mlp_flops / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype]},
-        "roofline": roofline,
+        "roofline": roofline_of(dominant),
+        "stages": stages,
+        "sort": sort_block,
     }
     if args.aux > 0:
         result["aux_us_per_call"] = aux_entry_points(api, torch, np, out, trace[t_idx], args.aux)
     pred.close()
+    del eq, ez, ex, out, ws
+    torch.cuda.empty_cache()
+    if headline and args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, blob, trace, noise, args.cpu_seconds)
+    return result
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000, help="timed decisions per workload")
+    ap.add_argument("--warmup", type=int, default=30)
+    names = ["tiny", "medium", "contended", "large_bf16", "replay"]
+    ap.add_argument("--workload", default="contended", choices=names,
+                    help="the workload the headline fields are measured on")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads measured as well and reported under `workloads` "
+                         "(default: large_bf16,replay with the default headline, otherwise none; `none` for none)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
+    ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
+                    help="also run a plain device-to-device copy of this many MiB three times (the known-size "
+                         "kernel that hardware-counter readings are scaled by)")
+    ap.add_argument("--weights", default="raw", choices=["raw", "calibrated"],
+                    help="raw: every tensor N(0, 0.1^2) as the workloads are defined; calibrated: the same plus "
+                         "emission biases that put predictions where normalised run-times sit")
+    ap.add_argument("--aux", type=int, default=0, metavar="CALLS",
+                    help="also time this many calls of the entry points around the decision (censored-run-time "
+                         "imputation, spread of the rank means) on the workload's own sample matrix")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if args.also is None:
+        also = ["large_bf16", "replay"] if args.workload == "contended" else []
+    else:
+        also = [w for w in args.also.split(",") if w and w != "none"]
+    for w in also:
+        if w not in names:
+            ap.error(f"--also: unknown workload {w}")
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    K, W = args.steps, args.warmup
+    head = run_workload(args, args.workload, K, W, headline=True)
+    result = {"metric": METRIC, "value": head.pop("value"), "unit": head.pop("unit"), "n_gpus": 1, "steps": K,
+              "warmup": W, "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": head.pop("dtype"), "data": "synthetic"}
+    head.pop("steps"); head.pop("warmup")
+    result.update(head)
+    if also:
+        result["workloads"] = {w: run_workload(args, w, K, W, headline=False) for w in also if w != args.workload}
     if args.calibration_copy > 0:
         src = torch.ones(args.calibration_copy << 18, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -338,8 +411,6 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if args.cpu_seconds > 0:
-        result["cpu_baseline"] = cpu_baseline(cfg, blob, trace, noise, args.cpu_seconds)
     print(json.dumps(result))
 
 

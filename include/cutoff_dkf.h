@@ -44,6 +44,7 @@ extern "C" {
 #define DKF_ENOMEM (-5)          /* host or device allocation failed */
 #define DKF_EBLOB (-6)           /* weight blob header/size does not match the configuration */
 #define DKF_EUNSUPPORTED (-7)    /* a size beyond what the kernels are built for (see each call) */
+#define DKF_ESTALLED (-8)        /* the filter's workgroups stopped waiting for each other: no valid encoding, no decision */
 
 #define DKF_DTYPE_F32 0          /* MLP GEMMs in fp32 */
 #define DKF_DTYPE_BF16 1         /* MLP GEMM inputs rounded to bf16, fp32 accumulate */
@@ -196,12 +197,28 @@ size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
  * finished by then, but the stream may report busy for a few microseconds
  * more.  If the ticket does not arrive the stream is synchronised instead.)
  * Returns DKF_OK, DKF_WARMUP (then *cstar_host = N), CUTOFF_NO_ELIGIBLE, or
- * an error.  DKF_EINVAL and DKF_EBADOBS leave the model untouched; after any
+ * an error (DKF_ESTALLED: see dkf_check; *cstar_host = N then).  DKF_EINVAL and DKF_EBADOBS leave the model untouched; after any
  * other error the observation has already entered the window but the
  * decision is lost: restore the window (dkf_set_state) or start over
  * (dkf_reset) before deciding again. */
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
                const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream);
+
+/* Failure detection for the filter of wide encoders (R > 256), whose recurrence
+ * is split over several workgroups that hand their part of the state to each
+ * other through memory every step.  A workgroup waits for the others a bounded
+ * number of polls; if that runs out (it cannot unless something else holds the
+ * device for seconds) it raises a fault word, fills its encodings with NaN and
+ * exits.  dkf_decide then returns DKF_ESTALLED instead of a cutoff (never
+ * CUTOFF_NO_ELIGIBLE).  For the separate calls, dkf_check synchronises `stream`
+ * and returns DKF_ESTALLED if the most recent dkf_filter_step on the model gave
+ * up (DKF_OK otherwise): samples drawn from that window are NaN.  The fault is
+ * cleared by the next filter step; the window itself is intact.
+ * dkf_set_exchange_spin_limit sets the number of polls (default 2^20; 0 makes
+ * every wait count as having run out, which is how the tests reach this path
+ * with all workgroups still exiting normally).  Host calls. */
+int dkf_check(dkf_model *m, void *stream);
+int dkf_set_exchange_spin_limit(dkf_model *m, int32_t polls);
 
 /* Device pointer to the [S][N] samples of the last dkf_decide (valid until the
  * next call on the model). */

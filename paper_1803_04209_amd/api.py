@@ -20,6 +20,7 @@ LIB_PATH = PKG / "libcutoff_dkf.so"
 
 DKF_OK, DKF_WARMUP, CUTOFF_NO_ELIGIBLE = 0, 1, 2
 DKF_EINVAL, DKF_ENOTREADY, DKF_EBADOBS, DKF_EHIP, DKF_ENOMEM, DKF_EBLOB, DKF_EUNSUPPORTED = -1, -2, -3, -4, -5, -6, -7
+DKF_ESTALLED = -8
 DKF_DTYPE_F32, DKF_DTYPE_BF16 = 0, 1
 DKF_NUM_STAGES = 9
 STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_scale_hidden",
@@ -28,7 +29,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
     "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
-    "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
+    "dkf_check", "dkf_set_exchange_spin_limit", "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
 
@@ -83,6 +84,8 @@ def _lib():
     lib.cutoff_select_static_max_workspace.restype = sz
     lib.cutoff_select_static_max_workspace.argtypes = []
     lib.dkf_decide.argtypes = [vp, vp, i32, vp, vp, vp, u64, C.POINTER(i32), vp]
+    lib.dkf_check.argtypes = [vp, vp]
+    lib.dkf_set_exchange_spin_limit.argtypes = [vp, i32]
     lib.dkf_decide_samples.restype = vp
     lib.dkf_decide_samples.argtypes = [vp]
     lib.dkf_impute_censored.argtypes = [vp, i32, i32, vp, vp, f32, vp, vp, vp, vp, sz, vp]
@@ -233,6 +236,16 @@ def dkf_decide(model: int, x_obs: np.ndarray, S: int, eps_q, eps_z, eps_x, seed:
         _dev(eps_x, f, name="eps_x"), int(seed), C.byref(c),
         _stream_ptr(stream) if stream is not None else None))
     return int(c.value), rc
+
+
+def dkf_check(model: int, stream=None) -> int:
+    """DKF_OK, or DKF_ESTALLED (returned, not raised) if the last filter step gave up."""
+    rc = _lib().dkf_check(model, _stream_ptr(stream))
+    return rc if rc == DKF_ESTALLED else _check("dkf_check", rc)
+
+
+def dkf_set_exchange_spin_limit(model: int, polls: int) -> None:
+    _check("dkf_set_exchange_spin_limit", _lib().dkf_set_exchange_spin_limit(model, polls))
 
 
 def dkf_impute_workspace(S: int, N: int) -> int:

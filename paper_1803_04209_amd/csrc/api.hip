@@ -88,6 +88,8 @@ struct dkf_model {
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
     float *proj_f = nullptr, *proj_b = nullptr, *ctx_f = nullptr, *ctx_b = nullptr;
+    int32_t *fault = nullptr;   // dev: raised by the multi-workgroup encoder when its bounded wait ran out
+    int spin_limit = kCoopSpinLimit;
     std::vector<float> window;  // host mirror, ring [L][N]
     int64_t pushes = 0;
     float scale = 0.f;
@@ -116,6 +118,9 @@ struct dkf_model {
     hipGraph_t graph = nullptr;
     hipGraphExec_t graph_exec = nullptr;
     int graph_S = 0;
+    int graph_spin_limit = 0;  // the captured kernels carry the limit of the time of capture
+    hipStream_t graph_stream = nullptr;  // stream of the last launch of graph_exec
+    bool graph_launched = false;
     const float *graph_eps[3] = {nullptr, nullptr, nullptr};
 
     size_t in_floats() const { return (size_t)Np + sizeof(Control) / sizeof(float); }
@@ -514,6 +519,8 @@ FilterArgs filter_args(const dkf_model *m, const float *input) {
     a.w_hh_f = m->w_hh_f; a.w_hh_b = m->w_hh_b;
     a.bias_f = m->bias_f; a.bias_b = m->bias_b;
     a.N = m->N; a.Np = m->Np; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
+    a.fault = m->fault;
+    a.spin_limit = m->spin_limit;
     a.encode = true;
     return a;
 }
@@ -680,7 +687,11 @@ int copy_ctx(dkf_model *m, float *dst, hipStream_t stream) {
     return DKF_OK;
 }
 
+// The previous launch may still count as in flight for the runtime (a decision returns as soon as
+// its ticket lands in host memory): wait for the stream it ran on before destroying the executable.
 void drop_graph(dkf_model *m) {
+    if (m->graph_exec && m->graph_launched) (void)hipStreamSynchronize(m->graph_stream);
+    m->graph_launched = false;
     if (m->graph_exec) { (void)hipGraphExecDestroy(m->graph_exec); m->graph_exec = nullptr; }
     if (m->graph) { (void)hipGraphDestroy(m->graph); m->graph = nullptr; }
     m->graph_S = 0;
@@ -703,6 +714,7 @@ const char *dkf_strerror(int code) {
         case DKF_ENOMEM: return "out of memory";
         case DKF_EBLOB: return "weight blob does not match the configuration";
         case DKF_EUNSUPPORTED: return "size or mode not supported";
+        case DKF_ESTALLED: return "filter state exchange gave up: no valid encoding";
         default: return "unknown code";
     }
 }
@@ -810,6 +822,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     DKF_CHECK(dev_alloc(m, m->cutoff_ws_bytes, &q, true)); m->cutoff_ws = q;
     DKF_CHECK(dev_alloc(m, 2 * sizeof(int32_t), &q, true)); m->d_cstar = static_cast<int32_t *>(q);
     DKF_CHECK(dev_alloc(m, 4096, &q, true)); m->sink = static_cast<float *>(q);
+    DKF_CHECK(dev_alloc(m, 256, &q, true)); m->fault = static_cast<int32_t *>(q);
     DKF_CHECK(dev_alloc(m, (size_t)L * Smax * Z * 4, &q, false)); m->gen_q = static_cast<float *>(q);
     DKF_CHECK(dev_alloc(m, (size_t)Smax * Z * 4, &q, false)); m->gen_z = static_cast<float *>(q);
     DKF_CHECK(dev_alloc(m, (size_t)Smax * N * 4, &q, false)); m->gen_x = static_cast<float *>(q);
@@ -920,7 +933,7 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         return DKF_WARMUP;
     }
     const bool reuse = m->graph_exec && m->graph_S == S && m->graph_eps[0] == eps_q && m->graph_eps[1] == eps_z &&
-                       m->graph_eps[2] == eps_x;
+                       m->graph_eps[2] == eps_x && m->graph_spin_limit == m->spin_limit;
     if (!reuse) {
         drop_graph(m);
         DKF_HIP_TRY(hipStreamSynchronize(stream));
@@ -936,7 +949,8 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
                            : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
         if (rc == DKF_OK)
             rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
-                                      m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream, &m->ctl_dev()->ticket);
+                                      m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream, &m->ctl_dev()->ticket,
+                                      m->fault);
         g_capturing--;
         hipGraph_t graph = nullptr;
         e = hipStreamEndCapture(stream, &graph);
@@ -945,9 +959,12 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         m->graph = graph;
         DKF_HIP_TRY(hipGraphInstantiate(&m->graph_exec, m->graph, nullptr, nullptr, 0));
         m->graph_S = S;
+        m->graph_spin_limit = m->spin_limit;
         m->graph_eps[0] = eps_q; m->graph_eps[1] = eps_z; m->graph_eps[2] = eps_x;
     }
     DKF_HIP_TRY(hipGraphLaunch(m->graph_exec, stream));
+    m->graph_stream = stream;
+    m->graph_launched = true;
     // The last kernel stores {c*, status} and then this decision's ticket into pinned host memory.
     // Watching for the ticket returns the decision a few microseconds before the runtime's own
     // completion path would; the stream is synchronised as well if the ticket does not show up.
@@ -962,6 +979,20 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
     if (box[2] != ticket) return DKF_EHIP;
     *cstar_host = box[0];
     return box[1];
+}
+
+int dkf_check(dkf_model *m, void *stream_) {
+    if (!m) return DKF_EINVAL;
+    DKF_HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream_)));
+    int32_t f = 0;
+    DKF_HIP_TRY(hipMemcpy(&f, m->fault, sizeof f, hipMemcpyDeviceToHost));
+    return f != 0 ? DKF_ESTALLED : DKF_OK;
+}
+
+int dkf_set_exchange_spin_limit(dkf_model *m, int32_t polls) {
+    if (!m || polls < 0) return DKF_EINVAL;
+    m->spin_limit = polls;
+    return DKF_OK;
 }
 
 const float *dkf_decide_samples(const dkf_model *m) { return m ? m->samples : nullptr; }

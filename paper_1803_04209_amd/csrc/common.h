@@ -94,10 +94,14 @@ struct FilterArgs {
     const float *w_hh_f, *w_hh_b;      // dev [R][R]
     const float *bias_f, *bias_b;      // dev [R]: b_ih + b_hh
     int N, Np, L, R, Rp;
+    int32_t *fault;   // dev: set to 1 by the multi-workgroup encoder when its bounded wait ran out;
+                      // cleared by the projection kernel that precedes it
+    int spin_limit;   // polls that wait may take per step (0: give up at the first wait)
     bool project;  // (register-resident kernel) compute the new observation's projection in-kernel
     bool mark_empty;  // (projection kernel) fill ctx with the multi-workgroup encoder's "not written yet" value
     bool encode;   // run the recurrences (after the projection) when the window is full
 };
+constexpr int kCoopSpinLimit = 1 << 20;  // default of FilterArgs::spin_limit
 int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream);
 
 // guide.hip
@@ -259,7 +263,8 @@ int launch_fill_normal3(float *out0, size_t n0, float *out1, size_t n1, float *o
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
-                         const int32_t *ticket = nullptr);  // dev: if set, *ticket is stored to out_cstar[2] after c*
+                         const int32_t *ticket = nullptr,  // dev: if set, *ticket is stored to out_cstar[2] after c*
+                         const int32_t *fault = nullptr);  // dev: if set and non-zero, the status becomes DKF_ESTALLED
 size_t cutoff_workspace_bytes(int S, int N);
 // the same with the workspace in a fixed device array of the library (no allocation anywhere)
 int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, int c_max, float t_floor,

@@ -388,7 +388,8 @@ template <int THREADS>
 __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, int S, int c_min, int c_max,
                                                   float t_floor, float *__restrict__ out_mean,
                                                   float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
-                                                  double *best_v, int *best_c, const int32_t *ticket) {
+                                                  double *best_v, int *best_c, const int32_t *ticket,
+                                                  const int32_t *fault) {
     double bv = -INFINITY;
     int bc = 0;
     for (int c = threadIdx.x + 1; c <= N; c += THREADS) {
@@ -418,8 +419,11 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
     }
     if (threadIdx.x == 0) {
         const bool none = best_c[0] == 0;
-        out_cstar[0] = none ? c_max : best_c[0];
-        out_cstar[1] = none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
+        // an earlier kernel of the same decision gave up (the filter's state exchange): the samples
+        // behind this c* are not a prediction
+        const bool stalled = fault && __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        out_cstar[0] = none || stalled ? c_max : best_c[0];
+        out_cstar[1] = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
         if (ticket) {  // a host polling out_cstar[2] (pinned memory) must see the decision first
             __threadfence_system();
             __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -433,11 +437,11 @@ __global__ __launch_bounds__(kArgmaxThreads) void omega_argmax(const double *__r
                                                                float *__restrict__ out_mean,
                                                                float *__restrict__ out_omega,
                                                                int32_t *__restrict__ out_cstar,
-                                                               const int32_t *ticket) {
+                                                               const int32_t *ticket, const int32_t *fault) {
     __shared__ double best_v[kArgmaxThreads];
     __shared__ int best_c[kArgmaxThreads];
     omega_argmax_body<kArgmaxThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                      best_c, ticket);
+                                      best_c, ticket, fault);
 }
 
 // Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
@@ -455,7 +459,7 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
                                                                    float t_floor, float *__restrict__ out_mean,
                                                                    float *__restrict__ out_omega,
                                                                    int32_t *__restrict__ out_cstar,
-                                                                   const int32_t *ticket) {
+                                                                   const int32_t *ticket, const int32_t *fault) {
     __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N], unused parts are zero
     __shared__ double best_v[kFusedThreads];
     __shared__ int best_c[kFusedThreads];
@@ -488,7 +492,7 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
     }
     __syncthreads();
     omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                     best_c, ticket);
+                                     best_c, ticket, fault);
 }
 
 struct SortPlan {
@@ -539,7 +543,7 @@ size_t cutoff_workspace_bytes(int S, int N) {
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
-                         const int32_t *ticket) {
+                         const int32_t *ticket, const int32_t *fault) {
     if (!samples || !out_cstar || !workspace) return DKF_EINVAL;
     if (S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return DKF_EINVAL;
     if (t_floor != t_floor) return DKF_EINVAL;
@@ -580,14 +584,14 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
         StageTimer timer(kStageArgmax, stream);
         if (N <= kFusedMeansMaxN && p.blocks * N <= kFusedMeansMaxSums) {
             hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
-                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket);
+                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault);
             DKF_HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
                                p.blocks, p.npad, N, part2);
             DKF_HIP_TRY(hipGetLastError());
             hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(kArgmaxThreads), 0, stream, part2, N, S, c_min, c_max, t_floor,
-                               out_mean, out_omega, out_cstar, ticket);
+                               out_mean, out_omega, out_cstar, ticket, fault);
             DKF_HIP_TRY(hipGetLastError());
         }
     }
@@ -638,7 +642,7 @@ int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, i
     // every word of the scratch the kernels read has been written earlier in the same call, so
     // nothing is cleared; what the previous call left behind is never looked at
     return launch_cutoff_select(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean, out_omega,
-                                out_cstar, ws, kStaticScratchBytes, stream, nullptr);
+                                out_cstar, ws, kStaticScratchBytes, stream, nullptr, nullptr);
 }
 
 }  // namespace dkf

@@ -53,6 +53,8 @@ __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a
         const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
         for (int i = threadIdx.x; i < n; i += kProjThreads) a.mirror[i] = a.input[i];
     }
+    if (a.mark_empty && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        __hip_atomic_store(a.fault, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // this step has not failed yet
     if (a.mark_empty) {  // the multi-workgroup encoder that follows polls ctx for values >= 0
         const int total = a.L * a.R;
         float *__restrict__ c = dir ? a.ctx_b : a.ctx_f;
@@ -429,12 +431,13 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a
 // the matrix from L2 per step.  The data is its own flag: a ReLU output is never negative, the
 // projection kernel that precedes this one fills ctx with kCoopEmpty, and thread k polls element
 // k of the step's row until it has been written (one memory round trip per step, no counters).
-// The wait is bounded: if a value does not arrive within kCoopSpinLimit polls (it always does
-// unless the device is shared with a kernel that never ends) the encodings this workgroup owns
-// are set to NaN, which surfaces as "no eligible cutoff", and every wave still exits.
+// The wait is bounded: if a value does not arrive within spin_limit polls (kCoopSpinLimit unless
+// the host lowered it; it always arrives unless the device is shared with a kernel that never
+// ends) the workgroup raises the step's fault word and sets the encodings it owns to NaN with
+// device-scope stores (a NaN also ends the wait of every workgroup polling them), and every wave
+// still exits.  The decision's last kernel turns a raised fault word into DKF_ESTALLED.
 constexpr int kCoopRows = 64;
 constexpr int kCoopTpr = kChainThreads / kCoopRows;  // 16 lanes per row = one DPP row
-constexpr int kCoopSpinLimit = 1 << 20;
 
 template <int KPT>
 __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a) {
@@ -524,20 +527,25 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
             const float *src = ctx + (size_t)t * Rp + tid;
             float v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             int polls = 0;
-            while (v < 0.f) {
-                if (++polls > kCoopSpinLimit) { bail = 1; v = 0.f; break; }
+            bool gave_up = a.spin_limit <= 0;  // a limit of zero counts as a wait that ran out
+            while (!gave_up && v < 0.f) {
+                if (++polls > a.spin_limit) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(1);
                 v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            if (gave_up) { bail = 1; v = 0.f; }
             h[((step + 1) & 1) * HBUF + my_slot] = v;
         }
         __syncthreads();
         if (bail) break;
     }
-    if (bail) {  // bounded wait ran out: poison what this workgroup owns so that the failure is visible
+    if (bail) {  // bounded wait ran out: report it, and poison what this workgroup owns
+        if (tid == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int i = tid; i < L * kCoopRows; i += kChainThreads) {
             const int r = blockIdx.x * kCoopRows + i % kCoopRows;
-            if (r < R) ctx[(size_t)(i / kCoopRows) * Rp + r] = __builtin_nanf("");
+            if (r < R)
+                __hip_atomic_store(ctx + (size_t)(i / kCoopRows) * Rp + r, __builtin_nanf(""), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

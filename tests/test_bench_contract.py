@@ -26,3 +26,14 @@ def test_stage_work_matches_the_layer_sizes():
     assert [w[s][1] for s in (2, 3, 4, 5)] == [2.0 * S * Z * H, 2.0 * S * H * N, 2.0 * S * N * H, 2.0 * S * H * N]
     assert w[8][1] == sum(w[s][1] for s in range(1, 6))
     assert w[6] == ("hbm", 4.0 * S * N)
+
+
+def test_sort_compare_exchange_counts():
+    sys.path.insert(0, str(ROOT))
+    import bench
+
+    # a bitonic network over n = 2^p keys has p (p + 1) / 2 stages of n / 2 compare-exchanges
+    assert bench.sort_compare_exchanges(1, 8) == 4 * 6
+    assert bench.sort_compare_exchanges(16384, 512) == 16384 * 256 * 45
+    assert bench.sort_compare_exchanges(8192, 2048) == 8192 * 1024 * 66
+    assert bench.sort_compare_exchanges(3, 158) == 3 * 128 * 36  # padded to 256 keys
