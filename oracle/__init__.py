@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     make_noise,
     philox4x32_10,
     rank_spread,
+    round_bf16,
     num_threads,
     set_threads,
     trace_throughput,

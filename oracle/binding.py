@@ -54,6 +54,9 @@ def _load():
     lib.oracle_filter_step.argtypes = [C.c_void_p, dp]
     lib.oracle_encode_window.argtypes = [C.c_void_p, dp, dp]
     lib.oracle_sample_runtimes.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp]
+    lib.oracle_set_mlp_bf16.argtypes = [C.c_void_p, C.c_int]
+    lib.oracle_round_bf16.restype = C.c_double
+    lib.oracle_round_bf16.argtypes = [C.c_double]
     lib.oracle_transition_terms.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp, dp, dp]
     lib.oracle_cutoff_select.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_cutoff_select_f32.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
@@ -71,6 +74,11 @@ def _load():
     lib.oracle_set_threads.argtypes = [C.c_int]
     _lib = lib
     return lib
+
+
+def round_bf16(v: float) -> float:
+    """Round to nearest-even bfloat16 (8 significant bits), returned as a double."""
+    return float(_load().oracle_round_bf16(float(v)))
 
 
 def num_threads() -> int:
@@ -123,7 +131,8 @@ def _f32(a):
 class OracleModel:
     """Weights + fixed-lag window of one predictor, on the CPU, in float64."""
 
-    def __init__(self, cfg, blob: np.ndarray, emit_mean_act: int = 0):
+    def __init__(self, cfg, blob: np.ndarray, emit_mean_act: int = 0, mlp_bf16: bool = False):
+        """mlp_bf16: the sampler's mixed-precision mode (MLP matrices and their inputs rounded to bf16)."""
         lib = _load()
         self.cfg = cfg
         self._c = _Config(cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim, int(emit_mean_act))
@@ -131,6 +140,12 @@ class OracleModel:
         self._h = lib.oracle_load_weights(C.byref(self._c), raw.ctypes.data, raw.size)
         if not self._h:
             raise ValueError("oracle_load_weights rejected the configuration or blob")
+        if mlp_bf16:
+            self.set_mlp_bf16(True)
+
+    def set_mlp_bf16(self, on: bool) -> None:
+        if _load().oracle_set_mlp_bf16(self._h, int(bool(on))) < 0:
+            raise MemoryError("oracle_set_mlp_bf16")
 
     def close(self):
         if getattr(self, "_h", None):

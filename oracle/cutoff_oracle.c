@@ -58,6 +58,10 @@ typedef struct {
     double *emean1_w, *emean1_b, *emean2_w, *emean2_b;
     double *escale1_w, *escale1_b, *escale2_w, *escale2_b;
     double *store;
+    /* mixed-precision mode (MLP matrices and MLP inputs rounded to bf16, everything else as before):
+     * the same tensors as `store`, every value rounded; see oracle_set_mlp_bf16 */
+    double *store_bf16;
+    int mlp_bf16;
     /* fixed-lag window of raw observations, oldest first */
     double *window; /* [L][N] */
     int32_t count;  /* observations pushed so far (saturates at INT32_MAX) */
@@ -94,6 +98,7 @@ void oracle_set_threads(int n) {
 void oracle_free(oracle_model *m) {
     if (!m) return;
     free(m->store);
+    free(m->store_bf16);
     free(m->window);
     free(m);
 }
@@ -147,6 +152,38 @@ void oracle_reset(oracle_model *m) {
 
 double oracle_scale(const oracle_model *m) { return m->scale; }
 
+/* ---- mixed precision: "MLPs in bf16 with fp32 accumulation" -------------------------------
+ * bfloat16 keeps 8 significant bits (1 implicit + 7 stored) and the exponent range of fp32.
+ * Round to nearest, ties to even, written from that definition (the default floating-point
+ * rounding mode is to-nearest-even, which is what nearbyint applies).  Zero, infinities and NaN
+ * pass through; the exponent range is not clamped (no value here comes near its ends). */
+double oracle_round_bf16(double v) {
+    if (v == 0.0 || !isfinite(v)) return v;
+    int e;
+    double f = frexp(v, &e);                       /* v = f 2^e, 0.5 <= |f| < 1 */
+    return ldexp(nearbyint(ldexp(f, 8)), e - 8);   /* 8 significant bits */
+}
+
+/* Switch the mixed-precision mode of the sampler on or off (off after loading).
+ * READING of "MLPs in bf16 with fp32 accumulation": every MLP matrix (guide: combiner, mean,
+ * scale; transition; emission) and every vector that is multiplied by one is rounded to bf16;
+ * sums, biases, nonlinearities, the noise mix and all outputs are not rounded (here: double, the
+ * kernel: fp32); the RNN encoders are not MLPs and stay in full precision.  In the guide's mean,
+ * K(h_out) with h_out = (tanh(.) + h_left + h_right)/3 is linear, so the encodings' share
+ * W (h_left + h_right)/3 + b is the same for every sample: it is formed once per window position
+ * in full precision with the unrounded matrix, and only the per-sample term W tanh(.)/3 is a
+ * product of rounded operands. */
+int oracle_set_mlp_bf16(oracle_model *m, int on) {
+    if (on && !m->store_bf16) {
+        size_t nf = blob_floats(&m->cfg);
+        m->store_bf16 = (double *)malloc(nf * sizeof(double));
+        if (!m->store_bf16) return ORACLE_EINVAL;
+        for (size_t i = 0; i < nf; ++i) m->store_bf16[i] = oracle_round_bf16(m->store[i]);
+    }
+    m->mlp_bf16 = on ? 1 : 0;
+    return ORACLE_OK;
+}
+
 /* ---- elementary functions ------------------------------------------------ */
 
 static double relu(double v) { return v > 0.0 ? v : 0.0; }
@@ -164,6 +201,20 @@ static void affine(const double *W, const double *b, const double *x, int n_in, 
         for (int i = 0; i < n_in; ++i) acc += W[(size_t)o * n_in + i] * x[i];
         y[o] = acc;
     }
+}
+
+/* One MLP layer y = W x + b in the model's precision mode: full precision, or (mixed precision) the
+ * matrix and the input vector rounded to bf16, the sum and the bias not.  W must point into
+ * m->store; xq is scratch for the rounded input (at least n_in doubles). */
+static void mlp_layer(const oracle_model *m, const double *W, const double *b, const double *x, int n_in,
+                      int n_out, double *y, double *xq) {
+    if (!m->mlp_bf16) {
+        affine(W, b, x, n_in, n_out, y);
+        return;
+    }
+    const double *Wq = m->store_bf16 + (W - m->store);
+    for (int i = 0; i < n_in; ++i) xq[i] = oracle_round_bf16(x[i]);
+    affine(Wq, b, xq, n_in, n_out, y);
 }
 
 /* ---- fixed-lag window and normaliser (Sec. 3.1.2; end of Sec. 3.1.3) ------ */
@@ -219,7 +270,7 @@ int oracle_encode_window(const oracle_model *m, double *hl, double *hr) {
 
 /* ---- one Monte-Carlo sample (Sec. 3.1.3, posterior-predictive approximation) */
 
-typedef struct { double *r1, *r2, *z, *mu, *pre, *zn, *g, *h, *lin, *G, *hid, *mean, *sd; } scratch;
+typedef struct { double *r1, *r2, *z, *mu, *pre, *zn, *g, *h, *lin, *G, *hid, *mean, *sd, *xq; } scratch;
 
 static scratch scratch_new(const oracle_config *c) {
     scratch s;
@@ -238,12 +289,15 @@ static scratch scratch_new(const oracle_config *c) {
     s.G = (double *)malloc(sizeof(double) * Z);
     s.mean = (double *)malloc(sizeof(double) * N);
     s.sd = (double *)malloc(sizeof(double) * N);
+    int widest = big > N ? big : N;
+    if (Z > widest) widest = Z;
+    s.xq = (double *)malloc(sizeof(double) * widest);
     return s;
 }
 
 static void scratch_free(scratch *s) {
     free(s->r1); free(s->r2); free(s->hid); free(s->z); free(s->mu); free(s->pre); free(s->zn);
-    free(s->g); free(s->h); free(s->lin); free(s->G); free(s->mean); free(s->sd);
+    free(s->g); free(s->h); free(s->lin); free(s->G); free(s->mean); free(s->sd); free(s->xq);
 }
 
 /* Optional taps on the inside of the gated transition of one sample (any may be NULL). */
@@ -266,11 +320,25 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
      * READING: the latent before the window is a learned vector z0. */
     for (int i = 0; i < Z; ++i) w->z[i] = m->z0[i];
     for (int t = 0; t < L; ++t) {
-        affine(m->comb_w, m->comb_b, w->z, Z, R, w->r1);
-        for (int r = 0; r < R; ++r)
-            w->r2[r] = (tanh(w->r1[r]) + hl[(size_t)t * R + r] + hr[(size_t)t * R + r]) / 3.0; /* h_out */
-        affine(m->mu_w, m->mu_b, w->r2, R, Z, w->mu);                                         /* mu_q = K(h_out) */
-        affine(m->sig_w, m->sig_b, w->mu, Z, Z, w->pre);                                      /* sigma_q = L(mu_q) */
+        mlp_layer(m, m->comb_w, m->comb_b, w->z, Z, R, w->r1, w->xq);
+        if (!m->mlp_bf16) {
+            for (int r = 0; r < R; ++r)
+                w->r2[r] = (tanh(w->r1[r]) + hl[(size_t)t * R + r] + hr[(size_t)t * R + r]) / 3.0; /* h_out */
+            affine(m->mu_w, m->mu_b, w->r2, R, Z, w->mu);                                     /* mu_q = K(h_out) */
+        } else {
+            /* the same K(h_out), split as oracle_set_mlp_bf16 describes */
+            const double *Wq = m->store_bf16 + (m->mu_w - m->store);
+            for (int r = 0; r < R; ++r) w->xq[r] = oracle_round_bf16(tanh(w->r1[r]));
+            for (int i = 0; i < Z; ++i) {
+                double per_sample = 0.0, context = 0.0;
+                for (int r = 0; r < R; ++r) {
+                    per_sample += Wq[(size_t)i * R + r] * w->xq[r];
+                    context += m->mu_w[(size_t)i * R + r] * (hl[(size_t)t * R + r] + hr[(size_t)t * R + r]);
+                }
+                w->mu[i] = per_sample / 3.0 + (context / 3.0 + m->mu_b[i]);
+            }
+        }
+        mlp_layer(m, m->sig_w, m->sig_b, w->mu, Z, Z, w->pre, w->xq);                         /* sigma_q = L(mu_q) */
         for (int i = 0; i < Z; ++i) {
             double sigma = softplus(w->pre[i]);
             /* READING: the second argument of N(.,.) is a standard deviation */
@@ -279,19 +347,19 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
     }
     if (zT_out) memcpy(zT_out, w->z, sizeof(double) * Z);
     /* Gated transition z_{T+1} ~ N(G(z_T), H(z_T)) */
-    affine(m->gate1_w, m->gate1_b, w->z, Z, H, w->hid);
+    mlp_layer(m, m->gate1_w, m->gate1_b, w->z, Z, H, w->hid, w->xq);
     if (tap && tap->gate_hidden) memcpy(tap->gate_hidden, w->hid, sizeof(double) * H);
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
-    affine(m->gate2_w, m->gate2_b, w->hid, H, Z, w->g);
+    mlp_layer(m, m->gate2_w, m->gate2_b, w->hid, H, Z, w->g, w->xq);
     if (tap && tap->gate_pre) memcpy(tap->gate_pre, w->g, sizeof(double) * Z);
     for (int i = 0; i < Z; ++i) w->g[i] = sigmoid(w->g[i]);
-    affine(m->prop1_w, m->prop1_b, w->z, Z, H, w->hid);
+    mlp_layer(m, m->prop1_w, m->prop1_b, w->z, Z, H, w->hid, w->xq);
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
-    affine(m->prop2_w, m->prop2_b, w->hid, H, Z, w->h);
-    affine(m->lin_w, m->lin_b, w->z, Z, Z, w->lin);
+    mlp_layer(m, m->prop2_w, m->prop2_b, w->hid, H, Z, w->h, w->xq);
+    mlp_layer(m, m->lin_w, m->lin_b, w->z, Z, Z, w->lin, w->xq);
     for (int i = 0; i < Z; ++i) w->G[i] = (1.0 - w->g[i]) * w->lin[i] + w->g[i] * w->h[i];
     for (int i = 0; i < Z; ++i) w->mu[i] = relu(w->G[i]);
-    affine(m->tscale_w, m->tscale_b, w->mu, Z, Z, w->pre);
+    mlp_layer(m, m->tscale_w, m->tscale_b, w->mu, Z, Z, w->pre, w->xq);
     for (int i = 0; i < Z; ++i) w->pre[i] = softplus(w->pre[i]);
     for (int i = 0; i < Z; ++i) w->zn[i] = w->G[i] + w->pre[i] * (double)eps_z[(size_t)k * Z + i];
     if (zn_out) memcpy(zn_out, w->zn, sizeof(double) * Z);
@@ -303,13 +371,13 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
         if (tap->Hs) memcpy(tap->Hs, w->pre, sizeof(double) * Z);
     }
     /* Emission x_{T+1} ~ N(I(z_{T+1}), J(z_{T+1})), J fed by I's output */
-    affine(m->emean1_w, m->emean1_b, w->zn, Z, H, w->hid);
+    mlp_layer(m, m->emean1_w, m->emean1_b, w->zn, Z, H, w->hid, w->xq);
     if (m->cfg.emit_mean_act == 1)
         for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
-    affine(m->emean2_w, m->emean2_b, w->hid, H, N, w->mean);
-    affine(m->escale1_w, m->escale1_b, w->mean, N, H, w->hid);
+    mlp_layer(m, m->emean2_w, m->emean2_b, w->hid, H, N, w->mean, w->xq);
+    mlp_layer(m, m->escale1_w, m->escale1_b, w->mean, N, H, w->hid, w->xq);
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
-    affine(m->escale2_w, m->escale2_b, w->hid, H, N, w->sd);
+    mlp_layer(m, m->escale2_w, m->escale2_b, w->hid, H, N, w->sd, w->xq);
     for (int j = 0; j < N; ++j) {
         w->sd[j] = softplus(w->sd[j]);
         /* back to seconds: the model lives in units of the normaliser */

@@ -162,6 +162,32 @@ def test_bf16_every_stage(api, cfg, act, sampler):
     g.close()
 
 
+@pytest.mark.parametrize("cfg", [
+    custom(N=128, L=10, Z=16, H=128, R=128, S=300), custom(N=64, L=4, Z=20, H=200, R=250, S=100),
+    custom(N=40, L=3, Z=64, H=300, R=512, S=41), custom(N=2175, L=2, Z=16, H=128, R=128, S=5603)],
+    ids=["medium-like", "quarter-256", "quarter-512", "2175"])
+@pytest.mark.parametrize("act", [0, 1])
+def test_bf16_matches_the_mixed_precision_oracle(api, cfg, act):
+    """Against the oracle's own mixed-precision mode (matrices and their inputs rounded to bf16 at
+    the same points, sums in fp64) the register-resident bf16 kernels must stay within half the
+    bf16 tolerance in the max norm (measured: 1e-3 .. 8e-3).  What is left is fp32 against fp64
+    summation and the hardware's exp2/log2: differences of 1e-7 that now and then move a value
+    across a bf16 rounding boundary, after which the two sides differ by a whole bf16 step there."""
+    std = 0.06 if cfg.rnn_dim >= 512 else 0.1
+    w = synth.make_weights(cfg, std)
+    blob = synth.pack_blob(cfg, w)
+    g = api.Predictor(cfg, blob, emit_mean_act=act, mlp_dtype=api.DKF_DTYPE_BF16)
+    o = oracle.OracleModel(cfg, blob, emit_mean_act=act, mlp_bf16=True)
+    tr = synth.make_trace(cfg)
+    for t in range(cfg.lag):
+        g.filter_step(tr[t])
+        o.filter_step(tr[t])
+    rows = None if cfg.samples <= 512 else np.arange(0, cfg.samples, 37, dtype=np.int32)
+    _, errs = compare_stages(api, cfg, g, o, rows=rows, tol=TOL_BF16 / 2)
+    print("bf16 kernel vs mixed-precision oracle", {k: f"{v:.1e}" for k, v in errs.items()})
+    g.close()
+
+
 def test_bf16_2175_workers_ragged_wide_tiles(api):
     """The paper's larger cluster size (2175 workers: not a multiple of anything), enough samples for
     the N-wide emission layers to take their 256-feature tiling, ragged last sample tile."""
@@ -198,28 +224,59 @@ def test_large_bf16_preset_damped_weights_sampled_rows(api):
     g.close()
 
 
+QUANTILES = (0.5, 0.9, 0.99, 0.999, 0.9999)
+
+
 def test_large_bf16_preset_raw_weights(api):
-    """The preset as specified (every tensor N(0, 0.1^2)).  With R = 512 the ReLU recurrences grow
-    about 2.6x in variance per step, activations reach 1e5..1e7 and the gate's sigmoid acts as a
-    hard switch: bf16 rounding flips a few percent of those switches, and a flipped element is off
-    by O(1).  So the guide output is held to 2e-2 in the max norm, the stages after the gate to a
-    small median error and a bounded share of flipped elements."""
+    """The preset as specified (every tensor N(0, 0.1^2)) is ill-conditioned: with R = 512 the ReLU
+    recurrences grow about 2.6x in variance per step, activations reach 1e5..1e7, the gate's sigmoid
+    is a hard switch and every layer amplifies what the one before it rounded away.  The mixed
+    precision the preset prescribes is then itself a few 1e-2 away from exact arithmetic, whoever
+    implements it.  What is held here:
+      * the guide's output z_T meets 2e-2 in the max norm against the fp64 oracle;
+      * after the gate, the kernel's error against the fp64 oracle is distributed like the error of
+        the oracle's own mixed-precision mode (same rounding points, fp64 sums) against fp64:
+        every quantile up to 99.99 % and the share of elements beyond 2e-2 stay within a factor
+        1.15 (+1e-4) of the oracle's own, per tensor (measured: within 3 %);
+      * the same weights at the same size with fp32 MLPs meet 1e-4 in the max norm
+        (test_large_preset_raw_weights_fp32), so nothing but the prescribed rounding is at work."""
     cfg = synth.CONFIGS["large_bf16"]
     g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 1)
-    rows = np.sort(np.random.default_rng(5).choice(cfg.samples, 64, replace=False)).astype(np.int32)
+    ob = oracle.OracleModel(cfg, synth.make_blob(cfg), mlp_bf16=True)
+    for t in range(cfg.lag + 1):
+        ob.filter_step(tr[t])
+    rows = np.arange(0, cfg.samples, 8, dtype=np.int32)
     eq, ez, ex = synth.make_noise(cfg)
     x, st = g.sample_runtimes(*cuda(eq, ez, ex), stages=True)
     xo, so = o.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
+    xb, sb = ob.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
     assert rel_err(st["z_T"].cpu().numpy()[rows], so["z_T"]) <= TOL_BF16
-    so["x"], st["x"] = xo, x
+    assert rel_err(sb["z_T"], so["z_T"]) <= TOL_BF16
+    so["x"], st["x"], sb["x"] = xo, x, xb
     for k in ("z_next", "emit_mean", "emit_sd", "x"):
-        r = elementwise_rel(st[k].cpu().numpy()[rows], so[k])
-        print(f"large_bf16 raw {k}: median {np.median(r):.1e}, share above 2e-2 {np.mean(r > TOL_BF16):.3f}")
-        assert np.median(r) <= 5e-3 and np.mean(r > TOL_BF16) <= 0.12
+        e_gpu = elementwise_rel(st[k].cpu().numpy()[rows], so[k]).ravel()
+        e_ref = elementwise_rel(sb[k], so[k]).ravel()
+        qg, qr = np.quantile(e_gpu, QUANTILES), np.quantile(e_ref, QUANTILES)
+        share_g, share_r = np.mean(e_gpu > TOL_BF16), np.mean(e_ref > TOL_BF16)
+        print(f"large_bf16 raw {k}: quantiles kernel {np.array2string(qg, precision=4)} mixed-precision oracle "
+              f"{np.array2string(qr, precision=4)}; share beyond 2e-2: {share_g:.4f} vs {share_r:.4f}")
+        assert np.all(qg <= 1.15 * qr + 1e-4), (k, qg, qr)
+        assert share_g <= 1.15 * share_r + 1e-4, (k, share_g, share_r)
     assert torch_isfinite(x)
     res = api.select_cutoff(x)
     ref = oracle.cutoff_select(x.cpu().numpy(), want_sorted=False, want_perm=False)
     assert res["status"] == ref["status"] and cstar_in_tie_band(res["cstar"], ref)
+    g.close()
+
+
+def test_large_preset_raw_weights_fp32(api):
+    """The large preset's sizes and raw weights with fp32 MLPs: every stage within 1e-4 of the
+    fp64 oracle in the max norm, on 1024 sampled rows of the full-size launch."""
+    cfg = synth.CONFIGS["large_bf16"]
+    g, o, _ = make_pair(api, cfg, pushes=cfg.lag + 1, mlp_dtype=api.DKF_DTYPE_F32)
+    rows = np.arange(0, cfg.samples, 8, dtype=np.int32)
+    _, errs = compare_stages(api, cfg, g, o, rows=rows, tol=TOL)
+    print("large preset, fp32 MLPs, raw weights:", {k: f"{v:.1e}" for k, v in errs.items()})
     g.close()
 
 

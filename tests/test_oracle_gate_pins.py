@@ -260,24 +260,26 @@ def test_steep_gate_switches_between_linear_and_proposed_mean():
 
 MUTATIONS = {
     "gate ReLU dropped":
-        ("    for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);\n    affine(m->gate2_w,",
-         "    affine(m->gate2_w,"),
+        ("    for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);\n    mlp_layer(m, m->gate2_w,",
+         "    mlp_layer(m, m->gate2_w,"),
     "sigmoid replaced by (1 + tanh)/2":
         ("for (int i = 0; i < Z; ++i) w->g[i] = sigmoid(w->g[i]);",
          "for (int i = 0; i < Z; ++i) w->g[i] = 0.5 * (1.0 + tanh(w->g[i]));"),
     "gate fed the proposed mean's first layer":
-        ("affine(m->gate1_w, m->gate1_b, w->z, Z, H, w->hid);", "affine(m->prop1_w, m->gate1_b, w->z, Z, H, w->hid);"),
+        ("mlp_layer(m, m->gate1_w, m->gate1_b, w->z, Z, H, w->hid, w->xq);",
+         "mlp_layer(m, m->prop1_w, m->gate1_b, w->z, Z, H, w->hid, w->xq);"),
     "gate and (1 - gate) swapped":
         ("(1.0 - w->g[i]) * w->lin[i] + w->g[i] * w->h[i]", "w->g[i] * w->lin[i] + (1.0 - w->g[i]) * w->h[i]"),
     "combiner ignores the previous latent":
-        ("affine(m->comb_w, m->comb_b, w->z, Z, R, w->r1);", "affine(m->comb_w, m->comb_b, m->z0, Z, R, w->r1);"),
+        ("mlp_layer(m, m->comb_w, m->comb_b, w->z, Z, R, w->r1, w->xq);",
+         "mlp_layer(m, m->comb_w, m->comb_b, m->z0, Z, R, w->r1, w->xq);"),
     "combiner divided by two":
         ("hr[(size_t)t * R + r]) / 3.0;", "hr[(size_t)t * R + r]) / 2.0;"),
     "transition scale fed G instead of ReLU(G)":
         ("for (int i = 0; i < Z; ++i) w->mu[i] = relu(w->G[i]);", "for (int i = 0; i < Z; ++i) w->mu[i] = w->G[i];"),
     "emission scale fed z instead of the mean":
-        ("affine(m->escale1_w, m->escale1_b, w->mean, N, H, w->hid);",
-         "affine(m->escale1_w, m->escale1_b, w->zn, N, H, w->hid);"),
+        ("mlp_layer(m, m->escale1_w, m->escale1_b, w->mean, N, H, w->hid, w->xq);",
+         "mlp_layer(m, m->escale1_w, m->escale1_b, w->zn, N, H, w->hid, w->xq);"),
 }
 
 

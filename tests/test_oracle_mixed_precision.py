@@ -1,0 +1,171 @@
+"""Pins for the oracle's mixed-precision mode ("MLPs in bf16 with fp32 accumulation") -- CPU only.
+
+The mode rounds every MLP matrix and every vector multiplied by one to bfloat16 and nothing else.
+Pinned by: the rounding itself against the library's bfloat16 conversion and against hand-picked
+ties; cases whose operands are exactly representable (the hand-worked cases of the gate pins must
+come out the same in either mode); single layers against the library's bfloat16 tensors; which
+quantities are rounded and which are not (biases, the encodings' share of the guide's mean, the
+noise mix); and the size of the difference from full precision on a well-conditioned model.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import cluster_synth as synth
+from test_oracle_gate_pins import TRANSITION_EXPECT, combiner_case, model, transition_case
+
+
+def bf16(a):
+    """The library's rounding: float32 -> bfloat16 (nearest even) -> float64."""
+    return torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def test_rounding_matches_the_library_and_known_ties():
+    r = np.random.default_rng(1)
+    v = np.concatenate([r.standard_normal(20000) * 10.0 ** r.uniform(-20, 20, 20000), [0.0, -0.0, 1.0, -3.5]])
+    v = v.astype(np.float32)
+    got = np.array([oracle.round_bf16(float(x)) for x in v])
+    assert np.array_equal(got, bf16(v))
+    # 8 significant bits: spacing 2^-7 in [1, 2); ties go to the even neighbour
+    assert oracle.round_bf16(1 + 2.0 ** -8) == 1.0                      # tie, 1.0 is even
+    assert oracle.round_bf16(1 + 3 * 2.0 ** -8) == 1 + 2 * 2.0 ** -7    # tie, the odd neighbour 1 + 2^-7 loses
+    assert oracle.round_bf16(1 + 2.0 ** -8 + 2.0 ** -30) == 1 + 2.0 ** -7  # just above a tie (a double, not a float)
+    assert oracle.round_bf16(-257.0) == -256.0 and oracle.round_bf16(259.0) == 260.0
+    assert np.isnan(oracle.round_bf16(float("nan"))) and oracle.round_bf16(float("inf")) == float("inf")
+
+
+def test_exactly_representable_cases_are_unchanged():
+    """Every operand of the hand-worked transition case fits 8 significant bits, so rounding is the
+    identity there and the literal expected values hold in mixed precision too."""
+    cfg, w, window, (eq, ez, ex) = transition_case()
+    m = model(cfg, w, window)
+    m.set_mlp_bf16(True)
+    x, st = m.sample_runtimes(eq, ez, ex, stages=True)
+    got = dict(st, x=x, **m.transition_terms(eq, ez, ex))
+    for k, v in TRANSITION_EXPECT.items():
+        assert np.allclose(got[k][0], v, rtol=2e-6, atol=1e-5), k
+
+
+def test_guide_mean_keeps_the_encodings_share_in_full_precision():
+    """Hand-worked combiner case with a window whose encodings do NOT fit 8 bits: the tanh term is
+    rounded (3/5 -> bf16, -4/5 -> bf16), the encodings' share and the bias are not."""
+    cfg, w, _, (eq, ez, ex) = combiner_case()
+    window = [[3.001, 5.003]]
+    m = model(cfg, w, window)
+    hl, hr = m.encode_window()
+    m.set_mlp_bf16(True)
+    _, st = m.sample_runtimes(eq, ez, ex, stages=True)
+    d = {k: v.astype(np.float64) for k, v in w.items()}
+    tanh_q = bf16(np.tanh(d["comb_w"] @ d["z0"] + d["comb_b"]))  # (0.6, -0.8, 0) to 8 bits
+    assert not np.array_equal(tanh_q, np.tanh(d["comb_w"] @ d["z0"] + d["comb_b"]))
+    mu = d["mu_w"] @ tanh_q / 3 + (d["mu_w"] @ (hl[0] + hr[0]) / 3 + d["mu_b"])
+    sigma = np.logaddexp(0, d["sig_w"] @ bf16(mu) + d["sig_b"])
+    assert np.allclose(st["z_T"][0], mu + sigma * eq[0, 0], rtol=1e-12, atol=1e-12)
+    # rounding h_out as a whole instead would move mu by about 2^-9 of the encodings' share
+    h_out_q = bf16((np.tanh(d["comb_w"] @ d["z0"] + d["comb_b"]) + hl[0] + hr[0]) / 3)
+    assert np.abs(d["mu_w"] @ h_out_q + d["mu_b"] - mu).max() > 1e-3
+
+
+def custom(N=6, L=2, Z=3, H=5, R=7, S=50):
+    return synth.ClusterConfig("custom", 9, N, L, Z, H, R, S, "f32", 50, "iid_stragglers_tiny")
+
+
+def test_emission_layers_round_matrices_and_inputs_only():
+    cfg = custom()
+    w = synth.make_weights(cfg, std=0.6)
+    m = oracle.OracleModel(cfg, synth.pack_blob(cfg, w), mlp_bf16=True)
+    for row in synth.make_trace(cfg)[:cfg.lag]:
+        m.filter_step(row)
+    eq, ez, ex = synth.make_noise(cfg)
+    x, st = m.sample_runtimes(eq, ez, ex, stages=True)
+    d = {k: v.astype(np.float64) for k, v in w.items()}
+    q = {k: bf16(v) for k, v in w.items()}
+    zn = st["z_next"]
+    hid = bf16(zn) @ q["emean1_w"].T + d["emean1_b"]            # bias not rounded
+    mean = bf16(hid) @ q["emean2_w"].T + d["emean2_b"]
+    sd = np.logaddexp(0, bf16(np.maximum(bf16(mean) @ q["escale1_w"].T + d["escale1_b"], 0)) @ q["escale2_w"].T
+                      + d["escale2_b"])
+    assert np.allclose(st["emit_mean"], mean, rtol=1e-12, atol=1e-13)
+    assert np.allclose(st["emit_sd"], sd, rtol=1e-12, atol=1e-13)
+    assert np.allclose(x, m.scale * (mean + sd * ex), rtol=1e-12, atol=1e-13)  # outputs and noise mix not rounded
+    assert not np.allclose(st["emit_mean"], zn @ d["emean1_w"].T @ d["emean2_w"].T + d["emean1_b"] @ d["emean2_w"].T
+                           + d["emean2_b"], rtol=1e-5)
+
+
+def test_transition_layers_round_matrices_and_inputs_only():
+    cfg = custom()
+    w = synth.make_weights(cfg, std=0.6)
+    m = oracle.OracleModel(cfg, synth.pack_blob(cfg, w), mlp_bf16=True)
+    for row in synth.make_trace(cfg)[:cfg.lag]:
+        m.filter_step(row)
+    eq, ez, ex = synth.make_noise(cfg)
+    _, st = m.sample_runtimes(eq, ez, ex, stages=True)
+    t = m.transition_terms(eq, ez, ex)
+    d = {k: v.astype(np.float64) for k, v in w.items()}
+    q = {k: bf16(v) for k, v in w.items()}
+    zq = bf16(st["z_T"])
+    gh = zq @ q["gate1_w"].T + d["gate1_b"]
+    assert np.allclose(t["gate_hidden"], gh, rtol=1e-12, atol=1e-13)
+    assert np.allclose(t["gate_pre"], bf16(np.maximum(gh, 0)) @ q["gate2_w"].T + d["gate2_b"], rtol=1e-12, atol=1e-13)
+    assert np.allclose(t["lin"], zq @ q["lin_w"].T + d["lin_b"], rtol=1e-12, atol=1e-13)
+    assert np.allclose(t["prop"], bf16(np.maximum(zq @ q["prop1_w"].T + d["prop1_b"], 0)) @ q["prop2_w"].T + d["prop2_b"],
+                       rtol=1e-12, atol=1e-13)
+    G = t["G"]
+    assert np.allclose(t["Hs"], np.logaddexp(0, bf16(np.maximum(G, 0)) @ q["tscale_w"].T + d["tscale_b"]),
+                       rtol=1e-12, atol=1e-13)
+    assert np.allclose(st["z_next"], G + t["Hs"] * ez, rtol=1e-12, atol=1e-13)  # G, H and the noise mix not rounded
+
+
+def test_rnn_encoders_are_untouched_and_mode_switches_back():
+    cfg = custom()
+    w = synth.make_weights(cfg, std=0.6)
+    m = oracle.OracleModel(cfg, synth.pack_blob(cfg, w))
+    for row in synth.make_trace(cfg)[:cfg.lag]:
+        m.filter_step(row)
+    eq, ez, ex = synth.make_noise(cfg)
+    enc = m.encode_window()
+    x64 = m.sample_runtimes(eq, ez, ex)
+    m.set_mlp_bf16(True)
+    assert all(np.array_equal(a, b) for a, b in zip(enc, m.encode_window()))
+    x16 = m.sample_runtimes(eq, ez, ex)
+    m.set_mlp_bf16(False)
+    assert np.array_equal(m.sample_runtimes(eq, ez, ex), x64)
+    rel = np.abs(x16 - x64) / np.maximum(np.abs(x64), np.sqrt(np.mean(x64 ** 2)))
+    assert 1e-5 < rel.max() < 2e-2  # different, by about the unit roundoff 2^-9 per layer
+
+
+def mixed_against_full(cfg, std, n_rows):
+    w = synth.make_weights(cfg, std)
+    blob = synth.pack_blob(cfg, w)
+    full, mixed = oracle.OracleModel(cfg, blob), oracle.OracleModel(cfg, blob, mlp_bf16=True)
+    tr = synth.make_trace(cfg)
+    for t in range(cfg.lag + 1):
+        full.filter_step(tr[t])
+        mixed.filter_step(tr[t])
+    eq, ez, ex = synth.make_noise(cfg)
+    rows = np.arange(0, cfg.samples, cfg.samples // n_rows, dtype=np.int32)
+    xf, sf = full.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
+    xm, sm = mixed.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
+    sf["x"], sm["x"] = xf, xm
+    out = {}
+    for k in ("z_T", "z_next", "emit_mean", "emit_sd", "x"):
+        rms = np.sqrt(np.mean(sf[k] ** 2))
+        out[k] = np.abs(sm[k] - sf[k]) / np.maximum(np.abs(sf[k]), rms)
+    return out
+
+
+def test_what_the_prescribed_precision_costs_on_the_large_preset():
+    """The large preset's sizes.  With damped weights (N(0, 0.03^2)) the prescribed mixed precision
+    stays within 2e-2 of exact arithmetic in the max norm; with the weights as specified
+    (N(0, 0.1^2): encodings of 1e5..1e7, a hard-switching gate) the guide's output still does, but
+    after the gate a few percent of the entries are further away than that -- in exact bf16
+    arithmetic with fp64 sums, i.e. for any implementation of the preset."""
+    cfg = synth.CONFIGS["large_bf16"]
+    damped = mixed_against_full(cfg, 0.03, 32)
+    assert all(e.max() <= 2e-2 for e in damped.values()), {k: e.max() for k, e in damped.items()}
+    raw = mixed_against_full(cfg, 0.1, 64)
+    assert raw["z_T"].max() <= 2e-2
+    for k in ("z_next", "emit_mean", "emit_sd", "x"):
+        assert raw[k].max() > 0.2 and 0.002 < np.mean(raw[k] > 2e-2) < 0.1, (k, raw[k].max(), np.mean(raw[k] > 2e-2))
+        assert np.median(raw[k]) < 5e-3
