@@ -311,6 +311,19 @@ typedef struct {
     double *Hs;          /* [Z] transition scale */
 } transition_taps;
 
+/* Encodings that enter h_out at window position t.  READING: h_left covers the observations up to
+ * and including x_t, h_right those from x_t on.  As printed (h_left over x_{T-l:t-1}, h_right over
+ * x_{t+1:T}) neither would contain x_t, so the last latent z_T would never see the newest
+ * observation; building with -DORACLE_A8_LITERAL gives that literal reading (an index shift, zero
+ * state at the window's ends) for the test that shows the difference. */
+#ifdef ORACLE_A8_LITERAL
+#define H_LEFT(t, r) ((t) > 0 ? hl[((size_t)(t) - 1) * R + (r)] : 0.0)
+#define H_RIGHT(t, r) ((t) < L - 1 ? hr[((size_t)(t) + 1) * R + (r)] : 0.0)
+#else
+#define H_LEFT(t, r) hl[(size_t)(t) * R + (r)]
+#define H_RIGHT(t, r) hr[(size_t)(t) * R + (r)]
+#endif
+
 static void sample_one(const oracle_model *m, const double *hl, const double *hr, int S, int k,
                        const float *eps_q, const float *eps_z, const float *eps_x, scratch *w,
                        double *x_out, double *zT_out, double *zn_out, double *mean_out, double *sd_out,
@@ -323,7 +336,7 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
         mlp_layer(m, m->comb_w, m->comb_b, w->z, Z, R, w->r1, w->xq);
         if (!m->mlp_bf16) {
             for (int r = 0; r < R; ++r)
-                w->r2[r] = (tanh(w->r1[r]) + hl[(size_t)t * R + r] + hr[(size_t)t * R + r]) / 3.0; /* h_out */
+                w->r2[r] = (tanh(w->r1[r]) + H_LEFT(t, r) + H_RIGHT(t, r)) / 3.0; /* h_out */
             affine(m->mu_w, m->mu_b, w->r2, R, Z, w->mu);                                     /* mu_q = K(h_out) */
         } else {
             /* the same K(h_out), split as oracle_set_mlp_bf16 describes */
@@ -333,7 +346,7 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
                 double per_sample = 0.0, context = 0.0;
                 for (int r = 0; r < R; ++r) {
                     per_sample += Wq[(size_t)i * R + r] * w->xq[r];
-                    context += m->mu_w[(size_t)i * R + r] * (hl[(size_t)t * R + r] + hr[(size_t)t * R + r]);
+                    context += m->mu_w[(size_t)i * R + r] * (H_LEFT(t, r) + H_RIGHT(t, r));
                 }
                 w->mu[i] = per_sample / 3.0 + (context / 3.0 + m->mu_b[i]);
             }

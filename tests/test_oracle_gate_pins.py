@@ -274,7 +274,7 @@ MUTATIONS = {
         ("mlp_layer(m, m->comb_w, m->comb_b, w->z, Z, R, w->r1, w->xq);",
          "mlp_layer(m, m->comb_w, m->comb_b, m->z0, Z, R, w->r1, w->xq);"),
     "combiner divided by two":
-        ("hr[(size_t)t * R + r]) / 3.0;", "hr[(size_t)t * R + r]) / 2.0;"),
+        ("H_RIGHT(t, r)) / 3.0;", "H_RIGHT(t, r)) / 2.0;"),
     "transition scale fed G instead of ReLU(G)":
         ("for (int i = 0; i < Z; ++i) w->mu[i] = relu(w->G[i]);", "for (int i = 0; i < Z; ++i) w->mu[i] = w->G[i];"),
     "emission scale fed z instead of the mean":
@@ -286,18 +286,20 @@ MUTATIONS = {
 class _Mutant:
     """The oracle's binding over a mutated copy of its C source (CPU only)."""
 
-    def __init__(self, tmp_path, old, new):
+    def __init__(self, tmp_path, old, new, defines=()):
         import ctypes as C
 
         from oracle import binding
 
         src = (ROOT / "oracle" / "cutoff_oracle.c").read_text()
-        assert src.count(old) == 1, old
+        if old is not None:
+            assert src.count(old) == 1, old
+            src = src.replace(old, new)
         c_file = tmp_path / "mutant.c"
-        c_file.write_text(src.replace(old, new))
+        c_file.write_text(src)
         so = tmp_path / "libmutant.so"
-        subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", "-o", str(so), str(c_file), "-lm"],
-                       check=True)
+        subprocess.run(["gcc", "-std=c99", "-O1", "-fopenmp", "-fPIC", "-shared", *defines, "-o", str(so), str(c_file),
+                        "-lm"], check=True)
         self._binding, self._saved, self._C, self._so = binding, binding._lib, C, so
 
     def __enter__(self):
@@ -333,3 +335,34 @@ def test_planted_mistake_is_caught(tmp_path, golden_dir, name):
             if not all(v == pytest.approx(cases[case]["out"][k], rel=1e-12, abs=1e-14) for k, v in got.items()):
                 failures.append(f"scalar chain {case}")
     assert failures, f"no pin noticed: {name}"
+
+
+def test_literal_reading_of_the_encodings_skips_the_observation_of_its_own_step(tmp_path):
+    """Sec. 3.1.3 prints h_left over x_{T-l:t-1} and h_right over x_{t+1:T}: the guide's step t would
+    then not use x_t itself.  Built that way (-DORACLE_A8_LITERAL) a window of one observation has
+    no influence on the prediction at all, and in a longer window the newest observation reaches
+    z_T only through the earlier latents; with the reading taken (both encodings include x_t) the
+    last step sees it directly."""
+    eq1 = np.zeros((1, 8, 3), np.float32)
+    cfg1 = cfg_of(N=4, L=1, Z=3, H=5, R=6, S=8)
+    w1 = synth.make_weights(cfg1, std=0.5)
+    x_a, x_b = np.array([1.0, 2.0, 3.0, 4.0]), np.array([4.0, 1.0, 2.0, 3.0])  # same mean: same normaliser
+    noise1 = (eq1, *synth.make_noise(cfg1)[1:])
+
+    def z_T(mod, cfg, w, window, noise):
+        _, st = model(cfg, w, window, mod=mod).sample_runtimes(*noise, stages=True)
+        return st["z_T"]
+
+    assert not np.allclose(z_T(oracle, cfg1, w1, [x_a], noise1), z_T(oracle, cfg1, w1, [x_b], noise1))
+    cfg3 = cfg_of(N=4, L=3, Z=3, H=5, R=6, S=8)
+    w3 = synth.make_weights(cfg3, std=0.5)
+    w3["comb_w"][:] = 0  # cut the chain: z_t no longer depends on z_{t-1}
+    noise3 = synth.make_noise(cfg3)
+    win_a, win_b = [x_b, x_a, x_a], [x_b, x_a, x_b]  # differ in the newest observation only
+    assert not np.allclose(z_T(oracle, cfg3, w3, win_a, noise3), z_T(oracle, cfg3, w3, win_b, noise3))
+    with _Mutant(tmp_path, None, None, defines=("-DORACLE_A8_LITERAL",)) as literal:
+        one_a, one_b = z_T(literal, cfg1, w1, [x_a], noise1), z_T(literal, cfg1, w1, [x_b], noise1)
+        three_a, three_b = z_T(literal, cfg3, w3, win_a, noise3), z_T(literal, cfg3, w3, win_b, noise3)
+        three_c = z_T(literal, cfg3, w3, [x_b, x_b, x_a], noise3)  # the middle observation does reach z_T
+    assert np.array_equal(one_a, one_b)
+    assert np.array_equal(three_a, three_b) and not np.allclose(three_a, three_c)
