@@ -19,8 +19,6 @@
 namespace dkf {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kPadKey = 0xFFFFFFFFu;
 constexpr uint32_t kNanKey = 0xFFFFFFFEu;
 
@@ -206,14 +204,15 @@ __device__ __forceinline__ void merge_up(T (&v)[E], int g) {
 
 // One lane group sorts one row per iteration; rank sums stay in registers
 // across iterations and are combined per block at the end in a fixed order.
-// partial: [gridDim.x][E << LG] fp32, indexed by rank.
-template <int E, int LG, bool WITH_PERM>
-__global__ __launch_bounds__(kThreads) void sort_rank_sums(const float *__restrict__ x, int S, int N,
+// partial: [gridDim.x][E << LG] fp32, indexed by rank.  THREADS: workgroup size (see plan_for).
+template <int E, int LG, bool WITH_PERM, int THREADS>
+__global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restrict__ x, int S, int N,
                                                             float *__restrict__ out_sorted,
                                                             int32_t *__restrict__ out_perm,
                                                             float *__restrict__ partial) {
     using Lay = Layout<E, LG>;
     using T = typename std::conditional<WITH_PERM, uint64_t, uint32_t>::type;
+    constexpr int kThreads = THREADS, kWaves = THREADS / 64;
     constexpr int G = 1 << LG;
     constexpr int NPAD = E * G;
     constexpr int kGroupsPerBlock = kThreads / G;
@@ -498,8 +497,12 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
 struct SortPlan {
     int e, lg;       // keys per lane, log2(lanes per row)
     int npad;        // e << lg
+    int threads;     // workgroup size of sort_rank_sums
     int blocks;      // grid of sort_rank_sums
 };
+
+// workgroup size by padded row width (must match the instantiations in launch_sort_case)
+constexpr int sort_threads(int npad) { return npad >= 2048 ? 256 : npad >= 1024 ? 512 : npad >= 512 ? 1024 : 256; }
 
 SortPlan plan_for(int S, int N) {
     int npad = 8;
@@ -512,9 +515,15 @@ SortPlan plan_for(int S, int N) {
     p.lg = 0;
     while ((1 << p.lg) < g) ++p.lg;
     p.npad = npad;
-    const int rows_per_block = kThreads / g;
+    p.threads = sort_threads(npad);
+    const int rows_per_block = p.threads / g;
     int blocks = (S + rows_per_block - 1) / rows_per_block;
-    const int cap = 2048;  // up to eight blocks per compute unit (measured best); more rows per group beyond that
+    // Up to eight small workgroups per compute unit (measured best) for narrow rows.  Rows of 512
+    // and 1024 keys take larger workgroups and a grid that is resident all at once, each workgroup
+    // looping over its share of the rows: fewer partial rows to write and re-read, fewer dispatches
+    // (measured 3-5 % faster).  At 2048 keys (three wavefronts per SIMD by registers) larger workgroups
+    // were slower; half as many small ones as before halve the partial rows at the same speed.
+    const int cap = npad >= 4096 ? 2048 : npad >= 1024 ? 1024 : npad >= 512 ? 512 : 2048;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     p.blocks = blocks;
@@ -526,10 +535,13 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 template <int E, int LG>
 void launch_sort(bool perm, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt, int32_t *pm,
                  float *partial) {
+    // the same workgroup shape with and without the permutation: the rank sums are added in the
+    // same order either way, so the means are bit-identical
+    constexpr int T = sort_threads(E << LG), TP = T;
     if (perm)
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, true>), grid, dim3(kThreads), 0, st, x, S, N, srt, pm, partial);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial);
     else
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, false>), grid, dim3(kThreads), 0, st, x, S, N, srt, pm, partial);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial);
 }
 
 }  // namespace

@@ -162,4 +162,8 @@ def test_benchmark_shapes(api, S, N):
     assert np.all(np.abs(mean - o["mean"]) <= 2e-6 * np.abs(o["mean"]) + 1e-12)
     assert cstar_in_tie_band(g["cstar"], o)
     g2 = api.select_cutoff(xd)  # the read-only configuration the benchmark times
+    mean2 = g2["mean"].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(mean2 - o["mean"]) <= 2e-6 * np.abs(o["mean"]) + 1e-12) and cstar_in_tie_band(g2["cstar"], o)
     assert g2["cstar"] == g["cstar"] and torch.equal(g2["mean"], g["mean"])
+    g3 = api.select_cutoff(xd)
+    assert g3["cstar"] == g2["cstar"] and torch.equal(g3["mean"], g2["mean"])  # the same call twice: bit-identical
