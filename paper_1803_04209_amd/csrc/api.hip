@@ -89,6 +89,8 @@ struct dkf_model {
     float *d_in = nullptr;  // [Np] observation + Control
     float *proj_f = nullptr, *proj_b = nullptr, *ctx_f = nullptr, *ctx_b = nullptr;
     int32_t *fault = nullptr;   // dev: raised by the multi-workgroup encoder when its bounded wait ran out
+    int32_t *xcd_claims = nullptr;  // dev int32[2], see FilterArgs
+    bool same_xcd = false;
     int spin_limit = kCoopSpinLimit;
     std::vector<float> window;  // host mirror, ring [L][N]
     int64_t pushes = 0;
@@ -521,6 +523,8 @@ FilterArgs filter_args(const dkf_model *m, const float *input) {
     a.N = m->N; a.Np = m->Np; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
     a.fault = m->fault;
     a.spin_limit = m->spin_limit;
+    a.xcd_claims = m->xcd_claims;
+    a.same_xcd = m->same_xcd;
     a.encode = true;
     return a;
 }
@@ -823,6 +827,8 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     DKF_CHECK(dev_alloc(m, 2 * sizeof(int32_t), &q, true)); m->d_cstar = static_cast<int32_t *>(q);
     DKF_CHECK(dev_alloc(m, 4096, &q, true)); m->sink = static_cast<float *>(q);
     DKF_CHECK(dev_alloc(m, 256, &q, true)); m->fault = static_cast<int32_t *>(q);
+    m->xcd_claims = m->fault + 16;
+    if (R > 256) DKF_CHECK(filter_xcd_census((R + 63) / 64, &m->same_xcd));  // wide encoders: several workgroups per direction
     DKF_CHECK(dev_alloc(m, (size_t)L * Smax * Z * 4, &q, false)); m->gen_q = static_cast<float *>(q);
     DKF_CHECK(dev_alloc(m, (size_t)Smax * Z * 4, &q, false)); m->gen_z = static_cast<float *>(q);
     DKF_CHECK(dev_alloc(m, (size_t)Smax * N * 4, &q, false)); m->gen_x = static_cast<float *>(q);

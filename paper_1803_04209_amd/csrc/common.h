@@ -97,11 +97,19 @@ struct FilterArgs {
     int32_t *fault;   // dev: set to 1 by the multi-workgroup encoder when its bounded wait ran out;
                       // cleared by the projection kernel that precedes it
     int spin_limit;   // polls that wait may take per step (0: give up at the first wait)
+    int32_t *xcd_claims;  // dev int32[2]: row blocks handed out so far per direction (same-XCD encoder);
+                          // cleared by the projection kernel
+    bool same_xcd;    // (multi-workgroup encoder) all workgroups of a direction run on one XCD and hand
+                      // their state over through that XCD's L2; false: any placement, through memory
     bool project;  // (register-resident kernel) compute the new observation's projection in-kernel
     bool mark_empty;  // (projection kernel) fill ctx with the multi-workgroup encoder's "not written yet" value
     bool encode;   // run the recurrences (after the projection) when the window is full
 };
 constexpr int kCoopSpinLimit = 1 << 20;  // default of FilterArgs::spin_limit
+// Whether a grid of 8 * blocks_per_direction workgroups of 1024 threads puts at least
+// blocks_per_direction of them on XCD 0 and on XCD 1 of the current device (measured by a small
+// census kernel; synchronises the device).  *ok is what FilterArgs::same_xcd may be set to.
+int filter_xcd_census(int blocks_per_direction, bool *ok);
 int launch_filter(const FilterArgs &a, bool project, bool encode, hipStream_t stream);
 
 // guide.hip

@@ -53,8 +53,11 @@ __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a
         const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
         for (int i = threadIdx.x; i < n; i += kProjThreads) a.mirror[i] = a.input[i];
     }
-    if (a.mark_empty && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    if (a.mark_empty && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
         __hip_atomic_store(a.fault, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // this step has not failed yet
+        __hip_atomic_store(a.xcd_claims, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.xcd_claims + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (a.mark_empty) {  // the multi-workgroup encoder that follows polls ctx for values >= 0
         const int total = a.L * a.R;
         float *__restrict__ c = dir ? a.ctx_b : a.ctx_f;
@@ -439,15 +442,39 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a
 constexpr int kCoopRows = 64;
 constexpr int kCoopTpr = kChainThreads / kCoopRows;  // 16 lanes per row = one DPP row
 
+// XCD this wavefront runs on: hardware register XCC_ID (id 20), bits 3:0
+__device__ __forceinline__ int xcd_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15; }
+
+// Placement of the workgroups (FilterArgs::same_xcd).  The state exchange costs one round trip to
+// the level of the memory system at which the workgroups of a direction are coherent: through
+// memory (device-scope stores and loads, about 2.3 us per step) when they may sit on different
+// XCDs, whose L2 caches are not coherent with each other; through the L2 (stores that stop there,
+// about 1.3 us per step) when they all sit on one XCD.  This second form leans on how the hardware
+// behaves (L1 write-through, one L2 per XCD), not on the language's memory model, which asks for
+// device scope on both sides; the bounded wait turns a failure of that assumption into
+// DKF_ESTALLED, never into a hang.  For it a grid of 8 * blocks workgroups is launched; every workgroup reads
+// the XCD it landed on, those on XCD 0 take the forward direction and those on XCD 1 the backward
+// one, each claiming the next row block of its direction from a counter, and the others leave at
+// once.  (The dispatcher deals workgroups to the XCDs in turn, so each XCD receives `blocks` of them;
+// filter_xcd_census checks this on the device before the path is enabled.)
 template <int KPT>
 __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a) {
     constexpr int SEG = KPT + 4;  // 4 pad floats per column segment: conflict-free b128 reads
     constexpr int HBUF = kCoopTpr * SEG;
     extern __shared__ __align__(16) float lds[];
-    __shared__ int bail;
+    __shared__ int bail, claim;
     const Control ctl = *a.ctl;
     if (ctl.count < a.L) return;  // still warming up: nothing to encode (uniform over the grid)
-    const int dir = blockIdx.y;
+    const int tid = threadIdx.x;
+    int dir = blockIdx.y, block = blockIdx.x;
+    if (a.same_xcd) {
+        dir = xcd_id();
+        if (dir > 1) return;
+        if (tid == 0) claim = __hip_atomic_fetch_add(a.xcd_claims + dir, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        block = claim;
+        if (block >= (a.R + kCoopRows - 1) / kCoopRows) return;  // this direction's row blocks are all taken
+    }
     const int R = a.R, Rp = a.Rp, L = a.L;
     const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
     const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
@@ -455,9 +482,8 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
     float *ctx = dir ? a.ctx_b : a.ctx_f;
     float *h = lds;               // two buffers [kCoopTpr][SEG]: previous state by column segment
     float *pre = lds + 2 * HBUF;  // [L][kCoopRows] input term of every step
-    const int tid = threadIdx.x;
     const int row_local = tid / kCoopTpr, seg = tid % kCoopTpr;
-    const int row = blockIdx.x * kCoopRows + row_local, k0 = seg * KPT;
+    const int row = block * kCoopRows + row_local, k0 = seg * KPT;
 
     float wreg[KPT];
     if (R == kCoopTpr * KPT && (R % kCoopRows) == 0) {  // the whole tile is inside the matrix: plain 16-byte loads
@@ -487,7 +513,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * kChainThreads;
-            const int step = i / kCoopRows, r = blockIdx.x * kCoopRows + i % kCoopRows;
+            const int step = i / kCoopRows, r = block * kCoopRows + i % kCoopRows;
             const int t = dir ? L - 1 - step : step;
             int slot = ctl.oldest + t;
             if (slot >= L) slot -= L;
@@ -518,20 +544,27 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
             }
             s = group_sum<kCoopTpr>(s);
         }
-        if (seg == 0 && row < R)
-            __hip_atomic_store(ctx + (size_t)t * Rp + row, fmaxf(pre[step * kCoopRows + row_local] + s, 0.f),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seg == 0 && row < R) {
+            const float hv = fmaxf(pre[step * kCoopRows + row_local] + s, 0.f);
+            // same XCD: a workgroup-scope store goes through the write-through L1 into the L2 all
+            // readers share and is not pushed on to memory first
+            if (a.same_xcd) __hip_atomic_store(ctx + (size_t)t * Rp + row, hv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            else __hip_atomic_store(ctx + (size_t)t * Rp + row, hv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (step == L - 1) break;
         // the whole state of this step, written by all workgroups of the direction
         if (tid < R) {
             const float *src = ctx + (size_t)t * Rp + tid;
-            float v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // device-scope load either way: it bypasses this compute unit's L1 (a workgroup-scope load
+            // may be served from it and never see the value: measured)
+            auto poll = [&]() { return __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+            float v = poll();
             int polls = 0;
             bool gave_up = a.spin_limit <= 0;  // a limit of zero counts as a wait that ran out
             while (!gave_up && v < 0.f) {
                 if (++polls > a.spin_limit) { gave_up = true; break; }
                 __builtin_amdgcn_s_sleep(1);
-                v = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v = poll();
             }
             if (gave_up) { bail = 1; v = 0.f; }
             h[((step + 1) & 1) * HBUF + my_slot] = v;
@@ -542,7 +575,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
     if (bail) {  // bounded wait ran out: report it, and poison what this workgroup owns
         if (tid == 0) __hip_atomic_store(a.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int i = tid; i < L * kCoopRows; i += kChainThreads) {
-            const int r = blockIdx.x * kCoopRows + i % kCoopRows;
+            const int r = block * kCoopRows + i % kCoopRows;
             if (r < R)
                 __hip_atomic_store(ctx + (size_t)(i / kCoopRows) * Rp + r, __builtin_nanf(""), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -550,11 +583,16 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_coop(FilterArgs a
     }
 }
 
+__global__ __launch_bounds__(kChainThreads) void xcd_census(int32_t *counts) {
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(counts + xcd_id(), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int KPT>
 int launch_encode_coop(const FilterArgs &a, hipStream_t stream) {
     const size_t lds = ((size_t)2 * kCoopTpr * (KPT + 4) + (size_t)a.L * kCoopRows) * sizeof(float);
     if (lds > 60 * 1024) return DKF_EUNSUPPORTED;
-    const dim3 grid((a.R + kCoopRows - 1) / kCoopRows, 2);
+    const int blocks = (a.R + kCoopRows - 1) / kCoopRows;
+    const dim3 grid = a.same_xcd ? dim3(8 * blocks) : dim3(blocks, 2);
     hipLaunchKernelGGL((encode_window_coop<KPT>), grid, dim3(kChainThreads), lds, stream, a);
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
@@ -584,6 +622,24 @@ size_t reg_encoder_lds(const FilterArgs &a) {
 }
 
 }  // namespace
+
+int filter_xcd_census(int blocks_per_direction, bool *ok) {
+    *ok = false;
+    if (blocks_per_direction < 1 || blocks_per_direction > 16) return DKF_OK;
+    int32_t *counts = nullptr, host[16] = {};
+    DKF_HIP_TRY(hipMalloc(reinterpret_cast<void **>(&counts), sizeof host));
+    hipError_t e = hipMemset(counts, 0, sizeof host);
+    for (int rep = 0; rep < 3 && e == hipSuccess; ++rep) {  // three launches: the dealing must not depend on where it starts
+        hipLaunchKernelGGL(xcd_census, dim3(8 * blocks_per_direction), dim3(kChainThreads), 0, nullptr, counts);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(host, counts, sizeof host, hipMemcpyDeviceToHost);
+    (void)hipFree(counts);
+    if (e != hipSuccess) { set_last_hip_error(e); return DKF_EHIP; }
+    *ok = host[0] == 3 * blocks_per_direction && host[1] == 3 * blocks_per_direction;
+    return DKF_OK;
+}
 
 int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t stream) {
     StageTimer timer(kStageFilter, stream);
