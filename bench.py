@@ -186,7 +186,7 @@ def run_workload(args, name, K, W, headline):
 
     cfg = synth.CONFIGS[name]
     S, N = cfg.samples, cfg.n_workers
-    KL = max(LATENCY_DECISIONS, K)          # decisions behind the latency percentiles
+    KL = max(args.latency_decisions, K)     # decisions behind the latency percentiles
     K_own = min(K, 300)                     # decisions of the built-in-noise region
     K_eager = min(K, 200)                   # eager steps behind the per-kernel times
     blob = synth.make_blob(cfg, calibrated=args.weights == "calibrated")
@@ -366,6 +366,9 @@ def main():
     ap.add_argument("--also", default=None,
                     help="comma-separated workloads measured as well and reported under `workloads` "
                          "(default: large_bf16,replay with the default headline, otherwise none; `none` for none)")
+    ap.add_argument("--latency-decisions", type=int, default=LATENCY_DECISIONS,
+                    help="fewest decisions the latency percentiles are taken from (lower it only to keep profiler "
+                         "output small)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle leg (0 skips it)")
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times (the known-size "
