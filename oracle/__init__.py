@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     build,
     cutoff_elfving,
     cutoff_select,
+    cutoff_select_rate,
     elfving_mean,
     fill_normal,
     impute_censored,

@@ -59,6 +59,7 @@ def _load():
     lib.oracle_round_bf16.argtypes = [C.c_double]
     lib.oracle_transition_terms.argtypes = [C.c_void_p, C.c_int, ip, C.c_int, fp, fp, fp, dp, dp, dp, dp, dp, dp, dp]
     lib.oracle_cutoff_select.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
+    lib.oracle_cutoff_select_rate.argtypes = [dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, dp, ip]
     lib.oracle_cutoff_select_f32.argtypes = [fp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, dp, ip, dp, dp, ip]
     lib.oracle_predict_cutoff.argtypes = [C.c_void_p, C.c_int, fp, fp, fp, C.c_int, C.c_int, C.c_double, ip]
     lib.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
@@ -250,6 +251,19 @@ def cutoff_select(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=True, w
     if rc < 0:
         raise ValueError(f"oracle_cutoff_select: error {rc}")
     return dict(status=rc, cstar=int(cstar[0]), mean=mean, omega=omega, sorted=srt, perm=perm)
+
+
+def cutoff_select_rate(samples, c_min=1, c_max=None, t_floor=0.0):
+    """Omega(c) = mean_k c / x_(c)^(k) and its (largest) maximiser.  Returns a dict (rate, omega, cstar, status)."""
+    a = np.ascontiguousarray(samples, dtype=np.float64)
+    S, N = a.shape
+    c_max = N if c_max is None else c_max
+    rate, omega = np.empty(N), np.empty(N)
+    cstar = np.zeros(1, dtype=np.int32)
+    rc = _load().oracle_cutoff_select_rate(_dp(a), S, N, c_min, c_max, float(t_floor), _dp(rate), _dp(omega), _ip(cstar))
+    if rc < 0:
+        raise ValueError(f"oracle_cutoff_select_rate: error {rc}")
+    return dict(status=rc, cstar=int(cstar[0]), rate=rate, omega=omega)
 
 
 def impute_censored(samples, x_obs, censored, tau, u):

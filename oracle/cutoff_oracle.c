@@ -568,6 +568,40 @@ int oracle_cutoff_select(const double *samples, int S, int N, int c_min, int c_m
     return ORACLE_OK;
 }
 
+/* The other reading of "expected gradients per second" (Sec. 3, definition of Omega): the
+ * expectation of the ratio, Omega(c) = E[c / x_(c)], estimated by the mean over the sampled rows of
+ * c / x^(k)_(c), instead of the ratio of c to the expected order statistic.  READING: a rank is
+ * eligible only if every sampled value of it exceeds t_floor >= 0 (a reciprocal of a non-positive
+ * time means nothing); bounds, ties and the no-eligible case as in oracle_cutoff_select.
+ * out_rate [N]: mean_k 1 / x^(k)_(c), +inf where some sample is <= t_floor; out_omega [N]: c * rate,
+ * -inf where ineligible.  Both optional. */
+int oracle_cutoff_select_rate(const double *samples, int S, int N, int c_min, int c_max, double t_floor,
+                              double *out_rate, double *out_omega, int32_t *out_cstar) {
+    if (!samples || !out_cstar || S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return ORACLE_EINVAL;
+    if (!(t_floor >= 0.0)) return ORACLE_EINVAL;
+    double *sum = (double *)calloc(N, sizeof(double));
+    keyed *row = (keyed *)malloc(sizeof(keyed) * N);
+    for (int k = 0; k < S; ++k) {
+        for (int j = 0; j < N; ++j) { row[j].v = samples[(size_t)k * N + j]; row[j].idx = j; }
+        qsort(row, N, sizeof(keyed), keyed_cmp);
+        for (int c = 0; c < N; ++c) sum[c] += row[c].v > t_floor ? 1.0 / row[c].v : INFINITY;
+    }
+    int best = -1;
+    double best_omega = -INFINITY;
+    for (int c = 1; c <= N; ++c) {
+        double rate = sum[c - 1] / (double)S;
+        double omega = -INFINITY;
+        if (c >= c_min && c <= c_max && isfinite(rate)) omega = (double)c * rate;
+        if (out_rate) out_rate[c - 1] = rate;
+        if (out_omega) out_omega[c - 1] = omega;
+        if (omega > -INFINITY && omega >= best_omega) { best_omega = omega; best = c; }
+    }
+    free(sum); free(row);
+    if (best < 0) { *out_cstar = c_max; return ORACLE_NO_ELIGIBLE; }
+    *out_cstar = best;
+    return ORACLE_OK;
+}
+
 /* Same, for an fp32 sample matrix (what the GPU hands over): every float is
  * exactly representable as a double, so order and ties are unchanged. */
 int oracle_cutoff_select_f32(const float *samples, int S, int N, int c_min, int c_max, double t_floor,

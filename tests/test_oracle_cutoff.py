@@ -210,3 +210,52 @@ def test_f64_and_f32_entries_agree():
     a = oracle.cutoff_select(x)
     b = oracle.cutoff_select(x.astype(np.float64))
     assert a["cstar"] == b["cstar"] and np.array_equal(a["perm"], b["perm"]) and np.array_equal(a["mean"], b["mean"])
+
+
+# ---- the other reading of Omega: the mean of c / x_(c) (Sec. 3) -----------------------------------
+
+def test_rate_rule_hand_worked_and_degenerate_cases():
+    # two rows (1, 2) and (4, 2): rank 1 -> (1/1 + 1/2)/2 = 3/4, rank 2 -> (1/2 + 1/4)/2 = 3/8;
+    # Omega = (3/4, 2 * 3/8): an exact tie, which goes to the larger cutoff
+    r = oracle.cutoff_select_rate(np.array([[1.0, 2.0], [4.0, 2.0]]))
+    assert np.array_equal(r["rate"], [0.75, 0.375]) and np.array_equal(r["omega"], [0.75, 0.75])
+    assert (r["cstar"], r["status"]) == (2, oracle.OK)
+    # identical rows: the mean of the ratio is the ratio of the mean
+    x = np.tile(np.array([[3.0, 1.0, 2.0, 8.0]]), (5, 1))
+    a, b = oracle.cutoff_select_rate(x), oracle.cutoff_select(x)
+    assert np.allclose(a["omega"], b["omega"], rtol=1e-15) and a["cstar"] == b["cstar"]
+    # a rank with one non-positive sample is out, for good: rank 1 here
+    x = np.array([[0.5, 1.0, 2.0], [-0.1, 1.0, 3.0]])
+    r = oracle.cutoff_select_rate(x)
+    assert np.isinf(r["rate"][0]) and np.isneginf(r["omega"][0]) and r["cstar"] in (2, 3)
+    r = oracle.cutoff_select_rate(-x)
+    assert (r["cstar"], r["status"]) == (3, oracle.NO_ELIGIBLE)
+    with pytest.raises(ValueError):
+        oracle.cutoff_select_rate(x, t_floor=-1.0)
+
+
+def test_rate_rule_uniform_order_statistics():
+    # x_(c) of N iid U(0,1) is Beta(c, N + 1 - c), whose reciprocal has mean N / (c - 1) and second
+    # moment N (N - 1) / ((c - 1)(c - 2)): Omega(c) = c N / (c - 1) for c >= 3 within 5 standard errors
+    S, N = 40000, 12
+    x = np.random.default_rng(3).random((S, N))
+    r = oracle.cutoff_select_rate(x, c_min=3)
+    c = np.arange(3, N + 1)
+    mean = N / (c - 1)
+    var = N * (N - 1) / ((c - 1) * (c - 2)) - mean ** 2
+    assert np.all(np.abs(r["rate"][2:] - mean) < 5 * np.sqrt(var / S))
+    assert r["cstar"] == 3  # c N / (c - 1) falls with c
+
+
+def test_rate_rule_against_enumeration_and_jensen():
+    rng = np.random.default_rng(8)
+    for S, N in [(1, 1), (7, 5), (50, 8)]:
+        x = rng.lognormal(0.0, 0.5, (S, N))
+        for c_min, c_max in [(1, N), (min(2, N), N), (1, max(1, N - 1))]:
+            r = oracle.cutoff_select_rate(x, c_min=c_min, c_max=c_max)
+            srt = np.sort(x, axis=1)
+            om = np.array([np.mean(c / srt[:, c - 1]) if c_min <= c <= c_max else -np.inf for c in range(1, N + 1)])
+            assert np.allclose(r["omega"], om, rtol=1e-13)
+            assert r["cstar"] == max(c for c in range(1, N + 1) if om[c - 1] == om.max())
+        # the mean of the ratio is never below the ratio of the mean (Jensen, 1/x convex on x > 0)
+        assert np.all(oracle.cutoff_select_rate(x)["omega"] >= oracle.cutoff_select(x)["omega"] * (1 - 1e-12))
