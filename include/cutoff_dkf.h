@@ -149,6 +149,23 @@ int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int
                   void *workspace, size_t workspace_bytes, void *stream);
 size_t cutoff_select_workspace(int32_t S, int32_t N);
 
+/* The cutoff under the other reading of "expected gradients per second"
+ * (Sec. 3, definition of Omega): the expectation of the ratio,
+ * Omega(c) = E[c / x_(c)], estimated by the mean over the sampled rows of
+ * c / x_(c), where cutoff_select takes the ratio c / E[x_(c)].  A rank is
+ * eligible only if every sampled value of it exceeds t_floor, which must be
+ * >= 0 (the Gaussian emission of Sec. 3.1.3 also draws non-positive times,
+ * whose reciprocal means nothing); by Jensen's inequality this Omega is never
+ * below cutoff_select's.  Arguments, order of equal keys, workspace, bounds,
+ * ties, status and errors as for cutoff_select, except:
+ *   out_rate [N] (dev, optional): mean over the rows of 1 / x_(c), +inf where
+ *     some row's value is <= t_floor (or the fp32 sum overflows);
+ *   out_omega [N]: c * out_rate, -inf where ineligible;
+ *   t_floor < 0 or NaN: DKF_EINVAL. */
+int cutoff_select_rate(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                       float *out_sorted, int32_t *out_perm, float *out_rate, float *out_omega, int32_t *out_cstar,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* cutoff_select for callers that cannot allocate device memory or hand over a
  * workspace: code running under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, results and error codes as

@@ -28,7 +28,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
-    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
+    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_rate", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
     "dkf_check", "dkf_set_exchange_spin_limit", "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
@@ -78,6 +78,7 @@ def _lib():
     lib.dkf_filter_step.argtypes = [vp, vp, vp]
     lib.dkf_sample_runtimes.argtypes = [vp, i32, vp, vp, vp, u64, vp, C.POINTER(dkf_stage_outputs), vp]
     lib.cutoff_select.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cutoff_select_rate.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cutoff_select_workspace.restype = sz
     lib.cutoff_select_workspace.argtypes = [i32, i32]
     lib.cutoff_select_static.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
@@ -193,6 +194,18 @@ def cutoff_select(samples, c_min: int, c_max: int, t_floor: float, out_sorted, o
         _dev(samples, torch.float32, name="samples"), S, N, c_min, c_max, float(t_floor),
         _dev(out_sorted, torch.float32, (S, N), "out_sorted"), _dev(out_perm, torch.int32, (S, N), "out_perm"),
         _dev(out_mean, torch.float32, (N,), "out_mean"), _dev(out_omega, torch.float32, (N,), "out_omega"),
+        _dev(out_cstar, torch.int32, (2,), "out_cstar"), _dev(workspace, torch.uint8, name="workspace"),
+        workspace.numel(), _stream_ptr(stream)))
+
+
+def cutoff_select_rate(samples, c_min: int, c_max: int, t_floor: float, out_sorted, out_perm, out_rate, out_omega,
+                       out_cstar, workspace, stream=None) -> int:
+    torch = _torch()
+    S, N = samples.shape
+    return _check("cutoff_select_rate", _lib().cutoff_select_rate(
+        _dev(samples, torch.float32, name="samples"), S, N, c_min, c_max, float(t_floor),
+        _dev(out_sorted, torch.float32, (S, N), "out_sorted"), _dev(out_perm, torch.int32, (S, N), "out_perm"),
+        _dev(out_rate, torch.float32, (N,), "out_rate"), _dev(out_omega, torch.float32, (N,), "out_omega"),
         _dev(out_cstar, torch.int32, (2,), "out_cstar"), _dev(workspace, torch.uint8, name="workspace"),
         workspace.numel(), _stream_ptr(stream)))
 
@@ -389,8 +402,9 @@ def rank_spread(sorted_rows, mean):
     return sd
 
 
-def select_cutoff(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=False, want_perm=False):
-    """Allocate outputs + workspace, call cutoff_select, return a dict of tensors and ints."""
+def select_cutoff(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=False, want_perm=False, rate=False):
+    """Allocate outputs + workspace, call cutoff_select (or, with rate=True, cutoff_select_rate, whose
+    out_rate then sits under the key "mean"), return a dict of tensors and ints."""
     torch = _torch()
     S, N = samples.shape
     c_max = N if c_max is None else c_max
@@ -404,6 +418,6 @@ def select_cutoff(samples, c_min=1, c_max=None, t_floor=0.0, want_sorted=False, 
     mean = torch.empty(N, dtype=torch.float32, device=dev)
     omega = torch.empty(N, dtype=torch.float32, device=dev)
     cstar = torch.zeros(2, dtype=torch.int32, device=dev)
-    cutoff_select(samples, c_min, c_max, t_floor, srt, perm, mean, omega, cstar, ws)
+    (cutoff_select_rate if rate else cutoff_select)(samples, c_min, c_max, t_floor, srt, perm, mean, omega, cstar, ws)
     c = cstar.cpu()
     return dict(cstar=int(c[0]), status=int(c[1]), mean=mean, omega=omega, sorted=srt, perm=perm)

@@ -908,6 +908,14 @@ int cutoff_select(const float *samples, int32_t S, int32_t N, int32_t c_min, int
                                 out_cstar, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+int cutoff_select_rate(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
+                       float *out_sorted, int32_t *out_perm, float *out_rate, float *out_omega, int32_t *out_cstar,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    return launch_cutoff_select(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_rate, out_omega,
+                                out_cstar, workspace, workspace_bytes, static_cast<hipStream_t>(stream), nullptr,
+                                nullptr, 1);
+}
+
 int cutoff_select_static(const float *samples, int32_t S, int32_t N, int32_t c_min, int32_t c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *stream) {

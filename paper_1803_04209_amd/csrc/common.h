@@ -272,7 +272,8 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
                          const int32_t *ticket = nullptr,  // dev: if set, *ticket is stored to out_cstar[2] after c*
-                         const int32_t *fault = nullptr);  // dev: if set and non-zero, the status becomes DKF_ESTALLED
+                         const int32_t *fault = nullptr,   // dev: if set and non-zero, the status becomes DKF_ESTALLED
+                         int rate = 0);  // 1: rank sums of reciprocals, Omega(c) = c * mean_k 1 / x_(c) (needs t_floor >= 0)
 size_t cutoff_workspace_bytes(int S, int N);
 // the same with the workspace in a fixed device array of the library (no allocation anywhere)
 int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, int c_max, float t_floor,

@@ -209,7 +209,7 @@ template <int E, int LG, bool WITH_PERM, int THREADS>
 __global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restrict__ x, int S, int N,
                                                             float *__restrict__ out_sorted,
                                                             int32_t *__restrict__ out_perm,
-                                                            float *__restrict__ partial) {
+                                                            float *__restrict__ partial, int rate, float t_floor) {
     using Lay = Layout<E, LG>;
     using T = typename std::conditional<WITH_PERM, uint64_t, uint32_t>::type;
     constexpr int kThreads = THREADS, kWaves = THREADS / 64;
@@ -286,7 +286,8 @@ __global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restric
                 uint32_t k;
                 if constexpr (WITH_PERM) k = (uint32_t)(v[q * 4 + j] >> 32); else k = v[q * 4 + j];
                 f[j] = value_of(k);
-                if (valid && i0 + j < N) acc[q * 4 + j] += f[j];
+                // rank sums of the values, or (rate rule) of their reciprocals, +inf once a value is not above the floor
+                if (valid && i0 + j < N) acc[q * 4 + j] += !rate ? f[j] : f[j] > t_floor ? 1.0f / f[j] : INFINITY;
             }
             if (valid && out_sorted) {
                 float *dst = out_sorted + (size_t)row * N;
@@ -388,7 +389,7 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
                                                   float t_floor, float *__restrict__ out_mean,
                                                   float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
                                                   double *best_v, int *best_c, const int32_t *ticket,
-                                                  const int32_t *fault) {
+                                                  const int32_t *fault, int rate = 0) {
     double bv = -INFINITY;
     int bc = 0;
     for (int c = threadIdx.x + 1; c <= N; c += THREADS) {
@@ -397,7 +398,11 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
         for (int p = 0; p < kMeanParts; ++p) sum += part2[(size_t)p * N + c - 1];
         const double m = sum / (double)S;
         double om = -INFINITY;
-        if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
+        if (!rate) {
+            if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
+        } else if (c >= c_min && c <= c_max && m < INFINITY) {  // m: mean reciprocal; infinite = some sample not above the floor
+            om = (double)c * m;
+        }
         if (out_mean) out_mean[c - 1] = (float)m;
         if (out_omega) out_omega[c - 1] = (float)om;
         if (om > -INFINITY && om >= bv) { bv = om; bc = c; }
@@ -436,11 +441,11 @@ __global__ __launch_bounds__(kArgmaxThreads) void omega_argmax(const double *__r
                                                                float *__restrict__ out_mean,
                                                                float *__restrict__ out_omega,
                                                                int32_t *__restrict__ out_cstar,
-                                                               const int32_t *ticket, const int32_t *fault) {
+                                                               const int32_t *ticket, const int32_t *fault, int rate) {
     __shared__ double best_v[kArgmaxThreads];
     __shared__ int best_c[kArgmaxThreads];
     omega_argmax_body<kArgmaxThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                      best_c, ticket, fault);
+                                      best_c, ticket, fault, rate);
 }
 
 // Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
@@ -458,7 +463,7 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
                                                                    float t_floor, float *__restrict__ out_mean,
                                                                    float *__restrict__ out_omega,
                                                                    int32_t *__restrict__ out_cstar,
-                                                                   const int32_t *ticket, const int32_t *fault) {
+                                                                   const int32_t *ticket, const int32_t *fault, int rate) {
     __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N], unused parts are zero
     __shared__ double best_v[kFusedThreads];
     __shared__ int best_c[kFusedThreads];
@@ -491,7 +496,7 @@ __global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *
     }
     __syncthreads();
     omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                     best_c, ticket, fault);
+                                     best_c, ticket, fault, rate);
 }
 
 struct SortPlan {
@@ -534,14 +539,14 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 template <int E, int LG>
 void launch_sort(bool perm, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt, int32_t *pm,
-                 float *partial) {
+                 float *partial, int rate, float t_floor) {
     // the same workgroup shape with and without the permutation: the rank sums are added in the
     // same order either way, so the means are bit-identical
     constexpr int T = sort_threads(E << LG), TP = T;
     if (perm)
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
     else
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
 }
 
 }  // namespace
@@ -555,8 +560,9 @@ size_t cutoff_workspace_bytes(int S, int N) {
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
-                         const int32_t *ticket, const int32_t *fault) {
+                         const int32_t *ticket, const int32_t *fault, int rate) {
     if (!samples || !out_cstar || !workspace) return DKF_EINVAL;
+    if (rate && !(t_floor >= 0.f)) return DKF_EINVAL;
     if (S < 1 || N < 1 || c_min < 1 || c_max > N || c_min > c_max) return DKF_EINVAL;
     if (t_floor != t_floor) return DKF_EINVAL;
     if (N > 4096) return DKF_EUNSUPPORTED;
@@ -574,7 +580,7 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     {
         StageTimer timer(kStageSort, stream);
 #define DKF_SORT_CASE(E_, LG_)                                                                    \
-    launch_sort<E_, LG_>(perm, grid, stream, samples, S, N, out_sorted, out_perm, partial);        \
+    launch_sort<E_, LG_>(perm, grid, stream, samples, S, N, out_sorted, out_perm, partial, rate, t_floor); \
     break
         switch (p.npad) {
             case 8: DKF_SORT_CASE(8, 0);
@@ -596,14 +602,14 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
         StageTimer timer(kStageArgmax, stream);
         if (N <= kFusedMeansMaxN && p.blocks * N <= kFusedMeansMaxSums) {
             hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
-                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault);
+                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate);
             DKF_HIP_TRY(hipGetLastError());
         } else {
             hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
                                p.blocks, p.npad, N, part2);
             DKF_HIP_TRY(hipGetLastError());
             hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(kArgmaxThreads), 0, stream, part2, N, S, c_min, c_max, t_floor,
-                               out_mean, out_omega, out_cstar, ticket, fault);
+                               out_mean, out_omega, out_cstar, ticket, fault, rate);
             DKF_HIP_TRY(hipGetLastError());
         }
     }
@@ -654,7 +660,7 @@ int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, i
     // every word of the scratch the kernels read has been written earlier in the same call, so
     // nothing is cleared; what the previous call left behind is never looked at
     return launch_cutoff_select(samples, S, N, c_min, c_max, t_floor, out_sorted, out_perm, out_mean, out_omega,
-                                out_cstar, ws, kStaticScratchBytes, stream, nullptr, nullptr);
+                                out_cstar, ws, kStaticScratchBytes, stream, nullptr, nullptr, 0);
 }
 
 }  // namespace dkf

@@ -167,3 +167,43 @@ def test_benchmark_shapes(api, S, N):
     assert g2["cstar"] == g["cstar"] and torch.equal(g2["mean"], g["mean"])
     g3 = api.select_cutoff(xd)
     assert g3["cstar"] == g2["cstar"] and torch.equal(g3["mean"], g2["mean"])  # the same call twice: bit-identical
+
+
+@pytest.mark.parametrize("kind", ["lognormal_stragglers", "normal", "uniform"])
+@pytest.mark.parametrize("S,N", [(1, 16), (1000, 48), (4099, 128), (130, 512), (67, 2048), (33, 158)])
+def test_rate_rule(api, kind, S, N):
+    """cutoff_select_rate: Omega(c) = mean over the rows of c / x_(c).  Reciprocals are taken in fp32
+    (correctly rounded) and summed like the rank sums, so the rates agree with the fp64 oracle to
+    3e-6; a rank with a value at or below the floor is out on both sides; sorting is unchanged."""
+    import torch
+
+    x = synth.make_runtime_matrix(kind, S, N, seed=3 * S + N)
+    if kind == "uniform":
+        x = x + np.float32(0.25)  # keep the reciprocals of the lowest ranks well conditioned
+    for kw in (dict(), dict(c_min=min(2, N), c_max=max(min(2, N), N - 1), t_floor=0.5)):
+        g = api.select_cutoff(torch.from_numpy(x).cuda(), want_sorted=True, want_perm=True, rate=True, **kw)
+        o = oracle.cutoff_select_rate(x, **kw)
+        ref = oracle.cutoff_select(x, t_floor=-np.inf)
+        assert np.array_equal(g["sorted"].cpu().numpy().view(np.uint32), ref["sorted"].astype(np.float32).view(np.uint32))
+        assert np.array_equal(g["perm"].cpu().numpy(), ref["perm"])
+        rate = g["mean"].cpu().numpy().astype(np.float64)
+        fin = np.isfinite(o["rate"])
+        assert np.array_equal(np.isposinf(rate), ~fin)
+        assert np.allclose(rate[fin], o["rate"][fin], rtol=3e-6, atol=0)
+        om = g["omega"].cpu().numpy().astype(np.float64)
+        assert np.array_equal(np.isneginf(om), np.isneginf(o["omega"]))
+        ok = np.isfinite(o["omega"])
+        assert np.allclose(om[ok], o["omega"][ok], rtol=3e-6, atol=0)
+        assert g["status"] == o["status"]
+        assert cstar_in_tie_band(g["cstar"], o, rel=6e-6) if o["status"] == oracle.OK else g["cstar"] == o["cstar"]
+
+
+def test_rate_rule_argument_errors(api):
+    import torch
+
+    x = torch.ones((4, 8), device="cuda")
+    with pytest.raises(api.DkfError) as e:
+        api.select_cutoff(x, rate=True, t_floor=-0.5)
+    assert e.value.code == api.DKF_EINVAL
+    with pytest.raises(api.DkfError):
+        api.select_cutoff(x, rate=True, t_floor=float("nan"))
