@@ -60,7 +60,7 @@ def stage_work(cfg):
 
 # Sources whose change invalidates stored hardware-counter readings of a stage's kernel.
 STAGE_SOURCES = {
-    "sampler_fused": ["chain.hip", "quad.hip", "common.h", "mfma_tile.h"],
+    "sampler_fused": ["chain.hip", "quad.hip", "split.hip", "mfma16.h", "common.h", "mfma_tile.h"],
     "sort_rank_sums": ["cutoff_select.hip", "common.h"],
     "guide_transition": ["gchain.hip", "guide.hip", "common.h", "mfma_tile.h"],
     "emit_hidden": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],

@@ -272,18 +272,23 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes);
 /* Which kernels dkf_sample_runtimes / dkf_decide use for the sampling stage
  * (Sec. 3.1.3: guide chain, transition draw, emission draw).  All variants
  * compute the same thing to the same tolerance; the default picks by size.
- *   DKF_SAMPLER_AUTO    four samples per wavefront up to 8192 samples, sixteen
- *                       above, the staged kernels for bf16 models and for
- *                       layer sizes the fused kernels are not built for
+ *   DKF_SAMPLER_AUTO    sixteen samples per workgroup up to 4096 samples where
+ *                       that kernel is built for the layer sizes, four per
+ *                       wavefront up to 8192, sixteen per wavefront above; the
+ *                       staged kernels for bf16 models and for layer sizes the
+ *                       fused kernels are not built for
  *   DKF_SAMPLER_WAVE16  one fused kernel, sixteen samples per wavefront
  *   DKF_SAMPLER_WAVE4   one fused kernel, four samples per wavefront
  *   DKF_SAMPLER_STAGED  guide/transition kernel + four GEMM kernels
+ *   DKF_SAMPLER_SPLIT   one fused kernel, sixteen samples per workgroup, every
+ *                       layer split over the workgroup's four wavefronts
  * Returns DKF_EUNSUPPORTED (and changes nothing) if the model's sizes or dtype
  * rule the requested variant out.  Host call; takes effect at the next call. */
 #define DKF_SAMPLER_AUTO 0
 #define DKF_SAMPLER_WAVE16 1
 #define DKF_SAMPLER_WAVE4 2
 #define DKF_SAMPLER_STAGED 3
+#define DKF_SAMPLER_SPLIT 4
 int dkf_set_sampler(dkf_model *m, int32_t variant);
 
 /* Per-kernel timing with HIP events recorded on the stream the kernels are

@@ -288,7 +288,7 @@ def dkf_set_state(model: int, state: bytes) -> None:
     _check("dkf_set_state", _lib().dkf_set_state(model, state, len(state)))
 
 
-SAMPLER_AUTO, SAMPLER_WAVE16, SAMPLER_WAVE4, SAMPLER_STAGED = 0, 1, 2, 3
+SAMPLER_AUTO, SAMPLER_WAVE16, SAMPLER_WAVE4, SAMPLER_STAGED, SAMPLER_SPLIT = 0, 1, 2, 3, 4
 
 
 def dkf_set_sampler(handle, variant: int) -> None:

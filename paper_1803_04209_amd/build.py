@@ -13,7 +13,7 @@ INCLUDE = PKG.parent / "include"
 BUILD = PKG / "_build"
 LIB = PKG / "libcutoff_dkf.so"
 
-SOURCES = ["api.hip", "filter.hip", "guide.hip", "gchain.hip", "chain.hip", "quad.hip", "noise.hip", "mlp_gemm.hip", "egemm.hip", "cutoff_select.hip", "impute.hip", "spread.hip"]
+SOURCES = ["api.hip", "filter.hip", "guide.hip", "gchain.hip", "chain.hip", "quad.hip", "split.hip", "noise.hip", "mlp_gemm.hip", "egemm.hip", "cutoff_select.hip", "impute.hip", "spread.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
     "-Wno-unused-command-line-argument",

@@ -76,6 +76,8 @@ struct dkf_model {
     bool use_quad = false;   // sizes covered by the four-samples-per-wavefront sampler (small S)
     const float *quad_guide = nullptr, *quad_stream = nullptr, *quad_bias = nullptr;
     int quad_chunks = 0;
+    bool use_split = false;  // sizes covered by the sixteen-samples-per-workgroup sampler
+    const float *split_stream = nullptr, *split_bias = nullptr;
     bool use_gchain = false;  // bf16 sizes covered by the register-resident guide/transition kernel
     const float *gc_tiles = nullptr, *gc_bias = nullptr, *gc_mu_w32 = nullptr, *gc_mu_b32 = nullptr;
     float *gc_cmu = nullptr;
@@ -283,6 +285,68 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     int rc = upload(m, g.data(), g.size(), &m->chain_guide);
     if (rc != DKF_OK) return rc;
     return upload(m, s.data(), s.size(), &m->chain_stream);
+}
+
+// One tile stream per wavefront for the sixteen-samples-per-workgroup sampler (split.hip), in the
+// order wavefront w consumes it (RQ = RB / 4, HQ = HB / 4, C = 2 HB tiles per chunk):
+//   guide:  comb [o < RQ][ib] (output block w RQ + o), mu [zb][i < RQ] (input block w RQ + i), sig [zb][ib];
+//   head, padded with zero tiles to whole chunks:  gate1 [o < HQ][ib], gate2 [zb][i < HQ], prop1, prop2
+//           likewise, lin [ob][ib], tscale [ob][ib], emean1 [o < HQ][ib];
+//   per own worker block nb = w NBW + u, one chunk:  emean2 row nb (ib < HB), escale1 column nb (ob < HB);
+//   per pair of own worker blocks, one chunk:  escale2 row nb (ib < HB) for each of the two;
+//   one spare chunk of zeros.
+// Biases: the table of the sixteen-per-wavefront kernel.
+int pack_split(dkf_model *m, const RawLayers &r) {
+    const int Z = m->Z, R = m->R, H = m->H, N = m->N;
+    const int ZB = (Z + 15) / 16, RB = (R + 15) / 16, HB = (H + 15) / 16, NB = (N + 15) / 16;
+    const int RQ = RB / 4, HQ = HB / 4, C = 2 * HB, NBW = (NB + 3) / 4;
+    const int per_wave = split_stream_tiles(Z, R, H, N);
+    if (per_wave <= 0) return DKF_EINVAL;
+    std::vector<float> s;
+    s.reserve((size_t)4 * per_wave * 256);
+    for (int w = 0; w < 4; ++w) {
+        const size_t start = s.size();
+        auto pad = [&] {
+            const size_t head = start + (size_t)(2 * RQ * ZB + ZB * ZB) * 256, chunk = (size_t)C * 256;
+            s.resize(head + (s.size() - head + chunk - 1) / chunk * chunk, 0.f);
+        };
+        auto zeros = [&](int tiles) { s.resize(s.size() + (size_t)tiles * 256, 0.f); };
+        for (int o = 0; o < RQ; ++o) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.comb, R, Z, w * RQ + o, ib);
+        for (int zb = 0; zb < ZB; ++zb) for (int i = 0; i < RQ; ++i) append_tile(s, r.mu, Z, R, zb, w * RQ + i);
+        for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.sig, Z, Z, zb, ib);
+        auto wide = [&](const float *wt) { for (int o = 0; o < HQ; ++o) for (int ib = 0; ib < ZB; ++ib) append_tile(s, wt, H, Z, w * HQ + o, ib); };
+        auto narrow = [&](const float *wt) { for (int zb = 0; zb < ZB; ++zb) for (int i = 0; i < HQ; ++i) append_tile(s, wt, Z, H, zb, w * HQ + i); };
+        auto small = [&](const float *wt) { for (int ob = 0; ob < ZB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(s, wt, Z, Z, ob, ib); };
+        wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale); wide(r.emean1);
+        pad();
+        for (int u = 0; u < NBW; ++u) {
+            const int nb = w * NBW + u;
+            if (nb >= NB) { zeros(C); continue; }
+            for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
+            for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
+        }
+        for (int u = 0; u < NBW; ++u) {
+            const int nb = w * NBW + u;
+            if (nb >= NB) { zeros(HB); continue; }
+            for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
+        }
+        pad();
+        zeros(C);
+        if (s.size() - start != (size_t)per_wave * 256) return DKF_EINVAL;
+    }
+    std::vector<float> bt;
+    auto add_bias = [&](const float *b, int n, int blocks) {
+        const size_t base = bt.size();
+        bt.resize(base + (size_t)blocks * 16, 0.f);
+        for (int i = 0; i < n; ++i) bt[base + i] = b[i];
+    };
+    add_bias(r.b_comb, R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
+    add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
+    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(r.b_escale1, H, HB);
+    add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);
+    int rc = upload(m, bt.data(), bt.size(), &m->split_bias);
+    if (rc == DKF_OK) rc = upload(m, s.data(), s.size(), &m->split_stream);
+    return rc;
 }
 
 // Tiles and biases of the bf16 guide/transition kernel (layout: GChainArgs).
@@ -569,16 +633,24 @@ constexpr long kTicketSpins = 50L * 1000 * 1000;
 // Up to this many samples the four-per-wavefront sampler is used where both are available (at
 // 16 per wavefront, 16384 samples are what fills every SIMD of the chip once).
 constexpr int kQuadMaxSamples = 8192;
+// Up to this many samples (one workgroup of sixteen per compute unit) the sampler that splits
+// every layer over a workgroup's wavefronts has the shortest critical path.
+constexpr int kSplitMaxSamples = 4096;
 
 int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
     // few samples: four per wavefront, so that they still spread over the whole chip
-    const bool quad = m->sampler == DKF_SAMPLER_WAVE4 ||
-                      (m->sampler == DKF_SAMPLER_AUTO && m->use_quad && (S <= kQuadMaxSamples || !m->use_chain));
+    const bool split = m->sampler == DKF_SAMPLER_SPLIT ||
+                       (m->sampler == DKF_SAMPLER_AUTO && m->use_split &&
+                        (S <= kSplitMaxSamples || (!m->use_chain && !m->use_quad)));
+    const bool quad = !split && (m->sampler == DKF_SAMPLER_WAVE4 ||
+                                 (m->sampler == DKF_SAMPLER_AUTO && m->use_quad && (S <= kQuadMaxSamples || !m->use_chain)));
     ChainArgs c{};
     c.ctl = m->ctl_dev();
     c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
-    if (quad) {
+    if (split) {
+        c.stream_tiles = m->split_stream; c.bias_table = m->split_bias;
+    } else if (quad) {
         c.guide_tiles = m->quad_guide; c.stream_tiles = m->quad_stream; c.stream_chunks = m->quad_chunks;
         c.bias_table = m->quad_bias;
     } else {
@@ -596,7 +668,7 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.out_sd_dbg = st ? st->emit_sd : nullptr;
     c.S = S; c.L = m->L; c.Z = m->Z; c.R = m->R; c.H = m->H; c.N = m->N; c.NB = (m->N + 15) / 16;
     c.emit_mean_act = m->cfg.emit_mean_act;
-    const int rc = quad ? launch_quad(c, stream) : launch_chain(c, stream);
+    const int rc = split ? launch_split(c, stream) : quad ? launch_quad(c, stream) : launch_chain(c, stream);
     if (rc != DKF_OK) return rc;
     if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
     return DKF_OK;
@@ -610,7 +682,7 @@ int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStr
 
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
-    if (m->sampler != DKF_SAMPLER_STAGED && (m->use_chain || m->use_quad)) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
+    if (m->sampler != DKF_SAMPLER_STAGED && (m->use_chain || m->use_quad || m->use_split)) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
     int rc = DKF_EUNSUPPORTED;
     if (m->sampler != DKF_SAMPLER_STAGED && m->use_gchain) {
         GChainArgs c{};
@@ -807,6 +879,8 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
     m->use_quad = !bf16 && quad_supported(Z, R, H, L, N);
     if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
+    m->use_split = !bf16 && split_supported(Z, R, H, L, N);
+    if (m->use_split) DKF_CHECK(pack_split(m, raw));
     m->use_gchain = bf16 && gchain_q(Z, R, H) != 0 && m->Zp == 64;
     if (m->use_gchain) DKF_CHECK(pack_gchain(m, raw));
     if (m->use_gchain) DKF_CHECK(pack_emission_frags(m, raw));
@@ -1081,7 +1155,8 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes) {
 }
 
 int dkf_set_sampler(dkf_model *m, int32_t variant) {
-    if (!m || variant < DKF_SAMPLER_AUTO || variant > DKF_SAMPLER_STAGED) return DKF_EINVAL;
+    if (!m || variant < DKF_SAMPLER_AUTO || variant > DKF_SAMPLER_SPLIT) return DKF_EINVAL;
+    if (variant == DKF_SAMPLER_SPLIT && !m->use_split) return DKF_EUNSUPPORTED;
     if (variant == DKF_SAMPLER_WAVE16 && !m->use_chain) return DKF_EUNSUPPORTED;
     if (variant == DKF_SAMPLER_WAVE4 && !m->use_quad) return DKF_EUNSUPPORTED;
     if (variant != m->sampler) m->graph_S = 0;  // a captured decision graph holds the old kernels

@@ -20,28 +20,13 @@
 // and immediately folded into the hidden layer of the scale network.
 #include "common.h"
 #include "mfma_tile.h"
+#include "mfma16.h"
 
 namespace dkf {
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kTileF4 = 64;  // float4 per weight tile (one per lane)
-
-__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-}
-
-// Keeps the instruction scheduler from hoisting later blocks' operand loads above this point
-// (otherwise dozens of weight tiles are prefetched into registers and the kernel spills).
-__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
-
-__device__ __forceinline__ f32x4 splat(float v) { f32x4 r = {v, v, v, v}; return r; }
-
-template <typename F>
-__device__ __forceinline__ f32x4 map4(f32x4 v, F f) {
-    f32x4 r = {f(v.x), f(v.y), f(v.z), f(v.w)};
-    return r;
-}
 
 // Stream of weight chunks (CH tiles each) from global memory through a two-buffer LDS ring.
 // While chunk c is consumed from LDS, chunk c + 1 sits in registers (requested one chunk
@@ -93,57 +78,6 @@ struct WeightStream {
         return buf[(cur_chunk & 1) * kChunkF4 + t * kTileF4 + lane];
     }
 };
-
-// Calls use(g, tiles) for every group of GROUP consecutive tiles (COUNT must be a multiple of
-// GROUP).  The next group is already being fetched while the current one feeds the matrix
-// cores; the scheduling fence after each group bounds how far ahead the compiler may hoist
-// operand loads (unbounded hoisting spills).
-template <int COUNT, int GROUP, typename LoadF, typename UseG>
-__device__ __forceinline__ void for_tile_groups(LoadF &&load, UseG &&use) {
-    static_assert(COUNT % GROUP == 0, "whole groups");
-    constexpr int kGroups = COUNT / GROUP;
-    f32x4 buf[2][GROUP];
-#pragma unroll
-    for (int j = 0; j < GROUP; ++j) buf[0][j] = load(j);
-#pragma unroll
-    for (int g = 0; g < kGroups; ++g) {
-        if (g + 1 < kGroups) {
-#pragma unroll
-            for (int j = 0; j < GROUP; ++j) buf[(g + 1) & 1][j] = load((g + 1) * GROUP + j);
-        }
-        use(g, buf[g & 1]);
-        sched_fence();
-    }
-}
-
-// A dependent v_mfma_f32_16x16x4_f32 cannot issue until its predecessor has left the pipe, so
-// every product below is spread over four accumulator chains that advance in turn.
-
-// GROUP output blocks, one tile each, same input block x:  out[j] += W_j x
-template <int GROUP>
-__device__ __forceinline__ void mma_wide(f32x4 *out, const f32x4 (&t)[GROUP], f32x4 x) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int j = 0; j < GROUP; ++j) out[j] = mfma16(t[j][e], x[e], out[j]);
-}
-
-// one output block accumulated over GROUP input blocks in four chains (one per k-slice)
-struct Acc4 {
-    f32x4 c[4];
-    __device__ __forceinline__ void init(f32x4 first) {
-        c[0] = first;
-        c[1] = c[2] = c[3] = splat(0.f);
-    }
-    __device__ __forceinline__ f32x4 sum() const { return (c[0] + c[1]) + (c[2] + c[3]); }
-};
-template <int GROUP>
-__device__ __forceinline__ void mma_narrow(Acc4 &acc, const f32x4 (&t)[GROUP], const f32x4 *x) {
-#pragma unroll
-    for (int j = 0; j < GROUP; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc.c[e] = mfma16(t[j][e], x[j][e], acc.c[e]);
-}
 
 // VEC: N and Z are multiples of 4, so every per-lane load/store is one aligned float4 and the
 // hot loops are free of branches (dead lanes and pad columns are handled by clamped addresses,

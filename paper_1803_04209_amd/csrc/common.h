@@ -262,6 +262,14 @@ __host__ __device__ constexpr QuadPlan quad_plan(int zq, int hg) {
 bool quad_supported(int Z, int R, int H, int L, int N);
 int launch_quad(const ChainArgs &a, hipStream_t stream);
 
+// split.hip: the same chain with sixteen samples per workgroup, every layer split over its four
+// wavefronts.  Same arguments; stream_tiles is one stream per wavefront (pack_split, api.hip),
+// split_stream_tiles() tiles apart; bias_table is the layout of chain.hip; guide_tiles, stream_chunks
+// and mean are not used.
+bool split_supported(int Z, int R, int H, int L, int N);
+int split_stream_tiles(int Z, int R, int H, int N);  // tiles of one wavefront's stream (0: sizes not built)
+int launch_split(const ChainArgs &a, hipStream_t stream);
+
 // noise.hip: out[0..n) = standard normals of stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x); the seed
 // is read from `ctl` when that is not NULL (captured graphs), else taken from `seed`
 int launch_fill_normal3(float *out0, size_t n0, float *out1, size_t n1, float *out2, size_t n2, const Control *ctl,

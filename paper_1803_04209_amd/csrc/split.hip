@@ -1,0 +1,472 @@
+// Posterior-predictive sampling for a few thousand samples (Sec. 3.1.3): the chain of layers of
+// chain.hip -- L guide steps, the gated transition draw, the emission draw -- with sixteen samples
+// per WORKGROUP instead of per wavefront.  The four wavefronts of a workgroup work on the same
+// sixteen samples and split every layer between them, so that 4096 samples put one wavefront on
+// every SIMD of the chip while each matrix instruction still carries sixteen samples.
+//
+// How a layer is split (activation blocks of 16 features x 16 samples as in mfma16.h):
+//   wide layers   (Z -> R, Z -> H):  by output blocks; every wavefront holds the whole latent, so
+//                                    nothing is exchanged before the layer;
+//   narrow layers (R -> Z, H -> Z):  by input blocks, each wavefront using the quarter of the hidden
+//                                    features it has just computed itself; the four partial results
+//                                    are added through LDS in a fixed order ((w0 + w1) + w2) + w3,
+//                                    after which every wavefront holds the whole latent again;
+//   Z -> Z layers:                   computed by all four wavefronts alike;
+//   emission:  a wavefront owns a contiguous quarter of the workers.  For each of its 16-worker
+//              blocks it forms the mean from the whole hidden layer (gathered once through LDS),
+//              keeps it in registers, and folds it at once into ITS partial sum of the scale
+//              network's hidden layer (a split over that layer's inputs); those partial sums are
+//              added through LDS once, and the scale and the draw are again by worker block.  The
+//              emission mean never leaves registers.
+// One exchange per guide step, one for the transition, two for the emission.
+//
+// Weights: a wavefront only ever touches its own quarter of every matrix.  Its share of the guide's
+// three matrices stays in registers for the L steps; everything else is laid out, when the
+// weights are loaded (pack_split, api.hip), as one stream per wavefront in exactly the order it is
+// consumed, and flows from L2 straight into a ring of registers one block of work ahead of the
+// matrix instructions: no staging in LDS, no barrier for the weights.
+#include "common.h"
+#include "mfma_tile.h"
+#include "mfma16.h"
+
+namespace dkf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileF4 = 64;
+
+template <int ZB, int RB, int HB>
+struct SplitShape {
+    static_assert(RB % 4 == 0 && HB % 4 == 0, "hidden widths split four ways");
+    static constexpr int RQ = RB / 4, HQ = HB / 4;
+    static constexpr int kGuide = 2 * RQ * ZB + ZB * ZB;       // tiles held in registers
+    static constexpr int C = 2 * HB;                           // ring size = tiles of one emission block
+    static constexpr int kHead = 5 * HQ * ZB + 2 * ZB * ZB;    // gate1 gate2 prop1 prop2 lin tscale emean1
+    static constexpr int kHeadChunks = (kHead + C - 1) / C;
+    // tiles of one wavefront's stream for nbw worker blocks per wavefront (one spare chunk at the end:
+    // the ring always requests one chunk ahead)
+    __host__ __device__ static constexpr int stream_tiles(int nbw) {
+        return kGuide + (kHeadChunks + nbw + (nbw + 1) / 2 + 1) * C;
+    }
+};
+
+template <int ZB, int RB, int HB, bool DBG>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void sample_split(ChainArgs a) {
+    using Sh = SplitShape<ZB, RB, HB>;
+    constexpr int RQ = Sh::RQ, HQ = Sh::HQ, C = Sh::C;
+    constexpr int Z16 = ZB * 16, R16 = RB * 16, H16 = HB * 16;
+    extern __shared__ __align__(16) char lds_raw[];
+    // LDS: exchange buffers, then the encodings' table and the bias table
+    f32x4 *x_mu = reinterpret_cast<f32x4 *>(lds_raw);          // [2][4][2 ZB][64]  latent-sized partial sums
+    f32x4 *x_h1 = x_mu + 2 * 4 * 2 * ZB * kTileF4;             // [HB][64]          hidden layer of the mean
+    f32x4 *x_h2 = x_h1 + HB * kTileF4;                         // [4][HB][64]       partial hidden layer of the scale
+    float *ctx = reinterpret_cast<float *>(x_h2 + 4 * HB * kTileF4);  // [L][R16]
+    float *bias = ctx + a.L * R16;
+    const int NB = a.NB, N16 = NB * 16;
+    const int NBW = (NB + 3) / 4;  // worker blocks per wavefront
+    float *lb_comb = bias, *lb_mu = lb_comb + R16, *lb_sig = lb_mu + Z16;
+    float *lb_gate1 = lb_sig + Z16, *lb_gate2 = lb_gate1 + H16, *lb_prop1 = lb_gate2 + Z16;
+    float *lb_prop2 = lb_prop1 + H16, *lb_lin = lb_prop2 + Z16, *lb_tscale = lb_lin + Z16;
+    float *lb_emean1 = lb_tscale + Z16, *lb_escale1 = lb_emean1 + H16, *lb_emean2 = lb_escale1 + H16;
+    float *lb_escale2 = lb_emean2 + N16;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int q = lane >> 4;
+    const int S = a.S, Z = a.Z, N = a.N;
+    const int smp = blockIdx.x * 16 + (lane & 15);
+    const bool live = smp < S;
+    const int sc = live ? smp : S - 1;  // clamped sample index: lanes past the end repeat the last sample
+
+    // this wavefront's weight stream
+    const f32x4 *T = reinterpret_cast<const f32x4 *>(a.stream_tiles) + (size_t)w * Sh::stream_tiles(NBW) * kTileF4 + lane;
+    f32x4 wc[RQ][ZB], wm[ZB][RQ], wsg[ZB][ZB];
+#pragma unroll
+    for (int o = 0; o < RQ; ++o)
+#pragma unroll
+        for (int ib = 0; ib < ZB; ++ib) wc[o][ib] = T[(o * ZB + ib) * kTileF4];
+#pragma unroll
+    for (int zb = 0; zb < ZB; ++zb)
+#pragma unroll
+        for (int i = 0; i < RQ; ++i) wm[zb][i] = T[(RQ * ZB + zb * RQ + i) * kTileF4];
+#pragma unroll
+    for (int zb = 0; zb < ZB; ++zb)
+#pragma unroll
+        for (int ib = 0; ib < ZB; ++ib) wsg[zb][ib] = T[(2 * RQ * ZB + zb * ZB + ib) * kTileF4];
+    // ring of the streamed tiles: slot i holds tile i of the current chunk; taking it requests tile i
+    // of the next chunk into the same slot
+    const f32x4 *cur = T + (size_t)Sh::kGuide * kTileF4;
+    f32x4 ring[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) ring[i] = cur[i * kTileF4];
+    auto take = [&](int i) {
+        const f32x4 t = ring[i];
+        ring[i] = cur[(C + i) * kTileF4];
+        return t;
+    };
+
+    // encodings and biases -> LDS
+    {
+        // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
+        // with tanh written as 1 - 2 r
+        const int n4 = a.L * R16 / 4;
+        for (int i = tid; i < n4; i += kThreads) {
+            const int t = (i * 4) / R16, r = (i * 4) % R16;
+            const f32x4 f = *reinterpret_cast<const f32x4 *>(a.ctx_f + (size_t)t * a.Rp + r);
+            const f32x4 b = *reinterpret_cast<const f32x4 *>(a.ctx_b + (size_t)t * a.Rp + r);
+            reinterpret_cast<f32x4 *>(ctx)[i] = (f + b + splat(1.0f)) * (1.0f / 3.0f);
+        }
+        const int b4 = (R16 + 6 * Z16 + 4 * H16 + 2 * N16) / 4;
+        const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(a.bias_table);
+        for (int i = tid; i < b4; i += kThreads) reinterpret_cast<f32x4 *>(bias)[i] = bsrc[i];
+    }
+    __syncthreads();
+    auto bias4 = [&](const float *tab, int blk) { return *reinterpret_cast<const f32x4 *>(tab + blk * 16 + 4 * q); };
+    auto z_valid = [&](int zb, int v) { return zb * 16 + 4 * q + v < Z; };
+    auto load_z_noise = [&](const float *base, int zb) {  // base -> [S][Z]; Z is a multiple of 4
+        const int f0 = zb * 16 + 4 * q;
+        const int fc = f0 < Z ? f0 : Z - 4;  // clamped: always a valid address
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(base + (size_t)sc * Z + fc);
+        return t * (f0 < Z ? 1.f : 0.f);
+    };
+    auto relu4 = [](f32x4 v) { return map4(v, [](float u) { return fmaxf(u, 0.f); }); };
+    auto softplus4 = [](f32x4 v) { return map4(v, [](float u) { return softplus_f(u); }); };
+
+    // Sum of the four wavefronts' partial blocks p[0..n), in the order ((w0 + w1) + w2) + w3; every
+    // wavefront ends up with the same full result.  Two buffers alternate, so one barrier per call.
+    int xbuf = 0;
+    auto all_sum = [&](auto &p) {
+        constexpr int n = sizeof(p) / sizeof(p[0]);
+        static_assert(n <= 2 * ZB, "exchange buffer size");
+        f32x4 *mine = x_mu + ((xbuf * 4 + w) * 2 * ZB) * kTileF4 + lane;
+#pragma unroll
+        for (int i = 0; i < n; ++i) mine[i * kTileF4] = p[i];
+        __syncthreads();
+        const f32x4 *all = x_mu + (xbuf * 4 * 2 * ZB) * kTileF4 + lane;
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const f32x4 *e = all + i * kTileF4;
+            p[i] = ((e[0] + e[2 * ZB * kTileF4]) + e[2 * 2 * ZB * kTileF4]) + e[3 * 2 * ZB * kTileF4];
+        }
+        xbuf ^= 1;
+    };
+
+    f32x4 z[ZB];
+#pragma unroll
+    for (int zb = 0; zb < ZB; ++zb) z[zb] = reinterpret_cast<const f32x4 *>(a.z0)[zb * 4 + q];
+
+    // ---- guide chain ------------------------------------------------------------------
+    f32x4 eps[ZB];
+#pragma unroll
+    for (int zb = 0; zb < ZB; ++zb) eps[zb] = load_z_noise(a.eps_q, zb);
+    for (int t = 0; t < a.L; ++t) {
+        f32x4 eps_next[ZB];  // next step's noise is fetched while this step computes
+        const int tn = t + 1 < a.L ? t + 1 : t;
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) eps_next[zb] = load_z_noise(a.eps_q + (size_t)tn * S * Z, zb);
+        // this wavefront's quarter of h_out = (tanh(W z + b) + h_left + h_right) / 3
+        f32x4 h[RQ];
+#pragma unroll
+        for (int o = 0; o < RQ; ++o) h[o] = bias4(lb_comb, w * RQ + o);
+#pragma unroll
+        for (int ib = 0; ib < ZB; ++ib) {
+            f32x4 tl[RQ];
+#pragma unroll
+            for (int o = 0; o < RQ; ++o) tl[o] = wc[o][ib];
+            mma_wide<RQ>(h, tl, z[ib]);
+        }
+        const float *ctx_t = ctx + t * R16 + 4 * q;
+#pragma unroll
+        for (int o = 0; o < RQ; ++o) {
+            const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + (w * RQ + o) * 16);  // (1 + h_left + h_right) / 3
+            const f32x4 r = map4(h[o], [](float v) { return fast_rcp(__expf(2.0f * v) + 1.0f); });
+            h[o] = r * (-2.0f / 3.0f) + c;
+        }
+        // mean: partial product over this wavefront's hidden features, then the sum over wavefronts
+        f32x4 mu[ZB];
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) {
+            Acc4 acc;
+            acc.init(splat(0.f));
+            f32x4 tl[RQ];
+#pragma unroll
+            for (int i = 0; i < RQ; ++i) tl[i] = wm[zb][i];
+            mma_narrow<RQ>(acc, tl, h);
+            mu[zb] = acc.sum();
+        }
+        all_sum(mu);
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) mu[zb] = mu[zb] + bias4(lb_mu, zb);
+        // scale from the mean, reparameterised draw (all wavefronts alike)
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) {
+            Acc4 acc;
+            acc.init(bias4(lb_sig, zb));
+#pragma unroll
+            for (int ib = 0; ib < ZB; ++ib) {
+                const f32x4 tl[1] = {wsg[zb][ib]};
+                mma_narrow<1>(acc, tl, &mu[ib]);
+            }
+            z[zb] = mu[zb] + softplus4(acc.sum()) * eps[zb];
+            eps[zb] = eps_next[zb];
+        }
+    }
+    auto store_z = [&](float *dst, int zb, f32x4 v) {
+        if (!DBG || !dst || !live || w != 0) return;
+        float *p = dst + (size_t)smp * Z + zb * 16 + 4 * q;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (z_valid(zb, k)) p[k] = v[k];
+    };
+#pragma unroll
+    for (int zb = 0; zb < ZB; ++zb) store_z(a.z_last, zb, z[zb]);
+
+    // ---- gated transition -----------------------------------------------------------------
+    // ring positions of the head of the stream (compile-time): gate1, gate2, prop1, prop2, lin, tscale, emean1
+    constexpr int pG1 = 0, pG2 = pG1 + HQ * ZB, pP1 = pG2 + ZB * HQ, pP2 = pP1 + HQ * ZB, pLin = pP2 + ZB * HQ,
+                  pTs = pLin + ZB * ZB, pE1 = pTs + ZB * ZB;
+    static_assert(pE1 + HQ * ZB == Sh::kHead, "head layout");
+    // The head may span several chunks of the ring; `head_take` follows a compile-time position.
+    int head_chunk = 0;
+    auto head_take = [&](int pos) {  // positions are visited in increasing order
+        if (pos / C != head_chunk) { cur += C * kTileF4; head_chunk = pos / C; }
+        return take(pos % C);
+    };
+    // this wavefront's quarter of a Z -> H layer
+    auto wide_quarter = [&](f32x4(&out)[HQ], const float *tab, int pos, const f32x4(&x)[ZB]) {
+        f32x4 tl[ZB][HQ];  // stream order [o][ib]; all tiles first, so that the HQ accumulator chains can advance in turn
+#pragma unroll
+        for (int o = 0; o < HQ; ++o)
+#pragma unroll
+            for (int ib = 0; ib < ZB; ++ib) tl[ib][o] = head_take(pos + o * ZB + ib);
+#pragma unroll
+        for (int o = 0; o < HQ; ++o) out[o] = bias4(tab, w * HQ + o);
+#pragma unroll
+        for (int ib = 0; ib < ZB; ++ib) mma_wide<HQ>(out, tl[ib], x[ib]);
+    };
+    // partial product of an H -> Z layer over this wavefront's quarter of the hidden features (no bias)
+    auto narrow_quarter = [&](f32x4(&out)[ZB], int pos, const f32x4(&x)[HQ]) {
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) {
+            Acc4 acc;
+            acc.init(splat(0.f));
+#pragma unroll
+            for (int i = 0; i < HQ; ++i) {  // stream order [zb][i]
+                const f32x4 tl[1] = {head_take(pos + zb * HQ + i)};
+                mma_narrow<1>(acc, tl, &x[i]);
+            }
+            out[zb] = acc.sum();
+        }
+    };
+    auto small_layer = [&](f32x4(&out)[ZB], const float *tab, int pos, const f32x4(&x)[ZB]) {
+#pragma unroll
+        for (int ob = 0; ob < ZB; ++ob) {
+            Acc4 acc;
+            acc.init(bias4(tab, ob));
+#pragma unroll
+            for (int ib = 0; ib < ZB; ++ib) {
+                const f32x4 tl[1] = {head_take(pos + ob * ZB + ib)};
+                mma_narrow<1>(acc, tl, &x[ib]);
+            }
+            out[ob] = acc.sum();
+        }
+    };
+
+    f32x4 zn[ZB];
+    {
+        f32x4 hid[HQ], g[ZB], prop[ZB], gp[2 * ZB], lin[ZB], G[ZB], rG[ZB], pre[ZB];
+        wide_quarter(hid, lb_gate1, pG1, z);
+#pragma unroll
+        for (int o = 0; o < HQ; ++o) hid[o] = relu4(hid[o]);
+        narrow_quarter(g, pG2, hid);
+        wide_quarter(hid, lb_prop1, pP1, z);
+#pragma unroll
+        for (int o = 0; o < HQ; ++o) hid[o] = relu4(hid[o]);
+        narrow_quarter(prop, pP2, hid);
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) { gp[zb] = g[zb]; gp[ZB + zb] = prop[zb]; }
+        all_sum(gp);  // gate and proposed mean in one exchange
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) { g[zb] = gp[zb]; prop[zb] = gp[ZB + zb]; }
+        small_layer(lin, lb_lin, pLin, z);
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) {
+            const f32x4 gate = map4(g[zb] + bias4(lb_gate2, zb), [](float v) { return sigmoid_f(v); });
+            G[zb] = (splat(1.f) - gate) * lin[zb] + gate * (prop[zb] + bias4(lb_prop2, zb));
+            rG[zb] = relu4(G[zb]);
+        }
+        small_layer(pre, lb_tscale, pTs, rG);
+#pragma unroll
+        for (int zb = 0; zb < ZB; ++zb) {
+            const f32x4 e = load_z_noise(a.eps_z, zb);
+            zn[zb] = G[zb] + softplus4(pre[zb]) * e;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (!z_valid(zb, v)) zn[zb][v] = 0.f;
+            store_z(a.z_next_dbg, zb, zn[zb]);
+        }
+    }
+
+    // ---- emission ---------------------------------------------------------------------------
+    // noise of this wavefront's worker blocks, requested now
+    const float scale = a.ctl->scale;
+    float *sink = a.sink + tid * 4;
+    const int nb0 = w * NBW;
+    auto load_eps_x = [&](int nb) {
+        const int n0 = nb * 16 + 4 * q;
+        const int nc = n0 < N ? n0 : N - 4;
+        return *reinterpret_cast<const f32x4 *>(a.eps_x + (size_t)sc * N + nc);
+    };
+    // hidden layer of the mean: own quarter, then gathered from all wavefronts
+    f32x4 h1[HB];
+    {
+        f32x4 own[HQ];
+        wide_quarter(own, lb_emean1, pE1, zn);
+        if (a.emit_mean_act) {
+#pragma unroll
+            for (int o = 0; o < HQ; ++o) own[o] = relu4(own[o]);
+        }
+#pragma unroll
+        for (int o = 0; o < HQ; ++o) x_h1[(w * HQ + o) * kTileF4 + lane] = own[o];
+        __syncthreads();
+#pragma unroll
+        for (int ob = 0; ob < HB; ++ob) h1[ob] = x_h1[ob * kTileF4 + lane];
+    }
+    // the rest of the head's last chunk is padding: taking it lets the ring request the next chunk's tiles
+#pragma unroll
+    for (int pos = Sh::kHead; pos < Sh::kHeadChunks * C; ++pos) (void)head_take(pos);
+    cur += C * kTileF4;  // the ring now holds the first emission block
+    // Mean of each own 16-worker block (kept in registers) and its contribution to the scale network's
+    // hidden layer.  One block = one chunk of the ring: HB tiles of the mean's second layer (row nb)
+    // followed by HB tiles of the scale network's first layer (column nb).
+    constexpr int kMaxBlocks = 8;  // worker blocks per wavefront held in registers (N <= 512)
+    f32x4 mean_own[kMaxBlocks], h2[HB];
+#pragma unroll
+    for (int ob = 0; ob < HB; ++ob) h2[ob] = splat(0.f);
+#pragma unroll
+    for (int u = 0; u < kMaxBlocks; ++u) {
+        if (u < NBW) {
+            const int nb = nb0 + u < NB ? nb0 + u : NB - 1;  // past the end: zero tiles, nothing kept
+            Acc4 acc;
+            acc.init(bias4(lb_emean2, nb));
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const f32x4 tl[1] = {take(i)};
+                mma_narrow<1>(acc, tl, &h1[i]);
+            }
+            const f32x4 m = acc.sum();
+            mean_own[u] = m;
+#pragma unroll
+            for (int g4 = 0; g4 < HB / 4; ++g4) {
+                f32x4 tl[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) tl[j] = take(HB + g4 * 4 + j);
+                mma_wide<4>(&h2[g4 * 4], tl, m);
+            }
+            cur += C * kTileF4;
+        }
+    }
+    // sum of the partial hidden layers over the wavefronts, bias, ReLU
+#pragma unroll
+    for (int ob = 0; ob < HB; ++ob) x_h2[(w * HB + ob) * kTileF4 + lane] = h2[ob];
+    __syncthreads();
+#pragma unroll
+    for (int ob = 0; ob < HB; ++ob) {
+        const f32x4 *e = x_h2 + ob * kTileF4 + lane;
+        const f32x4 s = ((e[0] + e[HB * kTileF4]) + e[2 * HB * kTileF4]) + e[3 * HB * kTileF4];
+        h2[ob] = relu4(s + bias4(lb_escale1, ob));
+    }
+    // scale, draw, back to seconds: two worker blocks per chunk of the ring
+    auto emit = [&](int nb_raw, f32x4 pre, f32x4 m, f32x4 e) {
+        const int n0 = nb_raw * 16 + 4 * q;
+        const f32x4 sd = softplus4(pre);
+        const f32x4 x = (m + sd * e) * scale;
+        // lanes past the last sample repeat sample S - 1 exactly (a harmless duplicate store); columns
+        // past N and blocks past the end go to the sink
+        float *xp = (nb_raw < NB && n0 < N) ? a.out_samples + (size_t)sc * N + n0 : sink;
+        *reinterpret_cast<f32x4 *>(xp) = x;
+        if constexpr (DBG) {
+            if (live && nb_raw < NB) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (n0 + v >= N) continue;
+                    if (a.out_mean_dbg) a.out_mean_dbg[(size_t)smp * N + n0 + v] = m[v];
+                    if (a.out_sd_dbg) a.out_sd_dbg[(size_t)smp * N + n0 + v] = sd[v];
+                }
+            }
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < kMaxBlocks; ++u) {
+        if (u < NBW) {
+            const int nb_raw = nb0 + u, nb = nb_raw < NB ? nb_raw : NB - 1;
+            const f32x4 e = load_eps_x(nb);
+            Acc4 acc;
+            acc.init(bias4(lb_escale2, nb));
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const f32x4 tl[1] = {take((u & 1) * HB + i)};
+                mma_narrow<1>(acc, tl, &h2[i]);
+            }
+            emit(nb_raw, acc.sum(), mean_own[u], e);
+            if (u & 1) cur += C * kTileF4;
+        }
+    }
+}
+
+template <int ZB, int RB, int HB>
+size_t split_lds_bytes(int L, int N) {
+    const size_t nb16 = (size_t)((N + 15) / 16) * 16;
+    const size_t bias_floats = RB * 16 + 6 * ZB * 16 + 4 * HB * 16 + 2 * nb16;
+    return (size_t)(2 * 4 * 2 * ZB + HB + 4 * HB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
+}
+
+template <int ZB, int RB, int HB, bool DBG>
+int launch_variant(const ChainArgs &a, size_t lds, hipStream_t stream) {
+    static size_t raised = 0;  // largest LDS size the attribute has been set to
+    if (lds > raised) {
+        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_split<ZB, RB, HB, DBG>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        raised = lds;
+    }
+    hipLaunchKernelGGL((sample_split<ZB, RB, HB, DBG>), dim3((a.S + 15) / 16), dim3(kThreads), lds, stream, a);
+    DKF_HIP_TRY(hipGetLastError());
+    return DKF_OK;
+}
+
+template <int ZB, int RB, int HB>
+int launch_one(const ChainArgs &a, hipStream_t stream) {
+    const size_t lds = split_lds_bytes<ZB, RB, HB>(a.L, a.N);
+    if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
+    const bool dbg = a.z_last || a.z_next_dbg || a.out_mean_dbg || a.out_sd_dbg;
+    return dbg ? launch_variant<ZB, RB, HB, true>(a, lds, stream) : launch_variant<ZB, RB, HB, false>(a, lds, stream);
+}
+
+}  // namespace
+
+// Sizes the kernel is built for: the latent and the widths of the two larger fp32 presets, at most
+// 512 workers (eight 16-worker blocks per wavefront stay in registers), N and Z multiples of 4.
+bool split_supported(int Z, int R, int H, int L, int N) {
+    const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16;
+    if (N < 4 || N > 512 || (N & 3) != 0 || Z < 4 || (Z & 3) != 0) return false;
+    if (zb == 1 && rb == 8 && hb == 8) return split_lds_bytes<1, 8, 8>(L, N) <= 160 * 1024;
+    if (zb == 2 && rb == 16 && hb == 16) return split_lds_bytes<2, 16, 16>(L, N) <= 160 * 1024;
+    return false;
+}
+
+int split_stream_tiles(int Z, int R, int H, int N) {
+    const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16, nbw = ((N + 15) / 16 + 3) / 4;
+    if (zb == 1 && rb == 8 && hb == 8) return SplitShape<1, 8, 8>::stream_tiles(nbw);
+    if (zb == 2 && rb == 16 && hb == 16) return SplitShape<2, 16, 16>::stream_tiles(nbw);
+    return 0;
+}
+
+int launch_split(const ChainArgs &a, hipStream_t stream) {
+    StageTimer timer(kStageSampler, stream);
+    const int zb = (a.Z + 15) / 16, rb = (a.R + 15) / 16, hb = (a.H + 15) / 16;
+    if (!split_supported(a.Z, a.R, a.H, a.L, a.N)) return DKF_EUNSUPPORTED;
+    if (zb == 1 && rb == 8 && hb == 8) return launch_one<1, 8, 8>(a, stream);
+    if (zb == 2 && rb == 16 && hb == 16) return launch_one<2, 16, 16>(a, stream);
+    return DKF_EUNSUPPORTED;
+}
+
+}  // namespace dkf

@@ -33,7 +33,7 @@ def cuda(*arrays):
 
 
 # kernel variants of the sampling stage (dkf_set_sampler): every one must meet the same tolerance
-WAVE16, WAVE4, STAGED = 1, 2, 3
+WAVE16, WAVE4, STAGED, SPLIT = 1, 2, 3, 4
 
 
 def make_pair(api, cfg, weights=None, act=0, pushes=None, std=0.1, mlp_dtype=None, sampler=0):
@@ -102,6 +102,24 @@ def test_fused_sampler_tails(api, cfg, act, sampler):
     g.close()
 
 
+@pytest.mark.parametrize("cfg", [
+    custom(N=100, L=4, Z=16, H=128, R=128, S=130), custom(N=128, L=2, Z=12, H=120, R=113, S=50),
+    custom(N=500, L=3, Z=32, H=256, R=256, S=40), custom(N=36, L=5, Z=20, H=250, R=244, S=17),
+    custom(N=512, L=2, Z=28, H=241, R=256, S=16), custom(N=4, L=1, Z=4, H=128, R=128, S=1)],
+    ids=["medium-like", "pad-features", "contended-like", "ragged", "full-width", "smallest"])
+@pytest.mark.parametrize("act", [0, 1])
+def test_split_sampler_tails(api, cfg, act):
+    """The sixteen-samples-per-workgroup kernel: ragged worker blocks (whole wavefronts without a
+    block of their own), pad features in every width, a partial last workgroup."""
+    g, o, _ = make_pair(api, cfg, act=act, std=0.3, sampler=SPLIT)
+    compare_stages(api, cfg, g, o)
+    eq, ez, ex = synth.make_noise(cfg)
+    x_plain = g.sample_runtimes(*cuda(eq, ez, ex))  # variant without the per-stage outputs
+    xo = o.sample_runtimes(eq, ez, ex)
+    assert rel_err(x_plain.cpu().numpy(), xo) <= TOL
+    g.close()
+
+
 def test_tiny_preset_every_decision_position(api):
     cfg = synth.CONFIGS["tiny"]
     g, o, tr = make_pair(api, cfg)
@@ -113,7 +131,7 @@ def test_tiny_preset_every_decision_position(api):
     g.close()
 
 
-@pytest.mark.parametrize("sampler", [WAVE16, WAVE4], ids=["wave16", "wave4"])
+@pytest.mark.parametrize("sampler", [WAVE16, WAVE4, SPLIT], ids=["wave16", "wave4", "split"])
 def test_medium_preset_full_size(api, sampler):
     cfg = synth.CONFIGS["medium"]
     g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 3, sampler=sampler)
@@ -122,7 +140,7 @@ def test_medium_preset_full_size(api, sampler):
 
 
 @pytest.mark.parametrize("name", ["contended", "replay"])
-@pytest.mark.parametrize("sampler", [WAVE16, WAVE4], ids=["wave16", "wave4"])
+@pytest.mark.parametrize("sampler", [WAVE16, WAVE4, SPLIT], ids=["wave16", "wave4", "split"])
 def test_large_fp32_presets_sampled_rows(api, name, sampler):
     cfg = synth.CONFIGS[name]
     g, o, tr = make_pair(api, cfg, pushes=cfg.lag + 2, sampler=sampler)
@@ -445,7 +463,7 @@ def test_sampler_variant_selection(api):
     """A variant the model's sizes rule out is refused and the current one stays."""
     cfg = custom(N=130, L=3, Z=70, H=129, R=200, S=33)  # latent too wide for both fused kernels
     g = api.Predictor(cfg, synth.make_blob(cfg))
-    for v in (WAVE16, WAVE4):
+    for v in (WAVE16, WAVE4, SPLIT):
         with pytest.raises(api.DkfError):
             g.set_sampler(v)
     g.set_sampler(STAGED)
