@@ -44,7 +44,12 @@ def sort_compare_exchanges(S, N):
 
 
 def stage_work(cfg):
-    """Algorithmic flops (MLP stages) and bytes (sort) of one decision, per stage id."""
+    """Algorithmic flops (MLP stages) and bytes (sort) of one decision, per stage id.
+
+    The bf16 emission runs as three kernels: the scale network's first layer is folded with the mean's
+    output layer into one H x H layer when the weights are loaded (counted as executed, 2 S H H, not
+    as the 2 S N H of the layer it replaces), and one kernel multiplies both N-wide output layers and
+    draws (stage 5 carries both, stage 3 has no kernel of its own)."""
     S, N, L, Z, H, R = cfg.samples, cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim
     work = {
         1: ("mfma", 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)),
@@ -55,6 +60,10 @@ def stage_work(cfg):
         6: ("hbm", 4.0 * S * N),
     }
     work[8] = ("mfma", sum(work[s][1] for s in range(1, 6)))  # the fused sampler kernel does stages 1-5
+    if cfg.mlp_dtype == "bf16":
+        del work[3]
+        work[4] = ("mfma", 2.0 * S * H * H)
+        work[5] = ("mfma", 4.0 * S * H * N)
     return work
 
 

@@ -61,6 +61,7 @@ typedef struct {
     /* mixed-precision mode (MLP matrices and MLP inputs rounded to bf16, everything else as before):
      * the same tensors as `store`, every value rounded; see oracle_set_mlp_bf16 */
     double *store_bf16;
+    double *fold_w, *fold_b; /* [H][H], [H]: J's first layer applied to I's hidden vector, see oracle_set_mlp_bf16 */
     int mlp_bf16;
     /* fixed-lag window of raw observations, oldest first */
     double *window; /* [L][N] */
@@ -99,6 +100,8 @@ void oracle_free(oracle_model *m) {
     if (!m) return;
     free(m->store);
     free(m->store_bf16);
+    free(m->fold_w);
+    free(m->fold_b);
     free(m->window);
     free(m);
 }
@@ -172,13 +175,31 @@ double oracle_round_bf16(double v) {
  * K(h_out) with h_out = (tanh(.) + h_left + h_right)/3 is linear, so the encodings' share
  * W (h_left + h_right)/3 + b is the same for every sample: it is formed once per window position
  * in full precision with the unrounded matrix, and only the per-sample term W tanh(.)/3 is a
- * product of rounded operands. */
+ * product of rounded operands.  Likewise in the emission: I ends in a linear layer, mean = W2 h + b2,
+ * and J's first layer is linear in the mean, so J's hidden pre-activation is
+ * W1' mean + b1' = (W1' W2) h + (W1' b2 + b1'): the H x H matrix W1' W2 is formed once from the
+ * unrounded matrices, then rounded like any other matrix, and multiplies the rounded h; the bias
+ * W1' b2 + b1' is not rounded.  The mean itself, W2 h + b2, stays a product of rounded operands.
+ * (With rounding off none of this applies: every layer is evaluated as the paper writes it.) */
 int oracle_set_mlp_bf16(oracle_model *m, int on) {
     if (on && !m->store_bf16) {
         size_t nf = blob_floats(&m->cfg);
+        size_t N = m->cfg.n_workers, H = m->cfg.hidden;
         m->store_bf16 = (double *)malloc(nf * sizeof(double));
-        if (!m->store_bf16) return ORACLE_EINVAL;
+        m->fold_w = (double *)malloc(H * H * sizeof(double));
+        m->fold_b = (double *)malloc(H * sizeof(double));
+        if (!m->store_bf16 || !m->fold_w || !m->fold_b) return ORACLE_EINVAL;
         for (size_t i = 0; i < nf; ++i) m->store_bf16[i] = oracle_round_bf16(m->store[i]);
+        for (size_t o = 0; o < H; ++o) {
+            for (size_t i = 0; i < H; ++i) {
+                double acc = 0.0;
+                for (size_t n = 0; n < N; ++n) acc += m->escale1_w[o * N + n] * m->emean2_w[n * H + i];
+                m->fold_w[o * H + i] = oracle_round_bf16(acc);
+            }
+            double acc = m->escale1_b[o];
+            for (size_t n = 0; n < N; ++n) acc += m->escale1_w[o * N + n] * m->emean2_b[n];
+            m->fold_b[o] = acc;
+        }
     }
     m->mlp_bf16 = on ? 1 : 0;
     return ORACLE_OK;
@@ -388,7 +409,13 @@ static void sample_one(const oracle_model *m, const double *hl, const double *hr
     if (m->cfg.emit_mean_act == 1)
         for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
     mlp_layer(m, m->emean2_w, m->emean2_b, w->hid, H, N, w->mean, w->xq);
-    mlp_layer(m, m->escale1_w, m->escale1_b, w->mean, N, H, w->hid, w->xq);
+    if (!m->mlp_bf16) {
+        mlp_layer(m, m->escale1_w, m->escale1_b, w->mean, N, H, w->hid, w->xq);
+    } else {
+        /* the same layer on I's hidden vector, as oracle_set_mlp_bf16 describes */
+        for (int i = 0; i < H; ++i) w->xq[i] = oracle_round_bf16(w->hid[i]);
+        affine(m->fold_w, m->fold_b, w->xq, H, H, w->hid);
+    }
     for (int i = 0; i < H; ++i) w->hid[i] = relu(w->hid[i]);
     mlp_layer(m, m->escale2_w, m->escale2_b, w->hid, H, N, w->sd, w->xq);
     for (int j = 0; j < N; ++j) {

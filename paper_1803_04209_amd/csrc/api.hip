@@ -85,7 +85,8 @@ struct dkf_model {
     // emission layers and activations in fragment order (egemm.hip), bf16 models with use_gchain
     const float *ef_w[4] = {}, *ef_b[4] = {};  // emean1, emean2, escale1, escale2
     int ef_Hp = 0, ef_Np = 0, ef_samp_tiles = 0;
-    float *zfrag = nullptr, *h1frag = nullptr, *h2frag = nullptr, *meanfrag = nullptr, *mean_tiles = nullptr;
+    float *zfrag = nullptr, *h1frag = nullptr, *h2frag = nullptr;
+
 
     // filter state
     float *d_in = nullptr;  // [Np] observation + Control
@@ -417,15 +418,34 @@ int pack_frag_layer(dkf_model *m, const float *w, const float *b, int n_out, int
     return rc;
 }
 
+// The bf16 emission (egemm.hip).  The mean ends in a linear layer and the scale network's first
+// layer is linear in the mean, so the two are folded once, in double precision, into one H x H
+// layer on the mean's hidden vector: M = W_J1 W_I2, c = W_J1 b_I2 + b_J1 (Sec. 3.1.3, J = MLP_2(I(z))).
 int pack_emission_frags(dkf_model *m, const RawLayers &r) {
-    const int Hp = round_up(m->H, 128), Np = round_up(m->N, 256);  // N-wide layers may run in 256-feature tiles
+    const int H = m->H, N = m->N;
+    const int Hp = round_up(H, 128), Np = round_up(N, 128);
     m->ef_Hp = Hp; m->ef_Np = Np;
-    m->ef_samp_tiles = (m->cfg.max_samples + 127) / 128;
-    int rc = pack_frag_layer(m, r.emean1, r.b_emean1, m->H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
-    if (rc == DKF_OK) rc = pack_frag_layer(m, r.emean2, r.b_emean2, m->N, m->H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
-    if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale1, r.b_escale1, m->H, m->N, Hp, Np, &m->ef_w[2], &m->ef_b[2]);
-    if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale2, r.b_escale2, m->N, m->H, Np, Hp, &m->ef_w[3], &m->ef_b[3]);
-    const size_t blocks = (size_t)m->ef_samp_tiles * 4;  // 32-sample blocks
+    m->ef_samp_tiles = (m->cfg.max_samples + 255) / 256;
+    std::vector<double> fold((size_t)H * H, 0.0), fold_b(H);
+    for (int o = 0; o < H; ++o) {
+        double *row = fold.data() + (size_t)o * H;
+        double b = r.b_escale1[o];
+        for (int n = 0; n < N; ++n) {
+            const double w = r.escale1[(size_t)o * N + n];
+            const float *src = r.emean2 + (size_t)n * H;
+            for (int i = 0; i < H; ++i) row[i] += w * src[i];
+            b += w * r.b_emean2[n];
+        }
+        fold_b[o] = b;
+    }
+    std::vector<float> fold_w((size_t)H * H), fold_bf(H);
+    for (size_t i = 0; i < fold.size(); ++i) fold_w[i] = (float)fold[i];
+    for (int o = 0; o < H; ++o) fold_bf[o] = (float)fold_b[o];
+    int rc = pack_frag_layer(m, r.emean1, r.b_emean1, H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, r.emean2, r.b_emean2, N, H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, fold_w.data(), fold_bf.data(), H, H, Hp, Hp, &m->ef_w[2], &m->ef_b[2]);
+    if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale2, r.b_escale2, N, H, Np, Hp, &m->ef_w[3], &m->ef_b[3]);
+    const size_t blocks = (size_t)m->ef_samp_tiles * 8;  // 32-sample blocks
     void *q = nullptr;
     if (rc == DKF_OK) rc = dev_alloc(m, blocks * 4 * 1024, &q, true);
     m->zfrag = static_cast<float *>(q);
@@ -433,37 +453,28 @@ int pack_emission_frags(dkf_model *m, const RawLayers &r) {
     m->h1frag = static_cast<float *>(q);
     if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Hp / 16) * 1024, &q, true);
     m->h2frag = static_cast<float *>(q);
-    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Np / 16) * 1024, &q, true);
-    m->meanfrag = static_cast<float *>(q);
-    if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Np / 32) * 4096, &q, true);
-    m->mean_tiles = static_cast<float *>(q);
     return rc;
 }
 
-// The four emission layers on fragments; z_{T+1} fragments come from the guide/transition kernel.
+// The emission on fragments: the mean's hidden layer, the scale's hidden layer (folded), and both
+// output layers with the draw; z_{T+1} fragments come from the guide/transition kernel.
 int enqueue_emission_frags(dkf_model *m, int S, const float *eps_x, float *out_samples, const dkf_stage_outputs *st,
                            hipStream_t stream) {
     FragGemmArgs e{};
     e.S = S; e.N = m->N; e.ctl = m->ctl_dev();
     const int Hp = m->ef_Hp, Np = m->ef_Np;
-    const int st128 = (S + 127) / 128;
-    // N-wide layers: 256-feature tiles once that still gives every compute unit about two workgroups
-    const bool big = (Np / 256) * st128 >= 384;
-    auto wide_tiles = [&] { e.tile = big ? 4 : 2; e.feat_tiles = big ? Np / 256 : Np / 128; e.samp_tiles = st128; };
-    auto narrow_tiles = [&] { e.tile = 2; e.feat_tiles = Hp / 128; e.samp_tiles = st128; };
+    e.tile = 2; e.samp_tiles = (S + 255) / 256;
     int rc;
-    e.wfrag = m->ef_w[0]; e.bias = m->ef_b[0]; e.xfrag = m->zfrag; e.k_steps = 4; narrow_tiles();
+    e.wfrag = m->ef_w[0]; e.bias = m->ef_b[0]; e.xfrag = m->zfrag; e.k_steps = 4; e.feat_tiles = Hp / 64;
     e.epilogue = m->cfg.emit_mean_act ? kFragRelu : kFragIdentity;
     e.out_frag = m->h1frag; e.out_k_steps = Hp / 16;
     if ((rc = launch_frag_gemm(e, kStageEmitHidden, stream)) != DKF_OK) return rc;
-    e.wfrag = m->ef_w[1]; e.bias = m->ef_b[1]; e.xfrag = m->h1frag; e.k_steps = Hp / 16; wide_tiles();
-    e.epilogue = kFragMean; e.out_frag = m->meanfrag; e.out_k_steps = Np / 16;
-    e.mean_tiles = m->mean_tiles; e.mean_blocks = Np / 32;
-    if ((rc = launch_frag_gemm(e, kStageEmitMean, stream)) != DKF_OK) return rc;
-    e.wfrag = m->ef_w[2]; e.bias = m->ef_b[2]; e.xfrag = m->meanfrag; e.k_steps = Np / 16; narrow_tiles();
-    e.epilogue = kFragRelu; e.out_frag = m->h2frag; e.out_k_steps = Hp / 16;
+    e.wfrag = m->ef_w[2]; e.bias = m->ef_b[2]; e.xfrag = m->h1frag; e.k_steps = Hp / 16;
+    e.epilogue = kFragRelu; e.out_frag = m->h2frag;
     if ((rc = launch_frag_gemm(e, kStageEmitScaleHidden, stream)) != DKF_OK) return rc;
-    e.wfrag = m->ef_w[3]; e.bias = m->ef_b[3]; e.xfrag = m->h2frag; e.k_steps = Hp / 16; wide_tiles();
+    e.wfrag = m->ef_w[3]; e.bias = m->ef_b[3]; e.xfrag = m->h2frag;
+    e.wfrag2 = m->ef_w[1]; e.bias2 = m->ef_b[1]; e.xfrag2 = m->h1frag;
+    e.feat_tiles = Np / 64;
     e.epilogue = kFragDraw; e.out_frag = nullptr; e.out_k_steps = 0;
     e.eps_x = eps_x; e.out_samples = out_samples;
     e.out_mean_dbg = st ? st->emit_mean : nullptr;

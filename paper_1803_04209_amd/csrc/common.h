@@ -164,19 +164,17 @@ int launch_gchain(const GChainArgs &a, hipStream_t stream);
 enum FragEpilogue : int {
     kFragIdentity = 0,  // y -> bf16 fragments
     kFragRelu = 1,      // relu(y) -> bf16 fragments
-    kFragMean = 2,      // y -> bf16 fragments and fp32 result tiles
-    kFragDraw = 3,      // sd = softplus(y); x = s * (mean + sd * eps) -> [S][N] rows
+    kFragDraw = 2,      // mean = y2; sd = softplus(y); x = s * (mean + sd * eps) -> [S][N] rows
 };
 struct FragGemmArgs {
-    int tile;            // workgroups of 64 * tile features x 128 samples: 2 or 4
-    const float *wfrag;  // [32-feature block][k_steps][64][16 B], feat_tiles * 2 * tile blocks
-    const float *xfrag;  // [32-sample block][k_steps][64][16 B], samp_tiles * 2 * tile blocks
+    int tile;            // workgroups of 32 * tile features x 256 samples: 2 or 4
+    const float *wfrag;  // [32-feature block][k_steps][64][16 B], feat_tiles * tile blocks
+    const float *xfrag;  // [32-sample block][k_steps][64][16 B], samp_tiles * 8 blocks
     const float *bias;   // fp32 per feature, zero padded
     int k_steps, feat_tiles, samp_tiles, epilogue;
     float *out_frag;     // [32-sample block][out_k_steps][64][16 B], out_k_steps = padded features / 16
     int out_k_steps;
-    float *mean_tiles;   // kFragMean: out, kFragDraw: in; [32-sample block][mean_blocks][4][64] float4
-    int mean_blocks;     // padded N / 32
+    const float *wfrag2, *xfrag2, *bias2;  // kFragDraw: the mean's product, same shapes as wfrag, xfrag, bias
     const Control *ctl;  // kFragDraw: the normaliser
     const float *eps_x;  // [S][N]
     float *out_samples, *out_mean_dbg, *out_sd_dbg;  // [S][N]

@@ -26,6 +26,11 @@ def test_stage_work_matches_the_layer_sizes():
     assert [w[s][1] for s in (2, 3, 4, 5)] == [2.0 * S * Z * H, 2.0 * S * H * N, 2.0 * S * N * H, 2.0 * S * H * N]
     assert w[8][1] == sum(w[s][1] for s in range(1, 6))
     assert w[6] == ("hbm", 4.0 * S * N)
+    # bf16: the folded H x H layer is counted as executed, both N-wide output layers run in the draw kernel
+    cfg = synth.CONFIGS["large_bf16"]
+    w = bench.stage_work(cfg)
+    S, N, H = cfg.samples, cfg.n_workers, cfg.hidden
+    assert 3 not in w and w[4][1] == 2.0 * S * H * H and w[5][1] == 2 * 2.0 * S * H * N
 
 
 def test_sort_compare_exchange_counts():

@@ -206,6 +206,25 @@ def test_bf16_matches_the_mixed_precision_oracle(api, cfg, act):
     g.close()
 
 
+@pytest.mark.parametrize("N,S", [(128, 256), (384, 1024), (256, 300), (200, 512)],
+                         ids=["one-tile", "several-tiles", "ragged-samples", "ragged-workers"])
+def test_bf16_draw_without_stage_outputs(api, N, S):
+    """A launch made of whole tiles that asks for no stage outputs takes a draw kernel of its own
+    (the mean's product is accumulated on top of bias + scale * noise): its samples against the
+    oracle, and against the kernel that also writes the mean and the scale."""
+    cfg = custom(N=N, L=3, Z=16, H=128, R=128, S=S)
+    g, o, _ = make_pair(api, cfg, std=0.08, mlp_dtype=api.DKF_DTYPE_BF16)
+    eq, ez, ex = synth.make_noise(cfg)
+    deq, dez, dex = cuda(eq, ez, ex)
+    x_plain = g.sample_runtimes(deq, dez, dex)
+    x_staged, _ = g.sample_runtimes(deq, dez, dex, stages=True)
+    xo = o.sample_runtimes(eq, ez, ex)
+    assert rel_err(x_plain.cpu().numpy(), xo) <= TOL_BF16
+    # same operands, same roundings; only the order of the fp32 additions differs
+    assert rel_err(x_plain.cpu().numpy(), x_staged.cpu().numpy().astype(np.float64)) <= 1e-5
+    g.close()
+
+
 def test_bf16_2175_workers_ragged_wide_tiles(api):
     """The paper's larger cluster size (2175 workers: not a multiple of anything), enough samples for
     the N-wide emission layers to take their 256-feature tiling, ragged last sample tile."""

@@ -5,7 +5,9 @@ Pinned by: the rounding itself against the library's bfloat16 conversion and aga
 ties; cases whose operands are exactly representable (the hand-worked cases of the gate pins must
 come out the same in either mode); single layers against the library's bfloat16 tensors; which
 quantities are rounded and which are not (biases, the encodings' share of the guide's mean, the
-noise mix); and the size of the difference from full precision on a well-conditioned model.
+noise mix), and where a product of two linear layers is rounded once instead of twice (the scale
+network's first layer on the mean's hidden vector); and the size of the difference from full
+precision on a well-conditioned model.
 """
 import numpy as np
 import pytest
@@ -84,10 +86,17 @@ def test_emission_layers_round_matrices_and_inputs_only():
     zn = st["z_next"]
     hid = bf16(zn) @ q["emean1_w"].T + d["emean1_b"]            # bias not rounded
     mean = bf16(hid) @ q["emean2_w"].T + d["emean2_b"]
-    sd = np.logaddexp(0, bf16(np.maximum(bf16(mean) @ q["escale1_w"].T + d["escale1_b"], 0)) @ q["escale2_w"].T
-                      + d["escale2_b"])
+    # J's first layer is linear in the mean and the mean is linear in hid: one H x H matrix, formed from
+    # the unrounded matrices and then rounded, on the rounded hid; its bias is not rounded
+    fold_w = bf16(d["escale1_w"] @ d["emean2_w"])
+    fold_b = d["escale1_w"] @ d["emean2_b"] + d["escale1_b"]
+    sd = np.logaddexp(0, bf16(np.maximum(bf16(hid) @ fold_w.T + fold_b, 0)) @ q["escale2_w"].T + d["escale2_b"])
     assert np.allclose(st["emit_mean"], mean, rtol=1e-12, atol=1e-13)
     assert np.allclose(st["emit_sd"], sd, rtol=1e-12, atol=1e-13)
+    # ... which is the layer-by-layer value up to the rounding of its operands, and not equal to it
+    layered = np.logaddexp(0, bf16(np.maximum(bf16(mean) @ q["escale1_w"].T + d["escale1_b"], 0)) @ q["escale2_w"].T
+                           + d["escale2_b"])
+    assert np.allclose(sd, layered, rtol=0.1) and not np.allclose(sd, layered, rtol=1e-6)
     assert np.allclose(x, m.scale * (mean + sd * ex), rtol=1e-12, atol=1e-13)  # outputs and noise mix not rounded
     assert not np.allclose(st["emit_mean"], zn @ d["emean1_w"].T @ d["emean2_w"].T + d["emean1_b"] @ d["emean2_w"].T
                            + d["emean2_b"], rtol=1e-5)
