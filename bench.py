@@ -44,26 +44,33 @@ def sort_compare_exchanges(S, N):
 
 
 def stage_work(cfg):
-    """Algorithmic flops (MLP stages) and bytes (sort) of one decision, per stage id.
+    """Work of one decision per stage id: (bound, algorithmic, executed).
 
-    The bf16 emission runs as three kernels: the scale network's first layer is folded with the mean's
-    output layer into one H x H layer when the weights are loaded (counted as executed, 2 S H H, not
-    as the 2 S N H of the layer it replaces), and one kernel multiplies both N-wide output layers and
-    draws (stage 5 carries both, stage 3 has no kernel of its own)."""
+    Algorithmic: the flops of the layers as the paper writes them (MLP stages) and the bytes of the
+    sample matrix (sort); their sum over the MLP stages is 2 S [L (2 Z R + Z^2) + (4 Z H + 2 Z^2) +
+    (Z H + 3 H N)].  Executed: what the kernels issue.  They differ in one layer: the scale network's
+    first layer is linear in the mean and the mean is linear in its hidden vector, so the kernels apply
+    the H x H product of the two matrices, formed when the weights are loaded (2 S H H flops for the
+    layer's 2 S N H).  The bf16 emission runs as three kernels: stage 4 is that folded layer, stage 5
+    multiplies both N-wide output layers and draws, stage 3 has no kernel of its own."""
     S, N, L, Z, H, R = cfg.samples, cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim
+    guide = 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)
+    layer = 2.0 * S * H * N
+    folded = 2.0 * S * H * H
     work = {
-        1: ("mfma", 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)),
-        2: ("mfma", 2.0 * S * Z * H),
-        3: ("mfma", 2.0 * S * H * N),
-        4: ("mfma", 2.0 * S * N * H),
-        5: ("mfma", 2.0 * S * H * N),
-        6: ("hbm", 4.0 * S * N),
+        1: ("mfma", guide, guide),
+        2: ("mfma", 2.0 * S * Z * H, 2.0 * S * Z * H),
+        3: ("mfma", layer, layer),
+        4: ("mfma", layer, layer),
+        5: ("mfma", layer, layer),
+        6: ("hbm", 4.0 * S * N, 4.0 * S * N),
     }
-    work[8] = ("mfma", sum(work[s][1] for s in range(1, 6)))  # the fused sampler kernel does stages 1-5
+    algorithmic = sum(work[s][1] for s in range(1, 6))
+    work[8] = ("mfma", algorithmic, algorithmic - layer + folded)  # the fused sampler kernel does stages 1-5
     if cfg.mlp_dtype == "bf16":
         del work[3]
-        work[4] = ("mfma", 2.0 * S * H * H)
-        work[5] = ("mfma", 4.0 * S * H * N)
+        work[4] = ("mfma", layer, folded)
+        work[5] = ("mfma", 2 * layer, 2 * layer)
     return work
 
 
@@ -278,7 +285,7 @@ def run_workload(args, name, K, W, headline):
         del work[8]
 
     def roofline_of(s):
-        bound, amount = work[s]
+        bound, amount, executed = work[s]
         secs = stage_us[s] * 1e-6
         if bound == "mfma":
             achieved, peak, unit = amount / secs / 1e12, PEAK_TFLOPS[cfg.mlp_dtype], "TFLOP/s"
@@ -287,6 +294,7 @@ def run_workload(args, name, K, W, headline):
         return {"kernel": api.STAGE_NAMES[s], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
                 "frac": achieved / peak, "traffic": stored_traffic(cfg.name, api.STAGE_NAMES[s]),
                 "launches": stage_n[s], "avg_launch_us": stage_us[s], "work_per_launch": amount,
+                "executed_per_launch": executed, "frac_executed": achieved / peak * executed / amount,
                 "timing": "mean of HIP-event pairs around each launch on the launch stream, host running ahead "
                           "(the pair also brackets the dispatch of the launch, a few microseconds)"}
 
@@ -305,8 +313,9 @@ def run_workload(args, name, K, W, headline):
         "binds": "valu" if valu_frac > hbm_frac else "hbm",
         "traffic": stored_traffic(cfg.name, "sort_rank_sums"),
     }
-    mlp_flops = sum(v for s, (b, v) in work.items() if b == "mfma")
-    mlp_us = sum(stage_us[s] for s, (b, _) in work.items() if b == "mfma")
+    mlp_flops = sum(v for s, (b, v, _) in work.items() if b == "mfma")
+    mlp_executed = sum(x for s, (b, _, x) in work.items() if b == "mfma")
+    mlp_us = sum(stage_us[s] for s, (b, _, _) in work.items() if b == "mfma")
 
     # Gradients per second the chosen cutoffs would have achieved on the iterations that followed
     # each decision (Fig. 2's three curves: chosen, wait for all, best cutoff in hindsight).
@@ -348,8 +357,10 @@ def run_workload(args, name, K, W, headline):
                           "note": "same graph path, eps tensors drawn per decision by the library (Philox4x32-10)"},
         "eager_pipelined": {"vectors_per_s": S * K_eager / eager_wall, "ms_per_step": eager_wall / K_eager * 1e3},
         "stage_us": {api.STAGE_NAMES[s]: round(stage_us[s], 2) for s in range(api.DKF_NUM_STAGES)},
-        "mlp_stages": {"flops": mlp_flops, "us": mlp_us, "tflops": mlp_flops / (mlp_us * 1e-6) / 1e12,
-                       "frac_of_peak": mlp_flops / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype]},
+        "mlp_stages": {"flops": mlp_flops, "flops_executed": mlp_executed, "us": mlp_us,
+                       "tflops": mlp_flops / (mlp_us * 1e-6) / 1e12,
+                       "frac_of_peak": mlp_flops / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype],
+                       "frac_of_peak_executed": mlp_executed / (mlp_us * 1e-6) / 1e12 / PEAK_TFLOPS[cfg.mlp_dtype]},
         "roofline": roofline_of(dominant),
         "stages": stages,
         "sort": sort_block,

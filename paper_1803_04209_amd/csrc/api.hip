@@ -221,13 +221,36 @@ struct RawLayers {
         *b_emean2, *b_escale1, *b_escale2;
 };
 
+// The mean I(z) ends in a linear layer, mean = W_I2 h + b_I2, and the scale network's first layer
+// is linear in the mean (Sec. 3.1.3, J = MLP_2(I(z))): W_J1 mean + b_J1 = (W_J1 W_I2) h + (W_J1 b_I2 + b_J1).
+// That H x H layer, formed once in double precision; w is [H][H] row-major.
+void fold_scale_hidden(const RawLayers &r, int H, int N, std::vector<float> &w, std::vector<float> &b) {
+    std::vector<double> acc((size_t)H * H, 0.0);
+    w.resize((size_t)H * H);
+    b.resize(H);
+    for (int o = 0; o < H; ++o) {
+        double *row = acc.data() + (size_t)o * H;
+        double bo = r.b_escale1[o];
+        for (int n = 0; n < N; ++n) {
+            const double ws = r.escale1[(size_t)o * N + n];
+            const float *src = r.emean2 + (size_t)n * H;
+            for (int i = 0; i < H; ++i) row[i] += ws * src[i];
+            bo += ws * r.b_emean2[n];
+        }
+        for (int i = 0; i < H; ++i) w[(size_t)o * H + i] = (float)row[i];
+        b[o] = (float)bo;
+    }
+}
+
 // Tile streams of the chained sampler.  Guide: comb [ob group][ib][ob in group], mu [zb][ib], sig [zb][ib].
 // Stream: chunks of CH = chain_chunk_tiles(HB) tiles in the order the kernel consumes them, every
 // layer padded with zero tiles to whole chunks:
 //   gate1 [ib][ob], gate2 [zb][ib], prop1, prop2, lin [ob][ib], tscale, emean1 [ib][ob] (one chunk each);
-//   then per group of K2 = CH / (2 HB) 16-worker blocks nb: { emean2 row nb (ib = 0..HB-1),
-//   escale1 column nb (ob = 0..HB-1) } for each nb of the group;
-//   then per group of 2 K2 blocks: escale2 row nb (ib = 0..HB-1) for each nb of the group.
+//   then per group of CH / HB output blocks ob: row ob (ib = 0..HB-1) of the folded H x H layer
+//   (fold_scale_hidden);
+//   then per group of K2 = CH / (2 HB) 16-worker blocks nb: { emean2 row nb, escale2 row nb
+//   (ib = 0..HB-1 each) } for each nb of the group.
+// The bias table's escale1 slot holds the folded layer's bias.
 int pack_chain(dkf_model *m, const RawLayers &r) {
     const int Z = m->Z, R = m->R, H = m->H, N = m->N;
     const int ZB = (Z + 15) / 16, RB = (R + 15) / 16, HB = (H + 15) / 16, NB = (N + 15) / 16;
@@ -256,17 +279,20 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     };
     wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale);
     wide(r.emean1);
+    std::vector<float> fold_w, fold_b;
+    fold_scale_hidden(r, H, N, fold_w, fold_b);
+    const int RA = CH / HB;
+    for (int c = 0; c < (HB + RA - 1) / RA; ++c)
+        for (int u = 0; u < RA; ++u) {
+            const int ob = c * RA + u;
+            if (ob >= HB) { zeros(HB); continue; }
+            for (int ib = 0; ib < HB; ++ib) append_tile(s, fold_w.data(), H, H, ob, ib);
+        }
     for (int c = 0; c < (NB + K2 - 1) / K2; ++c)
         for (int u = 0; u < K2; ++u) {
             const int nb = c * K2 + u;
             if (nb >= NB) { zeros(2 * HB); continue; }
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
-            for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
-        }
-    for (int c = 0; c < (NB + 2 * K2 - 1) / (2 * K2); ++c)
-        for (int u = 0; u < 2 * K2; ++u) {
-            const int nb = c * 2 * K2 + u;
-            if (nb >= NB) { zeros(HB); continue; }
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
         }
     if (s.size() % chunk != 0) return DKF_EINVAL;
@@ -279,7 +305,7 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     };
     add_bias(r.b_comb, R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
     add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
-    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(r.b_escale1, H, HB);
+    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(fold_b.data(), H, HB);
     add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);
     int rcb = upload(m, bt.data(), bt.size(), &m->chain_bias);
     if (rcb != DKF_OK) return rcb;
@@ -418,29 +444,14 @@ int pack_frag_layer(dkf_model *m, const float *w, const float *b, int n_out, int
     return rc;
 }
 
-// The bf16 emission (egemm.hip).  The mean ends in a linear layer and the scale network's first
-// layer is linear in the mean, so the two are folded once, in double precision, into one H x H
-// layer on the mean's hidden vector: M = W_J1 W_I2, c = W_J1 b_I2 + b_J1 (Sec. 3.1.3, J = MLP_2(I(z))).
+// The bf16 emission (egemm.hip), with the scale network's first layer folded (fold_scale_hidden).
 int pack_emission_frags(dkf_model *m, const RawLayers &r) {
     const int H = m->H, N = m->N;
     const int Hp = round_up(H, 128), Np = round_up(N, 128);
     m->ef_Hp = Hp; m->ef_Np = Np;
     m->ef_samp_tiles = (m->cfg.max_samples + 255) / 256;
-    std::vector<double> fold((size_t)H * H, 0.0), fold_b(H);
-    for (int o = 0; o < H; ++o) {
-        double *row = fold.data() + (size_t)o * H;
-        double b = r.b_escale1[o];
-        for (int n = 0; n < N; ++n) {
-            const double w = r.escale1[(size_t)o * N + n];
-            const float *src = r.emean2 + (size_t)n * H;
-            for (int i = 0; i < H; ++i) row[i] += w * src[i];
-            b += w * r.b_emean2[n];
-        }
-        fold_b[o] = b;
-    }
-    std::vector<float> fold_w((size_t)H * H), fold_bf(H);
-    for (size_t i = 0; i < fold.size(); ++i) fold_w[i] = (float)fold[i];
-    for (int o = 0; o < H; ++o) fold_bf[o] = (float)fold_b[o];
+    std::vector<float> fold_w, fold_bf;
+    fold_scale_hidden(r, H, N, fold_w, fold_bf);
     int rc = pack_frag_layer(m, r.emean1, r.b_emean1, H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
     if (rc == DKF_OK) rc = pack_frag_layer(m, r.emean2, r.b_emean2, N, H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
     if (rc == DKF_OK) rc = pack_frag_layer(m, fold_w.data(), fold_bf.data(), H, H, Hp, Hp, &m->ef_w[2], &m->ef_b[2]);

@@ -15,9 +15,10 @@
 // after the guide loop (transition, emission) is used once per wavefront and
 // is streamed from L2 through a double-buffered LDS ring, in a chunk order
 // laid down when the weights are loaded (ChainPack), so that the four
-// wavefronts of a workgroup share every fetch.  The emission scale network is
-// fused back-to-back: each 16-worker block of the mean is produced, stored,
-// and immediately folded into the hidden layer of the scale network.
+// wavefronts of a workgroup share every fetch.  The scale network's first
+// layer is folded with the mean's output layer when the weights are loaded, so
+// both hidden vectors are known before the first N-wide product and mean and
+// scale of a 16-worker block are produced, and drawn from, together.
 #include "common.h"
 #include "mfma_tile.h"
 #include "mfma16.h"
@@ -228,8 +229,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 
     // ---- streamed part: transition, then emission --------------------------------
     constexpr int CH = chain_chunk_tiles(HB);  // tiles per chunk
-    constexpr int K2 = CH / (2 * HB);          // 16-worker blocks per chunk in the fused mean/scale-hidden pass
-    constexpr int U3 = 2 * K2;                 // 16-worker blocks per chunk in the scale pass
+    constexpr int K2 = CH / (2 * HB);          // 16-worker blocks per chunk in the emission's output pass
     constexpr int GH = HB < 4 ? HB : 4;
     static_assert(ZB * HB <= CH && ZB * ZB <= CH, "a transition layer fits one chunk");
     WeightStream<CH> ws;
@@ -318,33 +318,23 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 #pragma unroll
         for (int ob = 0; ob < HB; ++ob) h1[ob] = relu4(h1[ob]);
     }
-    // mean, 16 workers at a time, each block folded into the scale network's hidden layer at once
+    // The scale network's hidden layer.  The mean is linear in h1 and this layer is linear in the
+    // mean, so it is one H x H layer on h1, M = W_J1 W_I2 and c = W_J1 b_I2 + b_J1, formed when the
+    // weights are loaded (the table slot of b_J1 holds c): the N-wide mean is never an operand.
     f32x4 h2[HB];
+    constexpr int RA = CH / HB;  // rows of M per chunk
 #pragma unroll
-    for (int ob = 0; ob < HB; ++ob) h2[ob] = bias4(lb_escale1, ob);
-    const int NB = a.NB;
-    float *mean_row = a.mean + (size_t)sc * a.ld_mean + 4 * q;
-    for (int c = 0; c < (NB + K2 - 1) / K2; ++c) {
+    for (int c = 0; c < (HB + RA - 1) / RA; ++c) {
 #pragma unroll
-        for (int u = 0; u < K2; ++u) {
-            const int nb_raw = c * K2 + u;
-            const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, nothing kept
-            {
-                const f32x4 m = narrow_block(u * 2 * HB, bias4(lb_emean2, nb), h1, nothing);
-                // lanes past the last sample repeat sample S-1 exactly, so their store is a harmless
-                // duplicate; blocks past the end go to the sink
-                float *dst = nb_raw < NB ? mean_row + nb * 16 : a.sink + tid * 4;
-                *reinterpret_cast<f32x4 *>(dst) = m;
-                for_tile_groups<HB, GH>([&](int i) { return ws.tile(u * 2 * HB + HB + i, lane); },
-                                        [&](int g, const f32x4(&tl)[GH]) { mma_wide<GH>(&h2[g * GH], tl, m); });
-            }
+        for (int u = 0; u < RA; ++u) {
+            const int ob = c * RA + u;
+            if (ob < HB) h2[ob] = relu4(narrow_block(u * HB, bias4(lb_escale1, ob), h1, nothing));
         }
         ws.advance();
     }
-#pragma unroll
-    for (int ob = 0; ob < HB; ++ob) h2[ob] = relu4(h2[ob]);
 
-    // scale, draw, back to seconds
+    // mean and scale of 16 workers at a time, draw, back to seconds
+    const int NB = a.NB;
     const float scale = a.ctl->scale;
     float *sink = a.sink + tid * 4;
     auto load_eps_x = [&](int nb) {
@@ -361,7 +351,6 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         }
         return e;
     };
-    auto load_mean = [&](int nb) { return *reinterpret_cast<const f32x4 *>(mean_row + nb * 16); };
     auto emit = [&](int nb, f32x4 pre, f32x4 m, f32x4 e) {  // softplus, draw, store
         const int n0 = nb * 16 + 4 * q;
         const f32x4 sd = softplus4(pre);
@@ -389,34 +378,30 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
             }
         }
     };
-    // The noise and the stored mean of a chunk's blocks are requested one chunk ahead, right
-    // after the weight stream's own request (loads return in order: nothing waits on a request
-    // younger than one chunk).  Each block's epilogue rides on the next block's first matrix
-    // instructions.
-    f32x4 e_next[U3], m_next[U3];
+    // The noise of a chunk's blocks is requested one chunk ahead, right after the weight stream's
+    // own request (loads return in order: nothing waits on a request younger than one chunk).
+    // Each block's epilogue rides on the next block's first matrix instructions.
+    f32x4 e_next[K2];
 #pragma unroll
-    for (int u = 0; u < U3; ++u) {
-        e_next[u] = load_eps_x(u < NB ? u : NB - 1);
-        m_next[u] = load_mean(u < NB ? u : NB - 1);
-    }
+    for (int u = 0; u < K2; ++u) e_next[u] = load_eps_x(u < NB ? u : NB - 1);
     f32x4 pre_p = splat(0.f), m_p = splat(0.f), e_p = splat(0.f);
     int nb_p = -1;  // nothing pending
-    for (int c = 0; c < (NB + U3 - 1) / U3; ++c) {
-        f32x4 e[U3], m[U3];
+    for (int c = 0; c < (NB + K2 - 1) / K2; ++c) {
+        f32x4 e[K2];
 #pragma unroll
-        for (int u = 0; u < U3; ++u) { e[u] = e_next[u]; m[u] = m_next[u]; }
+        for (int u = 0; u < K2; ++u) e[u] = e_next[u];
 #pragma unroll
-        for (int u = 0; u < U3; ++u) {
-            const int nn = (c + 1) * U3 + u;
+        for (int u = 0; u < K2; ++u) {
+            const int nn = (c + 1) * K2 + u;
             e_next[u] = load_eps_x(nn < NB ? nn : NB - 1);
-            m_next[u] = load_mean(nn < NB ? nn : NB - 1);
         }
 #pragma unroll
-        for (int u = 0; u < U3; ++u) {
-            const int nb_raw = c * U3 + u;
+        for (int u = 0; u < K2; ++u) {
+            const int nb_raw = c * K2 + u;
             const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, result goes to the sink
-            const f32x4 pre = narrow_block(u * HB, bias4(lb_escale2, nb), h2, [&] { emit(nb_p, pre_p, m_p, e_p); });
-            pre_p = pre; m_p = m[u]; e_p = e[u]; nb_p = nb_raw < NB ? nb_raw : -1;
+            const f32x4 m = narrow_block(u * 2 * HB, bias4(lb_emean2, nb), h1, [&] { emit(nb_p, pre_p, m_p, e_p); });
+            const f32x4 pre = narrow_block(u * 2 * HB + HB, bias4(lb_escale2, nb), h2, nothing);
+            pre_p = pre; m_p = m; e_p = e[u]; nb_p = nb_raw < NB ? nb_raw : -1;
         }
         ws.advance();
     }

@@ -25,12 +25,16 @@ def test_stage_work_matches_the_layer_sizes():
     # emission: Z->H, H->N, N->H, H->N
     assert [w[s][1] for s in (2, 3, 4, 5)] == [2.0 * S * Z * H, 2.0 * S * H * N, 2.0 * S * N * H, 2.0 * S * H * N]
     assert w[8][1] == sum(w[s][1] for s in range(1, 6))
-    assert w[6] == ("hbm", 4.0 * S * N)
-    # bf16: the folded H x H layer is counted as executed, both N-wide output layers run in the draw kernel
+    # the fused kernel applies the N->H layer folded into an H x H one
+    assert w[8][2] == w[8][1] - 2.0 * S * N * H + 2.0 * S * H * H
+    assert w[6][:2] == ("hbm", 4.0 * S * N)
+    # bf16: stage 4 is the folded layer, stage 5 both N-wide output layers; the algorithmic total is unchanged
     cfg = synth.CONFIGS["large_bf16"]
     w = bench.stage_work(cfg)
     S, N, H = cfg.samples, cfg.n_workers, cfg.hidden
-    assert 3 not in w and w[4][1] == 2.0 * S * H * H and w[5][1] == 2 * 2.0 * S * H * N
+    assert 3 not in w and w[4][1:] == (2.0 * S * N * H, 2.0 * S * H * H) and w[5][1] == w[5][2] == 2 * 2.0 * S * H * N
+    assert sum(w[s][1] for s in (1, 2, 4, 5)) == w[8][1]
+    assert abs(w[8][1] - 77.2e9) < 0.1e9  # the survey's figure for this configuration
 
 
 def test_sort_compare_exchange_counts():
