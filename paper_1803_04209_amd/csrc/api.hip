@@ -319,8 +319,8 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
 //   guide:  comb [o < RQ][ib] (output block w RQ + o), mu [zb][i < RQ] (input block w RQ + i), sig [zb][ib];
 //   head, padded with zero tiles to whole chunks:  gate1 [o < HQ][ib], gate2 [zb][i < HQ], prop1, prop2
 //           likewise, lin [ob][ib], tscale [ob][ib], emean1 [o < HQ][ib];
-//   per own worker block nb = w NBW + u, one chunk:  emean2 row nb (ib < HB), escale1 column nb (ob < HB);
-//   per pair of own worker blocks, one chunk:  escale2 row nb (ib < HB) for each of the two;
+//   the folded H x H layer (fold_scale_hidden):  row w HQ + o (ib < HB) for o < HQ, whole chunks;
+//   per own worker block nb = w NBW + u, one chunk:  emean2 row nb (ib < HB), escale2 row nb (ib < HB);
 //   one spare chunk of zeros.
 // Biases: the table of the sixteen-per-wavefront kernel.
 int pack_split(dkf_model *m, const RawLayers &r) {
@@ -329,6 +329,8 @@ int pack_split(dkf_model *m, const RawLayers &r) {
     const int RQ = RB / 4, HQ = HB / 4, C = 2 * HB, NBW = (NB + 3) / 4;
     const int per_wave = split_stream_tiles(Z, R, H, N);
     if (per_wave <= 0) return DKF_EINVAL;
+    std::vector<float> fold_w, fold_b;
+    fold_scale_hidden(r, H, N, fold_w, fold_b);
     std::vector<float> s;
     s.reserve((size_t)4 * per_wave * 256);
     for (int w = 0; w < 4; ++w) {
@@ -346,18 +348,13 @@ int pack_split(dkf_model *m, const RawLayers &r) {
         auto small = [&](const float *wt) { for (int ob = 0; ob < ZB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(s, wt, Z, Z, ob, ib); };
         wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale); wide(r.emean1);
         pad();
+        for (int o = 0; o < HQ; ++o) for (int ib = 0; ib < HB; ++ib) append_tile(s, fold_w.data(), H, H, w * HQ + o, ib);
         for (int u = 0; u < NBW; ++u) {
             const int nb = w * NBW + u;
             if (nb >= NB) { zeros(C); continue; }
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
-            for (int ob = 0; ob < HB; ++ob) append_tile(s, r.escale1, H, N, ob, nb);
-        }
-        for (int u = 0; u < NBW; ++u) {
-            const int nb = w * NBW + u;
-            if (nb >= NB) { zeros(HB); continue; }
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
         }
-        pad();
         zeros(C);
         if (s.size() - start != (size_t)per_wave * 256) return DKF_EINVAL;
     }
@@ -369,7 +366,7 @@ int pack_split(dkf_model *m, const RawLayers &r) {
     };
     add_bias(r.b_comb, R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
     add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
-    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(r.b_escale1, H, HB);
+    add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(fold_b.data(), H, HB);
     add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);
     int rc = upload(m, bt.data(), bt.size(), &m->split_bias);
     if (rc == DKF_OK) rc = upload(m, s.data(), s.size(), &m->split_stream);

@@ -12,12 +12,12 @@
 //                                    are added through LDS in a fixed order ((w0 + w1) + w2) + w3,
 //                                    after which every wavefront holds the whole latent again;
 //   Z -> Z layers:                   computed by all four wavefronts alike;
-//   emission:  a wavefront owns a contiguous quarter of the workers.  For each of its 16-worker
-//              blocks it forms the mean from the whole hidden layer (gathered once through LDS),
-//              keeps it in registers, and folds it at once into ITS partial sum of the scale
-//              network's hidden layer (a split over that layer's inputs); those partial sums are
-//              added through LDS once, and the scale and the draw are again by worker block.  The
-//              emission mean never leaves registers.
+//   emission:  the mean's hidden layer is computed by output blocks and gathered through LDS.  The
+//              scale network's first layer is linear in the mean and the mean linear in that
+//              hidden layer, so it is applied as their H x H product (formed when the weights are
+//              loaded): a second hidden layer, again by output blocks and gathered.  After that a
+//              wavefront owns a contiguous quarter of the workers and, for each of its 16-worker
+//              blocks, forms mean and scale from the two hidden layers and draws.
 // One exchange per guide step, one for the transition, two for the emission.
 //
 // Weights: a wavefront only ever touches its own quarter of every matrix.  Its share of the guide's
@@ -43,10 +43,12 @@ struct SplitShape {
     static constexpr int C = 2 * HB;                           // ring size = tiles of one emission block
     static constexpr int kHead = 5 * HQ * ZB + 2 * ZB * ZB;    // gate1 gate2 prop1 prop2 lin tscale emean1
     static constexpr int kHeadChunks = (kHead + C - 1) / C;
+    static_assert(HQ % 2 == 0, "a wavefront's rows of the folded layer fill whole chunks");
+    static constexpr int kFoldChunks = HQ * HB / C;
     // tiles of one wavefront's stream for nbw worker blocks per wavefront (one spare chunk at the end:
     // the ring always requests one chunk ahead)
     __host__ __device__ static constexpr int stream_tiles(int nbw) {
-        return kGuide + (kHeadChunks + nbw + (nbw + 1) / 2 + 1) * C;
+        return kGuide + (kHeadChunks + kFoldChunks + nbw + 1) * C;
     }
 };
 
@@ -59,8 +61,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // LDS: exchange buffers, then the encodings' table and the bias table
     f32x4 *x_mu = reinterpret_cast<f32x4 *>(lds_raw);          // [2][4][2 ZB][64]  latent-sized partial sums
     f32x4 *x_h1 = x_mu + 2 * 4 * 2 * ZB * kTileF4;             // [HB][64]          hidden layer of the mean
-    f32x4 *x_h2 = x_h1 + HB * kTileF4;                         // [4][HB][64]       partial hidden layer of the scale
-    float *ctx = reinterpret_cast<float *>(x_h2 + 4 * HB * kTileF4);  // [L][R16]
+    f32x4 *x_h2 = x_h1 + HB * kTileF4;                         // [HB][64]          hidden layer of the scale
+    float *ctx = reinterpret_cast<float *>(x_h2 + HB * kTileF4);  // [L][R16]
     float *bias = ctx + a.L * R16;
     const int NB = a.NB, N16 = NB * 16;
     const int NBW = (NB + 3) / 4;  // worker blocks per wavefront
@@ -334,48 +336,32 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // the rest of the head's last chunk is padding: taking it lets the ring request the next chunk's tiles
 #pragma unroll
     for (int pos = Sh::kHead; pos < Sh::kHeadChunks * C; ++pos) (void)head_take(pos);
-    cur += C * kTileF4;  // the ring now holds the first emission block
-    // Mean of each own 16-worker block (kept in registers) and its contribution to the scale network's
-    // hidden layer.  One block = one chunk of the ring: HB tiles of the mean's second layer (row nb)
-    // followed by HB tiles of the scale network's first layer (column nb).
-    constexpr int kMaxBlocks = 8;  // worker blocks per wavefront held in registers (N <= 512)
-    f32x4 mean_own[kMaxBlocks], h2[HB];
+    cur += C * kTileF4;  // the ring now holds the first chunk of the folded layer
+    // hidden layer of the scale network from h1 (the folded H x H layer; the table slot of b_J1 holds
+    // its bias): own quarter of the output blocks, row by row, then gathered
+    f32x4 h2[HB];
+    {
+        f32x4 own[HQ];
 #pragma unroll
-    for (int ob = 0; ob < HB; ++ob) h2[ob] = splat(0.f);
-#pragma unroll
-    for (int u = 0; u < kMaxBlocks; ++u) {
-        if (u < NBW) {
-            const int nb = nb0 + u < NB ? nb0 + u : NB - 1;  // past the end: zero tiles, nothing kept
+        for (int o = 0; o < HQ; ++o) {
             Acc4 acc;
-            acc.init(bias4(lb_emean2, nb));
+            acc.init(bias4(lb_escale1, w * HQ + o));
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
-                const f32x4 tl[1] = {take(i)};
+                const f32x4 tl[1] = {take((o * HB + i) % C)};
                 mma_narrow<1>(acc, tl, &h1[i]);
             }
-            const f32x4 m = acc.sum();
-            mean_own[u] = m;
-#pragma unroll
-            for (int g4 = 0; g4 < HB / 4; ++g4) {
-                f32x4 tl[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) tl[j] = take(HB + g4 * 4 + j);
-                mma_wide<4>(&h2[g4 * 4], tl, m);
-            }
-            cur += C * kTileF4;
+            own[o] = relu4(acc.sum());
+            if ((o + 1) * HB % C == 0) cur += C * kTileF4;
         }
-    }
-    // sum of the partial hidden layers over the wavefronts, bias, ReLU
 #pragma unroll
-    for (int ob = 0; ob < HB; ++ob) x_h2[(w * HB + ob) * kTileF4 + lane] = h2[ob];
-    __syncthreads();
+        for (int o = 0; o < HQ; ++o) x_h2[(w * HQ + o) * kTileF4 + lane] = own[o];
+        __syncthreads();
 #pragma unroll
-    for (int ob = 0; ob < HB; ++ob) {
-        const f32x4 *e = x_h2 + ob * kTileF4 + lane;
-        const f32x4 s = ((e[0] + e[HB * kTileF4]) + e[2 * HB * kTileF4]) + e[3 * HB * kTileF4];
-        h2[ob] = relu4(s + bias4(lb_escale1, ob));
+        for (int ob = 0; ob < HB; ++ob) h2[ob] = x_h2[ob * kTileF4 + lane];
     }
-    // scale, draw, back to seconds: two worker blocks per chunk of the ring
+    // mean, scale, draw, back to seconds: one worker block per chunk of the ring (HB tiles of the
+    // mean's output layer, row nb, then HB tiles of the scale's)
     auto emit = [&](int nb_raw, f32x4 pre, f32x4 m, f32x4 e) {
         const int n0 = nb_raw * 16 + 4 * q;
         const f32x4 sd = softplus4(pre);
@@ -395,21 +381,22 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             }
         }
     };
+    f32x4 e_next = load_eps_x(nb0 < NB ? nb0 : NB - 1);  // noise one block ahead
+    for (int u = 0; u < NBW; ++u) {
+        const int nb_raw = nb0 + u, nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, result to the sink
+        const f32x4 e = e_next;
+        e_next = load_eps_x(nb_raw + 1 < NB ? nb_raw + 1 : NB - 1);
+        Acc4 am, as;
+        am.init(bias4(lb_emean2, nb));
+        as.init(bias4(lb_escale2, nb));
 #pragma unroll
-    for (int u = 0; u < kMaxBlocks; ++u) {
-        if (u < NBW) {
-            const int nb_raw = nb0 + u, nb = nb_raw < NB ? nb_raw : NB - 1;
-            const f32x4 e = load_eps_x(nb);
-            Acc4 acc;
-            acc.init(bias4(lb_escale2, nb));
-#pragma unroll
-            for (int i = 0; i < HB; ++i) {
-                const f32x4 tl[1] = {take((u & 1) * HB + i)};
-                mma_narrow<1>(acc, tl, &h2[i]);
-            }
-            emit(nb_raw, acc.sum(), mean_own[u], e);
-            if (u & 1) cur += C * kTileF4;
+        for (int i = 0; i < HB; ++i) {
+            const f32x4 tm[1] = {take(i)}, ts[1] = {take(HB + i)};
+            mma_narrow<1>(am, tm, &h1[i]);
+            mma_narrow<1>(as, ts, &h2[i]);
         }
+        emit(nb_raw, as.sum(), am.sum(), e);
+        cur += C * kTileF4;
     }
 }
 
@@ -417,7 +404,7 @@ template <int ZB, int RB, int HB>
 size_t split_lds_bytes(int L, int N) {
     const size_t nb16 = (size_t)((N + 15) / 16) * 16;
     const size_t bias_floats = RB * 16 + 6 * ZB * 16 + 4 * HB * 16 + 2 * nb16;
-    return (size_t)(2 * 4 * 2 * ZB + HB + 4 * HB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
+    return (size_t)(2 * 4 * 2 * ZB + HB + HB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
 }
 
 template <int ZB, int RB, int HB, bool DBG>
@@ -443,11 +430,11 @@ int launch_one(const ChainArgs &a, hipStream_t stream) {
 
 }  // namespace
 
-// Sizes the kernel is built for: the latent and the widths of the two larger fp32 presets, at most
-// 512 workers (eight 16-worker blocks per wavefront stay in registers), N and Z multiples of 4.
+// Sizes the kernel is built for: the latent and the widths of the two larger fp32 presets, N and Z
+// multiples of 4, and as many workers as leave the bias table room in LDS.
 bool split_supported(int Z, int R, int H, int L, int N) {
     const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16;
-    if (N < 4 || N > 512 || (N & 3) != 0 || Z < 4 || (Z & 3) != 0) return false;
+    if (N < 4 || (N & 3) != 0 || Z < 4 || (Z & 3) != 0) return false;
     if (zb == 1 && rb == 8 && hb == 8) return split_lds_bytes<1, 8, 8>(L, N) <= 160 * 1024;
     if (zb == 2 && rb == 16 && hb == 16) return split_lds_bytes<2, 16, 16>(L, N) <= 160 * 1024;
     return false;
