@@ -139,7 +139,9 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
         __syncthreads();
     }
 
-    // epilogue
+    // epilogue.  The draw reads two values per result: all of a tile's reads are requested, from
+    // clamped addresses, before the first value is used (a read behind a branch is waited for
+    // where the branch joins, one memory round trip per element).
     float scale = 1.f;
     if constexpr (EPI == kEpiScaleDraw) scale = a.ctl->scale;
 #pragma unroll
@@ -149,24 +151,35 @@ __global__ __launch_bounds__(kThreads, 2) void mlp_gemm(GemmArgs a) {
         const float b = a.layer.bias[col];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
+            if constexpr (EPI == kEpiScaleDraw) {
+                const float *__restrict__ mean_in = a.mean;
+                const float *__restrict__ eps_in = a.eps_x;
+                const int cc = col < a.N ? col : a.N - 1;
+                float mean[16], eps[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wr * 64 + i * 32 + acc_row(e, lane);
-                if (row >= a.S) continue;
-                const float v = acc[i][j][e] + b;
-                if constexpr (EPI == kEpiBias) {
-                    a.out[(size_t)row * a.ldo + col] = v;
-                } else if constexpr (EPI == kEpiBiasRelu) {
-                    a.out[(size_t)row * a.ldo + col] = fmaxf(v, 0.f);
-                } else {
-                    if (col < a.N) {
-                        const float sd = softplus_f(v);
-                        const float mean = a.mean[(size_t)row * a.ld_mean + col];
-                        const float eps = a.eps_x[(size_t)row * a.N + col];
-                        a.out_samples[(size_t)row * a.N + col] = scale * (mean + sd * eps);
-                        if (a.out_mean_dbg) a.out_mean_dbg[(size_t)row * a.N + col] = mean;
-                        if (a.out_sd_dbg) a.out_sd_dbg[(size_t)row * a.N + col] = sd;
-                    }
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wr * 64 + i * 32 + acc_row(e, lane);
+                    const int rc = row < a.S ? row : a.S - 1;
+                    mean[e] = mean_in[(size_t)rc * a.ld_mean + cc];
+                    eps[e] = eps_in[(size_t)rc * a.N + cc];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wr * 64 + i * 32 + acc_row(e, lane);
+                    if (row >= a.S || col >= a.N) continue;
+                    const float sd = softplus_f(acc[i][j][e] + b);
+                    a.out_samples[(size_t)row * a.N + col] = scale * (mean[e] + sd * eps[e]);
+                    if (a.out_mean_dbg) a.out_mean_dbg[(size_t)row * a.N + col] = mean[e];
+                    if (a.out_sd_dbg) a.out_sd_dbg[(size_t)row * a.N + col] = sd;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = m0 + wr * 64 + i * 32 + acc_row(e, lane);
+                    if (row >= a.S) continue;
+                    const float v = acc[i][j][e] + b;
+                    a.out[(size_t)row * a.ldo + col] = EPI == kEpiBiasRelu ? fmaxf(v, 0.f) : v;
                 }
             }
         }
