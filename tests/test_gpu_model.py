@@ -67,6 +67,12 @@ def compare_stages(api, cfg, g, o, S=None, rows=None, tol=TOL):
         "samples": rel_err(x.cpu().numpy()[sel], xo),
     }
     assert all(e <= tol for e in errs.values()), errs
+    # the same call without stage outputs runs the kernels the decision path and the benchmark run
+    # (variants without the extra stores; for bf16 whole-tile launches a draw kernel of its own):
+    # the same samples up to the order of fp32 additions
+    x_plain = g.sample_runtimes(deq, dez, dex)
+    plain_err = rel_err(x_plain.cpu().numpy(), x.cpu().numpy().astype(np.float64))
+    assert plain_err <= 1e-5, plain_err
     return x, errs
 
 
