@@ -12,9 +12,12 @@
 //                output features from the full latent (which every wavefront holds);
 //   narrow layers (R -> Z, H -> Z): each wavefront multiplies its quarter of the
 //                hidden features (K split) and the four partial results are summed
-//                through LDS in a fixed order, after which every wavefront again
-//                holds the full latent;
-//   Z -> Z layers are computed by all four wavefronts alike.
+//                through LDS in a fixed order;
+//   in the guide's steps the latent is then finished by quarters: wavefront w
+//                owns the eight registers per lane that make up B fragment w of the
+//                latent, sums, scales (Z -> Z product for its tile), draws and rounds
+//                only those, and the four fragments are handed round through LDS;
+//   in the transition every wavefront holds the summed latent and one finishes.
 // The context enters the mean linearly, mu = W_mu (tanh(.) + h_l + h_r) / 3 + b,
 // so its share c_t = W_mu (h_l,t + h_r,t) / 3 + b_mu is computed once per window
 // position by guide_context (fp32, unrounded weights) and added after the
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw);
     float *bias = reinterpret_cast<float *>(lds_raw + 2 * 4 * 8 * 64 * 16);
     float *cmu = bias + a.bias_floats;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31, h = lane >> 5;
     const int S = a.S, Z = a.Z, L = a.L;
     const int smp = blockIdx.x * kRows + col;
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     stage_table(cmu, a.cmu, L * 64);
 
     // guide weights of this wavefront -> registers
-    bf16x8 wc[Q][ZK], wmu[ZT][2 * Q], wsig[ZT][ZK];
+    bf16x8 wc[Q][ZK], wmu[ZT][2 * Q], wsig[ZK];  // of the scale's matrix only the tile of this wavefront's quarter
 #pragma unroll
     for (int ob = 0; ob < Q; ++ob)
 #pragma unroll
@@ -113,9 +116,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int ks = 0; ks < 2 * Q; ++ks) wmu[nb][ks] = load_tile(T, tMu + (w * ZT + nb) * 2 * Q + ks, lane);
 #pragma unroll
-    for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) wsig[nb][ks] = load_tile(T, tSig + nb * ZK + ks, lane);
+    for (int ks = 0; ks < ZK; ++ks) wsig[ks] = load_tile(T, tSig + (w >> 1) * ZK + ks, lane);
 
     // z_0 as B operands: k-step ks, entry j <-> feature 16 ks + 8 (j / 4) + 4 h + j % 4
     bf16x8 zB[ZK];
@@ -175,10 +176,31 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         return v;
     };
 
-    f32x16 mu[ZT], zf[ZT];
+    // After the combiner and the mean's partial products a step continues on QUARTERS of the latent:
+    // wavefront w owns the eight registers per lane that are B fragment w of the latent (tile
+    // w / 2, registers 8 (w % 2) ..).  It adds the four partial sums of its quarter, finishes the mean
+    // there, hands the quarter to the others as one bf16 fragment, multiplies the scale's product
+    // for its tile from the four fragments, applies softplus and draws on its quarter only, and
+    // hands the new latent over the same way.  (Every wavefront finishing the whole latent by itself
+    // costs four times the transcendental work of this part and four times the LDS reads.)
+    // Three barriers per step; each buffer is written two barriers after its last read.
+    const int own_tile = w >> 1, own_half = w & 1;
+    f32x4 *frag_mu = red + (4 * 8) * 64, *frag_z = frag_mu + 4 * 64;  // [4][64] each, in the second exchange buffer
+    float zq[8] = {};  // this wavefront's quarter of z_t, fp32
+    // this quarter's features: register j <-> 32 own_tile + 16 own_half + 8 (j / 4) + 4 h + j % 4
+    const int qfeat0 = 32 * own_tile + 16 * own_half + 4 * h;
     for (int t = 0; t < L; ++t) {
-        f32x4 eps[ZT][4];
-        load_noise(a.eps_q + ((size_t)t * S + (live ? smp : 0)) * Z, eps);
+        f32x4 eps[2];
+        {
+            const float *__restrict__ row = a.eps_q + ((size_t)t * S + (live ? smp : 0)) * Z;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int f = qfeat0 + 8 * q;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (live && f < Z) v = *reinterpret_cast<const f32x4 *>(row + f);
+                eps[q] = v;
+            }
+        }
         // combiner: this wavefront's quarter of W_c z + b_c, all products issued before the first tanh
         // (k-step outermost: consecutive matrix instructions then belong to different accumulators;
         // one that continues the accumulator of the instruction just before it waits out its latency)
@@ -191,6 +213,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int ob = 0; ob < Q; ++ob) pre[ob] = mma(wc[ob][ks], zB[ks], pre[ob]);
         // tanh tile by tile, each straight into two B operands of the mean's partial product over
         // this wavefront's hidden features
+        f32x16 mu[ZT];
 #pragma unroll
         for (int nb = 0; nb < ZT; ++nb) mu[nb] = zero16();
 #pragma unroll
@@ -203,47 +226,72 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int nb = 0; nb < ZT; ++nb) mu[nb] = mma(wmu[nb][2 * ob + 1], h1, mu[nb]);
         }
-        all_sum(mu);
-        bf16x8 mB[ZK];
+        // partial sums -> LDS; own quarter summed in the order ((w0 + w1) + w2) + w3
+        {
+            f32x4 *mine = red + (w * 8) * 64 + lane;
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) {
-            const float *c = cmu + t * 64 + 32 * nb + 4 * h;
+            for (int nb = 0; nb < ZT; ++nb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v = {mu[nb][4 * q], mu[nb][4 * q + 1], mu[nb][4 * q + 2], mu[nb][4 * q + 3]};
+                    mine[(nb * 4 + q) * 64] = v;
+                }
+        }
+        __syncthreads();
+        float muq[8];
+        {
+            const f32x4 *all = red + lane;
+            const float *c = cmu + t * 64 + qfeat0;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int e = (own_tile * 4 + 2 * own_half + q) * 64;
+                const f32x4 s4 = ((all[e] + all[8 * 64 + e]) + all[16 * 64 + e]) + all[24 * 64 + e];
                 const f32x4 cq = *reinterpret_cast<const f32x4 *>(c + 8 * q);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mu[nb][4 * q + r] = mu[nb][4 * q + r] * (1.0f / 3.0f) + cq[r];
+                for (int r = 0; r < 4; ++r) muq[4 * q + r] = s4[r] * (1.0f / 3.0f) + cq[r];
             }
-            mB[2 * nb] = operand_of<0>(mu[nb]);
-            mB[2 * nb + 1] = operand_of<1>(mu[nb]);
         }
-        // scale from the mean, reparameterised draw.  Pad features need no masking: their mean is 0
-        // (zero weight rows, zero c_t) and their noise was loaded as 0.
+        {
+            bf16x8 mq;
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) zf[nb] = bias_tile(bias + oSig + 32 * nb + 4 * h);
-#pragma unroll
-        for (int ks = 0; ks < ZK; ++ks)
-#pragma unroll
-            for (int nb = 0; nb < ZT; ++nb) zf[nb] = mma(wsig[nb][ks], mB[ks], zf[nb]);
-#pragma unroll
-        for (int nb = 0; nb < ZT; ++nb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) zf[nb][i] = mu[nb][i] + softplus_f(zf[nb][i]) * eps[nb][i >> 2][i & 3];
-            zB[2 * nb] = operand_of<0>(zf[nb]);
-            zB[2 * nb + 1] = operand_of<1>(zf[nb]);
+            for (int j = 0; j < 8; ++j) mq[j] = (__bf16)muq[j];
+            frag_mu[w * 64 + lane] = __builtin_bit_cast(f32x4, mq);
         }
+        __syncthreads();
+        // scale from the mean (this wavefront's tile only), reparameterised draw on its quarter.  Pad
+        // features need no masking: their mean is 0 (zero weight rows, zero c_t) and their noise was
+        // loaded as 0.
+        f32x16 sg = bias_tile(bias + oSig + 32 * own_tile + 4 * h);
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) sg = mma(wsig[ks], __builtin_bit_cast(bf16x8, frag_mu[ks * 64 + lane]), sg);
+        {
+            // (two copies of the loop, each with constant register numbers: one loop that picks its
+            // half at run time is compiled into a sixteen-way select per element)
+            bf16x8 zb8;
+            if (own_half) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) zq[j] = muq[j] + softplus_f(sg[8 + j]) * eps[j >> 2][j & 3];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) zq[j] = muq[j] + softplus_f(sg[j]) * eps[j >> 2][j & 3];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) zb8[j] = (__bf16)zq[j];
+            frag_z[w * 64 + lane] = __builtin_bit_cast(f32x4, zb8);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) zB[ks] = __builtin_bit_cast(bf16x8, frag_z[ks * 64 + lane]);
     }
-    if (a.z_last && live && w == 0) {
+    if (a.z_last && live) {
 #pragma unroll
-        for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int f = 32 * nb + 8 * q + 4 * h;
-                if (f < Z) {
-                    f32x4 v = {zf[nb][4 * q], zf[nb][4 * q + 1], zf[nb][4 * q + 2], zf[nb][4 * q + 3]};
-                    *reinterpret_cast<f32x4 *>(a.z_last + (size_t)smp * Z + f) = v;
-                }
+        for (int q = 0; q < 2; ++q) {
+            const int f = qfeat0 + 8 * q;
+            if (f < Z) {
+                f32x4 v = {zq[4 * q], zq[4 * q + 1], zq[4 * q + 2], zq[4 * q + 3]};
+                *reinterpret_cast<f32x4 *>(a.z_last + (size_t)smp * Z + f) = v;
             }
+        }
     }
 
     // ---- gated transition: weights used once per workgroup, fetched from L2 into the registers
