@@ -43,8 +43,10 @@ def sort_compare_exchanges(S, N):
     return S * (npad // 2) * (p * (p + 1) // 2)
 
 
-def stage_work(cfg):
-    """Work of one decision per stage id: (bound, algorithmic, executed).
+def stage_work(cfg, folded=True):
+    """Work of one decision per stage id: (bound, algorithmic, executed); folded: whether the kernels
+    that run apply the scale network's first layer folded (all but the four-samples-per-wavefront
+    kernel and the staged fall-back).
 
     Algorithmic: the flops of the layers as the paper writes them (MLP stages) and the bytes of the
     sample matrix (sort); their sum over the MLP stages is 2 S [L (2 Z R + Z^2) + (4 Z H + 2 Z^2) +
@@ -56,7 +58,7 @@ def stage_work(cfg):
     S, N, L, Z, H, R = cfg.samples, cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim
     guide = 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)
     layer = 2.0 * S * H * N
-    folded = 2.0 * S * H * H
+    folded_flops = 2.0 * S * H * H
     work = {
         1: ("mfma", guide, guide),
         2: ("mfma", 2.0 * S * Z * H, 2.0 * S * Z * H),
@@ -66,10 +68,10 @@ def stage_work(cfg):
         6: ("hbm", 4.0 * S * N, 4.0 * S * N),
     }
     algorithmic = sum(work[s][1] for s in range(1, 6))
-    work[8] = ("mfma", algorithmic, algorithmic - layer + folded)  # the fused sampler kernel does stages 1-5
-    if cfg.mlp_dtype == "bf16":
+    work[8] = ("mfma", algorithmic, algorithmic - layer + folded_flops if folded else algorithmic)  # the fused sampler kernel does stages 1-5
+    if cfg.mlp_dtype == "bf16" and folded:
         del work[3]
-        work[4] = ("mfma", layer, folded)
+        work[4] = ("mfma", layer, folded_flops)
         work[5] = ("mfma", 2 * layer, 2 * layer)
     return work
 
@@ -263,7 +265,6 @@ def run_workload(args, name, K, W, headline):
             api.dkf_sample_runtimes(pred.handle, S, eq, ez, ex, 0, out)
             api.cutoff_select(out, 1, N, 0.0, None, None, None, None, cst, ws)
 
-    work = stage_work(cfg)
     api.dkf_timing_enable((1 << api.DKF_NUM_STAGES) - 1)
     eager_steps(21)
     for s in range(api.DKF_NUM_STAGES):
@@ -279,6 +280,10 @@ def run_workload(args, name, K, W, headline):
         stage_us[s], stage_n[s] = ms / max(n, 1) * 1e3, n
     api.dkf_timing_enable(0)
     fused = stage_us[8] > 0  # stages 1-5 ran as one kernel
+    variant = pred.sampler_in_use(S)
+    # the layer-by-layer kernels: four samples per wavefront, and the staged fall-back (which records a stage 3)
+    layered = variant == api.SAMPLER_WAVE4 or (not fused and stage_n[3] > 0)
+    work = stage_work(cfg, folded=not layered)
     if fused:
         work = {s: w for s, w in work.items() if s in (6, 8)}
     else:

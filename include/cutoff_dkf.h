@@ -291,6 +291,12 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes);
 #define DKF_SAMPLER_SPLIT 4
 int dkf_set_sampler(dkf_model *m, int32_t variant);
 
+/* Which of the variants above a dkf_sample_runtimes / dkf_decide call with S samples
+ * launches under the current setting (never DKF_SAMPLER_AUTO; DKF_SAMPLER_STAGED
+ * stands for every path made of several kernels, bf16 models included).  Host
+ * call, no device work.  DKF_EINVAL for a NULL model or S < 1. */
+int dkf_sampler_in_use(const dkf_model *m, int32_t S);
+
 /* Per-kernel timing with HIP events recorded on the stream the kernels are
  * launched on (process-wide, for benchmarks; not recorded inside dkf_decide's
  * captured graph).  Stage ids: 0 filter (projection + RNN chains), 1 guide

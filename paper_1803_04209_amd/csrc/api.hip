@@ -656,14 +656,21 @@ constexpr int kQuadMaxSamples = 8192;
 // every layer over a workgroup's wavefronts has the shortest critical path.
 constexpr int kSplitMaxSamples = 4096;
 
+// The kernel family a call with S samples launches: one of the fused fp32 kernels, or
+// DKF_SAMPLER_STAGED for everything that runs as several kernels.
+int sampler_for(const dkf_model *m, int S) {
+    if (m->sampler == DKF_SAMPLER_STAGED || !(m->use_chain || m->use_quad || m->use_split)) return DKF_SAMPLER_STAGED;
+    if (m->sampler != DKF_SAMPLER_AUTO) return m->sampler;
+    // few samples: sixteen per workgroup or four per wavefront, so that they still spread over the whole chip
+    if (m->use_split && (S <= kSplitMaxSamples || (!m->use_chain && !m->use_quad))) return DKF_SAMPLER_SPLIT;
+    if (m->use_quad && (S <= kQuadMaxSamples || !m->use_chain)) return DKF_SAMPLER_WAVE4;
+    return DKF_SAMPLER_WAVE16;
+}
+
 int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
-    // few samples: four per wavefront, so that they still spread over the whole chip
-    const bool split = m->sampler == DKF_SAMPLER_SPLIT ||
-                       (m->sampler == DKF_SAMPLER_AUTO && m->use_split &&
-                        (S <= kSplitMaxSamples || (!m->use_chain && !m->use_quad)));
-    const bool quad = !split && (m->sampler == DKF_SAMPLER_WAVE4 ||
-                                 (m->sampler == DKF_SAMPLER_AUTO && m->use_quad && (S <= kQuadMaxSamples || !m->use_chain)));
+    const int variant = sampler_for(m, S);
+    const bool split = variant == DKF_SAMPLER_SPLIT, quad = variant == DKF_SAMPLER_WAVE4;
     ChainArgs c{};
     c.ctl = m->ctl_dev();
     c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
@@ -701,7 +708,7 @@ int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStr
 
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
                    float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
-    if (m->sampler != DKF_SAMPLER_STAGED && (m->use_chain || m->use_quad || m->use_split)) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
+    if (sampler_for(m, S) != DKF_SAMPLER_STAGED) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
     int rc = DKF_EUNSUPPORTED;
     if (m->sampler != DKF_SAMPLER_STAGED && m->use_gchain) {
         GChainArgs c{};
@@ -1181,6 +1188,11 @@ int dkf_set_sampler(dkf_model *m, int32_t variant) {
     if (variant != m->sampler) m->graph_S = 0;  // a captured decision graph holds the old kernels
     m->sampler = variant;
     return DKF_OK;
+}
+
+int dkf_sampler_in_use(const dkf_model *m, int32_t S) {
+    if (!m || S < 1) return DKF_EINVAL;
+    return sampler_for(m, S);
 }
 
 int dkf_timing_enable(uint32_t stage_mask) {

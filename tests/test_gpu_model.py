@@ -485,6 +485,27 @@ def test_decide_graph_replays_match_eager(api, name):
     eager.close()
 
 
+def test_sampler_in_use_follows_sizes_and_setting(api):
+    cfg = synth.CONFIGS["medium"]
+    g = api.Predictor(cfg, synth.make_blob(cfg))
+    assert [g.sampler_in_use(S) for S in (1, 4096, 4097, 8192, 8193)] == [SPLIT, SPLIT, WAVE4, WAVE4, WAVE16]
+    g.set_sampler(WAVE16)
+    assert g.sampler_in_use(16) == WAVE16
+    g.set_sampler(STAGED)
+    assert g.sampler_in_use(16) == STAGED
+    with pytest.raises(api.DkfError):
+        g.sampler_in_use(0)
+    g.close()
+    cfg = synth.CONFIGS["tiny"]  # widths the sixteen-per-workgroup kernel is not built for
+    g = api.Predictor(cfg, synth.make_blob(cfg))
+    assert g.sampler_in_use(cfg.samples) == WAVE4
+    g.close()
+    cfg = custom(N=64, L=2, Z=16, H=128, R=128, S=64)
+    g = api.Predictor(cfg, synth.make_blob(cfg), mlp_dtype=api.DKF_DTYPE_BF16)
+    assert g.sampler_in_use(64) == STAGED
+    g.close()
+
+
 def test_sampler_variant_selection(api):
     """A variant the model's sizes rule out is refused and the current one stays."""
     cfg = custom(N=130, L=3, Z=70, H=129, R=200, S=33)  # latent too wide for both fused kernels
