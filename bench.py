@@ -53,8 +53,10 @@ def stage_work(cfg, folded=True):
     (Z H + 3 H N)].  Executed: what the kernels issue.  They differ in one layer: the scale network's
     first layer is linear in the mean and the mean is linear in its hidden vector, so the kernels apply
     the H x H product of the two matrices, formed when the weights are loaded (2 S H H flops for the
-    layer's 2 S N H).  The bf16 emission runs as three kernels: stage 4 is that folded layer, stage 5
-    multiplies both N-wide output layers and draws, stage 3 has no kernel of its own."""
+    layer's 2 S N H).  The bf16 emission runs as two kernels after the guide/transition kernel, which
+    also computes the mean's hidden layer (stage 2 then records nothing and its work is counted in
+    stage 1): stage 4 is the folded layer, stage 5 multiplies both N-wide output layers and draws,
+    stage 3 has no kernel of its own."""
     S, N, L, Z, H, R = cfg.samples, cfg.n_workers, cfg.lag, cfg.z_dim, cfg.hidden, cfg.rnn_dim
     guide = 2.0 * S * (L * (2 * Z * R + Z * Z) + 4 * Z * H + 2 * Z * Z)
     layer = 2.0 * S * H * N
@@ -284,6 +286,9 @@ def run_workload(args, name, K, W, headline):
     # the layer-by-layer kernels: four samples per wavefront, and the staged fall-back (which records a stage 3)
     layered = variant == api.SAMPLER_WAVE4 or (not fused and stage_n[3] > 0)
     work = stage_work(cfg, folded=not layered)
+    if not fused and stage_n[2] == 0:  # the guide/transition kernel also computes the mean's hidden layer
+        work[1] = ("mfma", work[1][1] + work[2][1], work[1][2] + work[2][2])
+        del work[2]
     if fused:
         work = {s: w for s, w in work.items() if s in (6, 8)}
     else:

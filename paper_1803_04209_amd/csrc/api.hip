@@ -85,7 +85,7 @@ struct dkf_model {
     // emission layers and activations in fragment order (egemm.hip), bf16 models with use_gchain
     const float *ef_w[4] = {}, *ef_b[4] = {};  // emean1, emean2, escale1, escale2
     int ef_Hp = 0, ef_Np = 0, ef_samp_tiles = 0;
-    float *zfrag = nullptr, *h1frag = nullptr, *h2frag = nullptr;
+    float *h1frag = nullptr, *h2frag = nullptr;
 
 
     // filter state
@@ -398,6 +398,7 @@ int pack_gchain(dkf_model *m, const RawLayers &r) {
     };
     wide(r.comb, R); narrow(r.mu, R); small(r.sig);
     wide(r.gate1, H); narrow(r.gate2, H); wide(r.prop1, H); narrow(r.prop2, H); small(r.lin); small(r.tscale);
+    wide(r.emean1, H);
     std::vector<float> bt;
     auto add_bias = [&](const float *b, int n, int padded) {
         const size_t base = bt.size();
@@ -406,6 +407,7 @@ int pack_gchain(dkf_model *m, const RawLayers &r) {
     };
     add_bias(r.b_comb, R, HP); add_bias(r.b_sig, Z, 64); add_bias(r.b_gate1, H, HP); add_bias(r.b_gate2, Z, 64);
     add_bias(r.b_prop1, H, HP); add_bias(r.b_prop2, Z, 64); add_bias(r.b_lin, Z, 64); add_bias(r.b_tscale, Z, 64);
+    add_bias(r.b_emean1, H, HP);
     m->gc_bias_floats = (int)bt.size();
     std::vector<float> as_floats(t.size() / 2);
     std::memcpy(as_floats.data(), t.data(), t.size() * sizeof(uint16_t));
@@ -449,14 +451,12 @@ int pack_emission_frags(dkf_model *m, const RawLayers &r) {
     m->ef_samp_tiles = (m->cfg.max_samples + 255) / 256;
     std::vector<float> fold_w, fold_bf;
     fold_scale_hidden(r, H, N, fold_w, fold_bf);
-    int rc = pack_frag_layer(m, r.emean1, r.b_emean1, H, m->Z, Hp, 64, &m->ef_w[0], &m->ef_b[0]);
-    if (rc == DKF_OK) rc = pack_frag_layer(m, r.emean2, r.b_emean2, N, H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
+    // (the mean's first layer is part of the guide/transition kernel's tiles: pack_gchain)
+    int rc = pack_frag_layer(m, r.emean2, r.b_emean2, N, H, Np, Hp, &m->ef_w[1], &m->ef_b[1]);
     if (rc == DKF_OK) rc = pack_frag_layer(m, fold_w.data(), fold_bf.data(), H, H, Hp, Hp, &m->ef_w[2], &m->ef_b[2]);
     if (rc == DKF_OK) rc = pack_frag_layer(m, r.escale2, r.b_escale2, N, H, Np, Hp, &m->ef_w[3], &m->ef_b[3]);
     const size_t blocks = (size_t)m->ef_samp_tiles * 8;  // 32-sample blocks
     void *q = nullptr;
-    if (rc == DKF_OK) rc = dev_alloc(m, blocks * 4 * 1024, &q, true);
-    m->zfrag = static_cast<float *>(q);
     if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Hp / 16) * 1024, &q, true);
     m->h1frag = static_cast<float *>(q);
     if (rc == DKF_OK) rc = dev_alloc(m, blocks * (Hp / 16) * 1024, &q, true);
@@ -464,8 +464,8 @@ int pack_emission_frags(dkf_model *m, const RawLayers &r) {
     return rc;
 }
 
-// The emission on fragments: the mean's hidden layer, the scale's hidden layer (folded), and both
-// output layers with the draw; z_{T+1} fragments come from the guide/transition kernel.
+// The emission on fragments: the scale's hidden layer (folded) and both output layers with the
+// draw; the mean's hidden layer comes, as fragments, from the guide/transition kernel.
 int enqueue_emission_frags(dkf_model *m, int S, const float *eps_x, float *out_samples, const dkf_stage_outputs *st,
                            hipStream_t stream) {
     FragGemmArgs e{};
@@ -473,10 +473,7 @@ int enqueue_emission_frags(dkf_model *m, int S, const float *eps_x, float *out_s
     const int Hp = m->ef_Hp, Np = m->ef_Np;
     e.tile = 2; e.samp_tiles = (S + 255) / 256;
     int rc;
-    e.wfrag = m->ef_w[0]; e.bias = m->ef_b[0]; e.xfrag = m->zfrag; e.k_steps = 4; e.feat_tiles = Hp / 64;
-    e.epilogue = m->cfg.emit_mean_act ? kFragRelu : kFragIdentity;
-    e.out_frag = m->h1frag; e.out_k_steps = Hp / 16;
-    if ((rc = launch_frag_gemm(e, kStageEmitHidden, stream)) != DKF_OK) return rc;
+    e.feat_tiles = Hp / 64; e.out_k_steps = Hp / 16;
     e.wfrag = m->ef_w[2]; e.bias = m->ef_b[2]; e.xfrag = m->h1frag; e.k_steps = Hp / 16;
     e.epilogue = kFragRelu; e.out_frag = m->h2frag;
     if ((rc = launch_frag_gemm(e, kStageEmitScaleHidden, stream)) != DKF_OK) return rc;
@@ -721,7 +718,7 @@ int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, 
         c.z_last = st ? st->z_last : nullptr;
         c.z_next_dbg = st ? st->z_next : nullptr;
         c.z_next = nullptr;
-        c.zfrag = m->zfrag;
+        c.h1frag = m->h1frag; c.h1_k_steps = m->ef_Hp / 16; c.emit_mean_act = m->cfg.emit_mean_act;
         c.S = S; c.L = m->L; c.Z = m->Z; c.Zp = m->Zp; c.R = m->R; c.H = m->H;
         const bool aligned = ((reinterpret_cast<uintptr_t>(eps_x) | reinterpret_cast<uintptr_t>(out_samples) |
                                (st ? reinterpret_cast<uintptr_t>(st->emit_mean) | reinterpret_cast<uintptr_t>(st->emit_sd) : 0)) & 15) == 0;

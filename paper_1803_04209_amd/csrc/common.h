@@ -141,10 +141,10 @@ struct GChainArgs {
     // W[32 ob + l % 32][16 ks + 8 (j / 4) + 4 (l / 32) + j % 4].  With Q = gchain_q() tiles of hidden
     // width per wavefront, in this order: comb [w][ob < Q][ks < 4]; mu [w][nb < 2][ks < 2Q] (k-step
     // 2 w Q + ks of the matrix); sig [nb][ks]; gate1, gate2, prop1, prop2 like comb / mu; lin,
-    // tscale like sig.
+    // tscale like sig; emean1 like comb.
     const float *tiles;
     // fp32 biases, zero padded: comb [128 Q], sig [64], gate1 [128 Q], gate2 [64], prop1 [128 Q],
-    // prop2 [64], lin [64], tscale [64]
+    // prop2 [64], lin [64], tscale [64], emean1 [128 Q]
     const float *bias_table;
     int bias_floats;
     const float *mu_w32, *mu_b32;  // unrounded W_mu [Z][R] and b_mu [Z] for the context's share of the mean
@@ -153,7 +153,10 @@ struct GChainArgs {
     const float *eps_q, *eps_z;    // [L][S][Z], [S][Z]
     float *z_last, *z_next_dbg;    // [S][Z] or NULL
     float *z_next;                 // [S][Zp] fp32 rows or NULL
-    float *zfrag;                  // [ceil(S/32)][4][64 lanes][16 B] z_{T+1} as bf16 B fragments, or NULL
+    // hidden layer of the emission's mean as bf16 B fragments [ceil(S/32)][h1_k_steps][64 lanes][16 B], or
+    // NULL; emit_mean_act: 0 identity, 1 ReLU; h1_k_steps: padded H / 16 of the consumer (at most 8 Q)
+    float *h1frag;
+    int h1_k_steps, emit_mean_act;
     int S, L, Z, Zp, R, H;
 };
 int gchain_q(int Z, int R, int H);  // 0: sizes the kernel is not built for

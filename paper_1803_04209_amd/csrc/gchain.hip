@@ -17,13 +17,14 @@
 //                owns the eight registers per lane that make up B fragment w of the
 //                latent, sums, scales (Z -> Z product for its tile), draws and rounds
 //                only those, and the four fragments are handed round through LDS;
-//   in the transition every wavefront holds the summed latent and one finishes.
+//   the transition ends the same way (gate, linear branch, scale and draw by quarters), and
+//                the hidden layer of the emission's mean follows while z_{T+1} is at hand.
 // The context enters the mean linearly, mu = W_mu (tanh(.) + h_l + h_r) / 3 + b,
 // so its share c_t = W_mu (h_l,t + h_r,t) / 3 + b_mu is computed once per window
 // position by guide_context (fp32, unrounded weights) and added after the
 // matrix product: the per-sample work of a step is tanh on the accumulators and
 // three products.  Transition weights are used once per workgroup and are
-// streamed from L2 in the same tile format.
+// fetched from L2, all at once, in the same tile format.
 #include "common.h"
 #include "mfma_tile.h"
 
@@ -71,9 +72,11 @@ __global__ __launch_bounds__(256) void guide_context(GChainArgs a) {
 template <int Q>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void guide_chain_bf16(GChainArgs a) {
     extern __shared__ __align__(16) char lds_raw[];
-    // LDS: red[2][4][8][64] float4 (two exchange buffers), bias table, c_t table
+    // LDS: red[2][4][8][64] float4 (two exchange buffers for partial sums), frags[3][4][64] float4
+    // (hand-over of finished quarters), bias table, c_t table
     f32x4 *red = reinterpret_cast<f32x4 *>(lds_raw);
-    float *bias = reinterpret_cast<float *>(lds_raw + 2 * 4 * 8 * 64 * 16);
+    f32x4 *frags = red + 2 * 4 * 8 * 64;  // [3][4][64]: quarters of a latent-sized vector as bf16 B fragments
+    float *bias = reinterpret_cast<float *>(frags + 3 * 4 * 64);
     float *cmu = bias + a.bias_floats;
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int col = lane & 31, h = lane >> 5;
@@ -84,11 +87,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     constexpr int HP = 128 * Q;  // padded hidden width
     // bias table offsets (floats)
     constexpr int oC = 0, oSig = oC + HP, oG1 = oSig + 64, oG2 = oG1 + HP, oP1 = oG2 + 64, oP2 = oP1 + HP,
-                  oLin = oP2 + 64, oTs = oLin + 64;
+                  oLin = oP2 + 64, oTs = oLin + 64, oE1 = oTs + 64;
     // tile offsets
     constexpr int nWide = 4 * Q * ZK, nNarrow = 4 * ZT * 2 * Q, nSmall = ZT * ZK;
     constexpr int tC = 0, tMu = tC + nWide, tSig = tMu + nNarrow, tG1 = tSig + nSmall, tG2 = tG1 + nWide,
-                  tP1 = tG2 + nNarrow, tP2 = tP1 + nWide, tLin = tP2 + nNarrow, tTs = tLin + nSmall;
+                  tP1 = tG2 + nNarrow, tP2 = tP1 + nWide, tLin = tP2 + nNarrow, tTs = tLin + nSmall, tE1 = tTs + nSmall;
 
     // tables -> LDS, eight loads in flight per thread (a load-store loop would pay one memory round
     // trip per iteration)
@@ -126,45 +129,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         for (int j = 0; j < 8; ++j) zB[ks][j] = (__bf16)a.z0[16 * ks + 8 * (j >> 2) + 4 * h + (j & 3)];
     __syncthreads();
 
-    int buf = 0;
-    // Sum the four wavefronts' partial tiles p[ZT] in the order ((w0 + w1) + w2) + w3; every
-    // wavefront ends up with the same full result.
-    auto all_sum = [&](f32x16 (&p)[ZT]) {
-        f32x4 *mine = red + ((buf * 4 + w) * 8) * 64 + lane;
-#pragma unroll
-        for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                f32x4 v = {p[nb][4 * q], p[nb][4 * q + 1], p[nb][4 * q + 2], p[nb][4 * q + 3]};
-                mine[(nb * 4 + q) * 64] = v;
-            }
-        __syncthreads();
-        const f32x4 *all = red + (buf * 4 * 8) * 64 + lane;
-#pragma unroll
-        for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int e = (nb * 4 + q) * 64;
-                const f32x4 s = ((all[e] + all[8 * 64 + e]) + all[16 * 64 + e]) + all[24 * 64 + e];
-                p[nb][4 * q] = s[0]; p[nb][4 * q + 1] = s[1]; p[nb][4 * q + 2] = s[2]; p[nb][4 * q + 3] = s[3];
-            }
-        buf ^= 1;
-    };
-    // feature (within the 64-wide latent) of element i of latent tile nb in this lane
-    auto zfeat = [&](int nb, int i) { return 32 * nb + 8 * (i >> 2) + 4 * h + (i & 3); };
-    // 16 floats of a [.][Z] noise row for this lane's features of latent tile nb (zero where there is no such feature)
-    auto load_noise = [&](const float *__restrict__ row, f32x4 (&e)[ZT][4]) {
-#pragma unroll
-        for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int f = 32 * nb + 8 * q + 4 * h;
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (live && f < Z) v = *reinterpret_cast<const f32x4 *>(row + f);
-                e[nb][q] = v;
-            }
-    };
-
     // accumulator tile that starts at the bias of this lane's 16 features (read from the LDS table)
     auto bias_tile = [&](const float *b) {  // b: table entry of the tile's first feature + 4 h
         f32x16 v;
@@ -185,7 +149,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // costs four times the transcendental work of this part and four times the LDS reads.)
     // Three barriers per step; each buffer is written two barriers after its last read.
     const int own_tile = w >> 1, own_half = w & 1;
-    f32x4 *frag_mu = red + (4 * 8) * 64, *frag_z = frag_mu + 4 * 64;  // [4][64] each, in the second exchange buffer
+    f32x4 *frag_mu = frags, *frag_z = frags + 4 * 64, *frag_g = frags + 8 * 64;
     float zq[8] = {};  // this wavefront's quarter of z_t, fp32
     // this quarter's features: register j <-> 32 own_tile + 16 own_half + 8 (j / 4) + 4 h + j % 4
     const int qfeat0 = 32 * own_tile + 16 * own_half + 4 * h;
@@ -294,21 +258,46 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
     }
 
-    // ---- gated transition: weights used once per workgroup, fetched from L2 into the registers
-    // the guide's weights occupied ------------------------------------------------------------
+    // ---- gated transition and the emission's first layer: weights used once per workgroup.  All of
+    // them are requested here, at once, into the registers the guide's weights occupied: one L2 round
+    // trip for the whole tail instead of one per layer. ---------------------------------------------
+    bf16x8 wg1[Q][ZK], wg2[ZT][2 * Q], wp1[Q][ZK], wp2[ZT][2 * Q], wl[ZK], wt[ZK], we[Q][ZK];
+#pragma unroll
+    for (int ob = 0; ob < Q; ++ob)
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) {
+            wg1[ob][ks] = load_tile(T, tG1 + (w * Q + ob) * ZK + ks, lane);
+            wp1[ob][ks] = load_tile(T, tP1 + (w * Q + ob) * ZK + ks, lane);
+            we[ob][ks] = load_tile(T, tE1 + (w * Q + ob) * ZK + ks, lane);
+        }
+#pragma unroll
+    for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+        for (int ks = 0; ks < 2 * Q; ++ks) {
+            wg2[nb][ks] = load_tile(T, tG2 + (w * ZT + nb) * 2 * Q + ks, lane);
+            wp2[nb][ks] = load_tile(T, tP2 + (w * ZT + nb) * 2 * Q + ks, lane);
+        }
+#pragma unroll
+    for (int ks = 0; ks < ZK; ++ks) {  // of the two Z -> Z layers only the tile of this wavefront's quarter
+        wl[ks] = load_tile(T, tLin + own_tile * ZK + ks, lane);
+        wt[ks] = load_tile(T, tTs + own_tile * ZK + ks, lane);
+    }
+    f32x4 epz[2];
+    {
+        const float *__restrict__ row = a.eps_z + (size_t)(live ? smp : 0) * Z;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int f = qfeat0 + 8 * q;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (live && f < Z) v = *reinterpret_cast<const f32x4 *>(row + f);
+            epz[q] = v;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
     // wide layer (Z -> H) of this wavefront's quarter + ReLU, then the narrow layer's partial
-    // product over that quarter, summed over the wavefronts
-    auto two_layer = [&](int t_wide, int o_wide, int t_narrow, f32x16 (&out)[ZT]) {
-        bf16x8 ww[Q][ZK], wn[ZT][2 * Q];
-#pragma unroll
-        for (int ob = 0; ob < Q; ++ob)
-#pragma unroll
-            for (int ks = 0; ks < ZK; ++ks) ww[ob][ks] = load_tile(T, t_wide + (w * Q + ob) * ZK + ks, lane);
-#pragma unroll
-        for (int nb = 0; nb < ZT; ++nb)
-#pragma unroll
-            for (int ks = 0; ks < 2 * Q; ++ks) wn[nb][ks] = load_tile(T, t_narrow + (w * ZT + nb) * 2 * Q + ks, lane);
-        f32x16 pre[Q];
+    // product over that quarter; the partial sums go to exchange buffer `xb`
+    auto two_layer = [&](const bf16x8 (&ww)[Q][ZK], int o_wide, const bf16x8 (&wn)[ZT][2 * Q], int xb) {
+        f32x16 pre[Q], out[ZT];
 #pragma unroll
         for (int ob = 0; ob < Q; ++ob) pre[ob] = bias_tile(bias + o_wide + 32 * (w * Q + ob) + 4 * h);
 #pragma unroll
@@ -327,69 +316,117 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int nb = 0; nb < ZT; ++nb) out[nb] = mma(wn[nb][2 * ob + 1], h1, out[nb]);
         }
-        all_sum(out);
+        f32x4 *mine = red + ((xb * 4 + w) * 8) * 64 + lane;
+#pragma unroll
+        for (int nb = 0; nb < ZT; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 v = {out[nb][4 * q], out[nb][4 * q + 1], out[nb][4 * q + 2], out[nb][4 * q + 3]};
+                mine[(nb * 4 + q) * 64] = v;
+            }
     };
-    f32x16 gate[ZT], prop[ZT];
-    two_layer(tG1, oG1, tG2, gate);
-    two_layer(tP1, oP1, tP2, prop);
-    if (w != 0) return;  // every wavefront now holds the same sums; one of them finishes and writes
-    f32x4 eps[ZT][4];
-    load_noise(a.eps_z + (size_t)(live ? smp : 0) * Z, eps);
-    bf16x8 wl[ZT][ZK], wt[ZT][ZK];
+    // this wavefront's quarter of the sum of the four partial tiles in buffer xb, ((w0 + w1) + w2) + w3
+    auto quarter_sum = [&](int xb, float (&s8)[8]) {
+        const f32x4 *all = red + (xb * 4 * 8) * 64 + lane;
 #pragma unroll
-    for (int nb = 0; nb < ZT; ++nb)
+        for (int q = 0; q < 2; ++q) {
+            const int e = (own_tile * 4 + 2 * own_half + q) * 64;
+            const f32x4 s4 = ((all[e] + all[8 * 64 + e]) + all[16 * 64 + e]) + all[24 * 64 + e];
 #pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) {
-            wl[nb][ks] = load_tile(T, tLin + nb * ZK + ks, lane);
-            wt[nb][ks] = load_tile(T, tTs + nb * ZK + ks, lane);
+            for (int r = 0; r < 4; ++r) s8[4 * q + r] = s4[r];
         }
-    f32x16 G[ZT];
-    bf16x8 gB[ZK];
+    };
+    // own half (eight registers) of a result tile, with constant register numbers in either case
+    auto own_regs = [&](const f32x16 &t, float (&o8)[8]) {
+        if (own_half) {
 #pragma unroll
-    for (int nb = 0; nb < ZT; ++nb) {
-        f32x16 lin = bias_tile(bias + oLin + 32 * nb + 4 * h);
+            for (int j = 0; j < 8; ++j) o8[j] = t[8 + j];
+        } else {
 #pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) lin = mma(wl[nb][ks], zB[ks], lin);
-        f32x16 relu;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int f = zfeat(nb, i);
-            const float g = sigmoid_f(gate[nb][i] + bias[oG2 + f]);
-            const float v = (1.f - g) * lin[i] + g * (prop[nb][i] + bias[oP2 + f]);
-            G[nb][i] = f < Z ? v : 0.f;
-            relu[i] = fmaxf(G[nb][i], 0.f);
+            for (int j = 0; j < 8; ++j) o8[j] = t[j];
         }
-        gB[2 * nb] = operand_of<0>(relu);
-        gB[2 * nb + 1] = operand_of<1>(relu);
+    };
+    two_layer(wg1, oG1, wg2, 0);
+    two_layer(wp1, oP1, wp2, 1);
+    // the Z -> Z layer of the linear branch, for the tile of this wavefront's quarter
+    f32x16 lin = bias_tile(bias + oLin + 32 * own_tile + 4 * h);
+#pragma unroll
+    for (int ks = 0; ks < ZK; ++ks) lin = mma(wl[ks], zB[ks], lin);
+    __syncthreads();
+    float gq[8], pq[8], lq[8], Gq[8];
+    quarter_sum(0, gq);
+    quarter_sum(1, pq);
+    own_regs(lin, lq);
+    {
+        bf16x8 g8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int f = qfeat0 + 8 * (j >> 2) + (j & 3);
+            const float g = sigmoid_f(gq[j] + bias[oG2 + f]);
+            const float v = (1.f - g) * lq[j] + g * (pq[j] + bias[oP2 + f]);
+            Gq[j] = f < Z ? v : 0.f;
+            g8[j] = (__bf16)fmaxf(Gq[j], 0.f);
+        }
+        frag_g[w * 64 + lane] = __builtin_bit_cast(f32x4, g8);
     }
+    __syncthreads();
+    f32x16 ts = bias_tile(bias + oTs + 32 * own_tile + 4 * h);
 #pragma unroll
-    for (int nb = 0; nb < ZT; ++nb) {
-        f32x16 acc = bias_tile(bias + oTs + 32 * nb + 4 * h);
+    for (int ks = 0; ks < ZK; ++ks) ts = mma(wt[ks], __builtin_bit_cast(bf16x8, frag_g[ks * 64 + lane]), ts);
+    float tq[8], znq[8];
+    own_regs(ts, tq);
+    {
+        bf16x8 z8;
 #pragma unroll
-        for (int ks = 0; ks < ZK; ++ks) acc = mma(wt[nb][ks], gB[ks], acc);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float zn = G[nb][i] + softplus_f(acc[i]) * eps[nb][i >> 2][i & 3];
-            acc[i] = zfeat(nb, i) < Z ? zn : 0.f;
+        for (int j = 0; j < 8; ++j) {
+            const int f = qfeat0 + 8 * (j >> 2) + (j & 3);
+            const float zn = Gq[j] + softplus_f(tq[j]) * epz[j >> 2][j & 3];
+            znq[j] = f < Z ? zn : 0.f;
+            z8[j] = (__bf16)znq[j];
         }
-        if (a.zfrag) {  // B fragments of the emission's first layer (all 32 lanes: rows beyond S are finite padding)
-            f32x4 *out = reinterpret_cast<f32x4 *>(a.zfrag) + ((size_t)blockIdx.x * ZK + 2 * nb) * 64 + lane;
-            out[0] = __builtin_bit_cast(f32x4, operand_of<0>(acc));
-            out[64] = __builtin_bit_cast(f32x4, operand_of<1>(acc));
-        }
-        if (!live) continue;
+        // (rows beyond S too: finite padding for the layers that follow)
+        frag_z[w * 64 + lane] = __builtin_bit_cast(f32x4, z8);
+    }
+    if (live) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int f = 32 * nb + 8 * q + 4 * h;
-            const f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        for (int q = 0; q < 2; ++q) {
+            const int f = qfeat0 + 8 * q;
+            const f32x4 v = {znq[4 * q], znq[4 * q + 1], znq[4 * q + 2], znq[4 * q + 3]};
             if (a.z_next) *reinterpret_cast<f32x4 *>(a.z_next + (size_t)smp * a.Zp + f) = v;
             if (a.z_next_dbg && f < Z) *reinterpret_cast<f32x4 *>(a.z_next_dbg + (size_t)smp * Z + f) = v;
+        }
+    }
+    // Hidden layer of the emission's mean (Z -> H), while z_{T+1} is at hand: each wavefront multiplies
+    // its quarter of the output features and writes them as the B fragments the emission's kernels read.
+    if (a.h1frag) {
+        __syncthreads();
+        bf16x8 znB[ZK];
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks) znB[ks] = __builtin_bit_cast(bf16x8, frag_z[ks * 64 + lane]);
+        f32x16 pre[Q];
+#pragma unroll
+        for (int ob = 0; ob < Q; ++ob) pre[ob] = bias_tile(bias + oE1 + 32 * (w * Q + ob) + 4 * h);
+#pragma unroll
+        for (int ks = 0; ks < ZK; ++ks)
+#pragma unroll
+            for (int ob = 0; ob < Q; ++ob) pre[ob] = mma(we[ob][ks], znB[ks], pre[ob]);
+#pragma unroll
+        for (int ob = 0; ob < Q; ++ob) {
+            const int mb = w * Q + ob;
+            if (2 * mb >= a.h1_k_steps) continue;  // feature blocks past the emission's padded width
+            if (a.emit_mean_act) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) pre[ob][i] = fmaxf(pre[ob][i], 0.f);
+            }
+            f32x4 *out = reinterpret_cast<f32x4 *>(a.h1frag) + ((size_t)blockIdx.x * a.h1_k_steps + 2 * mb) * 64 + lane;
+            out[0] = __builtin_bit_cast(f32x4, operand_of<0>(pre[ob]));
+            out[64] = __builtin_bit_cast(f32x4, operand_of<1>(pre[ob]));
         }
     }
 }
 
 size_t gchain_lds(const GChainArgs &a) {
-    return (size_t)2 * 4 * 8 * 64 * 16 + ((size_t)a.bias_floats + (size_t)a.L * 64) * sizeof(float);
+    return (size_t)(2 * 4 * 8 + 3 * 4) * 64 * 16 + ((size_t)a.bias_floats + (size_t)a.L * 64) * sizeof(float);
 }
 
 template <int Q>
