@@ -78,6 +78,16 @@ def stage_work(cfg, folded=True):
     return work
 
 
+# What the GPU parity tests establish for the arithmetic a workload runs in (tests/test_gpu_model.py).
+PARITY_NOTE = {
+    "default": "every stage within 1e-4 (relative to max(|ref|, rms)) of the fp64 oracle at this size",
+    ("bf16", "raw"): "with these untrained N(0, 0.1^2) weights the prescribed bf16 rounding itself is a few 1e-2 "
+                     "away from fp64 after the gate (the oracle's own mixed-precision mode shows the same "
+                     "distribution): z_T meets 2e-2 in the max norm, 1-5 % of the later entries do not; damped "
+                     "or calibrated weights meet 2e-2 on every stage",
+    ("bf16", "calibrated"): "every stage within 2e-2 (relative to max(|ref|, rms)) of the fp64 oracle at this size",
+}
+
 # Sources whose change invalidates stored hardware-counter readings of a stage's kernel.
 STAGE_SOURCES = {
     "sampler_fused": ["chain.hip", "quad.hip", "split.hip", "mfma16.h", "common.h", "mfma_tile.h"],
@@ -357,6 +367,7 @@ def run_workload(args, name, K, W, headline):
         "config": {"workload": f"{cfg.name}: N={N} L={cfg.lag} Z={cfg.z_dim} H={cfg.hidden} S={S}",
                    "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay)",
                    "weights": args.weights},
+        "parity_note": PARITY_NOTE.get((cfg.mlp_dtype, args.weights), PARITY_NOTE["default"]),
         "decisions_per_s": K / wall,
         "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3),
                        "decisions": KL},
