@@ -77,6 +77,7 @@ struct dkf_model {
     const float *quad_guide = nullptr, *quad_stream = nullptr, *quad_bias = nullptr;
     int quad_chunks = 0;
     bool use_split = false;  // sizes covered by the sixteen-samples-per-workgroup sampler
+    int split_waves = 8;     // wavefronts per workgroup of that sampler: two per SIMD, so that one's vector work overlaps the other's matrix work
     const float *split_stream = nullptr, *split_bias = nullptr;
     bool use_gchain = false;  // bf16 sizes covered by the register-resident guide/transition kernel
     const float *gc_tiles = nullptr, *gc_bias = nullptr, *gc_mu_w32 = nullptr, *gc_mu_b32 = nullptr;
@@ -315,43 +316,50 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
 }
 
 // One tile stream per wavefront for the sixteen-samples-per-workgroup sampler (split.hip), in the
-// order wavefront w consumes it (RQ = RB / 4, HQ = HB / 4, C = 2 HB tiles per chunk):
-//   guide:  comb [o < RQ][ib] (output block w RQ + o), mu [zb][i < RQ] (input block w RQ + i), sig [zb][ib];
+// order wavefront w of W = split_waves consumes it (RQ = RB / W, HQ = HB / W, C = 2 HB tiles per chunk, HB for W = 8):
+//   guide (wavefronts 0-3, RQ = RB / 4; zeros for the others):  comb [o < RQ][ib] (output block w RQ + o),
+//           mu [zb][i < RQ] (input block w RQ + i), sig [zb][ib];
 //   head, padded with zero tiles to whole chunks:  gate1 [o < HQ][ib], gate2 [zb][i < HQ], prop1, prop2
 //           likewise, lin [ob][ib], tscale [ob][ib], emean1 [o < HQ][ib];
-//   the folded H x H layer (fold_scale_hidden):  row w HQ + o (ib < HB) for o < HQ, whole chunks;
-//   per own worker block nb = w NBW + u, one chunk:  emean2 row nb (ib < HB), escale2 row nb (ib < HB);
+//   the folded H x H layer (fold_scale_hidden):  row w HQ + o (ib < HB) for o < HQ, padded to whole chunks;
+//   per own worker block nb = w NBW + u, 2 HB tiles:  emean2 row nb (ib < HB), escale2 row nb (ib < HB);
 //   one spare chunk of zeros.
 // Biases: the table of the sixteen-per-wavefront kernel.
 int pack_split(dkf_model *m, const RawLayers &r) {
     const int Z = m->Z, R = m->R, H = m->H, N = m->N;
     const int ZB = (Z + 15) / 16, RB = (R + 15) / 16, HB = (H + 15) / 16, NB = (N + 15) / 16;
-    const int RQ = RB / 4, HQ = HB / 4, C = 2 * HB, NBW = (NB + 3) / 4;
-    const int per_wave = split_stream_tiles(Z, R, H, N);
+    const int W = m->split_waves;
+    const int RQ = RB / 4, HQ = HB / W, C = W == 8 ? HB : 2 * HB, NBW = (NB + W - 1) / W;  // the guide chain runs on wavefronts 0-3
+    const int per_wave = split_stream_tiles(Z, R, H, N, W);
     if (per_wave <= 0) return DKF_EINVAL;
     std::vector<float> fold_w, fold_b;
     fold_scale_hidden(r, H, N, fold_w, fold_b);
     std::vector<float> s;
-    s.reserve((size_t)4 * per_wave * 256);
-    for (int w = 0; w < 4; ++w) {
+    s.reserve((size_t)W * per_wave * 256);
+    for (int w = 0; w < W; ++w) {
         const size_t start = s.size();
         auto pad = [&] {
             const size_t head = start + (size_t)(2 * RQ * ZB + ZB * ZB) * 256, chunk = (size_t)C * 256;
             s.resize(head + (s.size() - head + chunk - 1) / chunk * chunk, 0.f);
         };
         auto zeros = [&](int tiles) { s.resize(s.size() + (size_t)tiles * 256, 0.f); };
-        for (int o = 0; o < RQ; ++o) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.comb, R, Z, w * RQ + o, ib);
-        for (int zb = 0; zb < ZB; ++zb) for (int i = 0; i < RQ; ++i) append_tile(s, r.mu, Z, R, zb, w * RQ + i);
-        for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.sig, Z, Z, zb, ib);
+        if (w < 4) {
+            for (int o = 0; o < RQ; ++o) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.comb, R, Z, w * RQ + o, ib);
+            for (int zb = 0; zb < ZB; ++zb) for (int i = 0; i < RQ; ++i) append_tile(s, r.mu, Z, R, zb, w * RQ + i);
+            for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(s, r.sig, Z, Z, zb, ib);
+        } else {
+            zeros(2 * RQ * ZB + ZB * ZB);
+        }
         auto wide = [&](const float *wt) { for (int o = 0; o < HQ; ++o) for (int ib = 0; ib < ZB; ++ib) append_tile(s, wt, H, Z, w * HQ + o, ib); };
         auto narrow = [&](const float *wt) { for (int zb = 0; zb < ZB; ++zb) for (int i = 0; i < HQ; ++i) append_tile(s, wt, Z, H, zb, w * HQ + i); };
         auto small = [&](const float *wt) { for (int ob = 0; ob < ZB; ++ob) for (int ib = 0; ib < ZB; ++ib) append_tile(s, wt, Z, Z, ob, ib); };
         wide(r.gate1); narrow(r.gate2); wide(r.prop1); narrow(r.prop2); small(r.lin); small(r.tscale); wide(r.emean1);
         pad();
         for (int o = 0; o < HQ; ++o) for (int ib = 0; ib < HB; ++ib) append_tile(s, fold_w.data(), H, H, w * HQ + o, ib);
+        pad();
         for (int u = 0; u < NBW; ++u) {
             const int nb = w * NBW + u;
-            if (nb >= NB) { zeros(C); continue; }
+            if (nb >= NB) { zeros(2 * HB); continue; }
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.emean2, N, H, nb, ib);
             for (int ib = 0; ib < HB; ++ib) append_tile(s, r.escale2, N, H, nb, ib);
         }
@@ -672,7 +680,7 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.ctl = m->ctl_dev();
     c.ctx_f = m->ctx_f; c.ctx_b = m->ctx_b; c.Rp = m->Rp;
     if (split) {
-        c.stream_tiles = m->split_stream; c.bias_table = m->split_bias;
+        c.stream_tiles = m->split_stream; c.bias_table = m->split_bias; c.split_waves = m->split_waves;
     } else if (quad) {
         c.guide_tiles = m->quad_guide; c.stream_tiles = m->quad_stream; c.stream_chunks = m->quad_chunks;
         c.bias_table = m->quad_bias;
@@ -902,7 +910,7 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
     m->use_quad = !bf16 && quad_supported(Z, R, H, L, N);
     if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
-    m->use_split = !bf16 && split_supported(Z, R, H, L, N);
+    m->use_split = !bf16 && split_supported(Z, R, H, L, N, m->split_waves);
     if (m->use_split) DKF_CHECK(pack_split(m, raw));
     m->use_gchain = bf16 && gchain_q(Z, R, H) != 0 && m->Zp == 64;
     if (m->use_gchain) DKF_CHECK(pack_gchain(m, raw));

@@ -232,6 +232,7 @@ struct ChainArgs {
     float *z_last, *z_next_dbg, *out_mean_dbg, *out_sd_dbg;  // optional
     int S, L, Z, R, H, N, NB;
     int emit_mean_act;
+    int split_waves;  // split.hip only: wavefronts per workgroup the streams were packed for (4 or 8)
 };
 // tiles (16 x 16 weights, 1 KiB) per streamed chunk for a hidden width of hb 16-blocks
 __host__ __device__ constexpr int chain_chunk_tiles(int hb) { return hb >= 8 ? 32 : 4 * hb; }
@@ -263,12 +264,12 @@ __host__ __device__ constexpr QuadPlan quad_plan(int zq, int hg) {
 bool quad_supported(int Z, int R, int H, int L, int N);
 int launch_quad(const ChainArgs &a, hipStream_t stream);
 
-// split.hip: the same chain with sixteen samples per workgroup, every layer split over its four
-// wavefronts.  Same arguments; stream_tiles is one stream per wavefront (pack_split, api.hip),
+// split.hip: the same chain with sixteen samples per workgroup, every layer split over its four or
+// eight wavefronts (ChainArgs::split_waves).  Same arguments; stream_tiles is one stream per wavefront (pack_split, api.hip),
 // split_stream_tiles() tiles apart; bias_table is the layout of chain.hip; guide_tiles, stream_chunks
 // and mean are not used.
-bool split_supported(int Z, int R, int H, int L, int N);
-int split_stream_tiles(int Z, int R, int H, int N);  // tiles of one wavefront's stream (0: sizes not built)
+bool split_supported(int Z, int R, int H, int L, int N, int waves);
+int split_stream_tiles(int Z, int R, int H, int N, int waves);  // tiles of one wavefront's stream (0: sizes not built)
 int launch_split(const ChainArgs &a, hipStream_t stream);
 
 // noise.hip: out[0..n) = standard normals of stream `tensor` (0 eps_q, 1 eps_z, 2 eps_x); the seed

@@ -1,26 +1,29 @@
 // Posterior-predictive sampling for a few thousand samples (Sec. 3.1.3): the chain of layers of
 // chain.hip -- L guide steps, the gated transition draw, the emission draw -- with sixteen samples
-// per WORKGROUP instead of per wavefront.  The four wavefronts of a workgroup work on the same
-// sixteen samples and split every layer between them, so that 4096 samples put one wavefront on
-// every SIMD of the chip while each matrix instruction still carries sixteen samples.
+// per WORKGROUP instead of per wavefront.  The W (four or eight) wavefronts of a workgroup work on
+// the same sixteen samples and split every layer between them, so that 4096 samples put one or two
+// wavefronts on every SIMD of the chip while each matrix instruction still carries sixteen samples.
+// Two per SIMD is what pays: a wavefront's vector work does not run in the shadow of its own matrix
+// instructions, another wavefront's does.
 //
 // How a layer is split (activation blocks of 16 features x 16 samples as in mfma16.h):
 //   wide layers   (Z -> R, Z -> H):  by output blocks; every wavefront holds the whole latent, so
 //                                    nothing is exchanged before the layer;
-//   narrow layers (R -> Z, H -> Z):  by input blocks, each wavefront using the quarter of the hidden
-//                                    features it has just computed itself; the four partial results
-//                                    are added through LDS in a fixed order ((w0 + w1) + w2) + w3,
+//   narrow layers (R -> Z, H -> Z):  by input blocks, each wavefront using the share of the hidden
+//                                    features it has just computed itself; the W partial results
+//                                    are added through LDS in a fixed order ((w0 + w1) + w2) + ...,
 //                                    after which every wavefront holds the whole latent again;
-//   Z -> Z layers:                   computed by all four wavefronts alike;
+//   Z -> Z layers:                   computed by all wavefronts alike;
 //   emission:  the mean's hidden layer is computed by output blocks and gathered through LDS.  The
 //              scale network's first layer is linear in the mean and the mean linear in that
 //              hidden layer, so it is applied as their H x H product (formed when the weights are
-//              loaded): a second hidden layer, again by output blocks and gathered.  After that a
-//              wavefront owns a contiguous quarter of the workers and, for each of its 16-worker
-//              blocks, forms mean and scale from the two hidden layers and draws.
+//              loaded): a second hidden layer, again by output blocks and gathered.  Both stay in
+//              LDS (an operand block is read per tile).  After that a wavefront owns a contiguous
+//              share of the workers and, for each of its 16-worker blocks, forms mean and scale
+//              from the two hidden layers and draws.
 // One exchange per guide step, one for the transition, two for the emission.
 //
-// Weights: a wavefront only ever touches its own quarter of every matrix.  Its share of the guide's
+// Weights: a wavefront only ever touches its own share of every matrix.  Its share of the guide's
 // three matrices stays in registers for the L steps; everything else is laid out, when the
 // weights are loaded (pack_split, api.hip), as one stream per wavefront in exactly the order it is
 // consumed, and flows from L2 straight into a ring of registers one block of work ahead of the
@@ -28,51 +31,56 @@
 #include "common.h"
 #include "mfma_tile.h"
 #include "mfma16.h"
+#include <type_traits>
 
 namespace dkf {
 namespace {
 
-constexpr int kThreads = 256;
 constexpr int kTileF4 = 64;
 
-template <int ZB, int RB, int HB>
+template <int ZB, int RB, int HB, int W>
 struct SplitShape {
-    static_assert(RB % 4 == 0 && HB % 4 == 0, "hidden widths split four ways");
-    static constexpr int RQ = RB / 4, HQ = HB / 4;
-    static constexpr int kGuide = 2 * RQ * ZB + ZB * ZB;       // tiles held in registers
-    static constexpr int C = 2 * HB;                           // ring size = tiles of one emission block
+    static_assert(RB % 4 == 0 && HB % W == 0, "hidden widths split four and W ways");
+    static constexpr int GW = 4;                               // wavefronts that run the guide chain
+    static constexpr int RQ = RB / GW, HQ = HB / W;
+    static constexpr int kGuide = 2 * RQ * ZB + ZB * ZB;       // tiles held in registers (wavefronts below GW)
+    // ring size: the tiles of one emission block (mean row + scale row), or half of that where two
+    // wavefronts share a SIMD's registers
+    static constexpr int C = W == 8 ? HB : 2 * HB;
+    static constexpr int kBlockChunks = 2 * HB / C;
     static constexpr int kHead = 5 * HQ * ZB + 2 * ZB * ZB;    // gate1 gate2 prop1 prop2 lin tscale emean1
     static constexpr int kHeadChunks = (kHead + C - 1) / C;
-    static_assert(HQ % 2 == 0, "a wavefront's rows of the folded layer fill whole chunks");
-    static constexpr int kFoldChunks = HQ * HB / C;
+    static constexpr int kFold = HQ * HB;                      // this wavefront's rows of the folded layer
+    static constexpr int kFoldChunks = (kFold + C - 1) / C;
     // tiles of one wavefront's stream for nbw worker blocks per wavefront (one spare chunk at the end:
     // the ring always requests one chunk ahead)
     __host__ __device__ static constexpr int stream_tiles(int nbw) {
-        return kGuide + (kHeadChunks + kFoldChunks + nbw + 1) * C;
+        return kGuide + (kHeadChunks + kFoldChunks + nbw * kBlockChunks + 1) * C;
     }
 };
 
-template <int ZB, int RB, int HB, bool DBG>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void sample_split(ChainArgs a) {
-    using Sh = SplitShape<ZB, RB, HB>;
-    constexpr int RQ = Sh::RQ, HQ = Sh::HQ, C = Sh::C;
+template <int ZB, int RB, int HB, int W, bool DBG>
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W / 4, W / 4))) void sample_split(ChainArgs a) {
+    using Sh = SplitShape<ZB, RB, HB, W>;
+    constexpr int RQ = Sh::RQ, HQ = Sh::HQ, C = Sh::C, kThreads = 64 * W;
     constexpr int Z16 = ZB * 16, R16 = RB * 16, H16 = HB * 16;
     extern __shared__ __align__(16) char lds_raw[];
     // LDS: exchange buffers, then the encodings' table and the bias table
-    f32x4 *x_mu = reinterpret_cast<f32x4 *>(lds_raw);          // [2][4][2 ZB][64]  latent-sized partial sums
-    f32x4 *x_h1 = x_mu + 2 * 4 * 2 * ZB * kTileF4;             // [HB][64]          hidden layer of the mean
+    f32x4 *x_mu = reinterpret_cast<f32x4 *>(lds_raw);          // [2][W][2 ZB][64]  latent-sized partial sums
+    f32x4 *x_h1 = x_mu + 2 * W * 2 * ZB * kTileF4;             // [HB][64]          hidden layer of the mean
     f32x4 *x_h2 = x_h1 + HB * kTileF4;                         // [HB][64]          hidden layer of the scale
-    float *ctx = reinterpret_cast<float *>(x_h2 + HB * kTileF4);  // [L][R16]
+    f32x4 *x_sum = x_h2 + HB * kTileF4;                        // [ZB][64]          the latent after the guide chain (W = 8)
+    float *ctx = reinterpret_cast<float *>(x_sum + ZB * kTileF4);  // [L][R16]
     float *bias = ctx + a.L * R16;
     const int NB = a.NB, N16 = NB * 16;
-    const int NBW = (NB + 3) / 4;  // worker blocks per wavefront
+    const int NBW = (NB + W - 1) / W;  // worker blocks per wavefront
     float *lb_comb = bias, *lb_mu = lb_comb + R16, *lb_sig = lb_mu + Z16;
     float *lb_gate1 = lb_sig + Z16, *lb_gate2 = lb_gate1 + H16, *lb_prop1 = lb_gate2 + Z16;
     float *lb_prop2 = lb_prop1 + H16, *lb_lin = lb_prop2 + Z16, *lb_tscale = lb_lin + Z16;
     float *lb_emean1 = lb_tscale + Z16, *lb_escale1 = lb_emean1 + H16, *lb_emean2 = lb_escale1 + H16;
     float *lb_escale2 = lb_emean2 + N16;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = lane >> 4;
     const int S = a.S, Z = a.Z, N = a.N;
     const int smp = blockIdx.x * 16 + (lane & 15);
@@ -82,18 +90,20 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // this wavefront's weight stream
     const f32x4 *T = reinterpret_cast<const f32x4 *>(a.stream_tiles) + (size_t)w * Sh::stream_tiles(NBW) * kTileF4 + lane;
     f32x4 wc[RQ][ZB], wm[ZB][RQ], wsg[ZB][ZB];
+    if (w < Sh::GW) {
 #pragma unroll
-    for (int o = 0; o < RQ; ++o)
+        for (int o = 0; o < RQ; ++o)
 #pragma unroll
-        for (int ib = 0; ib < ZB; ++ib) wc[o][ib] = T[(o * ZB + ib) * kTileF4];
+            for (int ib = 0; ib < ZB; ++ib) wc[o][ib] = T[(o * ZB + ib) * kTileF4];
 #pragma unroll
-    for (int zb = 0; zb < ZB; ++zb)
+        for (int zb = 0; zb < ZB; ++zb)
 #pragma unroll
-        for (int i = 0; i < RQ; ++i) wm[zb][i] = T[(RQ * ZB + zb * RQ + i) * kTileF4];
+            for (int i = 0; i < RQ; ++i) wm[zb][i] = T[(RQ * ZB + zb * RQ + i) * kTileF4];
 #pragma unroll
-    for (int zb = 0; zb < ZB; ++zb)
+        for (int zb = 0; zb < ZB; ++zb)
 #pragma unroll
-        for (int ib = 0; ib < ZB; ++ib) wsg[zb][ib] = T[(2 * RQ * ZB + zb * ZB + ib) * kTileF4];
+            for (int ib = 0; ib < ZB; ++ib) wsg[zb][ib] = T[(2 * RQ * ZB + zb * ZB + ib) * kTileF4];
+    }
     // ring of the streamed tiles: slot i holds tile i of the current chunk; taking it requests tile i
     // of the next chunk into the same slot
     const f32x4 *cur = T + (size_t)Sh::kGuide * kTileF4;
@@ -133,34 +143,52 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     auto relu4 = [](f32x4 v) { return map4(v, [](float u) { return fmaxf(u, 0.f); }); };
     auto softplus4 = [](f32x4 v) { return map4(v, [](float u) { return softplus_f(u); }); };
 
-    // Sum of the four wavefronts' partial blocks p[0..n), in the order ((w0 + w1) + w2) + w3; every
-    // wavefront ends up with the same full result.  Two buffers alternate, so one barrier per call.
+    // Sum of the partial blocks p[0..n) of wavefronts 0 .. G-1, in the order ((w0 + w1) + w2) + ...;
+    // each of them ends up with the same full result.  Every wavefront of the workgroup must make
+    // the call (it holds a barrier); two buffers alternate, so one barrier per call.
     int xbuf = 0;
-    auto all_sum = [&](auto &p) {
-        constexpr int n = sizeof(p) / sizeof(p[0]);
-        static_assert(n <= 2 * ZB, "exchange buffer size");
-        f32x4 *mine = x_mu + ((xbuf * 4 + w) * 2 * ZB) * kTileF4 + lane;
+    auto all_sum = [&](auto &p, auto group) {
+        constexpr int n = sizeof(p) / sizeof(p[0]), G = decltype(group)::value;
+        static_assert(n <= 2 * ZB && G <= W, "exchange buffer size");
+        if (w < G) {
+            f32x4 *mine = x_mu + ((xbuf * W + w) * 2 * ZB) * kTileF4 + lane;
 #pragma unroll
-        for (int i = 0; i < n; ++i) mine[i * kTileF4] = p[i];
+            for (int i = 0; i < n; ++i) mine[i * kTileF4] = p[i];
+        }
         __syncthreads();
-        const f32x4 *all = x_mu + (xbuf * 4 * 2 * ZB) * kTileF4 + lane;
+        if (w < G) {
+            const f32x4 *all = x_mu + (xbuf * W * 2 * ZB) * kTileF4 + lane;
 #pragma unroll
-        for (int i = 0; i < n; ++i) {
-            const f32x4 *e = all + i * kTileF4;
-            p[i] = ((e[0] + e[2 * ZB * kTileF4]) + e[2 * 2 * ZB * kTileF4]) + e[3 * 2 * ZB * kTileF4];
+            for (int i = 0; i < n; ++i) {
+                const f32x4 *e = all + i * kTileF4;
+                f32x4 sum = e[0];
+#pragma unroll
+                for (int k = 1; k < G; ++k) sum = sum + e[k * 2 * ZB * kTileF4];
+                p[i] = sum;
+            }
         }
         xbuf ^= 1;
     };
+    constexpr std::integral_constant<int, Sh::GW> kGuideGroup{};
+    constexpr std::integral_constant<int, W> kEveryone{};
 
     f32x4 z[ZB];
 #pragma unroll
     for (int zb = 0; zb < ZB; ++zb) z[zb] = reinterpret_cast<const f32x4 *>(a.z0)[zb * 4 + q];
 
     // ---- guide chain ------------------------------------------------------------------
+    // The chain is one dependent sequence of small layers with an exchange per step: more than four
+    // wavefronts only make the exchange dearer (measured), so with eight the upper four sit out the
+    // chain at its barriers and receive the latent at the end.
     f32x4 eps[ZB];
 #pragma unroll
-    for (int zb = 0; zb < ZB; ++zb) eps[zb] = load_z_noise(a.eps_q, zb);
+    for (int zb = 0; zb < ZB; ++zb) eps[zb] = w < Sh::GW ? load_z_noise(a.eps_q, zb) : splat(0.f);
     for (int t = 0; t < a.L; ++t) {
+        if (w >= Sh::GW) {  // (uniform per wavefront)
+            f32x4 none[ZB];
+            all_sum(none, kGuideGroup);
+            continue;
+        }
         f32x4 eps_next[ZB];  // next step's noise is fetched while this step computes
         const int tn = t + 1 < a.L ? t + 1 : t;
 #pragma unroll
@@ -195,7 +223,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             mma_narrow<RQ>(acc, tl, h);
             mu[zb] = acc.sum();
         }
-        all_sum(mu);
+        all_sum(mu, kGuideGroup);
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) mu[zb] = mu[zb] + bias4(lb_mu, zb);
         // scale from the mean, reparameterised draw (all wavefronts alike)
@@ -221,6 +249,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     };
 #pragma unroll
     for (int zb = 0; zb < ZB; ++zb) store_z(a.z_last, zb, z[zb]);
+    if constexpr (W > Sh::GW) {  // the latent for the wavefronts that sat out
+        if (w == 0) {
+#pragma unroll
+            for (int zb = 0; zb < ZB; ++zb) x_sum[zb * kTileF4 + lane] = z[zb];
+        }
+        __syncthreads();
+        if (w >= Sh::GW) {
+#pragma unroll
+            for (int zb = 0; zb < ZB; ++zb) z[zb] = x_sum[zb * kTileF4 + lane];
+        }
+    }
 
     // ---- gated transition -----------------------------------------------------------------
     // ring positions of the head of the stream (compile-time): gate1, gate2, prop1, prop2, lin, tscale, emean1
@@ -286,7 +325,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         narrow_quarter(prop, pP2, hid);
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) { gp[zb] = g[zb]; gp[ZB + zb] = prop[zb]; }
-        all_sum(gp);  // gate and proposed mean in one exchange
+        all_sum(gp, kEveryone);  // gate and proposed mean in one exchange
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) { g[zb] = gp[zb]; prop[zb] = gp[ZB + zb]; }
         small_layer(lin, lb_lin, pLin, z);
@@ -312,14 +351,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     // noise of this wavefront's worker blocks, requested now
     const float scale = a.ctl->scale;
     float *sink = a.sink + tid * 4;
-    const int nb0 = w * NBW;
+    const int nb0 = w * NBW;  // first of this wavefront's worker blocks
     auto load_eps_x = [&](int nb) {
         const int n0 = nb * 16 + 4 * q;
         const int nc = n0 < N ? n0 : N - 4;
         return *reinterpret_cast<const f32x4 *>(a.eps_x + (size_t)sc * N + nc);
     };
-    // hidden layer of the mean: own quarter, then gathered from all wavefronts
-    f32x4 h1[HB];
+    // hidden layer of the mean: own share of the output blocks, gathered in LDS
     {
         f32x4 own[HQ];
         wide_quarter(own, lb_emean1, pE1, zn);
@@ -330,16 +368,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int o = 0; o < HQ; ++o) x_h1[(w * HQ + o) * kTileF4 + lane] = own[o];
         __syncthreads();
-#pragma unroll
-        for (int ob = 0; ob < HB; ++ob) h1[ob] = x_h1[ob * kTileF4 + lane];
     }
     // the rest of the head's last chunk is padding: taking it lets the ring request the next chunk's tiles
 #pragma unroll
     for (int pos = Sh::kHead; pos < Sh::kHeadChunks * C; ++pos) (void)head_take(pos);
     cur += C * kTileF4;  // the ring now holds the first chunk of the folded layer
-    // hidden layer of the scale network from h1 (the folded H x H layer; the table slot of b_J1 holds
-    // its bias): own quarter of the output blocks, row by row, then gathered
-    f32x4 h2[HB];
+    // hidden layer of the scale network from the mean's (the folded H x H layer; the table slot of
+    // b_J1 holds its bias): own share of the output blocks, row by row, gathered in LDS
     {
         f32x4 own[HQ];
 #pragma unroll
@@ -349,19 +384,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
                 const f32x4 tl[1] = {take((o * HB + i) % C)};
-                mma_narrow<1>(acc, tl, &h1[i]);
+                const f32x4 x = x_h1[i * kTileF4 + lane];
+                mma_narrow<1>(acc, tl, &x);
+                if ((o * HB + i + 1) % C == 0) cur += C * kTileF4;
+                if (i % 4 == 3) sched_fence();  // bounds how many operand blocks are fetched ahead
             }
             own[o] = relu4(acc.sum());
-            if ((o + 1) * HB % C == 0) cur += C * kTileF4;
+        }
+        if constexpr (Sh::kFold % C != 0) {  // padding of the last chunk
+#pragma unroll
+            for (int i = Sh::kFold % C; i < C; ++i) (void)take(i);
+            cur += C * kTileF4;
         }
 #pragma unroll
         for (int o = 0; o < HQ; ++o) x_h2[(w * HQ + o) * kTileF4 + lane] = own[o];
         __syncthreads();
-#pragma unroll
-        for (int ob = 0; ob < HB; ++ob) h2[ob] = x_h2[ob * kTileF4 + lane];
     }
-    // mean, scale, draw, back to seconds: one worker block per chunk of the ring (HB tiles of the
-    // mean's output layer, row nb, then HB tiles of the scale's)
+    // mean, scale, draw, back to seconds: per worker block HB tiles of the mean's output layer, row nb,
+    // then HB tiles of the scale's (one chunk of the ring, or two)
     auto emit = [&](int nb_raw, f32x4 pre, f32x4 m, f32x4 e) {
         const int n0 = nb_raw * 16 + 4 * q;
         const f32x4 sd = softplus4(pre);
@@ -389,70 +429,98 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         Acc4 am, as;
         am.init(bias4(lb_emean2, nb));
         as.init(bias4(lb_escale2, nb));
+        if constexpr (Sh::kBlockChunks == 1) {
 #pragma unroll
-        for (int i = 0; i < HB; ++i) {
-            const f32x4 tm[1] = {take(i)}, ts[1] = {take(HB + i)};
-            mma_narrow<1>(am, tm, &h1[i]);
-            mma_narrow<1>(as, ts, &h2[i]);
+            for (int i = 0; i < HB; ++i) {
+                const f32x4 tm[1] = {take(i)}, ts[1] = {take(HB + i)};
+                const f32x4 x1 = x_h1[i * kTileF4 + lane], x2 = x_h2[i * kTileF4 + lane];
+                mma_narrow<1>(am, tm, &x1);
+                mma_narrow<1>(as, ts, &x2);
+                if (i % 4 == 3) sched_fence();
+            }
+            cur += C * kTileF4;
+        } else {
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const f32x4 tm[1] = {take(i)};
+                const f32x4 x1 = x_h1[i * kTileF4 + lane];
+                mma_narrow<1>(am, tm, &x1);
+                if (i % 4 == 3) sched_fence();
+            }
+            cur += C * kTileF4;
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const f32x4 ts[1] = {take(i)};
+                const f32x4 x2 = x_h2[i * kTileF4 + lane];
+                mma_narrow<1>(as, ts, &x2);
+                if (i % 4 == 3) sched_fence();
+            }
+            cur += C * kTileF4;
         }
         emit(nb_raw, as.sum(), am.sum(), e);
-        cur += C * kTileF4;
     }
 }
 
-template <int ZB, int RB, int HB>
+template <int ZB, int RB, int HB, int W>
 size_t split_lds_bytes(int L, int N) {
     const size_t nb16 = (size_t)((N + 15) / 16) * 16;
     const size_t bias_floats = RB * 16 + 6 * ZB * 16 + 4 * HB * 16 + 2 * nb16;
-    return (size_t)(2 * 4 * 2 * ZB + HB + HB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
+    return (size_t)(2 * W * 2 * ZB + HB + HB + ZB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
 }
 
-template <int ZB, int RB, int HB, bool DBG>
+template <int ZB, int RB, int HB, int W, bool DBG>
 int launch_variant(const ChainArgs &a, size_t lds, hipStream_t stream) {
     static size_t raised = 0;  // largest LDS size the attribute has been set to
     if (lds > raised) {
-        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_split<ZB, RB, HB, DBG>),
+        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_split<ZB, RB, HB, W, DBG>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         raised = lds;
     }
-    hipLaunchKernelGGL((sample_split<ZB, RB, HB, DBG>), dim3((a.S + 15) / 16), dim3(kThreads), lds, stream, a);
+    hipLaunchKernelGGL((sample_split<ZB, RB, HB, W, DBG>), dim3((a.S + 15) / 16), dim3(64 * W), lds, stream, a);
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
 }
 
-template <int ZB, int RB, int HB>
+template <int ZB, int RB, int HB, int W>
 int launch_one(const ChainArgs &a, hipStream_t stream) {
-    const size_t lds = split_lds_bytes<ZB, RB, HB>(a.L, a.N);
+    const size_t lds = split_lds_bytes<ZB, RB, HB, W>(a.L, a.N);
     if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
     const bool dbg = a.z_last || a.z_next_dbg || a.out_mean_dbg || a.out_sd_dbg;
-    return dbg ? launch_variant<ZB, RB, HB, true>(a, lds, stream) : launch_variant<ZB, RB, HB, false>(a, lds, stream);
+    return dbg ? launch_variant<ZB, RB, HB, W, true>(a, lds, stream) : launch_variant<ZB, RB, HB, W, false>(a, lds, stream);
 }
 
 }  // namespace
 
 // Sizes the kernel is built for: the latent and the widths of the two larger fp32 presets, N and Z
-// multiples of 4, and as many workers as leave the bias table room in LDS.
-bool split_supported(int Z, int R, int H, int L, int N) {
+// multiples of 4, and as many workers as leave the bias table room in LDS.  waves: wavefronts per
+// workgroup, 4 or 8.
+bool split_supported(int Z, int R, int H, int L, int N, int waves) {
     const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16;
-    if (N < 4 || (N & 3) != 0 || Z < 4 || (Z & 3) != 0) return false;
-    if (zb == 1 && rb == 8 && hb == 8) return split_lds_bytes<1, 8, 8>(L, N) <= 160 * 1024;
-    if (zb == 2 && rb == 16 && hb == 16) return split_lds_bytes<2, 16, 16>(L, N) <= 160 * 1024;
+    if (N < 4 || (N & 3) != 0 || Z < 4 || (Z & 3) != 0 || (waves != 4 && waves != 8)) return false;
+    if (zb == 1 && rb == 8 && hb == 8)
+        return (waves == 4 ? split_lds_bytes<1, 8, 8, 4>(L, N) : split_lds_bytes<1, 8, 8, 8>(L, N)) <= 160 * 1024;
+    if (zb == 2 && rb == 16 && hb == 16)
+        return (waves == 4 ? split_lds_bytes<2, 16, 16, 4>(L, N) : split_lds_bytes<2, 16, 16, 8>(L, N)) <= 160 * 1024;
     return false;
 }
 
-int split_stream_tiles(int Z, int R, int H, int N) {
-    const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16, nbw = ((N + 15) / 16 + 3) / 4;
-    if (zb == 1 && rb == 8 && hb == 8) return SplitShape<1, 8, 8>::stream_tiles(nbw);
-    if (zb == 2 && rb == 16 && hb == 16) return SplitShape<2, 16, 16>::stream_tiles(nbw);
+int split_stream_tiles(int Z, int R, int H, int N, int waves) {
+    const int zb = (Z + 15) / 16, rb = (R + 15) / 16, hb = (H + 15) / 16, nbw = ((N + 15) / 16 + waves - 1) / waves;
+    if (zb == 1 && rb == 8 && hb == 8)
+        return waves == 4 ? SplitShape<1, 8, 8, 4>::stream_tiles(nbw) : SplitShape<1, 8, 8, 8>::stream_tiles(nbw);
+    if (zb == 2 && rb == 16 && hb == 16)
+        return waves == 4 ? SplitShape<2, 16, 16, 4>::stream_tiles(nbw) : SplitShape<2, 16, 16, 8>::stream_tiles(nbw);
     return 0;
 }
 
 int launch_split(const ChainArgs &a, hipStream_t stream) {
     StageTimer timer(kStageSampler, stream);
     const int zb = (a.Z + 15) / 16, rb = (a.R + 15) / 16, hb = (a.H + 15) / 16;
-    if (!split_supported(a.Z, a.R, a.H, a.L, a.N)) return DKF_EUNSUPPORTED;
-    if (zb == 1 && rb == 8 && hb == 8) return launch_one<1, 8, 8>(a, stream);
-    if (zb == 2 && rb == 16 && hb == 16) return launch_one<2, 16, 16>(a, stream);
+    if (!split_supported(a.Z, a.R, a.H, a.L, a.N, a.split_waves)) return DKF_EUNSUPPORTED;
+    if (zb == 1 && rb == 8 && hb == 8)
+        return a.split_waves == 4 ? launch_one<1, 8, 8, 4>(a, stream) : launch_one<1, 8, 8, 8>(a, stream);
+    if (zb == 2 && rb == 16 && hb == 16)
+        return a.split_waves == 4 ? launch_one<2, 16, 16, 4>(a, stream) : launch_one<2, 16, 16, 8>(a, stream);
     return DKF_EUNSUPPORTED;
 }
 
