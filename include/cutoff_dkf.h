@@ -281,7 +281,7 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes);
  *   DKF_SAMPLER_WAVE4   one fused kernel, four samples per wavefront
  *   DKF_SAMPLER_STAGED  guide/transition kernel + four GEMM kernels
  *   DKF_SAMPLER_SPLIT   one fused kernel, sixteen samples per workgroup, every
- *                       layer split over the workgroup's four wavefronts
+ *                       layer split over the workgroup's wavefronts
  * Returns DKF_EUNSUPPORTED (and changes nothing) if the model's sizes or dtype
  * rule the requested variant out.  Host call; takes effect at the next call. */
 #define DKF_SAMPLER_AUTO 0
