@@ -910,6 +910,9 @@ int dkf_load_weights(const dkf_config *cfg, const void *blob, size_t blob_bytes,
     if (m->use_chain) DKF_CHECK(pack_chain(m, raw));
     m->use_quad = !bf16 && quad_supported(Z, R, H, L, N);
     if (m->use_quad) DKF_CHECK(pack_quad(m, raw));
+    // eight wavefronts per workgroup where their exchange buffers fit into LDS next to the window's
+    // encodings, else four
+    m->split_waves = split_supported(Z, R, H, L, N, 8) ? 8 : 4;
     m->use_split = !bf16 && split_supported(Z, R, H, L, N, m->split_waves);
     if (m->use_split) DKF_CHECK(pack_split(m, raw));
     m->use_gchain = bf16 && gchain_q(Z, R, H) != 0 && m->Zp == 64;

@@ -112,12 +112,16 @@ def test_fused_sampler_tails(api, cfg, act, sampler):
     custom(N=100, L=4, Z=16, H=128, R=128, S=130), custom(N=128, L=2, Z=12, H=120, R=113, S=50),
     custom(N=500, L=3, Z=32, H=256, R=256, S=40), custom(N=36, L=5, Z=20, H=250, R=244, S=17),
     custom(N=512, L=2, Z=28, H=241, R=256, S=16), custom(N=4, L=1, Z=4, H=128, R=128, S=1),
-    custom(N=1100, L=2, Z=16, H=128, R=128, S=35)],
-    ids=["medium-like", "pad-features", "contended-like", "ragged", "full-width", "smallest", "many-workers"])
+    custom(N=1100, L=2, Z=16, H=128, R=128, S=35),
+    synth.ClusterConfig("custom", 9, 64, 60, 32, 256, 256, 19, "f32", 70, "iid_stragglers_tiny")],
+    ids=["medium-like", "pad-features", "contended-like", "ragged", "full-width", "smallest", "many-workers",
+         "long-window"])
 @pytest.mark.parametrize("act", [0, 1])
 def test_split_sampler_tails(api, cfg, act):
     """The sixteen-samples-per-workgroup kernel: ragged worker blocks (whole wavefronts without a
-    block of their own), pad features in every width, a partial last workgroup."""
+    block of their own), pad features in every width, a partial last workgroup; a window so long that
+    its encodings leave LDS room for four wavefronts' exchange buffers only (the kernel then runs
+    with four wavefronts per workgroup instead of eight)."""
     g, o, _ = make_pair(api, cfg, act=act, std=0.3, sampler=SPLIT)
     compare_stages(api, cfg, g, o)
     eq, ez, ex = synth.make_noise(cfg)
