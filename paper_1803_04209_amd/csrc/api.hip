@@ -258,9 +258,15 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     const int CH = chain_chunk_tiles(HB), K2 = CH / (2 * HB);
     std::vector<float> g, s;
     const int GO = RB < 4 ? RB : 4;
+    // The kernel evaluates tanh(v) as 1 - 2 / (exp2(2 log2(e) v) + 1): the constant goes into the
+    // combiner's matrix and bias here, so the pre-activation arrives as the exponent.
+    const double kTanhArg = 2.0 * 1.4426950408889634074;
+    std::vector<float> comb_w((size_t)R * Z), comb_b((size_t)R);
+    for (size_t i = 0; i < comb_w.size(); ++i) comb_w[i] = (float)(kTanhArg * (double)r.comb[i]);
+    for (int i = 0; i < R; ++i) comb_b[i] = (float)(kTanhArg * (double)r.b_comb[i]);
     for (int og = 0; og < RB / GO; ++og)
         for (int ib = 0; ib < ZB; ++ib)
-            for (int j = 0; j < GO; ++j) append_tile(g, r.comb, R, Z, og * GO + j, ib);
+            for (int j = 0; j < GO; ++j) append_tile(g, comb_w.data(), R, Z, og * GO + j, ib);
     for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < RB; ++ib) append_tile(g, r.mu, Z, R, zb, ib);
     for (int zb = 0; zb < ZB; ++zb) for (int ib = 0; ib < ZB; ++ib) append_tile(g, r.sig, Z, Z, zb, ib);
     const size_t chunk = (size_t)CH * 256;
@@ -304,7 +310,7 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
         bt.resize(base + (size_t)blocks * 16, 0.f);
         for (int i = 0; i < n; ++i) bt[base + i] = b[i];
     };
-    add_bias(r.b_comb, R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
+    add_bias(comb_b.data(), R, RB); add_bias(r.b_mu, Z, ZB); add_bias(r.b_sig, Z, ZB);
     add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
     add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(fold_b.data(), H, HB);
     add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);

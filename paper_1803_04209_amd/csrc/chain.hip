@@ -27,12 +27,16 @@ namespace dkf {
 namespace {
 
 constexpr int kThreads = 256;
+using AccN = Acc<1>;
 constexpr int kTileF4 = 64;  // float4 per weight tile (one per lane)
 
 // Stream of weight chunks (CH tiles each) from global memory through a two-buffer LDS ring.
 // While chunk c is consumed from LDS, chunk c + 1 sits in registers (requested one chunk
-// earlier); advance() writes it to the free buffer, requests chunk c + 2 and synchronises the
-// workgroup.  A chunk is sized so that its matrix work outlasts an L2 round trip.
+// earlier).  handover(), called in the middle of chunk c's matrix work, writes it to the other
+// buffer -- free since the barrier that ended chunk c - 1 -- and requests chunk c + 2; next(),
+// at the end of the chunk, is then a barrier and nothing else, so neither the LDS writes nor the
+// wait for the requested data stand between two chunks' matrix instructions.  A chunk is sized
+// so that its matrix work outlasts an L2 round trip.
 template <int CH>
 struct WeightStream {
     static constexpr int kChunkF4 = CH * kTileF4;
@@ -49,7 +53,7 @@ struct WeightStream {
 #pragma unroll
         for (int i = 0; i < kPerThread; ++i) {
             const int idx = tid + i * kThreads;
-            const f32x4 t = src[(size_t)chunk * kChunkF4 + (idx < kChunkF4 ? idx : 0)];
+            const f32x4 t = src[(size_t)chunk * kChunkF4 + (kChunkF4 % kThreads == 0 || idx < kChunkF4 ? idx : 0)];
             r[4 * i] = t.x; r[4 * i + 1] = t.y; r[4 * i + 2] = t.z; r[4 * i + 3] = t.w;
         }
         return r;
@@ -59,7 +63,7 @@ struct WeightStream {
         for (int i = 0; i < kPerThread; ++i) {
             const int idx = tid + i * kThreads;
             const f32x4 t = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            if (idx < kChunkF4) buf[b * kChunkF4 + idx] = t;
+            if (kChunkF4 % kThreads == 0 || idx < kChunkF4) buf[b * kChunkF4 + idx] = t;
         }
     }
     __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int t) {
@@ -69,10 +73,12 @@ struct WeightStream {
         regs = fetch(1);
         __syncthreads();
     }
-    __device__ __forceinline__ void advance() {
+    __device__ __forceinline__ void handover() {
+        commit(regs, (cur_chunk + 1) & 1);
+        regs = fetch(cur_chunk + 2);
+    }
+    __device__ __forceinline__ void next() {
         ++cur_chunk;
-        commit(regs, cur_chunk & 1);
-        regs = fetch(cur_chunk + 1);
         __syncthreads();
     }
     __device__ __forceinline__ f32x4 tile(int t, int lane) const {
@@ -111,9 +117,27 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     // guide weights, encodings and all biases -> LDS
     {
         const f32x4 *src = reinterpret_cast<const f32x4 *>(a.guide_tiles);
+        // every workgroup wants the same kilobytes at the same moment: each starts at a slab of its
+        // own so that the requests spread over the memory channels, and all of a thread's loads
+        // are in flight before the first is stored
         constexpr int kCopies = kGuideTiles * kTileF4 / kThreads;  // kTileF4 * tiles is a multiple of 64
+        if constexpr (kCopies <= 32) {
+            f32x4 t[kCopies];
+            const int rot = blockIdx.x % kCopies;
+#pragma unroll
+            for (int i = 0; i < kCopies; ++i) {
+                const int j = i + rot < kCopies ? i + rot : i + rot - kCopies;
+                t[i] = src[tid + j * kThreads];
+            }
+#pragma unroll
+            for (int i = 0; i < kCopies; ++i) {
+                const int j = i + rot < kCopies ? i + rot : i + rot - kCopies;
+                gw[tid + j * kThreads] = t[i];
+            }
+        } else {
 #pragma unroll 8
-        for (int i = 0; i < kCopies; ++i) gw[tid + i * kThreads] = src[tid + i * kThreads];
+            for (int i = 0; i < kCopies; ++i) gw[tid + i * kThreads] = src[tid + i * kThreads];
+        }
         for (int i = tid + kCopies * kThreads; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
         // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
         // with tanh written as 1 - 2 r
@@ -173,9 +197,11 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
             // comb tiles are stored [group of GO output blocks][input block][block in group]
             constexpr int GO = RB < 4 ? RB : 4;
             const float *ctx_t = ctx + t * R16 + 4 * q;
-            auto finish = [&](int ob) {  // h_out = (tanh(v) + h_left + h_right) / 3, tanh(v) = 1 - 2 / (exp(2v) + 1)
+            // h_out = (tanh(v) + h_left + h_right) / 3, tanh(v) = 1 - 2 / (exp(2v) + 1); the combiner's
+            // tiles and bias carry the factor 2 log2(e) (set when the weights are loaded), so h = 2 log2(e) v
+            auto finish = [&](int ob) {
                 const f32x4 c = *reinterpret_cast<const f32x4 *>(ctx_t + ob * 16);  // (1 + h_left + h_right) / 3
-                const f32x4 r = map4(h[ob], [](float v) { return fast_rcp(__expf(2.0f * v) + 1.0f); });
+                const f32x4 r = map4(h[ob], [](float v) { return fast_rcp(__builtin_amdgcn_exp2f(v) + 1.0f); });
                 h[ob] = r * (-2.0f / 3.0f) + c;
             };
 #pragma unroll
@@ -194,19 +220,21 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         }
         f32x4 mu[ZB];
         {
+            // all ZB output blocks in one run of tiles [zb][ib]: the operand pipeline starts once
             constexpr int GI = RB < 4 ? RB : 4;
+            AccN acc[ZB];
 #pragma unroll
-            for (int zb = 0; zb < ZB; ++zb) {
-                Acc4 acc;
-                acc.init(bias4(lb_mu, zb));
-                for_tile_groups<RB, GI>([&](int i) { return w_mu[(zb * RB + i) * kTileF4 + lane]; },
-                                        [&](int g, const f32x4(&tl)[GI]) { mma_narrow<GI>(acc, tl, &h[g * GI]); });
-                mu[zb] = acc.sum();
-            }
+            for (int zb = 0; zb < ZB; ++zb) acc[zb].init(bias4(lb_mu, zb));
+            for_tile_groups<ZB * RB, GI>([&](int i) { return w_mu[i * kTileF4 + lane]; },
+                                         [&](int g, const f32x4(&tl)[GI]) {
+                                             mma_narrow<GI>(acc[(g * GI) / RB], tl, &h[(g * GI) % RB]);
+                                         });
+#pragma unroll
+            for (int zb = 0; zb < ZB; ++zb) mu[zb] = acc[zb].sum();
         }
 #pragma unroll
         for (int zb = 0; zb < ZB; ++zb) {
-            Acc4 acc;
+            AccN acc;
             acc.init(bias4(lb_sig, zb));
 #pragma unroll
             for (int ib = 0; ib < ZB; ++ib) {
@@ -242,34 +270,47 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for_tile_groups<ZB * HB, GH>([&](int i) { return ws.tile(i, lane); },
                                      [&](int g, const f32x4(&tl)[GH]) {
                                          const int idx = g * GH;
+                                         if (g == ZB * HB / GH / 2) ws.handover();
                                          mma_wide<GH>(&out[idx % HB], tl, x[idx / HB]);
                                      });
-        ws.advance();
+        ws.next();
     };
     // one 16-feature output block from HB tiles starting at tile `base` of the current chunk;
-    // `ride` is vector work of an earlier block that may be interleaved with the first group
-    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB], auto &&ride) {
-        Acc4 acc;
+    // `ride` runs before the first group of tiles and `mid` before the middle one (vector work of
+    // an earlier block that may be interleaved, or the stream's hand-over)
+    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB], auto &&ride, auto &&mid) {
+        AccN acc;
         acc.init(b);
         for_tile_groups<HB, GH>([&](int i) { return ws.tile(base + i, lane); },
                                 [&](int g, const f32x4(&tl)[GH]) {
                                     if (g == 0) ride();
+                                    if (g == HB / GH / 2) mid();
                                     mma_narrow<GH>(acc, tl, &x[g * GH]);
                                 });
         return acc.sum();
     };
     auto nothing = [] {};
+    auto handover = [&] { ws.handover(); };
+    // U blocks of a chunk: the hand-over goes before the middle block, or into the middle of the only one
+    auto narrow_blocks = [&](auto u_const, int base, f32x4 b, const f32x4(&x)[HB], int u) {
+        constexpr int U = decltype(u_const)::value;
+        if (U == 1) return narrow_block(base, b, x, nothing, handover);
+        if (u == U / 2) return narrow_block(base, b, x, handover, nothing);
+        return narrow_block(base, b, x, nothing, nothing);
+    };
     // out = W h + b for an H -> Z layer: one chunk, tiles [zb][ib]
     auto narrow_from_h = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[HB]) {
 #pragma unroll
-        for (int zb = 0; zb < ZB; ++zb) out[zb] = narrow_block(zb * HB, bias4(tab, zb), x, nothing);
-        ws.advance();
+        for (int zb = 0; zb < ZB; ++zb)
+            out[zb] = narrow_blocks(std::integral_constant<int, ZB>{}, zb * HB, bias4(tab, zb), x, zb);
+        ws.next();
     };
     // Z -> Z layer: one chunk, tiles [ob][ib]
     auto small_layer = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[ZB]) {
+        ws.handover();  // a short chunk: nothing to hide behind
 #pragma unroll
         for (int ob = 0; ob < ZB; ++ob) {
-            Acc4 acc;
+            AccN acc;
             acc.init(bias4(tab, ob));
 #pragma unroll
             for (int ib = 0; ib < ZB; ++ib) {
@@ -278,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
             }
             out[ob] = acc.sum();
         }
-        ws.advance();
+        ws.next();
     };
 
     f32x4 zn[ZB];
@@ -328,9 +369,16 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 #pragma unroll
         for (int u = 0; u < RA; ++u) {
             const int ob = c * RA + u;
-            if (ob < HB) h2[ob] = relu4(narrow_block(u * HB, bias4(lb_escale1, ob), h1, nothing));
+            if (ob >= HB) continue;  // rows of zero tiles that fill the last chunk
+            // the hand-over goes before the chunk's second row, or into the middle of its only one
+            const bool two = RA >= 2 && c * RA + 1 < HB;
+            const f32x4 b = bias4(lb_escale1, ob);
+            const f32x4 v = two ? (u == 1 ? narrow_block(u * HB, b, h1, handover, nothing)
+                                          : narrow_block(u * HB, b, h1, nothing, nothing))
+                                : narrow_block(u * HB, b, h1, nothing, handover);
+            h2[ob] = relu4(v);
         }
-        ws.advance();
+        ws.next();
     }
 
     // mean and scale of 16 workers at a time, draw, back to seconds
@@ -399,11 +447,22 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for (int u = 0; u < K2; ++u) {
             const int nb_raw = c * K2 + u;
             const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, result goes to the sink
-            const f32x4 m = narrow_block(u * 2 * HB, bias4(lb_emean2, nb), h1, [&] { emit(nb_p, pre_p, m_p, e_p); });
-            const f32x4 pre = narrow_block(u * 2 * HB + HB, bias4(lb_escale2, nb), h2, nothing);
-            pre_p = pre; m_p = m; e_p = e[u]; nb_p = nb_raw < NB ? nb_raw : -1;
+            // mean and scale of the block in one run of 2 HB tiles; the previous block's epilogue rides
+            // on the first group, the stream's hand-over sits in the middle of the chunk
+            AccN am, as;
+            am.init(bias4(lb_emean2, nb));
+            as.init(bias4(lb_escale2, nb));
+            for_tile_groups<2 * HB, GH>([&](int i) { return ws.tile(u * 2 * HB + i, lane); },
+                                        [&](int g, const f32x4(&tl)[GH]) {
+                                            constexpr int kHalf = HB / GH;
+                                            if (g == 0) emit(nb_p, pre_p, m_p, e_p);
+                                            if (K2 == 1 ? g == kHalf : (u == K2 / 2 && g == 0)) ws.handover();
+                                            if (g < kHalf) mma_narrow<GH>(am, tl, &h1[g * GH]);
+                                            else mma_narrow<GH>(as, tl, &h2[(g - kHalf) * GH]);
+                                        });
+            pre_p = as.sum(); m_p = am.sum(); e_p = e[u]; nb_p = nb_raw < NB ? nb_raw : -1;
         }
-        ws.advance();
+        ws.next();
     }
     emit(nb_p, pre_p, m_p, e_p);
 }

@@ -60,21 +60,30 @@ __device__ __forceinline__ void mma_wide(f32x4 *out, const f32x4 (&t)[GROUP], f3
         for (int j = 0; j < GROUP; ++j) out[j] = mfma16(t[j][e], x[e], out[j]);
 }
 
-// one output block accumulated over GROUP input blocks in four chains (one per k-slice)
-struct Acc4 {
-    f32x4 c[4];
+// one output block accumulated over GROUP input blocks in C chains (k-slice e of a tile goes to
+// chain e % C); the chains are added in a fixed order at the end
+template <int C>
+struct Acc {
+    static_assert(C == 1 || C == 2 || C == 4, "chains");
+    f32x4 c[C];
     __device__ __forceinline__ void init(f32x4 first) {
         c[0] = first;
-        c[1] = c[2] = c[3] = splat(0.f);
+#pragma unroll
+        for (int i = 1; i < C; ++i) c[i] = splat(0.f);
     }
-    __device__ __forceinline__ f32x4 sum() const { return (c[0] + c[1]) + (c[2] + c[3]); }
+    __device__ __forceinline__ f32x4 sum() const {
+        if constexpr (C == 4) return (c[0] + c[1]) + (c[2] + c[3]);
+        else if constexpr (C == 2) return c[0] + c[1];
+        else return c[0];
+    }
 };
-template <int GROUP>
-__device__ __forceinline__ void mma_narrow(Acc4 &acc, const f32x4 (&t)[GROUP], const f32x4 *x) {
+using Acc4 = Acc<4>;
+template <int GROUP, int C>
+__device__ __forceinline__ void mma_narrow(Acc<C> &acc, const f32x4 (&t)[GROUP], const f32x4 *x) {
 #pragma unroll
     for (int j = 0; j < GROUP; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc.c[e] = mfma16(t[j][e], x[j][e], acc.c[e]);
+        for (int e = 0; e < 4; ++e) acc.c[e % C] = mfma16(t[j][e], x[j][e], acc.c[e % C]);
 }
 
 }  // namespace
