@@ -266,7 +266,7 @@ __device__ __forceinline__ uint32_t key_of_flat(float x) {
 // PLAIN: the decision's own configuration -- the row fills the network exactly (N = E << LG), the
 // rows divide evenly over the lane groups of the grid, values are summed (not reciprocals) and
 // neither the sorted rows nor the permutation are stored -- so the loop body has no row or column
-// checks at all.  The additions happen in the same order as in the general body.
+// checks at all, and needs fewer registers (its workgroup shape: sort_threads_plain).
 template <int E, int LG, bool WITH_PERM, int THREADS, bool PLAIN = false>
 __global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restrict__ x, int S, int N,
                                                             float *__restrict__ out_sorted,
@@ -584,12 +584,18 @@ struct SortPlan {
     int npad;        // e << lg
     int threads;     // workgroup size of sort_rank_sums
     int blocks;      // grid of sort_rank_sums
+    bool plain;      // the check-free loop body (and its workgroup shape) applies
 };
 
 // workgroup size by padded row width (must match the instantiations in launch_sort_case)
 constexpr int sort_threads(int npad) { return npad >= 2048 ? 256 : npad >= 1024 ? 512 : npad >= 512 ? 1024 : 256; }
 
-SortPlan plan_for(int S, int N) {
+// Workgroup size of the check-free body.  It needs fewer registers (four wavefronts per SIMD at
+// 2048 keys instead of three), so sixteen wavefronts per workgroup fit a compute unit at every
+// width up to 2048 and the grid is one or two workgroups per unit: 256-512 partial rows.
+constexpr int sort_threads_plain(int npad) { return npad >= 512 && npad <= 2048 ? 1024 : sort_threads(npad); }
+
+SortPlan plan_for(int S, int N, bool want_plain = false) {
     int npad = 8;
     while (npad < N) npad <<= 1;
     SortPlan p;
@@ -600,6 +606,20 @@ SortPlan plan_for(int S, int N) {
     p.lg = 0;
     while ((1 << p.lg) < g) ++p.lg;
     p.npad = npad;
+    p.plain = false;
+    if (want_plain && N == npad && (N & 3) == 0) {
+        const int threads = sort_threads_plain(npad);
+        const int rows = threads / g;
+        const int cap = npad >= 2048 ? 256 : npad >= 512 ? 512 : 2048;
+        int blocks = (S + rows - 1) / rows;
+        if (blocks > cap) blocks = cap;
+        if (S % (blocks * rows) == 0) {  // every lane group has a row in every pass
+            p.threads = threads;
+            p.blocks = blocks;
+            p.plain = true;
+            return p;
+        }
+    }
     p.threads = sort_threads(npad);
     const int rows_per_block = p.threads / g;
     int blocks = (S + rows_per_block - 1) / rows_per_block;
@@ -618,17 +638,16 @@ SortPlan plan_for(int S, int N) {
 size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 template <int E, int LG>
-void launch_sort(bool perm, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt, int32_t *pm,
-                 float *partial, int rate, float t_floor) {
+void launch_sort(bool perm, bool plain, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt,
+                 int32_t *pm, float *partial, int rate, float t_floor) {
     // the same workgroup shape with and without the permutation: the rank sums are added in the
-    // same order either way, so the means are bit-identical
-    constexpr int T = sort_threads(E << LG), TP = T;
-    const int rows_per_pass = (int)grid.x * (T >> LG);
-    const bool plain = !perm && !srt && !rate && N == (E << LG) && S % rows_per_pass == 0;
+    // same order either way, so the means are bit-identical (the check-free body has a shape of
+    // its own: its means agree with the others to rounding)
+    constexpr int T = sort_threads(E << LG), TP = T, TPL = sort_threads_plain(E << LG);
     if (perm)
         hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
     else if (plain)
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T, true>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, TPL, true>), grid, dim3(TPL), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
     else
         hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
 }
@@ -655,16 +674,17 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     if ((reinterpret_cast<uintptr_t>(samples) & 15) != 0) return DKF_EINVAL;
     if (out_sorted && (reinterpret_cast<uintptr_t>(out_sorted) & 15) != 0) return DKF_EINVAL;
 
-    const SortPlan p = plan_for(S, N);
+    const bool perm = out_perm != nullptr;
+    const SortPlan general = plan_for(S, N);  // the workspace is laid out for the larger grid
+    const SortPlan p = plan_for(S, N, !perm && !out_sorted && !rate);
     float *partial = static_cast<float *>(workspace);
     double *part2 = reinterpret_cast<double *>(static_cast<char *>(workspace) +
-                                               align256((size_t)p.blocks * p.npad * sizeof(float)));
-    const bool perm = out_perm != nullptr;
+                                               align256((size_t)general.blocks * general.npad * sizeof(float)));
     const dim3 grid(p.blocks);
     {
         StageTimer timer(kStageSort, stream);
 #define DKF_SORT_CASE(E_, LG_)                                                                    \
-    launch_sort<E_, LG_>(perm, grid, stream, samples, S, N, out_sorted, out_perm, partial, rate, t_floor); \
+    launch_sort<E_, LG_>(perm, p.plain, grid, stream, samples, S, N, out_sorted, out_perm, partial, rate, t_floor); \
     break
         switch (p.npad) {
             case 8: DKF_SORT_CASE(8, 0);
