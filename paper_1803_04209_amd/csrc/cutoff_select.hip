@@ -7,8 +7,9 @@
 //                    bitonic network held in registers (several keys per lane,
 //                    cross-lane exchanges inside one wavefront), and each rank's
 //                    values are summed over the rows a lane group visits;
-//   rank_partial_sums : fixed-order fp64 reduction of the per-block sums, 16 ways;
-//   omega_argmax   : the last 16-term sum, Omega(c) and the largest maximiser.
+//   rank_means_omega : fixed-order fp64 reduction of the per-block sums, Omega(c) and the
+//                    largest maximiser, 64 ranks per workgroup; the workgroup that finishes
+//                    last picks the best of the workgroups' candidates.
 // Keys are the order-preserving uint32 image of the fp32 bits, so all compares
 // are integer min/max; with a permutation requested the worker index rides in
 // the low half of a 64-bit key and breaks ties.
@@ -271,8 +272,11 @@ template <int E, int LG, bool WITH_PERM, int THREADS, bool PLAIN = false>
 __global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restrict__ x, int S, int N,
                                                             float *__restrict__ out_sorted,
                                                             int32_t *__restrict__ out_perm,
-                                                            float *__restrict__ partial, int rate, float t_floor) {
+                                                            float *__restrict__ partial, int rate, float t_floor,
+                                                            uint32_t *__restrict__ done_count) {
     using Lay = Layout<E, LG>;
+    // the counter of finished workgroups of the kernel that follows starts at zero
+    if (done_count && blockIdx.x == 0 && threadIdx.x == 0) *done_count = 0u;
     using T = typename std::conditional<WITH_PERM, uint64_t, uint32_t>::type;
     constexpr int kThreads = THREADS, kWaves = THREADS / 64;
     constexpr int G = 1 << LG;
@@ -422,44 +426,115 @@ __global__ __launch_bounds__(THREADS) void sort_rank_sums(const float *__restric
 
 constexpr int kMeanParts = 16;  // second-level partial sums per rank
 
-// part2[p][c] = sum over blocks b = 4p + sub (mod 64) of partial[b][c], fp64, fixed order.
-// grid: (ceil(N/64), kMeanParts); 64 ranks x 4 interleaved block subsets per workgroup.
-// sum over blocks b = first, first + 64, ... of partial[b][col]
-__device__ __forceinline__ double block_subset_sum(const float *__restrict__ partial, int blocks, int npad, int col,
-                                                   int first) {
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    const int stride = kMeanParts * 4;
-    int b = first;
-    for (; b + 15 * stride < blocks; b += 16 * stride) {  // sixteen independent loads in flight
-        float v[16];
+// Rank means, Omega and the argmax in one launch (N > 128).  Workgroup b owns ranks 64 b .. 64 b + 63:
+// wavefront w adds the per-block sums of rows w, w + 16, ... of those ranks (fp64, four fixed
+// chains, sixteen loads in flight), the sixteen wavefront sums of a rank are added in order, and
+// the first wavefront turns them into mean and Omega and finds the workgroup's best rank.  Only that
+// candidate (16 bytes) crosses workgroups: it is stored with device scope, a counter is advanced
+// with release/acquire order, and the workgroup that finds the counter complete reads all
+// candidates (at most 64) and writes the decision.  The sort kernel zeroes the counter.
+constexpr int kRankThreads = 1024;
+struct RankScratch {           // in the caller's workspace after the per-block sums
+    double cand_v[64];
+    int32_t cand_c[64];
+    uint32_t done;
+};
+
+__device__ __forceinline__ bool better_rank(double ov, int oc, double mv, int mc) {
+    return oc != 0 && (mc == 0 || ov > mv || (ov == mv && oc > mc));
+}
+// best (Omega, c) of the wavefront; c = 0 marks "none"; equal Omega: the larger c
+__device__ __forceinline__ void wave_best(double &bv, int &bc) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)(b + u * stride) * npad + col];
-#pragma unroll
-        for (int u = 0; u < 16; u += 4) {  // same order of additions as four rounds of four
-            s0 += (double)v[u]; s1 += (double)v[u + 1]; s2 += (double)v[u + 2]; s3 += (double)v[u + 3];
-        }
+    for (int d = 32; d > 0; d >>= 1) {
+        const double ov = __shfl_xor(bv, d, 64);
+        const int oc = __shfl_xor(bc, d, 64);
+        if (better_rank(ov, oc, bv, bc)) { bv = ov; bc = oc; }
     }
-    for (; b + 3 * stride < blocks; b += 4 * stride) {
-        const float v0 = partial[(size_t)b * npad + col];
-        const float v1 = partial[(size_t)(b + stride) * npad + col];
-        const float v2 = partial[(size_t)(b + 2 * stride) * npad + col];
-        const float v3 = partial[(size_t)(b + 3 * stride) * npad + col];
-        s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
-    }
-    for (; b < blocks; b += stride) s0 += (double)partial[(size_t)b * npad + col];
-    return (s0 + s1) + (s2 + s3);
 }
 
-__global__ __launch_bounds__(256) void rank_partial_sums(const float *__restrict__ partial, int blocks, int npad,
-                                                         int N, double *__restrict__ part2) {
-    __shared__ double red[4][64];
+__global__ __launch_bounds__(kRankThreads) void rank_means_omega(const float *__restrict__ partial, int blocks,
+                                                                 int npad, int N, int S, int c_min, int c_max,
+                                                                 float t_floor, float *__restrict__ out_mean,
+                                                                 float *__restrict__ out_omega,
+                                                                 int32_t *__restrict__ out_cstar,
+                                                                 const int32_t *ticket, const int32_t *fault,
+                                                                 int rate, RankScratch *__restrict__ rs) {
+    __shared__ double red[kMeanParts][64];
     const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6;
     const int col = blockIdx.x * 64 + lane;
-    const int first = blockIdx.y * 4 + sub;
-    red[sub][lane] = col < N ? block_subset_sum(partial, blocks, npad, col, first) : 0.0;
+    {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        if (col < N) {
+            const float *src = partial + col;
+            int b = sub;
+            for (; b + 15 * kMeanParts < blocks; b += 16 * kMeanParts) {
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(b + u * kMeanParts) * npad];
+#pragma unroll
+                for (int u = 0; u < 16; u += 4) {
+                    s0 += (double)v[u]; s1 += (double)v[u + 1]; s2 += (double)v[u + 2]; s3 += (double)v[u + 3];
+                }
+            }
+            for (; b + 3 * kMeanParts < blocks; b += 4 * kMeanParts) {
+                const float v0 = src[(size_t)b * npad], v1 = src[(size_t)(b + kMeanParts) * npad];
+                const float v2 = src[(size_t)(b + 2 * kMeanParts) * npad], v3 = src[(size_t)(b + 3 * kMeanParts) * npad];
+                s0 += (double)v0; s1 += (double)v1; s2 += (double)v2; s3 += (double)v3;
+            }
+            for (; b < blocks; b += kMeanParts) s0 += (double)src[(size_t)b * npad];
+        }
+        red[sub][lane] = (s0 + s1) + (s2 + s3);
+    }
     __syncthreads();
-    if (sub == 0 && col < N)
-        part2[(size_t)blockIdx.y * N + col] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    if (sub != 0) return;
+    // one wavefront from here on
+    double sum = red[0][lane];
+#pragma unroll
+    for (int k = 1; k < kMeanParts; ++k) sum += red[k][lane];
+    const int c = col + 1;
+    double bv = -INFINITY;
+    int bc = 0;
+    if (col < N) {
+        const double m = sum / (double)S;
+        double om = -INFINITY;
+        if (!rate) {
+            if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
+        } else if (c >= c_min && c <= c_max && m < INFINITY) {  // m: mean reciprocal; infinite = some sample not above the floor
+            om = (double)c * m;
+        }
+        if (out_mean) out_mean[col] = (float)m;
+        if (out_omega) out_omega[col] = (float)om;
+        if (om > -INFINITY) { bv = om; bc = c; }
+    }
+    wave_best(bv, bc);
+    uint32_t prev = 0;
+    if (lane == 0) {
+        __hip_atomic_store(&rs->cand_v[blockIdx.x], bv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&rs->cand_c[blockIdx.x], bc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __hip_atomic_fetch_add(&rs->done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    prev = __builtin_amdgcn_readfirstlane(prev);
+    if (prev + 1 != gridDim.x) return;
+    // the last workgroup: every candidate has been published before the count it saw
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    bv = -INFINITY;
+    bc = 0;
+    if (lane < (int)gridDim.x) {
+        bv = __hip_atomic_load(&rs->cand_v[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bc = __hip_atomic_load(&rs->cand_c[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    wave_best(bv, bc);
+    if (lane == 0) {
+        const bool none = bc == 0;
+        // an earlier kernel of the same decision gave up (the filter's state exchange): the samples
+        // behind this c* are not a prediction
+        const bool stalled = fault && __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        out_cstar[0] = none || stalled ? c_max : bc;
+        out_cstar[1] = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
+        if (ticket)  // a host polling out_cstar[2] (pinned memory) must see the decision first
+            __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
 }
 
 // Omega(c) = c / mean[c] where eligible; c* = largest maximiser.  One workgroup of THREADS
@@ -513,19 +588,6 @@ __device__ __forceinline__ void omega_argmax_body(const double *part2, int N, in
             __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
-}
-
-constexpr int kArgmaxThreads = 1024;  // one workgroup; a rank's 16 partial sums are 16 dependent-free loads per thread
-__global__ __launch_bounds__(kArgmaxThreads) void omega_argmax(const double *__restrict__ part2, int N, int S,
-                                                               int c_min, int c_max, float t_floor,
-                                                               float *__restrict__ out_mean,
-                                                               float *__restrict__ out_omega,
-                                                               int32_t *__restrict__ out_cstar,
-                                                               const int32_t *ticket, const int32_t *fault, int rate) {
-    __shared__ double best_v[kArgmaxThreads];
-    __shared__ int best_c[kArgmaxThreads];
-    omega_argmax_body<kArgmaxThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                      best_c, ticket, fault, rate);
 }
 
 // Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
@@ -639,17 +701,17 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 template <int E, int LG>
 void launch_sort(bool perm, bool plain, dim3 grid, hipStream_t st, const float *x, int S, int N, float *srt,
-                 int32_t *pm, float *partial, int rate, float t_floor) {
+                 int32_t *pm, float *partial, int rate, float t_floor, uint32_t *done) {
     // the same workgroup shape with and without the permutation: the rank sums are added in the
     // same order either way, so the means are bit-identical (the check-free body has a shape of
     // its own: its means agree with the others to rounding)
     constexpr int T = sort_threads(E << LG), TP = T, TPL = sort_threads_plain(E << LG);
     if (perm)
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, true, TP>), grid, dim3(TP), 0, st, x, S, N, srt, pm, partial, rate, t_floor, done);
     else if (plain)
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, TPL, true>), grid, dim3(TPL), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, TPL, true>), grid, dim3(TPL), 0, st, x, S, N, srt, pm, partial, rate, t_floor, done);
     else
-        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial, rate, t_floor);
+        hipLaunchKernelGGL((sort_rank_sums<E, LG, false, T>), grid, dim3(T), 0, st, x, S, N, srt, pm, partial, rate, t_floor, done);
 }
 
 }  // namespace
@@ -657,7 +719,7 @@ void launch_sort(bool perm, bool plain, dim3 grid, hipStream_t st, const float *
 size_t cutoff_workspace_bytes(int S, int N) {
     if (S < 1 || N < 1 || N > 4096) return 0;
     const SortPlan p = plan_for(S, N);
-    return align256((size_t)p.blocks * p.npad * sizeof(float)) + align256((size_t)kMeanParts * N * sizeof(double));
+    return align256((size_t)p.blocks * p.npad * sizeof(float)) + align256(sizeof(RankScratch));
 }
 
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
@@ -678,13 +740,13 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     const SortPlan general = plan_for(S, N);  // the workspace is laid out for the larger grid
     const SortPlan p = plan_for(S, N, !perm && !out_sorted && !rate);
     float *partial = static_cast<float *>(workspace);
-    double *part2 = reinterpret_cast<double *>(static_cast<char *>(workspace) +
-                                               align256((size_t)general.blocks * general.npad * sizeof(float)));
+    RankScratch *rs = reinterpret_cast<RankScratch *>(static_cast<char *>(workspace) +
+                                                      align256((size_t)general.blocks * general.npad * sizeof(float)));
     const dim3 grid(p.blocks);
     {
         StageTimer timer(kStageSort, stream);
 #define DKF_SORT_CASE(E_, LG_)                                                                    \
-    launch_sort<E_, LG_>(perm, p.plain, grid, stream, samples, S, N, out_sorted, out_perm, partial, rate, t_floor); \
+    launch_sort<E_, LG_>(perm, p.plain, grid, stream, samples, S, N, out_sorted, out_perm, partial, rate, t_floor, &rs->done); \
     break
         switch (p.npad) {
             case 8: DKF_SORT_CASE(8, 0);
@@ -709,11 +771,9 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
                                p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate);
             DKF_HIP_TRY(hipGetLastError());
         } else {
-            hipLaunchKernelGGL(rank_partial_sums, dim3((N + 63) / 64, kMeanParts), dim3(256), 0, stream, partial,
-                               p.blocks, p.npad, N, part2);
-            DKF_HIP_TRY(hipGetLastError());
-            hipLaunchKernelGGL(omega_argmax, dim3(1), dim3(kArgmaxThreads), 0, stream, part2, N, S, c_min, c_max, t_floor,
-                               out_mean, out_omega, out_cstar, ticket, fault, rate);
+            hipLaunchKernelGGL(rank_means_omega, dim3((N + 63) / 64), dim3(kRankThreads), 0, stream, partial, p.blocks,
+                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate,
+                               rs);
             DKF_HIP_TRY(hipGetLastError());
         }
     }
