@@ -671,6 +671,11 @@ SortPlan plan_for(int S, int N, bool want_plain = false) {
     p.plain = false;
     if (want_plain && N == npad && (N & 3) == 0) {
         const int threads = sort_threads_plain(npad);
+        // 512 keys with many rows: sixteen keys per lane and two rows per wavefront (an eighth fewer
+        // instructions per row: more stages stay inside a lane); with few rows that leaves compute
+        // units without work, so then a row keeps a wavefront of its own
+        const bool half_wave = npad == 512 && S >= 8192;
+        if (half_wave) { p.e = 16; p.lg = 5; g = 32; }
         const int rows = threads / g;
         const int cap = npad >= 2048 ? 256 : npad >= 512 ? 512 : 2048;
         int blocks = (S + rows - 1) / rows;
@@ -681,6 +686,7 @@ SortPlan plan_for(int S, int N, bool want_plain = false) {
             p.plain = true;
             return p;
         }
+        if (half_wave) { p.e = 8; p.lg = 6; g = 64; }
     }
     p.threads = sort_threads(npad);
     const int rows_per_block = p.threads / g;
@@ -755,7 +761,7 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
             case 64: DKF_SORT_CASE(8, 3);
             case 128: DKF_SORT_CASE(8, 4);
             case 256: DKF_SORT_CASE(8, 5);
-            case 512: DKF_SORT_CASE(8, 6);
+            case 512: if (p.e == 16) { DKF_SORT_CASE(16, 5); } else { DKF_SORT_CASE(8, 6); }
             case 1024: DKF_SORT_CASE(16, 6);
             case 2048: DKF_SORT_CASE(32, 6);
             case 4096: DKF_SORT_CASE(64, 6);
