@@ -1,7 +1,7 @@
 // Monte-Carlo order statistics and the cutoff decision on gfx950.
 //
 // Monte-Carlo estimate of the expected order statistics (Sec. 3.1.1, last
-// paragraph), then Omega(c) = c / mean x_(c) and its argmax (Sec. 3).  Three
+// paragraph), then Omega(c) = c / mean x_(c) and its argmax (Sec. 3).  Two
 // kernels:
 //   sort_rank_sums : every row of the [S][N] sample matrix is sorted by a
 //                    bitonic network held in registers (several keys per lane,
@@ -537,110 +537,6 @@ __global__ __launch_bounds__(kRankThreads) void rank_means_omega(const float *__
     }
 }
 
-// Omega(c) = c / mean[c] where eligible; c* = largest maximiser.  One workgroup of THREADS
-// threads; part2 may live in global memory or in LDS.
-template <int THREADS>
-__device__ __forceinline__ void omega_argmax_body(const double *part2, int N, int S, int c_min, int c_max,
-                                                  float t_floor, float *__restrict__ out_mean,
-                                                  float *__restrict__ out_omega, int32_t *__restrict__ out_cstar,
-                                                  double *best_v, int *best_c, const int32_t *ticket,
-                                                  const int32_t *fault, int rate = 0) {
-    double bv = -INFINITY;
-    int bc = 0;
-    for (int c = threadIdx.x + 1; c <= N; c += THREADS) {
-        double sum = 0.0;
-#pragma unroll
-        for (int p = 0; p < kMeanParts; ++p) sum += part2[(size_t)p * N + c - 1];
-        const double m = sum / (double)S;
-        double om = -INFINITY;
-        if (!rate) {
-            if (c >= c_min && c <= c_max && m > (double)t_floor) om = (double)c / m;
-        } else if (c >= c_min && c <= c_max && m < INFINITY) {  // m: mean reciprocal; infinite = some sample not above the floor
-            om = (double)c * m;
-        }
-        if (out_mean) out_mean[c - 1] = (float)m;
-        if (out_omega) out_omega[c - 1] = (float)om;
-        if (om > -INFINITY && om >= bv) { bv = om; bc = c; }
-    }
-    best_v[threadIdx.x] = bv;
-    best_c[threadIdx.x] = bc;
-    __syncthreads();
-    for (int d = THREADS / 2; d > 0; d >>= 1) {
-        if ((int)threadIdx.x < d) {
-            const double ov = best_v[threadIdx.x + d];
-            const int oc = best_c[threadIdx.x + d];
-            const double mv = best_v[threadIdx.x];
-            const int mc = best_c[threadIdx.x];
-            const bool take = oc != 0 && (mc == 0 || ov > mv || (ov == mv && oc > mc));
-            if (take) { best_v[threadIdx.x] = ov; best_c[threadIdx.x] = oc; }
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        const bool none = best_c[0] == 0;
-        // an earlier kernel of the same decision gave up (the filter's state exchange): the samples
-        // behind this c* are not a prediction
-        const bool stalled = fault && __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
-        out_cstar[0] = none || stalled ? c_max : best_c[0];
-        out_cstar[1] = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
-        if (ticket) {  // a host polling out_cstar[2] (pinned memory) must see the decision first
-            __threadfence_system();
-            __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-    }
-}
-
-// Both reduction levels and the argmax in one workgroup, for problems whose per-block sums are few
-// enough (a few thousand per thread at most) that one launch beats two: thread (part, col) adds
-// the blocks part, part + P, ... of one rank with eight loads in flight, the P parts of a rank are
-// added in order from LDS.  (A single launch in which the last workgroup of the sort does the
-// argmax was measured slower at every size: making one workgroup's sums visible to another
-// inside a kernel costs a write-back of the XCD's L2.)
-constexpr int kFusedMeansMaxN = 128;          // widest row the one-workgroup reduction takes
-constexpr int kFusedMeansMaxSums = 32768;     // most per-block sums it takes (blocks x N)
-
-constexpr int kFusedThreads = 1024;
-__global__ __launch_bounds__(kFusedThreads) void rank_means_argmax(const float *__restrict__ partial, int blocks,
-                                                                   int npad, int N, int S, int c_min, int c_max,
-                                                                   float t_floor, float *__restrict__ out_mean,
-                                                                   float *__restrict__ out_omega,
-                                                                   int32_t *__restrict__ out_cstar,
-                                                                   const int32_t *ticket, const int32_t *fault, int rate) {
-    __shared__ double part2[kMeanParts * kFusedMeansMaxN];  // [kMeanParts][N], unused parts are zero
-    __shared__ double best_v[kFusedThreads];
-    __shared__ int best_c[kFusedThreads];
-    int cols = 1;
-    while (cols < N) cols <<= 1;               // threads per part (a power of two >= N)
-    int P = kFusedThreads / cols;              // parts
-    if (P > kMeanParts) P = kMeanParts;
-    const int col = threadIdx.x % cols, part = threadIdx.x / cols;
-    for (int i = threadIdx.x; i < kMeanParts * N; i += kFusedThreads) part2[i] = 0.0;
-    __syncthreads();
-    if (col < N && part < P) {
-        double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        int b = part;
-        for (; b + 31 * P < blocks; b += 32 * P) {  // thirty-two loads in flight, added as four rounds of eight
-            float v[32];
-#pragma unroll
-            for (int j = 0; j < 32; ++j) v[j] = partial[(size_t)(b + j * P) * npad + col];
-#pragma unroll
-            for (int j = 0; j < 32; ++j) s[j & 7] += (double)v[j];
-        }
-        for (; b + 7 * P < blocks; b += 8 * P) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = partial[(size_t)(b + j * P) * npad + col];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) s[j] += (double)v[j];
-        }
-        for (int j = 0; b < blocks; b += P, ++j) s[j] += (double)partial[(size_t)b * npad + col];
-        part2[part * N + col] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
-    }
-    __syncthreads();
-    omega_argmax_body<kFusedThreads>(part2, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, best_v,
-                                     best_c, ticket, fault, rate);
-}
-
 struct SortPlan {
     int e, lg;       // keys per lane, log2(lanes per row)
     int npad;        // e << lg
@@ -772,16 +668,10 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
     }
     {
         StageTimer timer(kStageArgmax, stream);
-        if (N <= kFusedMeansMaxN && p.blocks * N <= kFusedMeansMaxSums) {
-            hipLaunchKernelGGL(rank_means_argmax, dim3(1), dim3(kFusedThreads), 0, stream, partial, p.blocks,
-                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate);
-            DKF_HIP_TRY(hipGetLastError());
-        } else {
-            hipLaunchKernelGGL(rank_means_omega, dim3((N + 63) / 64), dim3(kRankThreads), 0, stream, partial, p.blocks,
-                               p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate,
-                               rs);
-            DKF_HIP_TRY(hipGetLastError());
-        }
+        hipLaunchKernelGGL(rank_means_omega, dim3((N + 63) / 64), dim3(kRankThreads), 0, stream, partial, p.blocks,
+                           p.npad, N, S, c_min, c_max, t_floor, out_mean, out_omega, out_cstar, ticket, fault, rate,
+                           rs);
+        DKF_HIP_TRY(hipGetLastError());
     }
     return DKF_OK;
 }
