@@ -221,9 +221,12 @@ size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
                const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream);
 
-/* Failure detection for the filter of wide encoders (R > 256), whose recurrence
- * is split over several workgroups that hand their part of the state to each
- * other through memory every step.  A workgroup waits for the others a bounded
+/* Failure detection for filters whose workgroups wait for each other inside a
+ * launch: wide encoders (R > 256), whose recurrence is split over several
+ * workgroups that hand their part of the state to each other through memory
+ * every step, and encoders of 129-256 units with more than 128 workers, whose
+ * two workgroups wait for the input projection computed by other workgroups of
+ * the same launch.  A workgroup waits a bounded
  * number of polls; if that runs out (it cannot unless something else holds the
  * device for seconds) it raises a fault word, fills its encodings with NaN and
  * exits.  dkf_decide then returns DKF_ESTALLED instead of a cutoff (never

@@ -109,6 +109,7 @@ struct dkf_model {
     float *staging_graph = nullptr;
     int32_t *cstar_host = nullptr;  // pinned int32[4]: c*, status, ticket of the decision they belong to
     int32_t ticket = 0;             // sequence number of the last decision handed to the GPU
+    int32_t filter_seq = 0;         // Control::seq of the last filter step staged
 
     // workspace
     float *z_next = nullptr, *hid1 = nullptr, *mean = nullptr, *hid2 = nullptr;
@@ -616,6 +617,7 @@ FilterArgs filter_args(const dkf_model *m, const float *input) {
     a.bias_f = m->bias_f; a.bias_b = m->bias_b;
     a.N = m->N; a.Np = m->Np; a.L = m->L; a.R = m->R; a.Rp = m->Rp;
     a.fault = m->fault;
+    a.proj_flags = m->fault + 32;
     a.spin_limit = m->spin_limit;
     a.xcd_claims = m->xcd_claims;
     a.same_xcd = m->same_xcd;
@@ -625,6 +627,13 @@ FilterArgs filter_args(const dkf_model *m, const float *input) {
 
 // Host bookkeeping of one push: validates, updates the window mirror and the
 // normaliser, and fills `dst` (pinned) with the observation and its Control.
+// Control::seq of the next filter step: counts up for as long as the model lives (dkf_reset does
+// not rewind it), skipping zero, so a value is never seen twice by the device
+int32_t next_filter_seq(dkf_model *m) {
+    m->filter_seq = m->filter_seq == INT32_MAX ? 1 : m->filter_seq + 1;
+    return m->filter_seq;
+}
+
 int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *dst) {
     const int N = m->N, L = m->L;
     for (int j = 0; j < N; ++j)
@@ -650,6 +659,7 @@ int stage_observation(dkf_model *m, const float *x_obs, uint64_t seed, float *ds
     c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
     c.seed_lo = (uint32_t)seed;
     c.seed_hi = (uint32_t)(seed >> 32);
+    c.seq = next_filter_seq(m);
     std::memcpy(dst + m->Np, &c, sizeof c);
     return count < L ? DKF_WARMUP : DKF_OK;
 }
@@ -1112,9 +1122,9 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
 int dkf_check(dkf_model *m, void *stream_) {
     if (!m) return DKF_EINVAL;
     DKF_HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream_)));
-    int32_t f = 0;
-    DKF_HIP_TRY(hipMemcpy(&f, m->fault, sizeof f, hipMemcpyDeviceToHost));
-    return f != 0 ? DKF_ESTALLED : DKF_OK;
+    int32_t f[3] = {0, 0, 0};
+    DKF_HIP_TRY(hipMemcpy(f, m->fault, sizeof f, hipMemcpyDeviceToHost));
+    return (f[0] | f[1] | f[2]) != 0 ? DKF_ESTALLED : DKF_OK;
 }
 
 int dkf_set_exchange_spin_limit(dkf_model *m, int32_t polls) {
@@ -1186,6 +1196,7 @@ int dkf_set_state(dkf_model *m, const void *buf, size_t bytes) {
         c.oldest = stored < L ? 0 : (newest + 1) % L;
         c.scale = m->scale;
         c.inv_scale = m->scale > 0.f ? 1.0f / m->scale : 0.f;
+        c.seq = next_filter_seq(m);
         std::memcpy(dst + m->Np, &c, sizeof c);
         const int rc = launch_filter(filter_args(m, dst), true, slot == stored - 1 && stored == L, nullptr);
         if (rc != DKF_OK) return rc;

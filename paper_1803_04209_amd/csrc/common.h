@@ -63,6 +63,8 @@ struct Control {
     float inv_scale;    // 1/s
     uint32_t seed_lo;   // seed of the built-in generator for this step
     uint32_t seed_hi;
+    int32_t seq;        // number of this filter step in the life of the model (from 1, never repeated):
+                        // what the projection workgroups of the merged filter kernel publish when done
 };
 
 // Weights of one dense layer re-tiled as the B operand of the 32x32 matrix instructions,
@@ -94,8 +96,12 @@ struct FilterArgs {
     const float *w_hh_f, *w_hh_b;      // dev [R][R]
     const float *bias_f, *bias_b;      // dev [R]: b_ih + b_hh
     int N, Np, L, R, Rp;
-    int32_t *fault;   // dev: set to 1 by the multi-workgroup encoder when its bounded wait ran out;
-                      // cleared by the projection kernel that precedes it
+    int32_t *fault;   // dev int32[3]: [0] set to 1 by the multi-workgroup encoder when its bounded wait ran
+                      // out, cleared by the projection kernel that precedes it; [1 + direction] cleared
+                      // and, when its wait for the projection runs out, set by that direction's
+                      // workgroup of the merged kernel.  Readers take any non-zero word as "stalled".
+    int32_t *proj_flags;  // dev int32[32]: Control::seq of the last step whose rows projection workgroup i
+                          // of the merged kernel has finished
     int spin_limit;   // polls that wait may take per step (0: give up at the first wait)
     int32_t *xcd_claims;  // dev int32[2]: row blocks handed out so far per direction (same-XCD encoder);
                           // cleared by the projection kernel

@@ -529,7 +529,9 @@ __global__ __launch_bounds__(kRankThreads) void rank_means_omega(const float *__
         const bool none = bc == 0;
         // an earlier kernel of the same decision gave up (the filter's state exchange): the samples
         // behind this c* are not a prediction
-        const bool stalled = fault && __hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+        const bool stalled = fault && (__hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) |
+                                       __hip_atomic_load(fault + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) |
+                                       __hip_atomic_load(fault + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) != 0;
         out_cstar[0] = none || stalled ? c_max : bc;
         out_cstar[1] = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
         if (ticket)  // a host polling out_cstar[2] (pinned memory) must see the decision first

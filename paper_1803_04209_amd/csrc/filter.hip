@@ -342,13 +342,11 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg(FilterArgs a)
 // of what one row x 64 columns per thread reads: that variant is bound by LDS bandwidth) at the
 // price of four 16-lane reductions.  No fused projection: the input terms come from the ring.
 // Dynamic LDS: (L * 256 + 2 * 320) floats.
-__global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a) {
+template <bool MERGED>
+__device__ __forceinline__ void encode_reg4_body(const FilterArgs &a, int dir) {
     constexpr int ROWS = 256, TPR = 16, KPT = 16, RPT = 4, SEG = KPT + 4, HBUF = TPR * SEG;
     extern __shared__ __align__(16) float lds[];
-    const Control ctl = *a.ctl;
-    const int dir = blockIdx.x;
     const int R = a.R, L = a.L;
-    if (ctl.count < L) return;
     const float *__restrict__ w = dir ? a.w_hh_b : a.w_hh_f;
     const float *__restrict__ bias = dir ? a.bias_b : a.bias_f;
     const float *__restrict__ proj = dir ? a.proj_b : a.proj_f;
@@ -358,44 +356,86 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a
     const int tid = threadIdx.x;
     const int rg = tid / TPR, seg = tid % TPR, k0 = seg * KPT;
 
-    // input terms of every step first (their loads are then in flight together with the matrix's)
-    for (int i0 = tid; i0 < L * ROWS; i0 += 4 * kChainThreads) {
-        float pv[4], bv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * kChainThreads;
-            const int step = i / ROWS, r = i % ROWS;
-            const int t = dir ? L - 1 - step : step;
-            int slot = ctl.oldest + t;
-            if (slot >= L) slot -= L;
-            const bool ok = i < L * ROWS && r < R;
-            pv[u] = ok ? proj[(size_t)slot * R + r] : 0.f;
-            bv[u] = ok ? bias[r] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * kChainThreads;
-            if (i < L * ROWS) pre[i] = pv[u] * ctl.inv_scale + bv[u];
-        }
-    }
+    // The matrix is the longest transfer of the kernel (256 KiB into one compute unit) and depends
+    // on nothing: in the merged kernel it is requested first and the projection workgroups do
+    // their work meanwhile.
     float wreg[RPT][KPT];
-    if (R == ROWS) {  // the whole tile is inside the matrix: plain 16-byte loads
+    auto load_matrix = [&] {
+        if (R == ROWS) {  // the whole tile is inside the matrix: plain 16-byte loads
 #pragma unroll
-        for (int i = 0; i < RPT; ++i)
+            for (int i = 0; i < RPT; ++i)
 #pragma unroll
-            for (int j = 0; j < KPT; j += 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(w + (size_t)(rg * RPT + i) * ROWS + k0 + j);
-                wreg[i][j] = v.x; wreg[i][j + 1] = v.y; wreg[i][j + 2] = v.z; wreg[i][j + 3] = v.w;
+                for (int j = 0; j < KPT; j += 4) {
+                    const float4 v = *reinterpret_cast<const float4 *>(w + (size_t)(rg * RPT + i) * ROWS + k0 + j);
+                    wreg[i][j] = v.x; wreg[i][j + 1] = v.y; wreg[i][j + 2] = v.z; wreg[i][j + 3] = v.w;
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < RPT; ++i) {
+                const int row = rg * RPT + i;
+#pragma unroll
+                for (int j = 0; j < KPT; ++j) wreg[i][j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
             }
-    } else {
-#pragma unroll
-        for (int i = 0; i < RPT; ++i) {
-            const int row = rg * RPT + i;
-#pragma unroll
-            for (int j = 0; j < KPT; ++j) wreg[i][j] = (row < R && k0 + j < R) ? w[(size_t)row * R + k0 + j] : 0.f;
         }
-    }
+    };
+    if (MERGED) load_matrix();
+    // merged: the control block comes from where the host put it (later kernels read the mirror
+    // that the first projection workgroup writes)
+    const Control ctl = MERGED ? *reinterpret_cast<const Control *>(a.input + a.Np) : *a.ctl;
+    if (MERGED && tid == 0) __hip_atomic_store(a.fault + 1 + dir, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ctl.count < L) return;
+
+    // input terms of every step (merged: all but the newest observation's, which is being computed)
+    auto input_terms = [&](bool newest) {
+        for (int i0 = tid; i0 < L * ROWS; i0 += 4 * kChainThreads) {
+            float pv[4], bv[4];
+            bool mine[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kChainThreads;
+                const int step = i / ROWS, r = i % ROWS;
+                const int t = dir ? L - 1 - step : step;
+                int slot = ctl.oldest + t;
+                if (slot >= L) slot -= L;
+                mine[u] = i < L * ROWS && (!MERGED || (slot == ctl.slot) == newest);
+                const bool ok = mine[u] && r < R;
+                const float *src = proj + (size_t)slot * R + r;
+                // the newest row was written by other workgroups of this launch: read it past the caches
+                pv[u] = !ok ? 0.f : (MERGED && newest) ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+                bv[u] = ok ? bias[r] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kChainThreads;
+                if (mine[u]) pre[i] = pv[u] * ctl.inv_scale + bv[u];
+            }
+        }
+    };
+    input_terms(false);
+    if (!MERGED) load_matrix();
     for (int i = tid; i < 2 * HBUF; i += kChainThreads) h[i] = 0.f;
+    if (MERGED) {
+        // Wait until every projection workgroup has published this step's number (bounded: when the
+        // polls run out the direction's fault word is raised and the workgroup leaves; the decision's
+        // last kernel and dkf_check report that as DKF_ESTALLED).
+        bool arrived = true;
+        const int P = (int)gridDim.x - 2;
+        if (tid < P) {
+            for (int polls = 0;; ++polls) {  // (a limit of zero gives up before the first look)
+                if (polls >= a.spin_limit) { arrived = false; break; }
+                if (__hip_atomic_load(a.proj_flags + tid, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == ctl.seq) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+        if (__syncthreads_or(!arrived)) {
+            // no encoding this step: the direction's rows become NaN, so that samples drawn from them
+            // cannot pass for a prediction
+            if (tid == 0) __hip_atomic_store(a.fault + 1 + dir, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int i = tid; i < L * R; i += kChainThreads) ctx[(size_t)(i / R) * a.Rp + i % R] = __builtin_nanf("");
+            return;
+        }
+        input_terms(true);
+    }
     __syncthreads();
 
     const int my_row = rg * RPT + (seg & (RPT - 1));  // lanes 0..3 of a row group write one row each
@@ -409,7 +449,7 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a
                 const float4 hv = *reinterpret_cast<const float4 *>(hp + j);
 #pragma unroll
                 for (int i = 0; i < RPT; ++i)
-                    s[i] += (wreg[i][j] * hv.x + wreg[i][j + 1] * hv.y) + (wreg[i][j + 2] * hv.z + wreg[i][j + 3] * hv.w);
+                    s[i] = fmaf(wreg[i][j + 3], hv.w, fmaf(wreg[i][j + 2], hv.z, fmaf(wreg[i][j + 1], hv.y, fmaf(wreg[i][j], hv.x, s[i]))));
             }
 #pragma unroll
             for (int i = 0; i < RPT; ++i) s[i] = group_sum<TPR>(s[i]);
@@ -424,6 +464,71 @@ __global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a
         }
         __syncthreads();
     }
+}
+
+__global__ __launch_bounds__(kChainThreads) void encode_window_reg4(FilterArgs a) { encode_reg4_body<false>(a, blockIdx.x); }
+
+// Projection and recurrences of a step in one launch (128 < R <= 256, input matrix too large for the
+// two encoder workgroups to read alone).  Workgroups 0 and 1 are the encoders of encode_window_reg4;
+// workgroups 2 ... are the projection: 16 rows of one direction each (a wavefront per row), the
+// observation read straight from where the host staged it.  The encoders spend their first
+// microseconds fetching the recurrent matrix, which is when the projection is computed; a
+// projection workgroup publishes the step's number (Control::seq) in its flag word after its rows,
+// and an encoder starts the recurrence once every flag shows that number.  Nothing is ever reset:
+// the number is different for every step of a model's life.
+constexpr int kMergedProjRows = kChainThreads / 64;
+__global__ __launch_bounds__(kChainThreads) void encode_window_reg4_merged(FilterArgs a) {
+    if (blockIdx.x < 2) {
+        encode_reg4_body<true>(a, blockIdx.x);
+        return;
+    }
+    const int pb = blockIdx.x - 2, per_dir = ((int)gridDim.x - 2) / 2;
+    const int dir = pb / per_dir;
+    const Control ctl = *reinterpret_cast<const Control *>(a.input + a.Np);
+    // the observation crosses to this compute unit once (it may sit in host memory), then every
+    // wavefront reads it from LDS
+    extern __shared__ __align__(16) float xs[];  // [Np]
+    {
+        const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
+        const bool mirror = pb == 0 && a.mirror != a.input;  // device copy for the kernels that follow
+        for (int i = threadIdx.x; i < n; i += kChainThreads) {
+            const float v = a.input[i];
+            if (i < a.Np) xs[i] = v;
+            if (mirror) a.mirror[i] = v;
+        }
+    }
+    __syncthreads();
+    const float *x = xs;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = (pb % per_dir) * kMergedProjRows + wave;
+    const int N = a.N;
+    if (r < a.R) {
+        const float *__restrict__ wr = (dir ? a.w_ih_b : a.w_ih_f) + (size_t)r * N;
+        float s = 0.f;
+        if ((N & 3) == 0) {
+            for (int j0 = 0; j0 < N; j0 += 1024) {  // up to four 16-byte loads of the row in flight
+                float4 wv[4], xv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = j0 + lane * 4 + 256 * q;
+                    const int jc = j < N ? j : 0;
+                    wv[q] = *reinterpret_cast<const float4 *>(wr + jc);
+                    xv[q] = *reinterpret_cast<const float4 *>(x + jc);
+                    if (j >= N) wv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) s += wv[q].x * xv[q].x + wv[q].y * xv[q].y + wv[q].z * xv[q].z + wv[q].w * xv[q].w;
+            }
+        } else {
+            for (int j = lane; j < N; j += 64) s += wr[j] * x[j];
+        }
+        s = wave_sum(s);
+        if (lane == 0)
+            __hip_atomic_store((dir ? a.proj_b : a.proj_f) + (size_t)ctl.slot * a.R + r, s, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(a.proj_flags + pb, ctl.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Wide encoders (R > 256): the R x R matrix no longer fits one compute unit's registers, so each
@@ -655,6 +760,16 @@ int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t
     const int reg_rows = a.R <= 32 ? 32 : a.R <= 64 ? 64 : a.R <= 128 ? 128 : 256;  // rows the register kernel covers
     const bool fuse = project && reg_ok && (size_t)reg_rows * a.N <= 32768;
     const bool coop = encode && !reg_ok;  // wide encoders or long windows: several workgroups per direction
+    // 128 < R <= 256 with a large input matrix: projection and recurrences as one launch
+    const bool merged = project && encode && reg_ok && !fuse && a.R > 128 && (a.R + kMergedProjRows - 1) / kMergedProjRows <= 16;
+    if (merged) {
+        size_t lds = ((size_t)a.L * 256 + 2 * 16 * 20) * sizeof(float);
+        if (lds < a.Np * sizeof(float)) lds = a.Np * sizeof(float);  // (the projection workgroups stage the observation)
+        const int per_dir = (a.R + kMergedProjRows - 1) / kMergedProjRows;
+        hipLaunchKernelGGL(encode_window_reg4_merged, dim3(2 + 2 * per_dir), dim3(kChainThreads), lds, stream, a);
+        DKF_HIP_TRY(hipGetLastError());
+        return DKF_OK;
+    }
     if ((project && !fuse) || coop) {
         if (project && a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
             const size_t bytes = a.Np * sizeof(float) + sizeof(Control);

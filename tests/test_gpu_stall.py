@@ -2,7 +2,8 @@
 
 Wide encoders (R > 256) split the recurrence of the guide's RNNs (Sec. 3.1.3) over several
 workgroups that exchange their part of the state through memory, waiting a bounded number of
-polls.  The host lowers that number to zero for a few calls, so every wait counts as having run
+polls; encoders of 129-256 units with a large input matrix wait the same way for the projection
+workgroups of their launch.  The host lowers that number to zero for a few calls, so every wait counts as having run
 out: every workgroup then takes the give-up path and exits normally.  The decision must come back
 as DKF_ESTALLED (not as the informational CUTOFF_NO_ELIGIBLE), the separate calls must report it
 through dkf_check, and the model must work again once the limit is restored.
@@ -25,11 +26,13 @@ def api():
     return api
 
 
-@pytest.mark.parametrize("dtype,R", [("f32", 320), ("bf16", 512)])
-def test_stalled_exchange_is_an_error_and_recovers(api, dtype, R):
+@pytest.mark.parametrize("dtype,R,N", [("f32", 320, 96), ("bf16", 512, 96), ("f32", 256, 192)])
+def test_stalled_exchange_is_an_error_and_recovers(api, dtype, R, N):
+    """(R = 256 with 192 workers: one workgroup per direction, which waits for the projection
+    workgroups of the same launch instead.)"""
     import torch
 
-    cfg = synth.ClusterConfig("wide", 9, 96, 4, 64 if dtype == "bf16" else 8, R if dtype == "bf16" else 40, R, 160,
+    cfg = synth.ClusterConfig("wide", 9, N, 4, 64 if dtype == "bf16" else 8, R if dtype == "bf16" else 40, R, 160,
                               dtype, 50, "iid_stragglers_tiny")
     blob = synth.make_blob(cfg, std=0.05)
     tr = synth.make_trace(cfg)
