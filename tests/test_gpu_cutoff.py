@@ -210,3 +210,29 @@ def test_rate_rule_argument_errors(api):
     assert e.value.code == api.DKF_EINVAL
     with pytest.raises(api.DkfError):
         api.select_cutoff(x, rate=True, t_floor=float("nan"))
+
+
+@pytest.mark.parametrize("S,N", [(300, 16), (257, 158), (4096, 512), (512, 2048)])
+def test_workspace_contents_do_not_matter(api, S, N):
+    """The caller's workspace may hold anything: the counter of finished workgroups and the
+    candidates in it are written before they are read in every call.  Same decision from a
+    workspace of all-ones bits, of zeros, and from one the previous call left behind."""
+    import torch
+
+    x = synth.make_runtime_matrix("lognormal_stragglers", S, N, seed=7 * S + N)
+    o = oracle.cutoff_select(x, want_sorted=False, want_perm=False)
+    xd = torch.from_numpy(x).cuda()
+    ws = torch.empty(api.cutoff_select_workspace(S, N), dtype=torch.uint8, device="cuda")
+    mean = torch.empty(N, dtype=torch.float32, device="cuda")
+    omega = torch.empty(N, dtype=torch.float32, device="cuda")
+    results = []
+    for fill in (0xFF, 0x00, None, None):
+        if fill is not None:
+            ws.fill_(fill)
+        cstar = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+        api.cutoff_select(xd, 1, N, 0.0, None, None, mean, omega, cstar, ws)
+        c = cstar.cpu()
+        results.append((int(c[0]), int(c[1]), mean.clone()))
+        assert cstar_in_tie_band(int(c[0]), o)
+    for r in results[1:]:
+        assert r[0] == results[0][0] and r[1] == results[0][1] and torch.equal(r[2], results[0][2])
