@@ -178,3 +178,39 @@ def test_what_the_prescribed_precision_costs_on_the_large_preset():
     for k in ("z_next", "emit_mean", "emit_sd", "x"):
         assert raw[k].max() > 0.2 and 0.002 < np.mean(raw[k] > 2e-2) < 0.1, (k, raw[k].max(), np.mean(raw[k] > 2e-2))
         assert np.median(raw[k]) < 5e-3
+
+
+def test_flipped_gates_explain_the_large_misses_but_not_every_miss():
+    """Large preset, weights as specified, exact arithmetic against the prescribed mixed precision
+    (both on the CPU).  A row is called clean when every gate pre-activation of Sec. 3.1.3's
+    transition is further from zero than four times what the rounding moved it (and keeps its
+    sign).  The O(1) differences all sit in the other rows -- a hard gate switched the other way --
+    but the clean rows, where nothing switched, still end up further than 2e-2 from exact
+    arithmetic in the emission's scale and in x: eight rounded layers in sequence, the last
+    multiplied by the noise.  So no element-wise bound of 2e-2 holds on this preset for any
+    implementation of its precision, with or without protecting the gate."""
+    cfg = synth.CONFIGS["large_bf16"]
+    blob = synth.pack_blob(cfg, synth.make_weights(cfg, 0.1))
+    full, mixed = oracle.OracleModel(cfg, blob), oracle.OracleModel(cfg, blob, mlp_bf16=True)
+    tr = synth.make_trace(cfg)
+    for t in range(cfg.lag + 1):
+        full.filter_step(tr[t])
+        mixed.filter_step(tr[t])
+    eq, ez, ex = synth.make_noise(cfg)
+    rows = np.arange(0, cfg.samples, cfg.samples // 256, dtype=np.int32)
+    xf, sf = full.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
+    xm, sm = mixed.sample_runtimes(eq, ez, ex, rows=rows, stages=True)
+    sf["x"], sm["x"] = xf, xm
+    pf = full.transition_terms(eq, ez, ex, rows=rows)["gate_pre"]
+    pm = mixed.transition_terms(eq, ez, ex, rows=rows)["gate_pre"]
+    moved = np.abs(pm - pf)
+    near = np.abs(pf) <= 4 * moved + 1e-4 * np.sqrt(np.mean(pf ** 2))
+    clean = ~(near.any(axis=1) | (np.sign(pf) != np.sign(pm)).any(axis=1))
+    assert 0.3 < clean.mean() < 0.9
+
+    def worst(k, sel):
+        rms = np.sqrt(np.mean(sf[k] ** 2))
+        return (np.abs(sm[k] - sf[k]) / np.maximum(np.abs(sf[k]), rms))[sel].max()
+
+    assert worst("z_next", ~clean) > 0.5 and worst("z_next", clean) < 0.03  # the flips are where the band says
+    assert worst("emit_sd", clean) > 2e-2 and worst("x", clean) > 2e-2      # and still no 2e-2 without them
