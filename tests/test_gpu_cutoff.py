@@ -236,3 +236,30 @@ def test_workspace_contents_do_not_matter(api, S, N):
         assert cstar_in_tie_band(int(c[0]), o)
     for r in results[1:]:
         assert r[0] == results[0][0] and r[1] == results[0][1] and torch.equal(r[2], results[0][2])
+
+
+@pytest.mark.parametrize("N", [8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("S", [1024, 8192])
+def test_read_only_call_at_every_network_width(api, S, N):
+    """Rows that fill the sorting network exactly, in numbers that divide evenly over the grid: the
+    read-only call (no sorted rows, no permutation: what a decision runs) takes the loop body
+    without row or column checks at every width, two rows per wavefront at 512 keys and 8192 rows.
+    Means against the fp64 oracle, c* in its tie band, and the rows themselves through the
+    general body."""
+    import torch
+
+    x = synth.make_runtime_matrix("lognormal_stragglers", S, N, seed=31 * S + N)
+    x[3 % S, : min(N, 5)] = [0.0, -0.0, np.inf, -np.inf, 1e-30][: min(N, 5)]
+    o = oracle.cutoff_select(x, want_sorted=False, want_perm=False)
+    xd = torch.from_numpy(x).cuda()
+    g = api.select_cutoff(xd)
+    mean = g["mean"].cpu().numpy().astype(np.float64)
+    fin = np.isfinite(o["mean"])
+    assert np.array_equal(mean[~fin], o["mean"][~fin])
+    assert np.all(np.abs(mean[fin] - o["mean"][fin]) <= 2e-6 * np.abs(o["mean"][fin]) + 1e-12)
+    assert cstar_in_tie_band(g["cstar"], o)
+    full = api.select_cutoff(xd, want_sorted=True)
+    assert torch.allclose(g["mean"], full["mean"], rtol=1e-6, atol=0.0, equal_nan=True)
+    rows = np.random.default_rng(N).choice(S, 64, replace=False)
+    assert np.array_equal(full["sorted"][rows].cpu().numpy().view(np.uint32),
+                          np.sort(x[rows], axis=1).view(np.uint32))
