@@ -30,59 +30,53 @@ constexpr int kThreads = 256;
 using AccN = Acc<1>;
 constexpr int kTileF4 = 64;  // float4 per weight tile (one per lane)
 
-// Stream of weight chunks (CH tiles each) from global memory through a two-buffer LDS ring.
-// While chunk c is consumed from LDS, chunk c + 1 sits in registers (requested one chunk
-// earlier).  handover(), called in the middle of chunk c's matrix work, writes it to the other
-// buffer -- free since the barrier that ended chunk c - 1 -- and requests chunk c + 2; next(),
-// at the end of the chunk, is then a barrier and nothing else, so neither the LDS writes nor the
-// wait for the requested data stand between two chunks' matrix instructions.  A chunk is sized
-// so that its matrix work outlasts an L2 round trip.
+// Stream of weight chunks (CH tiles each) from global memory through a two-buffer LDS ring, moved
+// by global_load_lds_dwordx4: a wavefront's instruction carries one 1 KiB tile (16 bytes per lane,
+// consecutive lanes to consecutive LDS addresses, which is the tile's layout) from L2 into LDS
+// without passing through registers, so a chunk costs each wavefront CH / 4 load instructions and
+// nothing else -- no LDS stores, no staging registers.  While chunk c is consumed, chunk c + 1 is
+// on its way into the other buffer: it is requested right after the barrier that ended chunk
+// c - 1 (every wavefront is then done with that buffer), and next() at the end of chunk c waits for
+// the wavefront's own requests (they count in vmcnt like any load; the compiler does not connect
+// them with the LDS reads that follow, hence the explicit wait) before the barrier that makes all
+// of them visible.  A chunk is sized so that its matrix work outlasts an L2 round trip.
 template <int CH>
 struct WeightStream {
     static constexpr int kChunkF4 = CH * kTileF4;
-    static constexpr int kPerThread = (kChunkF4 + kThreads - 1) / kThreads;
-    typedef float Regs __attribute__((ext_vector_type(4 * kPerThread)));  // one value: stays in registers
+    static constexpr int kTilesPerWave = CH / (kThreads / 64);
+    static_assert(CH % (kThreads / 64) == 0, "whole tiles per wavefront");
+    static constexpr int kWaitVm0 = 0x0F70;  // s_waitcnt vmcnt(0), the other counters untouched
     const f32x4 *src;
     f32x4 *buf;
-    int total, cur_chunk, tid;
-    Regs regs;
+    int total, cur_chunk, lane, wave;
 
-    __device__ __forceinline__ Regs fetch(int chunk) const {
-        if (chunk >= total) chunk = total - 1;  // past the end: refetch the last chunk (never used)
-        Regs r;
+    __device__ __forceinline__ void request(int chunk, int b) const {
+        if (chunk >= total) chunk = total - 1;  // past the end: the last chunk again (never used)
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int idx = tid + i * kThreads;
-            const f32x4 t = src[(size_t)chunk * kChunkF4 + (kChunkF4 % kThreads == 0 || idx < kChunkF4 ? idx : 0)];
-            r[4 * i] = t.x; r[4 * i + 1] = t.y; r[4 * i + 2] = t.z; r[4 * i + 3] = t.w;
-        }
-        return r;
-    }
-    __device__ __forceinline__ void commit(Regs r, int b) const {
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            const int idx = tid + i * kThreads;
-            const f32x4 t = {r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]};
-            if (kChunkF4 % kThreads == 0 || idx < kChunkF4) buf[b * kChunkF4 + idx] = t;
+        for (int i = 0; i < kTilesPerWave; ++i) {
+            const int tile = wave * kTilesPerWave + i;
+            __builtin_amdgcn_global_load_lds(src + (size_t)chunk * kChunkF4 + tile * kTileF4 + lane,
+                                             (__attribute__((address_space(3))) void *)(buf + b * kChunkF4 + tile * kTileF4),
+                                             16, 0, 0);
         }
     }
-    __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int t) {
-        src = s; buf = b; total = n; tid = t; cur_chunk = 0;
-        regs = fetch(0);
-        commit(regs, 0);
-        regs = fetch(1);
+    __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int tid) {
+        src = s; buf = b; total = n; cur_chunk = 0;
+        lane = tid & 63;
+        wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        request(0, 0);
+        request(1, 1);
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
-    }
-    __device__ __forceinline__ void handover() {
-        commit(regs, (cur_chunk + 1) & 1);
-        regs = fetch(cur_chunk + 2);
     }
     __device__ __forceinline__ void next() {
-        ++cur_chunk;
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
+        ++cur_chunk;
+        request(cur_chunk + 1, (cur_chunk + 1) & 1);
     }
-    __device__ __forceinline__ f32x4 tile(int t, int lane) const {
-        return buf[(cur_chunk & 1) * kChunkF4 + t * kTileF4 + lane];
+    __device__ __forceinline__ f32x4 tile(int t, int lane_) const {
+        return buf[(cur_chunk & 1) * kChunkF4 + t * kTileF4 + lane_];
     }
 };
 
@@ -270,44 +264,26 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for_tile_groups<ZB * HB, GH>([&](int i) { return ws.tile(i, lane); },
                                      [&](int g, const f32x4(&tl)[GH]) {
                                          const int idx = g * GH;
-                                         if (g == ZB * HB / GH / 2) ws.handover();
                                          mma_wide<GH>(&out[idx % HB], tl, x[idx / HB]);
                                      });
         ws.next();
     };
-    // one 16-feature output block from HB tiles starting at tile `base` of the current chunk;
-    // `ride` runs before the first group of tiles and `mid` before the middle one (vector work of
-    // an earlier block that may be interleaved, or the stream's hand-over)
-    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB], auto &&ride, auto &&mid) {
+    // one 16-feature output block from HB tiles starting at tile `base` of the current chunk
+    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB]) {
         AccN acc;
         acc.init(b);
         for_tile_groups<HB, GH>([&](int i) { return ws.tile(base + i, lane); },
-                                [&](int g, const f32x4(&tl)[GH]) {
-                                    if (g == 0) ride();
-                                    if (g == HB / GH / 2) mid();
-                                    mma_narrow<GH>(acc, tl, &x[g * GH]);
-                                });
+                                [&](int g, const f32x4(&tl)[GH]) { mma_narrow<GH>(acc, tl, &x[g * GH]); });
         return acc.sum();
-    };
-    auto nothing = [] {};
-    auto handover = [&] { ws.handover(); };
-    // U blocks of a chunk: the hand-over goes before the middle block, or into the middle of the only one
-    auto narrow_blocks = [&](auto u_const, int base, f32x4 b, const f32x4(&x)[HB], int u) {
-        constexpr int U = decltype(u_const)::value;
-        if (U == 1) return narrow_block(base, b, x, nothing, handover);
-        if (u == U / 2) return narrow_block(base, b, x, handover, nothing);
-        return narrow_block(base, b, x, nothing, nothing);
     };
     // out = W h + b for an H -> Z layer: one chunk, tiles [zb][ib]
     auto narrow_from_h = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[HB]) {
 #pragma unroll
-        for (int zb = 0; zb < ZB; ++zb)
-            out[zb] = narrow_blocks(std::integral_constant<int, ZB>{}, zb * HB, bias4(tab, zb), x, zb);
+        for (int zb = 0; zb < ZB; ++zb) out[zb] = narrow_block(zb * HB, bias4(tab, zb), x);
         ws.next();
     };
     // Z -> Z layer: one chunk, tiles [ob][ib]
     auto small_layer = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[ZB]) {
-        ws.handover();  // a short chunk: nothing to hide behind
 #pragma unroll
         for (int ob = 0; ob < ZB; ++ob) {
             AccN acc;
@@ -369,14 +345,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 #pragma unroll
         for (int u = 0; u < RA; ++u) {
             const int ob = c * RA + u;
-            if (ob >= HB) continue;  // rows of zero tiles that fill the last chunk
-            // the hand-over goes before the chunk's second row, or into the middle of its only one
-            const bool two = RA >= 2 && c * RA + 1 < HB;
-            const f32x4 b = bias4(lb_escale1, ob);
-            const f32x4 v = two ? (u == 1 ? narrow_block(u * HB, b, h1, handover, nothing)
-                                          : narrow_block(u * HB, b, h1, nothing, nothing))
-                                : narrow_block(u * HB, b, h1, nothing, handover);
-            h2[ob] = relu4(v);
+            if (ob < HB) h2[ob] = relu4(narrow_block(u * HB, bias4(lb_escale1, ob), h1));  // (else: zero tiles that fill the last chunk)
         }
         ws.next();
     }
@@ -448,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
             const int nb_raw = c * K2 + u;
             const int nb = nb_raw < NB ? nb_raw : NB - 1;  // past the end: zero tiles, result goes to the sink
             // mean and scale of the block in one run of 2 HB tiles; the previous block's epilogue rides
-            // on the first group, the stream's hand-over sits in the middle of the chunk
+            // on the first group
             AccN am, as;
             am.init(bias4(lb_emean2, nb));
             as.init(bias4(lb_escale2, nb));
@@ -456,7 +425,6 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
                                         [&](int g, const f32x4(&tl)[GH]) {
                                             constexpr int kHalf = HB / GH;
                                             if (g == 0) emit(nb_p, pre_p, m_p, e_p);
-                                            if (K2 == 1 ? g == kHalf : (u == K2 / 2 && g == 0)) ws.handover();
                                             if (g < kHalf) mma_narrow<GH>(am, tl, &h1[g * GH]);
                                             else mma_narrow<GH>(as, tl, &h2[(g - kHalf) * GH]);
                                         });
