@@ -35,8 +35,9 @@ constexpr int kTileF4 = 64;  // float4 per weight tile (one per lane)
 // consecutive lanes to consecutive LDS addresses, which is the tile's layout) from L2 into LDS
 // without passing through registers, so a chunk costs each wavefront CH / 4 load instructions and
 // nothing else -- no LDS stores, no staging registers.  While chunk c is consumed, chunk c + 1 is
-// on its way into the other buffer: it is requested right after the barrier that ended chunk
-// c - 1 (every wavefront is then done with that buffer), and next() at the end of chunk c waits for
+// on its way into the other buffer (every wavefront was done with that one at the barrier that ended
+// chunk c - 1): its load instructions are handed out between the groups of chunk c's matrix
+// instructions (spread), whose shadow hides their issue, and next() at the end of chunk c waits for
 // the wavefront's own requests (they count in vmcnt like any load; the compiler does not connect
 // them with the LDS reads that follow, hence the explicit wait) before the barrier that makes all
 // of them visible.  A chunk is sized so that its matrix work outlasts an L2 round trip.
@@ -50,22 +51,30 @@ struct WeightStream {
     f32x4 *buf;
     int total, cur_chunk, lane, wave;
 
-    __device__ __forceinline__ void request(int chunk, int b) const {
+    // this wavefront's tiles [first, last) of `chunk` -> buffer b
+    __device__ __forceinline__ void request(int chunk, int b, int first = 0, int last = kTilesPerWave) const {
         if (chunk >= total) chunk = total - 1;  // past the end: the last chunk again (never used)
 #pragma unroll
         for (int i = 0; i < kTilesPerWave; ++i) {
+            if (i < first || i >= last) continue;
             const int tile = wave * kTilesPerWave + i;
             __builtin_amdgcn_global_load_lds(src + (size_t)chunk * kChunkF4 + tile * kTileF4 + lane,
                                              (__attribute__((address_space(3))) void *)(buf + b * kChunkF4 + tile * kTileF4),
                                              16, 0, 0);
         }
     }
+    // Called once for every k < n by the n groups of a chunk's matrix work: the request for the
+    // chunk after the current one, handed out over the first half of them (the second half of the
+    // chunk is the time the last of it has to arrive).
+    __device__ __forceinline__ void spread(int k, int n) const {
+        const int m = n >= 2 ? n / 2 : 1;
+        if (k < m) request(cur_chunk + 1, (cur_chunk + 1) & 1, k * kTilesPerWave / m, (k + 1) * kTilesPerWave / m);
+    }
     __device__ __forceinline__ void start(const f32x4 *s, f32x4 *b, int n, int tid) {
         src = s; buf = b; total = n; cur_chunk = 0;
         lane = tid & 63;
         wave = __builtin_amdgcn_readfirstlane(tid >> 6);
         request(0, 0);
-        request(1, 1);
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
     }
@@ -73,7 +82,6 @@ struct WeightStream {
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
         ++cur_chunk;
-        request(cur_chunk + 1, (cur_chunk + 1) & 1);
     }
     __device__ __forceinline__ f32x4 tile(int t, int lane_) const {
         return buf[(cur_chunk & 1) * kChunkF4 + t * kTileF4 + lane_];
@@ -264,22 +272,27 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for_tile_groups<ZB * HB, GH>([&](int i) { return ws.tile(i, lane); },
                                      [&](int g, const f32x4(&tl)[GH]) {
                                          const int idx = g * GH;
+                                         ws.spread(g, ZB * HB / GH);
                                          mma_wide<GH>(&out[idx % HB], tl, x[idx / HB]);
                                      });
         ws.next();
     };
-    // one 16-feature output block from HB tiles starting at tile `base` of the current chunk
-    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB]) {
+    // one 16-feature output block from HB tiles starting at tile `base` of the current chunk; the
+    // block is number u of the U its chunk holds (for the stream's requests)
+    auto narrow_block = [&](int base, f32x4 b, const f32x4(&x)[HB], int u, int U) {
         AccN acc;
         acc.init(b);
         for_tile_groups<HB, GH>([&](int i) { return ws.tile(base + i, lane); },
-                                [&](int g, const f32x4(&tl)[GH]) { mma_narrow<GH>(acc, tl, &x[g * GH]); });
+                                [&](int g, const f32x4(&tl)[GH]) {
+                                    ws.spread(u * (HB / GH) + g, U * (HB / GH));
+                                    mma_narrow<GH>(acc, tl, &x[g * GH]);
+                                });
         return acc.sum();
     };
     // out = W h + b for an H -> Z layer: one chunk, tiles [zb][ib]
     auto narrow_from_h = [&](f32x4(&out)[ZB], const float *tab, const f32x4(&x)[HB]) {
 #pragma unroll
-        for (int zb = 0; zb < ZB; ++zb) out[zb] = narrow_block(zb * HB, bias4(tab, zb), x);
+        for (int zb = 0; zb < ZB; ++zb) out[zb] = narrow_block(zb * HB, bias4(tab, zb), x, zb, ZB);
         ws.next();
     };
     // Z -> Z layer: one chunk, tiles [ob][ib]
@@ -288,6 +301,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
         for (int ob = 0; ob < ZB; ++ob) {
             AccN acc;
             acc.init(bias4(tab, ob));
+            ws.spread(ob, ZB);
 #pragma unroll
             for (int ib = 0; ib < ZB; ++ib) {
                 const f32x4 tl[1] = {ws.tile(ob * ZB + ib, lane)};
@@ -345,7 +359,9 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 #pragma unroll
         for (int u = 0; u < RA; ++u) {
             const int ob = c * RA + u;
-            if (ob < HB) h2[ob] = relu4(narrow_block(u * HB, bias4(lb_escale1, ob), h1));  // (else: zero tiles that fill the last chunk)
+            // (rows past the end are zero tiles that fill the last chunk: only their requests are made)
+            if (ob < HB) h2[ob] = relu4(narrow_block(u * HB, bias4(lb_escale1, ob), h1, u, RA));
+            else ws.spread(u, RA);
         }
         ws.next();
     }
@@ -425,6 +441,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
                                         [&](int g, const f32x4(&tl)[GH]) {
                                             constexpr int kHalf = HB / GH;
                                             if (g == 0) emit(nb_p, pre_p, m_p, e_p);
+                                            ws.spread(u * 2 * kHalf + g, K2 * 2 * kHalf);
                                             if (g < kHalf) mma_narrow<GH>(am, tl, &h1[g * GH]);
                                             else mma_narrow<GH>(as, tl, &h2[(g - kHalf) * GH]);
                                         });
