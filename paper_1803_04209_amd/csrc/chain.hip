@@ -54,13 +54,21 @@ struct WeightStream {
     // this wavefront's tiles [first, last) of `chunk` -> buffer b
     __device__ __forceinline__ void request(int chunk, int b, int first = 0, int last = kTilesPerWave) const {
         if (chunk >= total) chunk = total - 1;  // past the end: the last chunk again (never used)
+        // (the instruction's immediate offset moves both addresses, and tiles are 1 KiB apart in memory
+        // and in LDS alike: four tiles share one address computation)
+        typedef __attribute__((address_space(3))) void *LdsPtr;
 #pragma unroll
         for (int i = 0; i < kTilesPerWave; ++i) {
             if (i < first || i >= last) continue;
-            const int tile = wave * kTilesPerWave + i;
-            __builtin_amdgcn_global_load_lds(src + (size_t)chunk * kChunkF4 + tile * kTileF4 + lane,
-                                             (__attribute__((address_space(3))) void *)(buf + b * kChunkF4 + tile * kTileF4),
-                                             16, 0, 0);
+            const int tile0 = wave * kTilesPerWave + (i & ~3);
+            const f32x4 *g = src + (size_t)chunk * kChunkF4 + tile0 * kTileF4 + lane;
+            LdsPtr l = (LdsPtr)(buf + b * kChunkF4 + tile0 * kTileF4);
+            switch (i & 3) {
+                case 0: __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0); break;
+                case 1: __builtin_amdgcn_global_load_lds(g, l, 16, 1024, 0); break;
+                case 2: __builtin_amdgcn_global_load_lds(g, l, 16, 2048, 0); break;
+                default: __builtin_amdgcn_global_load_lds(g, l, 16, 3072, 0); break;
+            }
         }
     }
     // Called once for every k < n by the n groups of a chunk's matrix work: the request for the
