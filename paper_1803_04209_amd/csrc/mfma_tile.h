@@ -84,7 +84,8 @@ __device__ __forceinline__ float tanh_f(float v) {  // 1 - 2 / (exp(2v) + 1)
 }
 __device__ __forceinline__ float softplus_f(float v) {  // max(v, 0) + ln(1 + exp(-|v|))
     const float e = __builtin_amdgcn_exp2f(fabsf(v) * -1.44269504088896341f);
-    return fmaxf(v, 0.f) + 0.693147180559945309f * __builtin_amdgcn_logf(1.0f + e);
+    // (max(v, 0) as a median of three: fmaxf costs a second instruction that quiets signalling NaNs)
+    return __builtin_amdgcn_fmed3f(v, 0.f, __builtin_huge_valf()) + 0.693147180559945309f * __builtin_amdgcn_logf(1.0f + e);
 }
 __device__ __forceinline__ float sigmoid_f(float v) {
     const float e = __builtin_amdgcn_exp2f(fabsf(v) * -1.44269504088896341f);
