@@ -315,6 +315,7 @@ int pack_chain(dkf_model *m, const RawLayers &r) {
     add_bias(r.b_gate1, H, HB); add_bias(r.b_gate2, Z, ZB); add_bias(r.b_prop1, H, HB); add_bias(r.b_prop2, Z, ZB);
     add_bias(r.b_lin, Z, ZB); add_bias(r.b_tscale, Z, ZB); add_bias(r.b_emean1, H, HB); add_bias(fold_b.data(), H, HB);
     add_bias(r.b_emean2, N, NB); add_bias(r.b_escale2, N, NB);
+    bt.resize((size_t)chain_bias_floats(RB * 16, ZB * 16, HB * 16, NB * 16), 0.f);  // whole KiB for the copy into LDS
     int rcb = upload(m, bt.data(), bt.size(), &m->chain_bias);
     if (rcb != DKF_OK) return rcb;
     int rc = upload(m, g.data(), g.size(), &m->chain_guide);

@@ -124,44 +124,47 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
     const bool live = smp < S;
     const int sc = live ? smp : S - 1;  // clamped sample index for loads
 
-    // guide weights, encodings and all biases -> LDS
+    // guide weights, encodings and all biases -> LDS.  The two tables that are copied as they are go
+    // straight from L2 into LDS, a 1 KiB tile per instruction (as the weight stream below); every
+    // workgroup wants the same kilobytes at the same moment, so each starts at a tile of its own and
+    // the requests spread over the memory channels.  Nothing waits before everything is requested.
     {
+        typedef __attribute__((address_space(3))) void *LdsPtr;
+        const int wv = __builtin_amdgcn_readfirstlane(wave);
         const f32x4 *src = reinterpret_cast<const f32x4 *>(a.guide_tiles);
-        // every workgroup wants the same kilobytes at the same moment: each starts at a slab of its
-        // own so that the requests spread over the memory channels, and all of a thread's loads
-        // are in flight before the first is stored
-        constexpr int kCopies = kGuideTiles * kTileF4 / kThreads;  // kTileF4 * tiles is a multiple of 64
-        if constexpr (kCopies <= 32) {
-            f32x4 t[kCopies];
-            const int rot = blockIdx.x % kCopies;
+        constexpr int kPerWave = (kGuideTiles + 3) / 4;
+        const int rot = (int)(blockIdx.x % kPerWave) * 4;
 #pragma unroll
-            for (int i = 0; i < kCopies; ++i) {
-                const int j = i + rot < kCopies ? i + rot : i + rot - kCopies;
-                t[i] = src[tid + j * kThreads];
-            }
-#pragma unroll
-            for (int i = 0; i < kCopies; ++i) {
-                const int j = i + rot < kCopies ? i + rot : i + rot - kCopies;
-                gw[tid + j * kThreads] = t[i];
-            }
-        } else {
-#pragma unroll 8
-            for (int i = 0; i < kCopies; ++i) gw[tid + i * kThreads] = src[tid + i * kThreads];
+        for (int j = 0; j < kPerWave; ++j) {
+            int tile = j * 4 + wv + rot;
+            if (tile >= kPerWave * 4) tile -= kPerWave * 4;
+            if (tile < kGuideTiles)
+                __builtin_amdgcn_global_load_lds(src + tile * kTileF4 + lane, (LdsPtr)(gw + tile * kTileF4), 16, 0, 0);
         }
-        for (int i = tid + kCopies * kThreads; i < kGuideTiles * kTileF4; i += kThreads) gw[i] = src[i];
-        // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
-        // with tanh written as 1 - 2 r
-        const int n4 = a.L * R16 / 4;
-        for (int i = tid; i < n4; i += kThreads) {
-            const int t = (i * 4) / R16, r = (i * 4) % R16;
-            const f32x4 f = *reinterpret_cast<const f32x4 *>(a.ctx_f + (size_t)t * a.Rp + r);
-            const f32x4 b = *reinterpret_cast<const f32x4 *>(a.ctx_b + (size_t)t * a.Rp + r);
-            reinterpret_cast<f32x4 *>(ctx)[i] = (f + b + splat(1.0f)) * (1.0f / 3.0f);
-        }
-        // all biases: one table, already in LDS order
-        const int b4 = (R16 + 6 * Z16 + 4 * H16 + 2 * N16) / 4;
+        // all biases: one table, already in LDS order, padded to whole tiles
+        const int bias_tiles = chain_bias_floats(R16, Z16, H16, N16) / 256;
         const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(a.bias_table);
-        for (int i = tid; i < b4; i += kThreads) reinterpret_cast<f32x4 *>(bias)[i] = bsrc[i];
+        for (int tile = wv; tile < bias_tiles; tile += kThreads / 64)
+            __builtin_amdgcn_global_load_lds(bsrc + tile * kTileF4 + lane,
+                                             (LdsPtr)(reinterpret_cast<f32x4 *>(bias) + tile * kTileF4), 16, 0, 0);
+        // (1 + h_left + h_right) / 3 per position: the constant part of h_out = (tanh(.) + ...) / 3
+        // with tanh written as 1 - 2 r; four positions per thread requested before the first is stored
+        const int n4 = a.L * R16 / 4;
+        for (int i0 = tid; i0 < n4; i0 += 4 * kThreads) {
+            f32x4 f[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kThreads < n4 ? i0 + u * kThreads : i0;
+                const int t = (i * 4) / R16, r = (i * 4) % R16;
+                f[u] = *reinterpret_cast<const f32x4 *>(a.ctx_f + (size_t)t * a.Rp + r);
+                b[u] = *reinterpret_cast<const f32x4 *>(a.ctx_b + (size_t)t * a.Rp + r);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * kThreads < n4)
+                    reinterpret_cast<f32x4 *>(ctx)[i0 + u * kThreads] = (f[u] + b[u] + splat(1.0f)) * (1.0f / 3.0f);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's tiles are in LDS
     }
     __syncthreads();
     auto bias4 = [&](const float *tab, int blk) { return *reinterpret_cast<const f32x4 *>(tab + blk * 16 + 4 * q); };
@@ -463,7 +466,7 @@ __global__ __launch_bounds__(kThreads) void sample_chain(ChainArgs a) {
 template <int ZB, int RB, int HB>
 size_t chain_lds_bytes(int L, int N) {
     const size_t nb16 = (size_t)((N + 15) / 16) * 16;
-    const size_t bias_floats = RB * 16 + 6 * ZB * 16 + 4 * HB * 16 + 2 * nb16;
+    const size_t bias_floats = chain_bias_floats(RB * 16, ZB * 16, HB * 16, (int)nb16);
     return (size_t)(2 * RB * ZB + ZB * ZB + 2 * chain_chunk_tiles(HB)) * kTileF4 * 16 +
            ((size_t)L * RB * 16 + bias_floats) * 4;
 }

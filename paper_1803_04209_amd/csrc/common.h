@@ -240,6 +240,11 @@ struct ChainArgs {
     int emit_mean_act;
     int split_waves;  // split.hip only: wavefronts per workgroup the streams were packed for (4 or 8)
 };
+// floats of the chained sampler's bias table (widths padded to 16-blocks), itself padded to whole
+// KiB: the kernel copies it into LDS a KiB at a time
+__host__ __device__ constexpr int chain_bias_floats(int r16, int z16, int h16, int n16) {
+    return (r16 + 6 * z16 + 4 * h16 + 2 * n16 + 255) / 256 * 256;
+}
 // tiles (16 x 16 weights, 1 KiB) per streamed chunk for a hidden width of hb 16-blocks
 __host__ __device__ constexpr int chain_chunk_tiles(int hb) { return hb >= 8 ? 32 : 4 * hb; }
 bool chain_supported(int Z, int R, int H, int L, int N);
