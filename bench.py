@@ -90,8 +90,8 @@ PARITY_NOTE = {
 
 # Sources whose change invalidates stored hardware-counter readings of a stage's kernel.
 STAGE_SOURCES = {
-    "sampler_fused": ["chain.hip", "quad.hip", "split.hip", "mfma16.h", "common.h", "mfma_tile.h"],
-    "sort_rank_sums": ["cutoff_select.hip", "common.h"],
+    "sampler_fused": ["chain.hip", "quad.hip", "split.hip", "mfma16.h", "common.h", "mfma_tile.h", "rowsort.h"],
+    "sort_rank_sums": ["cutoff_select.hip", "rowsort.h", "common.h"],
     "guide_transition": ["gchain.hip", "guide.hip", "common.h", "mfma_tile.h"],
     "emit_hidden": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
     "emit_mean": ["egemm.hip", "mlp_gemm.hip", "common.h", "mfma_tile.h"],
@@ -367,6 +367,9 @@ def run_workload(args, name, K, W, headline):
         "config": {"workload": f"{cfg.name}: N={N} L={cfg.lag} Z={cfg.z_dim} H={cfg.hidden} S={S}",
                    "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay)",
                    "weights": args.weights},
+        # True: in the timed dkf_decide path the sampler sorts the rows it draws and there is no row-sort
+        # launch; the per-stage figures below are of the eager calls, which sort in cutoff_select
+        "decide_sorts_in_sampler": pred.decide_sorts_in_sampler(S),
         "parity_note": PARITY_NOTE.get((cfg.mlp_dtype, args.weights), PARITY_NOTE["default"]),
         "decisions_per_s": K / wall,
         "latency_ms": {"p50": float(np.median(lat) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3),

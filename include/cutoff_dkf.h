@@ -300,6 +300,15 @@ int dkf_set_sampler(dkf_model *m, int32_t variant);
  * call, no device work.  DKF_EINVAL for a NULL model or S < 1. */
 int dkf_sampler_in_use(const dkf_model *m, int32_t S);
 
+/* Whether a dkf_decide call with S samples has the sampler sort the rows it draws
+ * (order statistics of Sec. 3.1.1, last paragraph, taken before the samples leave
+ * the compute unit: the decision then has no row-sort launch and reads no sample
+ * back): 1 for DKF_SAMPLER_SPLIT with eight wavefronts per workgroup, 128 or 512
+ * workers and S a multiple of 16, else 0.  dkf_sample_runtimes and cutoff_select
+ * called separately always sort in cutoff_select.  Host call, no device work.
+ * DKF_EINVAL for a NULL model or S < 1. */
+int dkf_decide_sorts_in_sampler(const dkf_model *m, int32_t S);
+
 /* Per-kernel timing with HIP events recorded on the stream the kernels are
  * launched on (process-wide, for benchmarks; not recorded inside dkf_decide's
  * captured graph).  Stage ids: 0 filter (projection + RNN chains), 1 guide

@@ -29,7 +29,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
     "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_rate", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
-    "dkf_check", "dkf_set_exchange_spin_limit", "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_sampler_in_use", "dkf_timing_enable", "dkf_timing_read",
+    "dkf_check", "dkf_set_exchange_spin_limit", "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_sampler_in_use", "dkf_decide_sorts_in_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
 
@@ -99,6 +99,7 @@ def _lib():
     lib.dkf_set_state.argtypes = [vp, vp, sz]
     lib.dkf_set_sampler.argtypes = [C.c_void_p, C.c_int32]
     lib.dkf_sampler_in_use.argtypes = [C.c_void_p, C.c_int32]
+    lib.dkf_decide_sorts_in_sampler.argtypes = [C.c_void_p, C.c_int32]
     lib.dkf_timing_enable.argtypes = [C.c_uint32]
     lib.dkf_timing_read.argtypes = [i32, C.POINTER(i32), C.POINTER(C.c_double)]
     _handle = lib
@@ -300,6 +301,10 @@ def dkf_sampler_in_use(handle, S: int) -> int:
     return _check("dkf_sampler_in_use", _lib().dkf_sampler_in_use(handle, int(S)))
 
 
+def dkf_decide_sorts_in_sampler(handle, S: int) -> bool:
+    return bool(_check("dkf_decide_sorts_in_sampler", _lib().dkf_decide_sorts_in_sampler(handle, int(S))))
+
+
 def dkf_timing_enable(stage_mask: int) -> None:
     _check("dkf_timing_enable", _lib().dkf_timing_enable(stage_mask))
 
@@ -337,6 +342,9 @@ class Predictor:
 
     def sampler_in_use(self, S: int) -> int:
         return dkf_sampler_in_use(self.handle, S)
+
+    def decide_sorts_in_sampler(self, S: int) -> bool:
+        return dkf_decide_sorts_in_sampler(self.handle, S)
 
     def reset(self):
         dkf_reset(self.handle)

@@ -690,7 +690,8 @@ int sampler_for(const dkf_model *m, int S) {
 }
 
 int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
-                  float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
+                  float *out_samples, const dkf_stage_outputs *st, hipStream_t stream, float *rank_partial = nullptr,
+                  uint32_t *rank_done = nullptr) {
     const int variant = sampler_for(m, S);
     const bool split = variant == DKF_SAMPLER_SPLIT, quad = variant == DKF_SAMPLER_WAVE4;
     ChainArgs c{};
@@ -716,6 +717,8 @@ int enqueue_chain(dkf_model *m, int S, const float *eps_q, const float *eps_z, c
     c.out_sd_dbg = st ? st->emit_sd : nullptr;
     c.S = S; c.L = m->L; c.Z = m->Z; c.R = m->R; c.H = m->H; c.N = m->N; c.NB = (m->N + 15) / 16;
     c.emit_mean_act = m->cfg.emit_mean_act;
+    if (rank_partial && !split) return DKF_EINVAL;
+    c.rank_partial = rank_partial; c.rank_done = rank_done;
     const int rc = split ? launch_split(c, stream) : quad ? launch_quad(c, stream) : launch_chain(c, stream);
     if (rc != DKF_OK) return rc;
     if (st && st->ctx) return copy_ctx(m, st->ctx, stream);
@@ -728,9 +731,19 @@ int enqueue_noise(dkf_model *m, int S, const Control *ctl, uint64_t seed, hipStr
                                (size_t)S * m->N, ctl, seed, stream);
 }
 
+// Whether the sampler a decision with S samples launches also sorts the rows it draws (then the
+// decision has no row-sort launch): the eight-wavefront split sampler at the widths it is built for.
+bool sampler_sorts_rows(const dkf_model *m, int S) {
+    return sampler_for(m, S) == DKF_SAMPLER_SPLIT &&
+           split_sorts_rows(m->Z, m->R, m->H, m->L, m->N, S, m->split_waves) && S / 16 <= cutoff_rank_sum_rows(S, m->N);
+}
+
 int enqueue_sample(dkf_model *m, int S, const float *eps_q, const float *eps_z, const float *eps_x,
-                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream) {
-    if (sampler_for(m, S) != DKF_SAMPLER_STAGED) return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream);
+                   float *out_samples, const dkf_stage_outputs *st, hipStream_t stream, float *rank_partial = nullptr,
+                   uint32_t *rank_done = nullptr) {
+    if (sampler_for(m, S) != DKF_SAMPLER_STAGED)
+        return enqueue_chain(m, S, eps_q, eps_z, eps_x, out_samples, st, stream, rank_partial, rank_done);
+    if (rank_partial) return DKF_EINVAL;
     int rc = DKF_EUNSUPPORTED;
     if (m->sampler != DKF_SAMPLER_STAGED && m->use_gchain) {
         GChainArgs c{};
@@ -1083,13 +1096,18 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
         int rc = launch_filter(filter_args(m, m->staging_graph), true, true, stream);
         hipError_t e = hipSuccess;
         if (rc == DKF_OK && own_noise) rc = enqueue_noise(m, S, m->ctl_dev(), 0, stream);  // seed travels in the control block
+        // where the sampler can, it sorts the rows it has just drawn and hands over their rank sums
+        const bool fused_sort = sampler_sorts_rows(m, S);
+        float *rank_partial = nullptr;
+        uint32_t *rank_done = nullptr;
+        if (fused_sort) cutoff_rank_sums_at(m->cutoff_ws, S, m->N, &rank_partial, &rank_done);
         if (rc == DKF_OK)
-            rc = own_noise ? enqueue_sample(m, S, m->gen_q, m->gen_z, m->gen_x, m->samples, nullptr, stream)
-                           : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream);
+            rc = own_noise ? enqueue_sample(m, S, m->gen_q, m->gen_z, m->gen_x, m->samples, nullptr, stream, rank_partial, rank_done)
+                           : enqueue_sample(m, S, eps_q, eps_z, eps_x, m->samples, nullptr, stream, rank_partial, rank_done);
         if (rc == DKF_OK)
             rc = launch_cutoff_select(m->samples, S, m->N, 1, m->N, 0.f, nullptr, nullptr, nullptr, nullptr,
                                       m->cstar_host, m->cutoff_ws, m->cutoff_ws_bytes, stream, &m->ctl_dev()->ticket,
-                                      m->fault);
+                                      m->fault, 0, fused_sort ? S / 16 : 0);
         g_capturing--;
         hipGraph_t graph = nullptr;
         e = hipStreamEndCapture(stream, &graph);
@@ -1219,6 +1237,11 @@ int dkf_set_sampler(dkf_model *m, int32_t variant) {
 int dkf_sampler_in_use(const dkf_model *m, int32_t S) {
     if (!m || S < 1) return DKF_EINVAL;
     return sampler_for(m, S);
+}
+
+int dkf_decide_sorts_in_sampler(const dkf_model *m, int32_t S) {
+    if (!m || S < 1) return DKF_EINVAL;
+    return sampler_sorts_rows(m, S) ? 1 : 0;
 }
 
 int dkf_timing_enable(uint32_t stage_mask) {

@@ -239,7 +239,16 @@ struct ChainArgs {
     int S, L, Z, R, H, N, NB;
     int emit_mean_act;
     int split_waves;  // split.hip only: wavefronts per workgroup the streams were packed for (4 or 8)
+    // split.hip only, optional (see split_sorts_rows): the workgroup also sorts its sixteen rows and
+    // writes their rank sums, [S / 16][N] fp32 by rank, which is what the row-sort kernel would have
+    // left for rank_means_omega; *rank_done is that kernel's counter of finished workgroups, cleared here
+    float *rank_partial;
+    uint32_t *rank_done;
 };
+// Whether launch_split can sort the rows it draws (ChainArgs::rank_partial): eight wavefronts per
+// workgroup, N = 128 or 512 workers (a row fills the sorting network exactly), whole workgroups of
+// sixteen samples.
+bool split_sorts_rows(int Z, int R, int H, int L, int N, int S, int waves);
 // floats of the chained sampler's bias table (widths padded to 16-blocks), itself padded to whole
 // KiB: the kernel copies it into LDS a KiB at a time
 __host__ __device__ constexpr int chain_bias_floats(int r16, int z16, int h16, int n16) {
@@ -294,8 +303,14 @@ int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_ma
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
                          const int32_t *ticket = nullptr,  // dev: if set, *ticket is stored to out_cstar[2] after c*
                          const int32_t *fault = nullptr,   // dev: if set and non-zero, the status becomes DKF_ESTALLED
-                         int rate = 0);  // 1: rank sums of reciprocals, Omega(c) = c * mean_k 1 / x_(c) (needs t_floor >= 0)
+                         int rate = 0,  // 1: rank sums of reciprocals, Omega(c) = c * mean_k 1 / x_(c) (needs t_floor >= 0)
+                         int presorted_blocks = 0);  // > 0: the rows are sorted already and that many rows of rank sums
+                                                     // lie where cutoff_rank_sums_at says; `samples` is not read
 size_t cutoff_workspace_bytes(int S, int N);
+// For a producer that sorts its own rows (split.hip): where in a workspace of cutoff_workspace_bytes(S, N)
+// its rank sums [rows][N] go, the counter it has to clear, and how many rows there is room for.
+void cutoff_rank_sums_at(void *workspace, int S, int N, float **partial, uint32_t **done);
+int cutoff_rank_sum_rows(int S, int N);
 // the same with the workspace in a fixed device array of the library (no allocation anywhere)
 int launch_cutoff_select_static(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                                 float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,

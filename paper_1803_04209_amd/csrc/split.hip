@@ -31,6 +31,7 @@
 #include "common.h"
 #include "mfma_tile.h"
 #include "mfma16.h"
+#include "rowsort.h"
 #include <type_traits>
 
 namespace dkf {
@@ -59,7 +60,8 @@ struct SplitShape {
     }
 };
 
-template <int ZB, int RB, int HB, int W, bool DBG>
+// SLG > 0: the workgroup also sorts its sixteen rows (N = 8 << SLG workers) and writes their rank sums.
+template <int ZB, int RB, int HB, int W, bool DBG, int SLG = 0>
 __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W / 4, W / 4))) void sample_split(ChainArgs a) {
     using Sh = SplitShape<ZB, RB, HB, W>;
     constexpr int RQ = Sh::RQ, HQ = Sh::HQ, C = Sh::C, kThreads = 64 * W;
@@ -400,6 +402,11 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W / 4, W
         for (int o = 0; o < HQ; ++o) x_h2[(w * HQ + o) * kTileF4 + lane] = own[o];
         __syncthreads();
     }
+    // rows of the workgroup for the sort below: [16][N + 4] floats (the pad keeps the sixteen samples
+    // of a store on different banks), then the wavefronts' rank sums [W][8][N / 8]
+    constexpr int kSortStride = (8 << SLG) + 4;
+    float *sort_rows = reinterpret_cast<float *>(x_mu);
+    static_assert(SLG == 0 || (16 * kSortStride + W * (8 << SLG)) * 4 <= 2 * W * 2 * ZB * kTileF4 * 16, "sort buffers fit the exchange buffers");
     // mean, scale, draw, back to seconds: per worker block HB tiles of the mean's output layer, row nb,
     // then HB tiles of the scale's (one chunk of the ring, or two)
     auto emit = [&](int nb_raw, f32x4 pre, f32x4 m, f32x4 e) {
@@ -410,6 +417,9 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W / 4, W
         // past N and blocks past the end go to the sink
         float *xp = (nb_raw < NB && n0 < N) ? a.out_samples + (size_t)sc * N + n0 : sink;
         *reinterpret_cast<f32x4 *>(xp) = x;
+        if constexpr (SLG > 0) {  // and into this workgroup's copy of its sixteen rows (exchange buffers: free by now)
+            if (nb_raw < NB) *reinterpret_cast<f32x4 *>(sort_rows + (lane & 15) * kSortStride + n0) = x;
+        }
         if constexpr (DBG) {
             if (live && nb_raw < NB) {
 #pragma unroll
@@ -459,6 +469,53 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(W / 4, W
         }
         emit(nb_raw, as.sum(), am.sum(), e);
     }
+    // ---- order statistics of the sixteen rows (Sec. 3.1.1, last paragraph) -------------------
+    // A lane group of N / 8 lanes sorts one row, eight keys per lane, exactly as the row-sort
+    // kernel does; the rank sums of the workgroup's rows are added in a fixed order and written as
+    // row blockIdx.x of the table rank_means_omega reduces.
+    if constexpr (SLG > 0) {
+        constexpr int E = 8, G = 1 << SLG, NPAD = E * G, RPW = 64 / G;  // RPW rows per wavefront at a time
+        static_assert(16 % RPW == 0, "whole passes");
+        using Lay = Layout<E, SLG>;
+        float *red = sort_rows + 16 * kSortStride;  // [W][E][G]
+        __syncthreads();  // every wavefront's worker blocks of the sixteen rows have been written
+        const int g = lane & (G - 1), sub = lane >> SLG;
+        float acc[E];
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] = 0.f;
+        for (int r0 = w * RPW; r0 < 16; r0 += W * RPW) {  // (the same trips for every lane of a wavefront)
+            const float *src = sort_rows + (r0 + sub) * kSortStride;
+            uint32_t v[E];
+#pragma unroll
+            for (int qq = 0; qq < E / 4; ++qq) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(src + Lay::load_index(g, qq * 4));
+                v[qq * 4] = key_of_flat(t[0]); v[qq * 4 + 1] = key_of_flat(t[1]);
+                v[qq * 4 + 2] = key_of_flat(t[2]); v[qq * 4 + 3] = key_of_flat(t[3]);
+            }
+            sort_in_lane<uint32_t, E>(v);
+            merge_up<uint32_t, E, SLG, Lay::kLgE + 1>(v, g);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] += value_of(v[e]);
+        }
+#pragma unroll
+        for (int d = G; d < 64; d <<= 1) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] += __shfl_xor(acc[e], d, 64);
+        }
+        if (lane < G) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) red[(w * E + e) * G + lane] = acc[e];
+        }
+        __syncthreads();
+        for (int idx = tid; idx < E * G; idx += kThreads) {
+            const int e = idx / G, gg = idx % G;
+            float sum = red[e * G + gg];
+#pragma unroll
+            for (int k = 1; k < W; ++k) sum += red[(k * E + e) * G + gg];
+            a.rank_partial[(size_t)blockIdx.x * NPAD + Lay::rank(gg, e)] = sum;
+        }
+        if (blockIdx.x == 0 && tid == 0) *a.rank_done = 0u;  // the counter of the reduction that follows
+    }
 }
 
 template <int ZB, int RB, int HB, int W>
@@ -468,15 +525,15 @@ size_t split_lds_bytes(int L, int N) {
     return (size_t)(2 * W * 2 * ZB + HB + HB + ZB) * kTileF4 * 16 + ((size_t)L * RB * 16 + bias_floats) * 4;
 }
 
-template <int ZB, int RB, int HB, int W, bool DBG>
+template <int ZB, int RB, int HB, int W, bool DBG, int SLG = 0>
 int launch_variant(const ChainArgs &a, size_t lds, hipStream_t stream) {
     static size_t raised = 0;  // largest LDS size the attribute has been set to
     if (lds > raised) {
-        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_split<ZB, RB, HB, W, DBG>),
+        DKF_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(sample_split<ZB, RB, HB, W, DBG, SLG>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         raised = lds;
     }
-    hipLaunchKernelGGL((sample_split<ZB, RB, HB, W, DBG>), dim3((a.S + 15) / 16), dim3(64 * W), lds, stream, a);
+    hipLaunchKernelGGL((sample_split<ZB, RB, HB, W, DBG, SLG>), dim3((a.S + 15) / 16), dim3(64 * W), lds, stream, a);
     DKF_HIP_TRY(hipGetLastError());
     return DKF_OK;
 }
@@ -486,6 +543,16 @@ int launch_one(const ChainArgs &a, hipStream_t stream) {
     const size_t lds = split_lds_bytes<ZB, RB, HB, W>(a.L, a.N);
     if (lds > 160 * 1024) return DKF_EUNSUPPORTED;
     const bool dbg = a.z_last || a.z_next_dbg || a.out_mean_dbg || a.out_sd_dbg;
+    if (a.rank_partial) {  // the caller has asked split_sorts_rows
+        if constexpr (W == 8) {
+            if (dbg || !a.rank_done || a.S % 16 != 0) return DKF_EINVAL;
+            if (a.N == 128) return launch_variant<ZB, RB, HB, W, false, 4>(a, lds, stream);
+            if constexpr (ZB >= 2) {  // (the rows of 512 workers need the exchange buffers of the wider latent)
+                if (a.N == 512) return launch_variant<ZB, RB, HB, W, false, 6>(a, lds, stream);
+            }
+        }
+        return DKF_EUNSUPPORTED;
+    }
     return dbg ? launch_variant<ZB, RB, HB, W, true>(a, lds, stream) : launch_variant<ZB, RB, HB, W, false>(a, lds, stream);
 }
 
@@ -502,6 +569,12 @@ bool split_supported(int Z, int R, int H, int L, int N, int waves) {
     if (zb == 2 && rb == 16 && hb == 16)
         return (waves == 4 ? split_lds_bytes<2, 16, 16, 4>(L, N) : split_lds_bytes<2, 16, 16, 8>(L, N)) <= 160 * 1024;
     return false;
+}
+
+bool split_sorts_rows(int Z, int R, int H, int L, int N, int S, int waves) {
+    const int zb = (Z + 15) / 16;
+    return waves == 8 && (N == 128 || (N == 512 && zb >= 2)) && S >= 16 && S % 16 == 0 &&
+           split_supported(Z, R, H, L, N, waves);
 }
 
 int split_stream_tiles(int Z, int R, int H, int N, int waves) {

@@ -467,6 +467,8 @@ def test_decide_graph_replays_match_eager(api, name):
     S = cfg.samples
     eq, ez, ex = cuda(*synth.make_noise(cfg))
     graph, eager = api.Predictor(cfg, blob), api.Predictor(cfg, blob)
+    # medium and replay: the decision's sampler sorts its own rows, the eager calls sort in cutoff_select
+    assert graph.decide_sorts_in_sampler(S) == (name in ("medium", "replay"))
     for t in range(cfg.lag + (12 if cfg.samples * cfg.n_workers <= 1 << 20 else 4)):
         c, status = graph.decide(tr[t], S, eq, ez, ex)
         re = eager.filter_step(tr[t])
@@ -485,6 +487,39 @@ def test_decide_graph_replays_match_eager(api, name):
             nq, nz, nx = cuda(*synth.make_noise(cfg, draw=t))
             eq.copy_(nq); ez.copy_(nz); ex.copy_(nx)
             torch.cuda.synchronize()
+    graph.close()
+    eager.close()
+
+
+@pytest.mark.parametrize("widths", [dict(N=128, Z=16, H=128, R=128), dict(N=512, Z=32, H=256, R=256),
+                                    dict(N=128, Z=32, H=256, R=256)])
+@pytest.mark.parametrize("S", [16, 272, 1000, 4096])
+def test_decide_with_rows_sorted_in_the_sampler(api, widths, S):
+    """dkf_decide where the sampler sorts its own rows (S a multiple of 16) and where it cannot
+    (S = 1000): the decision equals cutoff_select's on the samples of the eager call, and the
+    oracle's rule holds, over several steps with fresh noise."""
+    cfg = custom(L=4, S=S, **widths)
+    blob = synth.make_blob(cfg, std=0.05)
+    tr = synth.make_trace(cfg)
+    graph, eager = api.Predictor(cfg, blob), api.Predictor(cfg, blob)
+    assert graph.sampler_in_use(S) == SPLIT
+    assert graph.decide_sorts_in_sampler(S) == (S % 16 == 0)
+    for t in range(cfg.lag + 5):
+        eq, ez, ex = cuda(*synth.make_noise(cfg, draw=t))
+        c, status = graph.decide(tr[t], S, eq, ez, ex)
+        re = eager.filter_step(tr[t])
+        if t < cfg.lag - 1:
+            assert status == api.DKF_WARMUP == re
+            continue
+        x = eager.sample_runtimes(eq, ez, ex)
+        res = api.select_cutoff(x)
+        orc = oracle.cutoff_select(x.cpu().numpy(), want_sorted=False, want_perm=False)
+        assert status == res["status"]
+        # (the two paths add the rank sums in different orders: equal decisions up to ties in Omega)
+        assert c == res["cstar"] or cstar_in_tie_band(c, orc)
+        assert cstar_in_tie_band(c, orc)
+    with pytest.raises(api.DkfError):
+        graph.decide_sorts_in_sampler(0)
     graph.close()
     eager.close()
 
