@@ -45,7 +45,7 @@ def check(api, x, **kw):
     tol = 2e-6 * np.maximum(mag, 1e-30)
     fin_m = np.isfinite(o["mean"])
     assert np.array_equal(mean[~fin_m], o["mean"][~fin_m]), "infinite rank means"
-    assert np.all(np.abs(mean - o["mean"])[fin_m] <= (tol + 1e-7 * np.abs(o["mean"]))[fin_m]), "rank means"
+    assert np.all(np.abs(mean[fin_m] - o["mean"][fin_m]) <= tol[fin_m] + 1e-7 * np.abs(o["mean"][fin_m])), "rank means"
     assert g["status"] == o["status"]
     assert cstar_in_tie_band(g["cstar"], o), (g["cstar"], o["cstar"])
     om = g["omega"].cpu().numpy().astype(np.float64)
