@@ -77,7 +77,7 @@ struct dkf_model {
     const float *quad_guide = nullptr, *quad_stream = nullptr, *quad_bias = nullptr;
     int quad_chunks = 0;
     bool use_split = false;  // sizes covered by the sixteen-samples-per-workgroup sampler
-    int split_waves = 8;     // wavefronts per workgroup of that sampler: two per SIMD, so that one's vector work overlaps the other's matrix work
+    int split_waves = 8;     // wavefronts per workgroup of that sampler: two per SIMD, so that one issues while the other waits
     const float *split_stream = nullptr, *split_bias = nullptr;
     bool use_gchain = false;  // bf16 sizes covered by the register-resident guide/transition kernel
     const float *gc_tiles = nullptr, *gc_bias = nullptr, *gc_mu_w32 = nullptr, *gc_mu_b32 = nullptr;
