@@ -17,8 +17,10 @@ struct U4 { uint32_t x, y, z, w; };
 __device__ __forceinline__ U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+        // (each 64-bit product written as one: a single multiply instruction yields both halves)
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c.x, p1 = (uint64_t)0xCD9E8D57u * c.z;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
         c = U4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
@@ -29,11 +31,12 @@ __device__ __forceinline__ U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
 __device__ __forceinline__ void box_muller(uint32_t w0, uint32_t w1, float &n0, float &n1) {
     const float u1 = (float)((w0 >> 8) + 1u) * (1.0f / 16777216.0f);
     const float u2 = (float)(w1 >> 8) * (1.0f / 16777216.0f);
-    const float r = sqrtf(-2.0f * logf(u1));
-    float s, c;
-    sincospif(2.0f * u2, &s, &c);
-    n0 = r * c;
-    n1 = r * s;
+    // hardware log2 / sqrt / sin / cos (the last two take their argument in revolutions, which is
+    // what u2 is): u1 is a normal number in (0, 1] and u2 lies in [0, 1), so none of the library
+    // routines' range handling is needed; absolute error of a normal about 1e-6
+    const float r = __builtin_amdgcn_sqrtf(-1.38629436111989062f * __builtin_amdgcn_logf(u1));  // -2 ln u1 = -2 ln 2 log2 u1
+    n0 = r * __builtin_amdgcn_cosf(u2);
+    n1 = r * __builtin_amdgcn_sinf(u2);
 }
 
 // four consecutive elements 4g .. 4g+3 of tensor `tensor`
