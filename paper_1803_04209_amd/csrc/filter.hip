@@ -42,6 +42,24 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// mirror = input (observation + control block; `input` is pinned host memory): one workgroup, every
+// read across the bus in flight at once
+__global__ __launch_bounds__(1024) void mirror_observation(FilterArgs a) {
+    const int n = a.Np + (int)(sizeof(Control) / sizeof(float));
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = threadIdx.x + u * 1024;
+        v[u] = i < n ? a.input[i] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = threadIdx.x + u * 1024;
+        if (i < n) a.mirror[i] = v[u];
+    }
+    for (int i = threadIdx.x + 4096; i < n; i += 1024) a.mirror[i] = a.input[i];
+}
+
 // proj_dir[slot][r] = sum_j w_ih_dir[r][j] * x[j]      grid: (ceil(R/16), 2)
 __global__ __launch_bounds__(kProjThreads) void project_observation(FilterArgs a) {
     const Control ctl = *reinterpret_cast<const Control *>(a.input + a.Np);
@@ -772,8 +790,8 @@ int launch_filter(const FilterArgs &args, bool project, bool encode, hipStream_t
     }
     if ((project && !fuse) || coop) {
         if (project && a.input != a.mirror) {  // many workgroups re-read the vector: bring it into HBM first
-            const size_t bytes = a.Np * sizeof(float) + sizeof(Control);
-            DKF_HIP_TRY(hipMemcpyAsync(a.mirror, a.input, bytes, hipMemcpyHostToDevice, stream));
+            hipLaunchKernelGGL(mirror_observation, dim3(1), dim3(kChainThreads), 0, stream, a);
+            DKF_HIP_TRY(hipGetLastError());
         }
         a.input = a.mirror;  // (without `project` the observation of the last push is projected again: same result)
         a.mark_empty = coop;
