@@ -209,8 +209,8 @@ size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
  * Noise comes from the caller's tensors (eps_* as in dkf_sample_runtimes, read
  * at every call from the same addresses) or, if they are NULL, from `seed`.
  * Blocks until the decision has arrived and writes c* to *cstar_host.  (The
- * last kernel of the graph stores the decision and a per-call ticket in pinned
- * host memory, which the call watches; every kernel of the decision has
+ * last kernel of the graph stores the decision and a per-call ticket, as one
+ * 64-bit word, in pinned host memory, which the call watches; every kernel of the decision has
  * finished by then, but the stream may report busy for a few microseconds
  * more.  If the ticket does not arrive the stream is synchronised instead.)
  * Returns DKF_OK, DKF_WARMUP (then *cstar_host = N), CUTOFF_NO_ELIGIBLE, or

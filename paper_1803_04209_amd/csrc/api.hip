@@ -107,7 +107,7 @@ struct dkf_model {
     bool staging_used[kStagingSlots] = {};
     int staging_next = 0;
     float *staging_graph = nullptr;
-    int32_t *cstar_host = nullptr;  // pinned int32[4]: c*, status, ticket of the decision they belong to
+    int32_t *cstar_host = nullptr;  // pinned int32[4]: c*, status, then one 64-bit word {ticket | status | c*} of the same decision
     int32_t ticket = 0;             // sequence number of the last decision handed to the GPU
     int32_t filter_seq = 0;         // Control::seq of the last filter step staged
 
@@ -1122,20 +1122,25 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
     DKF_HIP_TRY(hipGraphLaunch(m->graph_exec, stream));
     m->graph_stream = stream;
     m->graph_launched = true;
-    // The last kernel stores {c*, status} and then this decision's ticket into pinned host memory.
-    // Watching for the ticket returns the decision a few microseconds before the runtime's own
-    // completion path would; the stream is synchronised as well if the ticket does not show up.
-    volatile int32_t *box = m->cstar_host;
+    // The last kernel stores this decision's ticket, the status and c* as one 64-bit word into pinned
+    // host memory (words 2 and 3 of the box).  Watching for the ticket returns the decision a few
+    // microseconds before the runtime's own completion path would; the stream is synchronised as
+    // well if the ticket does not show up.
+    const uint64_t *word = reinterpret_cast<const uint64_t *>(m->cstar_host + 2);
+    uint64_t v = 0;
     bool seen = false;
     for (long spin = 0; spin < kTicketSpins; ++spin) {
-        if (box[2] == ticket) { seen = true; break; }
+        v = __atomic_load_n(word, __ATOMIC_ACQUIRE);
+        if ((uint32_t)(v >> 32) == (uint32_t)ticket) { seen = true; break; }
         __builtin_ia32_pause();
     }
-    if (!seen) DKF_HIP_TRY(hipStreamSynchronize(stream));
-    __atomic_thread_fence(__ATOMIC_ACQUIRE);
-    if (box[2] != ticket) return DKF_EHIP;
-    *cstar_host = box[0];
-    return box[1];
+    if (!seen) {
+        DKF_HIP_TRY(hipStreamSynchronize(stream));
+        v = __atomic_load_n(word, __ATOMIC_ACQUIRE);
+        if ((uint32_t)(v >> 32) != (uint32_t)ticket) return DKF_EHIP;
+    }
+    *cstar_host = (int32_t)(v & 0xFFFFu);
+    return (int)(int16_t)((v >> 16) & 0xFFFFu);
 }
 
 int dkf_check(dkf_model *m, void *stream_) {

@@ -301,7 +301,8 @@ int launch_fill_normal3(float *out0, size_t n0, float *out1, size_t n1, float *o
 int launch_cutoff_select(const float *samples, int S, int N, int c_min, int c_max, float t_floor,
                          float *out_sorted, int32_t *out_perm, float *out_mean, float *out_omega,
                          int32_t *out_cstar, void *workspace, size_t workspace_bytes, hipStream_t stream,
-                         const int32_t *ticket = nullptr,  // dev: if set, *ticket is stored to out_cstar[2] after c*
+                         const int32_t *ticket = nullptr,  // dev: if set, out_cstar is 16-byte aligned int32[4] and words 2..3 receive
+                                                           // one 64-bit word: *ticket << 32 | (status & 0xFFFF) << 16 | c*
                          const int32_t *fault = nullptr,   // dev: if set and non-zero, the status becomes DKF_ESTALLED
                          int rate = 0,  // 1: rank sums of reciprocals, Omega(c) = c * mean_k 1 / x_(c) (needs t_floor >= 0)
                          int presorted_blocks = 0);  // > 0: the rows are sorted already and that many rows of rank sums

@@ -293,10 +293,20 @@ __global__ __launch_bounds__(kRankThreads) void rank_means_omega(const float *__
         const bool stalled = fault && (__hip_atomic_load(fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) |
                                        __hip_atomic_load(fault + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) |
                                        __hip_atomic_load(fault + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) != 0;
-        out_cstar[0] = none || stalled ? c_max : bc;
-        out_cstar[1] = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
-        if (ticket)  // a host polling out_cstar[2] (pinned memory) must see the decision first
-            __hip_atomic_store(out_cstar + 2, *ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        const int cs = none || stalled ? c_max : bc;
+        const int st = stalled ? DKF_ESTALLED : none ? CUTOFF_NO_ELIGIBLE : DKF_OK;
+        if (ticket) {
+            // For a host that watches pinned memory: ticket, status and c* travel as ONE 64-bit word
+            // (ticket in the high half, then 16 bits of status and 16 of c*), so whoever sees the
+            // ticket has the decision with it and no store has to wait for another (a release
+            // store at system scope would first write the whole L2 back).
+            const uint64_t word = ((uint64_t)(uint32_t)*ticket << 32) | ((uint64_t)((uint32_t)st & 0xFFFFu) << 16) |
+                                  (uint64_t)((uint32_t)cs & 0xFFFFu);
+            __hip_atomic_store(reinterpret_cast<uint64_t *>(out_cstar + 2), word, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        out_cstar[0] = cs;
+        out_cstar[1] = st;
     }
 }
 
