@@ -230,40 +230,32 @@ def run_workload(args, name, K, W, headline):
         pred.filter_step(trace[t_idx]); t_idx += 1
 
     # ---- region 1: K synchronous decisions through the captured graph (value, ms_per_step) ---------
-    for _ in range(W):
-        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+    # (dkf_decide_trace: the library's own loop of dkf_decide calls over consecutive rows of the trace,
+    # so that neither the rate nor the latencies contain the interpreter's per-call cost)
+    pred.decide_trace(trace[t_idx:t_idx + W], S, eq, ez, ex); t_idx += W
     torch.cuda.synchronize()
-    cuts = np.empty(K, dtype=np.int64)
     first_timed = t_idx
     t_start = time.perf_counter()
-    for i in range(K):
-        cuts[i], _ = pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+    cuts, _, _ = pred.decide_trace(trace[t_idx:t_idx + K], S, eq, ez, ex); t_idx += K
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
+    cuts = cuts.astype(np.int64)
 
     # ---- region 1a: latency of single decisions, at least LATENCY_DECISIONS of them -----------------
-    for _ in range(W):
-        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
+    pred.decide_trace(trace[t_idx:t_idx + W], S, eq, ez, ex); t_idx += W
     torch.cuda.synchronize()
-    lat = np.empty(KL)
-    for i in range(KL):
-        t0 = time.perf_counter()
-        pred.decide(trace[t_idx], S, eq, ez, ex); t_idx += 1
-        lat[i] = time.perf_counter() - t0
+    _, _, lat_us = pred.decide_trace(trace[t_idx:t_idx + KL], S, eq, ez, ex); t_idx += KL
+    lat = lat_us.astype(np.float64) * 1e-6
     torch.cuda.synchronize()
 
     # ---- region 1b: the same path, the library drawing its own noise (counter-based generator) ------
-    for i in range(W):
-        pred.decide(trace[t_idx], S, seed=i); t_idx += 1
+    pred.decide_trace(trace[t_idx:t_idx + W], S, seed=0); t_idx += W
     torch.cuda.synchronize()
-    lat_own = np.empty(K_own)
     t_start = time.perf_counter()
-    for i in range(K_own):
-        t0 = time.perf_counter()
-        pred.decide(trace[t_idx], S, seed=W + i); t_idx += 1
-        lat_own[i] = time.perf_counter() - t0
+    _, _, lat_own_us = pred.decide_trace(trace[t_idx:t_idx + K_own], S, seed=W); t_idx += K_own
     torch.cuda.synchronize()
     wall_own = time.perf_counter() - t_start
+    lat_own = lat_own_us.astype(np.float64) * 1e-6
 
     # ---- region 2: the same steps enqueued eagerly, one HIP event pair around every kernel launch ---
     out = torch.empty((S, N), dtype=torch.float32, device="cuda")
@@ -365,7 +357,7 @@ def run_workload(args, name, K, W, headline):
         "value": S * K / wall, "unit": "vectors/s", "steps": K, "warmup": W, "ms_per_step": wall / K * 1e3,
         "dtype": cfg.mlp_dtype,
         "config": {"workload": f"{cfg.name}: N={N} L={cfg.lag} Z={cfg.z_dim} H={cfg.hidden} S={S}",
-                   "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay)",
+                   "noise": "caller-supplied N(0,1) tensors resident in HBM", "path": "dkf_decide (hipGraph replay), called in sequence by dkf_decide_trace",
                    "weights": args.weights},
         # True: in the timed dkf_decide path the sampler sorts the rows it draws and there is no row-sort
         # launch; the per-stage figures below are of the eager calls, which sort in cutoff_select

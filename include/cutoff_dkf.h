@@ -221,6 +221,21 @@ size_t cutoff_rank_spread_workspace(int32_t S, int32_t N);
 int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, const float *eps_z,
                const float *eps_x, uint64_t seed, int32_t *cstar_host, void *stream);
 
+/* Sequential online replay: the server loop of Alg. 1 with the model in it.
+ * For t = 0 .. T-1 row t of trace_host ([T][N], host memory, seconds) is pushed
+ * and decided on exactly as by dkf_decide(m, trace_host + t N, S, eps_*, seed + t,
+ * ...); the filtering state is carried from step to step.  Per-step results go to
+ * host arrays of T entries, each of which may be NULL: cstar_host (c* of the
+ * step; N while warming up), status_host (what dkf_decide returned: DKF_OK,
+ * DKF_WARMUP, CUTOFF_NO_ELIGIBLE or DKF_ESTALLED) and latency_us_host (wall time
+ * of the step on the calling thread, from the observation in hand to c* in
+ * hand).  Stops at the first step whose dkf_decide returns another error and
+ * returns that code (entries from that step on are not written); else DKF_OK.
+ * DKF_EINVAL for a NULL model or trace or T < 1. */
+int dkf_decide_trace(dkf_model *m, const float *trace_host, int32_t T, int32_t S, const float *eps_q,
+                     const float *eps_z, const float *eps_x, uint64_t seed, int32_t *cstar_host,
+                     int32_t *status_host, float *latency_us_host, void *stream);
+
 /* Failure detection for filters whose workgroups wait for each other inside a
  * launch: wide encoders (R > 256), whose recurrence is split over several
  * workgroups that hand their part of the state to each other through memory

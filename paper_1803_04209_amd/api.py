@@ -28,7 +28,7 @@ STAGE_NAMES = ["filter", "guide_transition", "emit_hidden", "emit_mean", "emit_s
 
 EXPORTS = [
     "dkf_strerror", "dkf_last_hip_error", "dkf_blob_bytes", "dkf_load_weights", "dkf_free", "dkf_reset",
-    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_rate", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide",
+    "dkf_filter_step", "dkf_sample_runtimes", "cutoff_select", "cutoff_select_rate", "cutoff_select_workspace", "cutoff_select_static", "cutoff_select_static_max_workspace", "dkf_decide", "dkf_decide_trace",
     "dkf_check", "dkf_set_exchange_spin_limit", "dkf_decide_samples", "dkf_impute_censored", "dkf_impute_workspace", "cutoff_rank_spread", "cutoff_rank_spread_workspace", "dkf_get_state", "dkf_set_state", "dkf_set_sampler", "dkf_sampler_in_use", "dkf_decide_sorts_in_sampler", "dkf_timing_enable", "dkf_timing_read",
 ]
 
@@ -85,6 +85,7 @@ def _lib():
     lib.cutoff_select_static_max_workspace.restype = sz
     lib.cutoff_select_static_max_workspace.argtypes = []
     lib.dkf_decide.argtypes = [vp, vp, i32, vp, vp, vp, u64, C.POINTER(i32), vp]
+    lib.dkf_decide_trace.argtypes = [vp, vp, i32, i32, vp, vp, vp, u64, vp, vp, vp, vp]
     lib.dkf_check.argtypes = [vp, vp]
     lib.dkf_set_exchange_spin_limit.argtypes = [vp, i32]
     lib.dkf_decide_samples.restype = vp
@@ -253,6 +254,21 @@ def dkf_decide(model: int, x_obs: np.ndarray, S: int, eps_q, eps_z, eps_x, seed:
     return int(c.value), rc
 
 
+def dkf_decide_trace(model: int, trace: np.ndarray, S: int, eps_q, eps_z, eps_x, seed: int = 0, stream=None):
+    """One dkf_decide per row of `trace` ([T][N]) inside the library.  Returns (c* int32[T], status int32[T],
+    latency in microseconds float32[T])."""
+    torch = _torch()
+    f = torch.float32
+    x = np.ascontiguousarray(trace, dtype=np.float32)
+    T = int(x.shape[0])
+    c, st, lat = np.zeros(T, np.int32), np.zeros(T, np.int32), np.zeros(T, np.float32)
+    _check("dkf_decide_trace", _lib().dkf_decide_trace(
+        model, x.ctypes.data, T, S, _dev(eps_q, f, name="eps_q"), _dev(eps_z, f, name="eps_z"),
+        _dev(eps_x, f, name="eps_x"), int(seed), c.ctypes.data, st.ctypes.data, lat.ctypes.data,
+        _stream_ptr(stream) if stream is not None else None))
+    return c, st, lat
+
+
 def dkf_check(model: int, stream=None) -> int:
     """DKF_OK, or DKF_ESTALLED (returned, not raised) if the last filter step gave up."""
     rc = _lib().dkf_check(model, _stream_ptr(stream))
@@ -376,6 +392,9 @@ class Predictor:
 
     def decide(self, x_obs, S, eps_q=None, eps_z=None, eps_x=None, seed=0):
         return dkf_decide(self.handle, x_obs, S, eps_q, eps_z, eps_x, seed)
+
+    def decide_trace(self, trace, S, eps_q=None, eps_z=None, eps_x=None, seed=0):
+        return dkf_decide_trace(self.handle, trace, S, eps_q, eps_z, eps_x, seed)
 
     def decide_samples(self, S):
         """Copy of the [S][N] samples behind the last decide()."""

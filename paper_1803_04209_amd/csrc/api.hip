@@ -1,6 +1,7 @@
 // C ABI of libcutoff_dkf.so: model object, host-side window bookkeeping,
 // weight re-tiling, stream/graph orchestration.  All arithmetic of the
 // predictor runs in the kernels of the other .hip files; this file only moves data and launches them.
+#include <chrono>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -1141,6 +1142,23 @@ int dkf_decide(dkf_model *m, const float *x_obs, int32_t S, const float *eps_q, 
     }
     *cstar_host = (int32_t)(v & 0xFFFFu);
     return (int)(int16_t)((v >> 16) & 0xFFFFu);
+}
+
+int dkf_decide_trace(dkf_model *m, const float *trace_host, int32_t T, int32_t S, const float *eps_q,
+                     const float *eps_z, const float *eps_x, uint64_t seed, int32_t *cstar_host,
+                     int32_t *status_host, float *latency_us_host, void *stream_) {
+    if (!m || !trace_host || T < 1) return DKF_EINVAL;
+    for (int32_t t = 0; t < T; ++t) {
+        int32_t c = 0;
+        const auto t0 = std::chrono::steady_clock::now();
+        const int rc = dkf_decide(m, trace_host + (size_t)t * m->N, S, eps_q, eps_z, eps_x, seed + (uint64_t)t, &c, stream_);
+        const auto t1 = std::chrono::steady_clock::now();
+        if (rc < 0 && rc != DKF_ESTALLED) return rc;
+        if (cstar_host) cstar_host[t] = rc == DKF_ESTALLED ? m->N : c;
+        if (status_host) status_host[t] = rc;
+        if (latency_us_host) latency_us_host[t] = std::chrono::duration<float, std::micro>(t1 - t0).count();
+    }
+    return DKF_OK;
 }
 
 int dkf_check(dkf_model *m, void *stream_) {

@@ -524,6 +524,40 @@ def test_decide_with_rows_sorted_in_the_sampler(api, widths, S):
     eager.close()
 
 
+def test_decide_trace_equals_the_single_calls(api):
+    """dkf_decide_trace: the same decisions, statuses and final state as one dkf_decide per row."""
+    cfg = synth.CONFIGS["tiny"]
+    blob = synth.make_blob(cfg)
+    tr = synth.make_trace(cfg)
+    S = cfg.samples
+    eq, ez, ex = cuda(*synth.make_noise(cfg))
+    T = cfg.lag + 20
+    one, many = api.Predictor(cfg, blob), api.Predictor(cfg, blob)
+    singles = [one.decide(tr[t], S, eq, ez, ex) for t in range(T)]
+    c, st, lat = many.decide_trace(tr[:T], S, eq, ez, ex)
+    assert [(int(a), int(b)) for a, b in zip(c, st)] == singles
+    assert st[:cfg.lag - 1].tolist() == [api.DKF_WARMUP] * (cfg.lag - 1) and np.all(c[:cfg.lag - 1] == cfg.n_workers)
+    assert np.all(lat > 0) and np.all(lat < 1e6)
+    assert one.get_state() == many.get_state()
+    # the library's own noise: seed + t per step
+    singles = [one.decide(tr[T + t], S, seed=77 + t) for t in range(6)]
+    c, st, _ = many.decide_trace(tr[T:T + 6], S, seed=77)
+    assert [(int(a), int(b)) for a, b in zip(c, st)] == singles
+    # a bad observation stops the replay with its error; the steps before it have been taken
+    bad = tr[T + 6:T + 10].copy()
+    bad[2, 0] = -1.0
+    with pytest.raises(api.DkfError) as e:
+        many.decide_trace(bad, S, eq, ez, ex)
+    assert e.value.code == api.DKF_EBADOBS
+    for t in range(2):
+        one.decide(bad[t], S, eq, ez, ex)
+    assert one.get_state() == many.get_state()
+    with pytest.raises(api.DkfError):
+        many.decide_trace(tr[:0], S, eq, ez, ex)
+    one.close()
+    many.close()
+
+
 def test_sampler_in_use_follows_sizes_and_setting(api):
     cfg = synth.CONFIGS["medium"]
     g = api.Predictor(cfg, synth.make_blob(cfg))
