@@ -230,9 +230,10 @@ def run_workload(args, name, K, W, headline):
         pred.filter_step(trace[t_idx]); t_idx += 1
 
     # ---- region 1: K synchronous decisions through the captured graph (value, ms_per_step) ---------
+    Wn = max(W, 1)  # (at least one untimed decision per region: the first one with a given noise source captures the graph)
     # (dkf_decide_trace: the library's own loop of dkf_decide calls over consecutive rows of the trace,
     # so that neither the rate nor the latencies contain the interpreter's per-call cost)
-    pred.decide_trace(trace[t_idx:t_idx + W], S, eq, ez, ex); t_idx += W
+    pred.decide_trace(trace[t_idx:t_idx + Wn], S, eq, ez, ex); t_idx += Wn
     torch.cuda.synchronize()
     first_timed = t_idx
     t_start = time.perf_counter()
@@ -242,17 +243,17 @@ def run_workload(args, name, K, W, headline):
     cuts = cuts.astype(np.int64)
 
     # ---- region 1a: latency of single decisions, at least LATENCY_DECISIONS of them -----------------
-    pred.decide_trace(trace[t_idx:t_idx + W], S, eq, ez, ex); t_idx += W
+    pred.decide_trace(trace[t_idx:t_idx + Wn], S, eq, ez, ex); t_idx += Wn
     torch.cuda.synchronize()
     _, _, lat_us = pred.decide_trace(trace[t_idx:t_idx + KL], S, eq, ez, ex); t_idx += KL
     lat = lat_us.astype(np.float64) * 1e-6
     torch.cuda.synchronize()
 
     # ---- region 1b: the same path, the library drawing its own noise (counter-based generator) ------
-    pred.decide_trace(trace[t_idx:t_idx + W], S, seed=0); t_idx += W
+    pred.decide_trace(trace[t_idx:t_idx + Wn], S, seed=0); t_idx += Wn
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    _, _, lat_own_us = pred.decide_trace(trace[t_idx:t_idx + K_own], S, seed=W); t_idx += K_own
+    _, _, lat_own_us = pred.decide_trace(trace[t_idx:t_idx + K_own], S, seed=Wn); t_idx += K_own
     torch.cuda.synchronize()
     wall_own = time.perf_counter() - t_start
     lat_own = lat_own_us.astype(np.float64) * 1e-6
